@@ -1,0 +1,304 @@
+"""Pins for the CPU fp64 oracle: closed forms, independent formulations, library
+routines and brute force, chosen so that a dropped term, wrong sign or index, or a
+transposed operand in ``oracle/strd_oracle.c`` fails at least one of them.  CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+RNG = np.random.default_rng(1234)
+
+
+def _ssd_case(T, H, P, G, n, seed=0, with_D=True, with_S=True):
+    r = np.random.default_rng(seed)
+    x = r.standard_normal((T, H, P))
+    dt = np.log1p(np.exp(r.standard_normal((T, H))))
+    A = -np.exp(r.uniform(0, 2, H))
+    B = r.standard_normal((T, G, n))
+    C = r.standard_normal((T, G, n))
+    D = r.standard_normal(H) if with_D else None
+    S = r.standard_normal((H, P, n)) if with_S else None
+    return x, dt, A, B, C, D, S
+
+
+# ---------------------------------------------------------------- SSD ----
+
+def test_ssd_hand_worked_two_tokens(golden_dir):
+    gold = {}
+    for line in open(os.path.join(golden_dir, "ssd_two_token.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            gold[k] = float(v)
+    x = np.array([3.0, -1.0]).reshape(2, 1, 1)
+    dt = np.array([0.5, 2.0]).reshape(2, 1)
+    A = np.array([-1.0])
+    B = np.array([[1.0, 2.0], [0.5, -1.0]]).reshape(2, 1, 2)
+    C = np.array([[1.0, 1.0], [2.0, 0.5]]).reshape(2, 1, 2)
+    for fn in (oracle.ssd_seq, lambda *a: oracle.ssd_chunked(*a, chunk=1),
+               lambda *a: oracle.ssd_chunked(*a, chunk=2)):
+        y, S = fn(x, dt, A, B, C)
+        assert y[0, 0, 0] == pytest.approx(gold["y0"], rel=1e-14)
+        assert y[1, 0, 0] == pytest.approx(gold["y1"], rel=1e-13)
+        assert S[0, 0, 0] == pytest.approx(gold["S1_0"], rel=1e-13)
+        assert S[0, 0, 1] == pytest.approx(gold["S1_1"], rel=1e-13)
+    y = oracle.ssd_unrolled(x, dt, A, B, C)
+    assert y[1, 0, 0] == pytest.approx(gold["y1"], rel=1e-13)
+
+
+@pytest.mark.parametrize("T,chunk", [(1, 4), (37, 5), (64, 64), (70, 64), (96, 256)])
+def test_ssd_three_formulations_agree(T, chunk):
+    x, dt, A, B, C, D, S = _ssd_case(T, H=4, P=3, G=2, n=5, seed=T)
+    y1, s1 = oracle.ssd_seq(x, dt, A, B, C, D, S)
+    y2 = oracle.ssd_unrolled(x, dt, A, B, C, D, S)
+    y3, s3 = oracle.ssd_chunked(x, dt, A, B, C, D, S, chunk=chunk)
+    np.testing.assert_allclose(y2, y1, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(y3, y1, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(s3, s1, rtol=1e-10, atol=1e-11)
+
+
+def test_ssd_no_decay_is_prefix_sum():
+    T, P = 19, 4
+    x = RNG.standard_normal((T, 1, P))
+    dt = np.ones((T, 1))
+    A = np.zeros(1)
+    B = np.zeros((T, 1, 3)); B[:, 0, 0] = 1.0
+    C = B.copy()
+    for y in (oracle.ssd_seq(x, dt, A, B, C)[0], oracle.ssd_chunked(x, dt, A, B, C, chunk=4)[0],
+              oracle.ssd_unrolled(x, dt, A, B, C)):
+        np.testing.assert_allclose(y[:, 0, :], np.cumsum(x[:, 0, :], axis=0), rtol=1e-12)
+
+
+def test_ssd_constant_decay_geometric_series():
+    T, a = 25, 0.8
+    x = np.ones((T, 1, 1))
+    dt = np.ones((T, 1))
+    A = np.array([np.log(a)])
+    B = np.ones((T, 1, 1)); C = np.ones((T, 1, 1))
+    want = (1 - a ** (np.arange(T) + 1)) / (1 - a)
+    np.testing.assert_allclose(oracle.ssd_seq(x, dt, A, B, C)[0][:, 0, 0], want, rtol=1e-12)
+    np.testing.assert_allclose(oracle.ssd_chunked(x, dt, A, B, C, chunk=7)[0][:, 0, 0], want, rtol=1e-12)
+
+
+def test_ssd_state_is_outer_product_layout():
+    # one token, S_0 = 0: S = x (dt b)^T with shape [P, n] -- catches a transposed state
+    x = np.array([2.0, 3.0, 5.0]).reshape(1, 1, 3)
+    dt = np.array([[0.5]]); A = np.array([-1.0])
+    B = np.array([7.0, 11.0]).reshape(1, 1, 2); C = np.array([1.0, 0.0]).reshape(1, 1, 2)
+    y, S = oracle.ssd_seq(x, dt, A, B, C)
+    np.testing.assert_allclose(S[0], np.outer([2, 3, 5], [3.5, 5.5]))
+    np.testing.assert_allclose(y[0, 0], [7.0, 10.5, 17.5])
+
+
+def test_ssd_group_mapping_is_block_of_heads():
+    # H=4, G=2: heads 0,1 read group 0; heads 2,3 read group 1
+    T = 6
+    x, dt, A, B, C, _, _ = _ssd_case(T, H=4, P=2, G=2, n=3, seed=5, with_D=False, with_S=False)
+    y, _ = oracle.ssd_seq(x, dt, A, B, C)
+    for h in range(4):
+        g = h // 2
+        yh, _ = oracle.ssd_seq(x[:, h:h + 1], dt[:, h:h + 1], A[h:h + 1], B[:, g:g + 1], C[:, g:g + 1])
+        np.testing.assert_allclose(y[:, h], yh[:, 0], rtol=1e-13)
+
+
+def test_ssd_split_call_equals_single_call():
+    x, dt, A, B, C, D, S = _ssd_case(50, H=2, P=3, G=1, n=4, seed=9)
+    y, s = oracle.ssd_seq(x, dt, A, B, C, D, S)
+    ya, sa = oracle.ssd_seq(x[:21], dt[:21], A, B[:21], C[:21], D, S)
+    yb, sb = oracle.ssd_seq(x[21:], dt[21:], A, B[21:], C[21:], D, sa)
+    np.testing.assert_allclose(np.concatenate([ya, yb]), y, rtol=1e-12)
+    np.testing.assert_allclose(sb, s, rtol=1e-12)
+
+
+def test_ssd_D_is_a_skip_connection():
+    x, dt, A, B, C, D, S = _ssd_case(9, H=2, P=3, G=1, n=4, seed=3)
+    y0, _ = oracle.ssd_seq(x, dt, A, B, C, None, S)
+    y1, _ = oracle.ssd_seq(x, dt, A, B, C, D, S)
+    np.testing.assert_allclose(y1 - y0, D[None, :, None] * x, rtol=1e-10, atol=1e-12)
+
+
+# -------------------------------------------------------- Mamba score ----
+
+def test_score_mamba_scalar_case():
+    N, n = 7, 5
+    B = RNG.standard_normal((N, 1, n)); C = RNG.standard_normal((1, 1, n))
+    dt = RNG.uniform(0.1, 2, (N, 1))
+    want = dt[:, 0] * np.abs(B[:, 0] @ C[0, 0])
+    np.testing.assert_allclose(oracle.score_mamba(B, C, dt), want, rtol=1e-13)
+
+
+def test_score_mamba_abs_before_sum_and_head_mean():
+    # two text rows with opposite-sign alignments must not cancel
+    B = np.array([1.0, 0.0]).reshape(1, 1, 2)
+    C = np.array([[2.0, 0.0], [-2.0, 0.0]]).reshape(2, 1, 2)
+    dt = np.array([[1.0, 3.0]])           # H=2 heads in one group: mean dt = 2
+    assert oracle.score_mamba(B, C, dt)[0] == pytest.approx(4.0)
+
+
+def test_score_mamba_group_form_and_einsum():
+    N, M, H, G, n = 11, 6, 8, 2, 5
+    B = RNG.standard_normal((N, G, n)); C = RNG.standard_normal((M, G, n))
+    dt = RNG.uniform(0.1, 2, (N, H))
+    s = oracle.score_mamba(B, C, dt)
+    dbar = dt.reshape(N, G, H // G).mean(-1)                    # group-mean of Delta
+    want = (dbar[:, None, :] * np.abs(np.einsum("ign,mgn->img", B, C))).sum((1, 2)) / (M * G)
+    np.testing.assert_allclose(s, want, rtol=1e-12)
+    assert (s >= 0).all()
+    np.testing.assert_allclose(oracle.score_mamba(B, -3.0 * C, dt), 3.0 * s, rtol=1e-12)
+
+
+def test_score_mamba_full_equals_decay_free_when_A_is_zero():
+    N, M, H, G, n = 13, 4, 4, 2, 6
+    B = RNG.standard_normal((N + M, G, n)); C = RNG.standard_normal((N + M, G, n))
+    dt = RNG.uniform(0.1, 2, (N + M, H))
+    full = oracle.score_mamba_full(B, C, dt, np.zeros(H), N)
+    free = oracle.score_mamba(B[:N], C[N:], dt[:N])
+    np.testing.assert_allclose(full, free, rtol=1e-13)
+    decayed = oracle.score_mamba_full(B, C, dt, -np.ones(H), N)
+    assert (decayed < free).all()
+
+
+def test_score_mamba_full_is_impulse_response_of_the_recurrence():
+    # |w_{t,j}| read off the recurrence: x = unit impulse at token j, P = 1 -> y_t = w_{t,j}
+    N, M, H, G, n = 6, 3, 2, 1, 4
+    T = N + M
+    B = RNG.standard_normal((T, G, n)); C = RNG.standard_normal((T, G, n))
+    dt = RNG.uniform(0.1, 1.5, (T, H)); A = -RNG.uniform(0.2, 1.5, H)
+    want = np.zeros(N)
+    for j in range(N):
+        x = np.zeros((T, H, 1)); x[j] = 1.0
+        y, _ = oracle.ssd_seq(x, dt, A, B, C)
+        want[j] = np.abs(y[N:, :, 0]).sum() / (M * H)
+    np.testing.assert_allclose(oracle.score_mamba_full(B, C, dt, A, N), want, rtol=1e-12)
+
+
+# ----------------------------------------------------- attention score ----
+
+def test_score_attn_sums_to_one_and_uniform_for_zero_query():
+    q = RNG.standard_normal((5, 4, 8)); k = RNG.standard_normal((33, 2, 8))
+    assert oracle.score_attn(q, k).sum() == pytest.approx(1.0, rel=1e-13)
+    np.testing.assert_allclose(oracle.score_attn(np.zeros_like(q), k), np.full(33, 1 / 33), rtol=1e-13)
+
+
+def test_score_attn_matches_library_softmax_with_gqa():
+    from scipy.special import softmax
+    M, N, Hq, Hkv, d = 5, 29, 6, 2, 7
+    q = RNG.standard_normal((M, Hq, d)); k = RNG.standard_normal((N, Hkv, d))
+    kk = np.repeat(k, Hq // Hkv, axis=1)                         # head h reads kv head h // rep
+    z = np.einsum("mhd,nhd->mhn", q, kk) * 0.37
+    want = softmax(z, axis=-1).mean((0, 1))
+    np.testing.assert_allclose(oracle.score_attn(q, k, scale=0.37), want, rtol=1e-12)
+
+
+def test_score_attn_dominant_key_and_permutation():
+    M, N, H, d = 3, 17, 2, 4
+    q = np.abs(RNG.standard_normal((M, H, d))) + 0.5
+    k = RNG.standard_normal((N, H, d)) * 0.01
+    k[5] = 60.0
+    s = oracle.score_attn(q, k)
+    assert s[5] > 1 - 1e-9
+    k = RNG.standard_normal((N, H, d))
+    perm = RNG.permutation(N)
+    np.testing.assert_allclose(oracle.score_attn(q, k[perm]), oracle.score_attn(q, k)[perm], rtol=1e-13)
+
+
+# --------------------------------------------------------------- top-k ----
+
+def test_select_topk_brute_force_tiny():
+    for N in range(1, 7):
+        for vals in itertools.product([0.0, 0.5, 2.0], repeat=N):
+            s = np.array(vals)
+            for K in range(0, N + 1):
+                idx = oracle.select_topk(s, K)
+                # brute force over all K-subsets: maximal score sum, then lexicographically smallest
+                best = None
+                for sub in itertools.combinations(range(N), K):
+                    key = (-sum(s[list(sub)]), sub)
+                    if best is None or key < best:
+                        best = key
+                assert tuple(idx) == best[1]
+
+
+def test_select_topk_properties():
+    s = RNG.random(500)
+    idx = oracle.select_topk(s, 123)
+    assert (np.diff(idx) > 0).all()
+    want = np.sort(np.argsort(-s, kind="stable")[:123])
+    np.testing.assert_array_equal(idx, want)
+    np.testing.assert_array_equal(oracle.select_topk(s, 500), np.arange(500))
+    np.testing.assert_array_equal(oracle.select_topk(np.full(40, 0.25), 9), np.arange(9))
+    t = np.array([1.0, 3.0, 3.0, 0.0, 3.0, 2.0])
+    np.testing.assert_array_equal(oracle.select_topk(t, 2), [1, 2])     # ties: lowest index wins
+    np.testing.assert_array_equal(oracle.select_topk(t, 4), [1, 2, 4, 5])
+
+
+# ------------------------------------------------------------- compact ----
+
+def test_compact_is_row_gather_plus_text_tail():
+    N, M = 20, 3
+    src = RNG.integers(0, 2 ** 16, (N + M, 6)).astype(np.uint16)
+    idx = np.array([0, 4, 5, 19], np.int32)
+    dst, pos = oracle.compact(src, idx, N, M)
+    np.testing.assert_array_equal(dst, np.concatenate([src[idx], src[N:]]))
+    np.testing.assert_array_equal(pos, np.concatenate([idx, np.arange(N, N + M)]))
+    dst2, pos2 = oracle.compact(src, np.arange(N, dtype=np.int32), N, M)
+    np.testing.assert_array_equal(dst2, src)
+    # composing two compactions composes the position maps
+    idx_b = np.array([1, 3], np.int32)
+    _, pos_b = oracle.compact(dst, idx_b, 4, M, pos_in=pos)
+    np.testing.assert_array_equal(pos_b, [4, 19, 20, 21, 22])
+
+
+# ----------------------------------------------------------- attention ----
+
+def test_attn_matches_library_sdpa_with_gqa():
+    T, Hq, Hkv, d = 23, 6, 3, 8
+    q = RNG.standard_normal((T, Hq, d)); k = RNG.standard_normal((T, Hkv, d)); v = RNG.standard_normal((T, Hkv, d))
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(np.repeat(k, Hq // Hkv, 1)).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(np.repeat(v, Hq // Hkv, 1)).permute(1, 0, 2)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+    got = oracle.attn(q, k, v)
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+    rows = np.array([0, 7, 22], np.int32)
+    np.testing.assert_allclose(oracle.attn(q, k, v, rows=rows), got[rows], rtol=1e-14)
+
+
+def test_attn_special_cases():
+    T, H, d = 9, 2, 4
+    k = RNG.standard_normal((T, H, d)); v = RNG.standard_normal((T, H, d))
+    o = oracle.attn(np.zeros((T, H, d)), k, v)
+    want = np.cumsum(v, 0) / (np.arange(T) + 1)[:, None, None]
+    np.testing.assert_allclose(o, want, rtol=1e-12)
+    q = RNG.standard_normal((T, H, d))
+    np.testing.assert_allclose(oracle.attn(q, k, v)[0], v[0], rtol=1e-14)   # first row sees itself only
+
+
+# ------------------------------------------------------- reduced layer ----
+
+def test_full_budget_reproduces_the_unreduced_layer():
+    N, M, H, P, G, n = 40, 5, 2, 3, 1, 4
+    x, dt, A, B, C, _, _ = _ssd_case(N + M, H, P, G, n, seed=77, with_D=False, with_S=False)
+    s = oracle.score_mamba(B[:N], C[N:], dt[:N])
+    idx = oracle.select_topk(s, N)
+    xs, pos = oracle.compact(x, idx, N, M)
+    np.testing.assert_array_equal(pos, np.arange(N + M))
+    y_full, _ = oracle.ssd_seq(x, dt, A, B, C)
+    y_red, _ = oracle.ssd_seq(xs, oracle.compact(dt, idx, N, M)[0], A, oracle.compact(B, idx, N, M)[0],
+                              oracle.compact(C, idx, N, M)[0])
+    np.testing.assert_array_equal(y_red, y_full)
+
+
+def test_reduced_scan_runs_over_retained_positions_only():
+    # dropping a token removes both its input and its decay step from the product
+    N, M, H, P, G, n = 6, 2, 1, 2, 1, 3
+    x, dt, A, B, C, _, _ = _ssd_case(N + M, H, P, G, n, seed=5, with_D=False, with_S=False)
+    idx = np.array([0, 2, 3, 5], np.int32)
+    keep = np.concatenate([idx, np.arange(N, N + M)])
+    y_red, _ = oracle.ssd_seq(oracle.compact(x, idx, N, M)[0], oracle.compact(dt, idx, N, M)[0], A,
+                              oracle.compact(B, idx, N, M)[0], oracle.compact(C, idx, N, M)[0])
+    y_want = oracle.ssd_unrolled(x[keep], dt[keep], A, B[keep], C[keep])
+    np.testing.assert_allclose(y_red, y_want, rtol=1e-12)
