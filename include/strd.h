@@ -1,0 +1,164 @@
+/*
+ * strd.h -- C ABI of the stateful token-reduced prefill library for MI355X (gfx950).
+ *
+ * One hybrid layer of "Stateful Token Reduction for Long-Video Hybrid VLMs" is
+ * prefilled on a reduced token set: score the vision tokens against the text
+ * query, keep the top K in temporal order, compact every per-token tensor, run the
+ * layer mixer (Mamba-2 scan or causal GQA attention) on the K + M survivors.
+ *
+ * Common rules for every entry point
+ *   - A sequence is N vision tokens followed by M text tokens (Sec. 3.1).  All
+ *     tensors are token-major, contiguous, batch 1.
+ *   - Pointers marked [dev] are device pointers owned by the caller; [host] are
+ *     host pointers.  The library allocates, frees and retains nothing.
+ *   - `io` is the element type of the tensors declared `const void*` / `void*`
+ *     (STRD_F32 or STRD_BF16); accumulation, exponentials, decay, state and scores
+ *     are always fp32.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and the call returns without synchronising.
+ *   - `ws` is caller-provided scratch [dev] of at least the size the matching
+ *     *_workspace() query returns (may be NULL when that size is 0); its contents
+ *     are undefined before and after the call.  Buffers must be 16-byte aligned.
+ *   - Return value: STRD_OK or a negative strd_status.  On STRD_EINVAL,
+ *     STRD_EUNSUPPORTED and STRD_EWORKSPACE nothing was launched and no output was
+ *     written.  STRD_EHIP reports a failed launch (hipGetLastError).
+ *   - Shapes the kernels are not built for give STRD_EUNSUPPORTED; there is no CPU
+ *     or library fallback.
+ */
+#ifndef STRD_H
+#define STRD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { STRD_F32 = 0, STRD_BF16 = 1 } strd_dtype;
+
+typedef enum {
+    STRD_OK = 0,
+    STRD_EINVAL = -1,       /* inconsistent sizes or NULL where data is required  */
+    STRD_EUNSUPPORTED = -2, /* valid problem, no kernel built for this shape       */
+    STRD_EWORKSPACE = -3,   /* ws == NULL or ws_bytes too small                    */
+    STRD_EHIP = -4          /* the HIP runtime refused a launch                    */
+} strd_status;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *strd_status_string(int status);
+
+/* ABI version: major * 1000 + minor. */
+int strd_version(void);
+
+/* ---------------------------------------------------------------------------
+ * score_attn -- attention-layer importance (Sec. 3.1 "Attention Layers"):
+ *     s_i = 1/(M*Hq) * sum_{m,h} softmax_i( scale * q_m^h . k_i^{kv(h)} )
+ * The softmax runs over the N vision keys only, so sum_i s_i = 1.  Query head h
+ * reads key head kv(h) = h / (Hq/Hkv).
+ *   q_txt  [dev] [M, Hq, d]   text-row queries (already projected / rotated)
+ *   k_vis  [dev] [N, Hkv, d]  vision-row keys
+ *   scores [dev] [N] fp32     output
+ * Requires M,N >= 1, Hq % Hkv == 0.  Deterministic (fixed reduction order).
+ * ------------------------------------------------------------------------- */
+size_t strd_score_attn_workspace(int M, int N, int Hq, int Hkv, int d, strd_dtype io);
+int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, int N, int Hq,
+                    int Hkv, int d, float scale, strd_dtype io, void *ws, size_t ws_bytes,
+                    void *stream);
+
+/* ---------------------------------------------------------------------------
+ * score_mamba -- Decoupled Content Alignment (Eq. "ssm_importance"), the
+ * decay-free Mamba-2 score.  Delta is per head while b, c are per group, so the
+ * mean runs over every head:
+ *     s_i = 1/(M*H) * sum_{m,h} dt_i^h * | b_i^{g(h)} . c_m^{g(h)} |,  g(h) = h/(H/G)
+ * which equals the paper's group form with the group-mean of Delta in b-bar.
+ *   B_vis  [dev] [N, G, n]   vision-row input projections b
+ *   C_txt  [dev] [M, G, n]   text-row output projections c
+ *   dt_vis [dev] [N, H] fp32 discretisation steps (> 0, already softplus'd)
+ *   scores [dev] [N] fp32    output
+ * Requires M,N >= 1, H % G == 0.  Deterministic.
+ * ------------------------------------------------------------------------- */
+size_t strd_score_mamba_workspace(int M, int N, int H, int G, int n, strd_dtype io);
+int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, float *scores,
+                     int M, int N, int H, int G, int n, strd_dtype io, void *ws, size_t ws_bytes,
+                     void *stream);
+
+/* ---------------------------------------------------------------------------
+ * select_topk -- keep the K highest-scoring vision tokens, in temporal order
+ * (Sec. 3.1 "Token Selection").  Ties at the K-th score go to the lowest index.
+ *   scores [dev] [N] fp32, finite and >= 0 (both score kinds are); -0.0 counts as 0
+ *   idx    [dev] [K] int32 output, strictly ascending
+ * Requires 1 <= K <= N.  Bit-exact and deterministic.
+ * ------------------------------------------------------------------------- */
+size_t strd_select_topk_workspace(int N, int K);
+int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes,
+                     void *stream);
+
+/* ---------------------------------------------------------------------------
+ * compact -- drop the unselected vision tokens of one per-token tensor
+ * (Sec. 3.1: retained tokens continue; text tokens are never dropped):
+ *     dst[r, :]   = src[idx[r], :]   r < K
+ *     dst[K+m, :] = src[N+m, :]      m < M
+ *     pos_out     = the same gather applied to pos_in (identity map if pos_in NULL)
+ *   src     [dev] [N+M rows of row_bytes]      dst [dev] [K+M rows]; must not overlap src
+ *   idx     [dev] [K] int32, ascending, each in [0, N) (not checked on the device)
+ *   pos_in  [dev] [N+M] int32 or NULL          pos_out [dev] [K+M] int32 or NULL
+ * row_bytes > 0 and a multiple of 4; rows need only their natural alignment when
+ * row_bytes % 16 != 0.  src/dst may be NULL when only the position map is wanted.
+ * Requires 0 <= K <= N, M >= 0.  Bit-exact copy.
+ * ------------------------------------------------------------------------- */
+int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, int K,
+                 int64_t row_bytes, const int32_t *pos_in, int32_t *pos_out, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * ssd_prefill -- Mamba-2 mixer over T tokens (Eqs. "ssm_state_update",
+ * "ssm_output"), per head h with group g(h):
+ *     S_t = exp(dt_t * A) * S_{t-1} + x_t (dt_t * b_t)^T ,   y_t = S_t c_t (+ D x_t)
+ * evaluated in its chunked (state-space-dual) form with the state carried on chip.
+ *   x   [dev] [T, H, P]          dt [dev] [T, H] fp32 (> 0)     A [dev] [H] fp32 (<= 0)
+ *   B,C [dev] [T, G, n]          D  [dev] [H] fp32 or NULL
+ *   S_in  [dev] [H, P, n] fp32 or NULL (zero state)
+ *   y     [dev] [T, H, P]        S_out [dev] [H, P, n] fp32 or NULL
+ * `chunk` is the caller's chunk length (> 0); results do not depend on it beyond
+ * rounding and the kernels tile time themselves.  S_out of one call fed as S_in of
+ * the next continues the same scan.  Requires T >= 0, H % G == 0.
+ * ------------------------------------------------------------------------- */
+size_t strd_ssd_prefill_workspace(int T, int H, int P, int G, int n, int chunk, strd_dtype io);
+int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void *B, const void *C,
+                     const float *D, const float *S_in, void *y, float *S_out, int T, int H, int P,
+                     int G, int n, int chunk, strd_dtype io, void *ws, size_t ws_bytes,
+                     void *stream);
+
+/* ---------------------------------------------------------------------------
+ * attn_prefill -- causal softmax attention with grouped-query heads over T tokens
+ * (App. "Attention via Kernel Functions", first equation):
+ *     o_t^h = sum_{j<=t} softmax_j( scale * q_t^h . k_j^{kv(h)} ) v_j^{kv(h)}
+ * in the order the tokens have in the (compacted) sequence.
+ *   q [dev] [T, Hq, d]    k, v [dev] [T, Hkv, d]    o [dev] [T, Hq, d]
+ * Requires T >= 0, Hq % Hkv == 0.
+ * ------------------------------------------------------------------------- */
+size_t strd_attn_prefill_workspace(int T, int Hq, int Hkv, int d, strd_dtype io);
+int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv,
+                      int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * schedule_budgets -- per-layer token budgets of a retention schedule (Sec. 3.2
+ * and App. "Reduction Schedule Configurations").  alpha_l is relative to the
+ * original count N0; budgets never grow with depth and never fall below
+ * min(K_min, current count):
+ *     K_l = min(K_{l-1}, max(floor(alpha_l * N0), min(K_min, K_{l-1}))),  K_{-1} = N0
+ *   alpha [host] [L] doubles in [0, 1]      K_out [host] [L] int32
+ * Host-only helper; touches no device.
+ * ------------------------------------------------------------------------- */
+int strd_schedule_budgets(const double *alpha, int L, int N0, int K_min, int32_t *K_out);
+
+/* Sigmoid retention schedule (App. "Sigmoid Schedule"), layers l = 0..L-1:
+ *     alpha_l = a_end + (a_start - a_end) * sigmoid(k * (x0 - l / L))
+ *   alpha_out [host] [L] doubles */
+int strd_schedule_sigmoid(int L, double a_start, double a_end, double k, double x0,
+                          double *alpha_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRD_H */

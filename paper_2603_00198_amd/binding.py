@@ -1,0 +1,248 @@
+"""ctypes binding of libstrd.so: same names as the C entry points, torch tensors in and out.
+
+Only marshalling happens here: shape checks, output/workspace allocation through torch
+(device memory plumbing) and the current HIP stream.  Every step of the path runs in the
+library's kernels; if the library is missing the import of any function fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libstrd.so")
+
+STRD_F32, STRD_BF16 = 0, 1
+_c = ctypes
+_vp, _int, _i64, _f32, _sz = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_float, _c.c_size_t
+
+_SIGNATURES = {
+    "strd_status_string": (_c.c_char_p, [_int]),
+    "strd_version": (_int, []),
+    "strd_score_attn_workspace": (_sz, [_int] * 5 + [_int]),
+    "strd_score_attn": (_int, [_vp, _vp, _vp] + [_int] * 5 + [_f32, _int, _vp, _sz, _vp]),
+    "strd_score_mamba_workspace": (_sz, [_int] * 5 + [_int]),
+    "strd_score_mamba": (_int, [_vp, _vp, _vp, _vp] + [_int] * 5 + [_int, _vp, _sz, _vp]),
+    "strd_select_topk_workspace": (_sz, [_int, _int]),
+    "strd_select_topk": (_int, [_vp, _int, _int, _vp, _vp, _sz, _vp]),
+    "strd_compact": (_int, [_vp, _vp, _vp, _int, _int, _int, _i64, _vp, _vp, _vp]),
+    "strd_ssd_prefill_workspace": (_sz, [_int] * 6 + [_int]),
+    "strd_ssd_prefill": (_int, [_vp] * 9 + [_int] * 6 + [_int, _vp, _sz, _vp]),
+    "strd_attn_prefill_workspace": (_sz, [_int] * 4 + [_int]),
+    "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
+    "strd_schedule_budgets": (_int, [_vp, _int, _int, _int, _vp]),
+    "strd_schedule_sigmoid": (_int, [_int, _c.c_double, _c.c_double, _c.c_double, _c.c_double, _vp]),
+}
+
+_lib = None
+
+
+class StrdError(RuntimeError):
+    pass
+
+
+def lib():
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise StrdError("%s is missing: run `python -m paper_2603_00198_amd.build` "
+                            "(there is no fallback path)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def exported_symbols() -> Sequence[str]:
+    return tuple(_SIGNATURES)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise StrdError("%s failed: %s" % (what, lib().strd_status_string(rc).decode()))
+
+
+def _io(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return STRD_F32
+    if t.dtype == torch.bfloat16:
+        return STRD_BF16
+    raise StrdError("unsupported tensor dtype %s (fp32 or bf16)" % t.dtype)
+
+
+def _dev(*ts: Optional[torch.Tensor]):
+    for t in ts:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise StrdError("tensors must live on the GPU")
+        if not t.is_contiguous():
+            raise StrdError("tensors must be contiguous")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(nbytes: int, like: torch.Tensor) -> Tuple[Optional[torch.Tensor], int]:
+    if nbytes == 0:
+        return None, 0
+    return torch.empty(nbytes, dtype=torch.uint8, device=like.device), nbytes
+
+
+def score_attn(q_txt: torch.Tensor, k_vis: torch.Tensor, scale: Optional[float] = None,
+               out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """s[N] fp32 from text queries [M,Hq,d] and vision keys [N,Hkv,d]."""
+    _dev(q_txt, k_vis, out, ws)
+    M, Hq, d = q_txt.shape
+    N, Hkv, d2 = k_vis.shape
+    if d != d2 or q_txt.dtype != k_vis.dtype:
+        raise StrdError("q/k mismatch")
+    io = _io(q_txt)
+    if scale is None:
+        scale = d ** -0.5
+    if out is None:
+        out = torch.empty(N, dtype=torch.float32, device=q_txt.device)
+    need = lib().strd_score_attn_workspace(M, N, Hq, Hkv, d, io)
+    if ws is None:
+        ws, _ = _ws(need, q_txt)
+    _check(lib().strd_score_attn(_ptr(q_txt), _ptr(k_vis), _ptr(out), M, N, Hq, Hkv, d, scale, io,
+                                 _ptr(ws), 0 if ws is None else ws.numel(), _stream()), "score_attn")
+    return out
+
+
+def score_mamba(B_vis: torch.Tensor, C_txt: torch.Tensor, dt_vis: torch.Tensor,
+                out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """s[N] fp32 from vision b [N,G,n], text c [M,G,n] and vision dt [N,H] (fp32)."""
+    _dev(B_vis, C_txt, dt_vis, out, ws)
+    N, G, n = B_vis.shape
+    M = C_txt.shape[0]
+    H = dt_vis.shape[1]
+    if C_txt.shape[1:] != (G, n) or dt_vis.shape[0] != N or dt_vis.dtype != torch.float32 \
+            or B_vis.dtype != C_txt.dtype:
+        raise StrdError("B/C/dt mismatch")
+    io = _io(B_vis)
+    if out is None:
+        out = torch.empty(N, dtype=torch.float32, device=B_vis.device)
+    need = lib().strd_score_mamba_workspace(M, N, H, G, n, io)
+    if ws is None:
+        ws, _ = _ws(need, B_vis)
+    _check(lib().strd_score_mamba(_ptr(B_vis), _ptr(C_txt), _ptr(dt_vis), _ptr(out), M, N, H, G, n, io,
+                                  _ptr(ws), 0 if ws is None else ws.numel(), _stream()), "score_mamba")
+    return out
+
+
+def select_topk(scores: torch.Tensor, K: int, out: Optional[torch.Tensor] = None,
+                ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """idx[K] int32 ascending: the K highest scores, ties to the lowest index."""
+    _dev(scores, out, ws)
+    if scores.dtype != torch.float32 or scores.dim() != 1:
+        raise StrdError("scores must be a 1-D fp32 tensor")
+    N = scores.shape[0]
+    if out is None:
+        out = torch.empty(K, dtype=torch.int32, device=scores.device)
+    need = lib().strd_select_topk_workspace(N, K)
+    if ws is None:
+        ws, _ = _ws(need, scores)
+    _check(lib().strd_select_topk(_ptr(scores), N, K, _ptr(out), _ptr(ws), 0 if ws is None else ws.numel(),
+                                  _stream()), "select_topk")
+    return out
+
+
+def compact(src: Optional[torch.Tensor], idx: torch.Tensor, N: int, M: int,
+            pos_in: Optional[torch.Tensor] = None, want_pos: bool = False,
+            out: Optional[torch.Tensor] = None):
+    """Gather rows idx (vision) + the M text rows of src [N+M, ...]; returns dst or (dst, pos_out)."""
+    _dev(src, idx, pos_in, out)
+    if idx.dtype != torch.int32:
+        raise StrdError("idx must be int32")
+    K = idx.shape[0]
+    dst, row_bytes = None, 0
+    if src is not None:
+        if src.shape[0] != N + M:
+            raise StrdError("src must have N+M rows")
+        row_bytes = (src.numel() // max(src.shape[0], 1)) * src.element_size() if src.shape[0] else 0
+        if src.shape[0] == 0:
+            row_bytes = int(torch.Size(src.shape[1:]).numel()) * src.element_size()
+        dst = out if out is not None else torch.empty((K + M,) + tuple(src.shape[1:]), dtype=src.dtype,
+                                                      device=src.device)
+    pos_out = None
+    if want_pos or pos_in is not None:
+        pos_out = torch.empty(K + M, dtype=torch.int32, device=idx.device)
+    _check(lib().strd_compact(_ptr(src), _ptr(idx), _ptr(dst), N, M, K, row_bytes, _ptr(pos_in), _ptr(pos_out),
+                              _stream()), "compact")
+    if pos_out is not None:
+        return dst, pos_out
+    return dst
+
+
+def ssd_prefill(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,
+                D: Optional[torch.Tensor] = None, S_in: Optional[torch.Tensor] = None, chunk: int = 256,
+                want_state: bool = True, out: Optional[torch.Tensor] = None,
+                ws: Optional[torch.Tensor] = None):
+    """Mamba-2 scan: returns (y [T,H,P], S_out [H,P,n] fp32 or None)."""
+    _dev(x, dt, A, B, C, D, S_in, out, ws)
+    T, H, P = x.shape
+    G, n = B.shape[1:]
+    if dt.shape != (T, H) or A.shape != (H,) or B.shape != (T, G, n) or C.shape != (T, G, n) \
+            or dt.dtype != torch.float32 or A.dtype != torch.float32 or B.dtype != x.dtype or C.dtype != x.dtype:
+        raise StrdError("ssd_prefill: inconsistent shapes or dtypes")
+    for t, shp in ((D, (H,)), (S_in, (H, P, n))):
+        if t is not None and (tuple(t.shape) != shp or t.dtype != torch.float32):
+            raise StrdError("ssd_prefill: D / S_in must be fp32 of shape %s" % (shp,))
+    io = _io(x)
+    y = out if out is not None else torch.empty_like(x)
+    S_out = torch.empty(H, P, n, dtype=torch.float32, device=x.device) if want_state else None
+    need = lib().strd_ssd_prefill_workspace(T, H, P, G, n, chunk, io)
+    if ws is None:
+        ws, _ = _ws(need, x)
+    _check(lib().strd_ssd_prefill(_ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(S_in), _ptr(y),
+                                  _ptr(S_out), T, H, P, G, n, chunk, io, _ptr(ws),
+                                  0 if ws is None else ws.numel(), _stream()), "ssd_prefill")
+    return y, S_out
+
+
+def attn_prefill(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: Optional[float] = None,
+                 out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Causal GQA attention: o [T,Hq,d]."""
+    _dev(q, k, v, out, ws)
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    if k.shape != (T, Hkv, d) or v.shape != (T, Hkv, d) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise StrdError("attn_prefill: inconsistent shapes or dtypes")
+    io = _io(q)
+    if scale is None:
+        scale = d ** -0.5
+    o = out if out is not None else torch.empty_like(q)
+    need = lib().strd_attn_prefill_workspace(T, Hq, Hkv, d, io)
+    if ws is None:
+        ws, _ = _ws(need, q)
+    _check(lib().strd_attn_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(o), T, Hq, Hkv, d, scale, io, _ptr(ws),
+                                   0 if ws is None else ws.numel(), _stream()), "attn_prefill")
+    return o
+
+
+def schedule_budgets(alpha: Sequence[float], N0: int, K_min: int = 0):
+    """Per-layer budgets K_l from retention ratios alpha_l (host only)."""
+    L = len(alpha)
+    a = (ctypes.c_double * L)(*[float(v) for v in alpha])
+    k = (ctypes.c_int32 * L)()
+    _check(lib().strd_schedule_budgets(ctypes.cast(a, _vp), L, int(N0), int(K_min), ctypes.cast(k, _vp)),
+           "schedule_budgets")
+    return list(k)
+
+
+def schedule_sigmoid(L: int, a_start: float = 1.0, a_end: float = 0.125, k: float = 20.0, x0: float = 0.11):
+    """Sigmoid retention ratios alpha_l, l = 0..L-1 (host only)."""
+    out = (ctypes.c_double * L)()
+    _check(lib().strd_schedule_sigmoid(int(L), a_start, a_end, k, x0, ctypes.cast(out, _vp)), "schedule_sigmoid")
+    return list(out)

@@ -1,0 +1,145 @@
+// C ABI of the library: argument checks, workspace accounting and kernel selection.
+// Every entry point validates on the host, then enqueues kernels on the caller's stream.
+#include <math.h>
+
+#include "common.h"
+
+using namespace strd;
+
+namespace {
+
+inline bool io_ok(strd_dtype io) { return io == STRD_F32 || io == STRD_BF16; }
+inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
+
+}  // namespace
+
+extern "C" {
+
+const char *strd_status_string(int status) {
+    switch (status) {
+        case STRD_OK: return "STRD_OK";
+        case STRD_EINVAL: return "STRD_EINVAL: inconsistent arguments";
+        case STRD_EUNSUPPORTED: return "STRD_EUNSUPPORTED: no kernel for this shape";
+        case STRD_EWORKSPACE: return "STRD_EWORKSPACE: workspace missing or too small";
+        case STRD_EHIP: return "STRD_EHIP: HIP launch failed";
+        default: return "unknown strd status";
+    }
+}
+
+int strd_version(void) { return 1000; }
+
+// ------------------------------------------------------------------ score_attn -------------
+size_t strd_score_attn_workspace(int M, int N, int Hq, int Hkv, int d, strd_dtype io) {
+    (void)N; (void)Hkv; (void)d; (void)io;
+    if (M < 1 || Hq < 1) return 0;
+    return score_attn_general_ws(M, Hq);
+}
+
+int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, int N, int Hq, int Hkv,
+                    int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (!q_txt || !k_vis || !scores || M < 1 || N < 1 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io))
+        return STRD_EINVAL;
+    if ((long long)M * Hq > (1 << 30)) return STRD_EUNSUPPORTED;
+    const size_t need = strd_score_attn_workspace(M, N, Hq, Hkv, d, io);
+    if (!ws || ws_bytes < need) return STRD_EWORKSPACE;
+    return score_attn_general(q_txt, k_vis, scores, M, N, Hq, Hkv, d, scale, io, ws, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ score_mamba ------------
+size_t strd_score_mamba_workspace(int M, int N, int H, int G, int n, strd_dtype io) {
+    (void)M; (void)N; (void)H; (void)G; (void)n; (void)io;
+    return 0;
+}
+
+int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, float *scores, int M, int N,
+                     int H, int G, int n, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (!B_vis || !C_txt || !dt_vis || !scores || M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G || !io_ok(io))
+        return STRD_EINVAL;
+    const size_t need = strd_score_mamba_workspace(M, N, H, G, n, io);
+    if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    return score_mamba_general(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, io, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ select_topk ------------
+size_t strd_select_topk_workspace(int N, int K) {
+    (void)N; (void)K;
+    return 0;
+}
+
+int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes, void *stream) {
+    (void)ws; (void)ws_bytes;
+    if (!scores || !idx || N < 1 || K < 1 || K > N) return STRD_EINVAL;
+    return select_topk_launch(scores, N, K, idx, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ compact ----------------
+int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, int K, int64_t row_bytes,
+                 const int32_t *pos_in, int32_t *pos_out, void *stream) {
+    if (N < 0 || M < 0 || K < 0 || K > N || (K > 0 && !idx)) return STRD_EINVAL;
+    if ((src == nullptr) != (dst == nullptr)) return STRD_EINVAL;
+    if (src && (row_bytes <= 0 || row_bytes % 4)) return STRD_EINVAL;
+    if (!src && !pos_out) return STRD_EINVAL;
+    if ((long long)K + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+    return compact_launch(src, idx, dst, N, M, K, row_bytes, pos_in, pos_out, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ ssd_prefill ------------
+size_t strd_ssd_prefill_workspace(int T, int H, int P, int G, int n, int chunk, strd_dtype io) {
+    (void)T; (void)H; (void)P; (void)G; (void)n; (void)chunk; (void)io;
+    return 0;
+}
+
+int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
+                     const float *S_in, void *y, float *S_out, int T, int H, int P, int G, int n, int chunk,
+                     strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (T < 0 || H < 1 || P < 1 || G < 1 || n < 1 || H % G || chunk < 1 || !io_ok(io) || !A) return STRD_EINVAL;
+    if (T > 0 && (!x || !dt || !B || !C || !y)) return STRD_EINVAL;
+    const size_t need = strd_ssd_prefill_workspace(T, H, P, G, n, chunk, io);
+    if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    if (!ssd_general_supported(n)) return STRD_EUNSUPPORTED;
+    return ssd_general(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, n, io, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ attn_prefill -----------
+size_t strd_attn_prefill_workspace(int T, int Hq, int Hkv, int d, strd_dtype io) {
+    (void)T; (void)Hq; (void)Hkv; (void)d; (void)io;
+    return 0;
+}
+
+int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d,
+                      float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (T < 0 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io)) return STRD_EINVAL;
+    if (T > 0 && (!q || !k || !v || !o)) return STRD_EINVAL;
+    const size_t need = strd_attn_prefill_workspace(T, Hq, Hkv, d, io);
+    if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    if (!attn_general_supported(d)) return STRD_EUNSUPPORTED;
+    return attn_general(q, k, v, o, T, Hq, Hkv, d, scale, io, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ schedules (host) -------
+int strd_schedule_budgets(const double *alpha, int L, int N0, int K_min, int32_t *K_out) {
+    if (!alpha || !K_out || L < 0 || N0 < 0 || K_min < 0) return STRD_EINVAL;
+    long long cur = N0;
+    for (int l = 0; l < L; ++l) {
+        if (!(alpha[l] >= 0.0 && alpha[l] <= 1.0)) return STRD_EINVAL;
+        // the small bias keeps products such as 0.15 * 36864 from landing one below
+        // their exact value because alpha is not representable in binary
+        long long want = (long long)floor(alpha[l] * (double)N0 + 1e-9);
+        const long long floor_k = K_min < cur ? K_min : cur;
+        if (want < floor_k) want = floor_k;
+        if (want < cur) cur = want;
+        K_out[l] = (int32_t)cur;
+    }
+    return STRD_OK;
+}
+
+int strd_schedule_sigmoid(int L, double a_start, double a_end, double k, double x0, double *alpha_out) {
+    if (!alpha_out || L < 1) return STRD_EINVAL;
+    for (int l = 0; l < L; ++l) {
+        const double z = k * (x0 - (double)l / (double)L);
+        alpha_out[l] = a_end + (a_start - a_end) / (1.0 + exp(-z));
+    }
+    return STRD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,258 @@
+"""Element-by-element parity of the HIP library (through the C ABI) with the CPU fp64 oracle on
+identical seeded inputs, at sizes the oracle finishes in seconds that still span several tiles
+and a ragged tail.  Needs a GPU: run with -m gpu."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_00198_amd as strd
+from paper_2603_00198_amd import synth
+from util import TOL, assert_close, assert_topk_equivalent
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ------------------------------------------------------------------ compact ----------------
+@pytest.mark.parametrize("N,M,K,row_elems,dtype", [
+    (1024, 32, 512, 256, torch.float32),      # tiny pair, hidden rows
+    (1000, 7, 333, 130, torch.bfloat16),      # 260-byte rows: not a multiple of 16
+    (4096, 128, 1024, 4096, torch.bfloat16),  # 8 KB rows
+    (300, 0, 300, 2, torch.float32),          # K = N, no text
+    (300, 5, 0, 8, torch.float32),            # nothing retained
+    (77, 3, 20, 1, torch.float32),            # 4-byte rows (dt of one head)
+])
+def test_compact_bit_exact(N, M, K, row_elems, dtype):
+    _say("compact N=%d M=%d K=%d row=%d %s" % (N, M, K, row_elems, dtype))
+    g = torch.Generator().manual_seed(N + K)
+    src = torch.randn(N + M, row_elems, generator=g).to(dtype)
+    idx = torch.sort(torch.randperm(N, generator=g)[:K]).values.to(torch.int32)
+    pos_in = torch.randperm(10 * (N + M), generator=g)[: N + M].to(torch.int32)
+    dst, pos = strd.compact(src.to(DEV), idx.to(DEV), N, M, pos_in=pos_in.to(DEV))
+    raw = src.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).numpy()
+    want, want_pos = oracle.compact(raw, idx.numpy(), N, M, pos_in=pos_in.numpy())
+    got = dst.cpu().view(torch.int16 if dtype == torch.bfloat16 else torch.int32).numpy()
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(pos.cpu().numpy(), want_pos)
+    _, pos_id = strd.compact(None, idx.to(DEV), N, M, want_pos=True)
+    np.testing.assert_array_equal(pos_id.cpu().numpy(), oracle.compact(raw, idx.numpy(), N, M)[1])
+
+
+# ------------------------------------------------------------------ select_topk ------------
+def _topk_case(scores, K):
+    got = strd.select_topk(torch.from_numpy(scores).to(DEV), K).cpu().numpy()
+    want = oracle.select_topk(scores.astype(np.float64), K)
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (5, 3), (1024, 512), (4097, 1000), (8192, 2048), (10000, 9999),
+                                 (50000, 1), (131072, 32768), (131072, 13107), (200003, 65536)])
+def test_select_topk_bit_exact_random(N, K):
+    _say("topk random N=%d K=%d" % (N, K))
+    r = np.random.default_rng(N * 7 + K)
+    _topk_case(r.random(N, dtype=np.float32) ** 4, K)
+
+
+@pytest.mark.parametrize("levels", [1, 2, 7, 300])
+def test_select_topk_ties_go_to_lowest_index(levels):
+    _say("topk ties levels=%d" % levels)
+    r = np.random.default_rng(levels)
+    N = 20000
+    s = (r.integers(0, levels, N) / np.float32(levels)).astype(np.float32)
+    s[::97] = -0.0 if levels > 1 else s[::97]
+    for K in (1, 777, N // 2, N - 1, N):
+        _topk_case(s, K)
+
+
+def test_select_topk_tiny_and_denormal_scores():
+    _say("topk denormals")
+    r = np.random.default_rng(3)
+    s = (r.random(9000, dtype=np.float32) * np.float32(1e-41)).astype(np.float32)  # denormal range
+    s[100:200] = 0.0
+    _topk_case(s, 4000)
+    _topk_case(s, 8950)
+
+
+# ------------------------------------------------------------------ scores -----------------
+def _mamba_case(w, seed=0):
+    h = synth.hidden_states(w, DEV, seed)
+    return synth.mamba_inputs(w, h, seed)
+
+
+def _attn_case(w, seed=0):
+    h = synth.hidden_states(w, DEV, seed)
+    return synth.attn_inputs(w, h, seed)
+
+
+MAMBA_CASES = {
+    "c1": synth.WORKLOADS["c1"],
+    "c2-short": synth.shrink(synth.WORKLOADS["c2"], N=1500, M=37, d_model=512),
+    "odd": synth.shrink(synth.WORKLOADS["c2"], N=700, M=5, d_model=128,
+                        mamba=synth.MambaShape(H=6, P=24, n=40, G=3, chunk=64)),
+}
+ATTN_CASES = {
+    "c1": synth.WORKLOADS["c1"],
+    "c3-short": synth.shrink(synth.WORKLOADS["c3"], N=1500, M=37, d_model=512),
+    "odd": synth.shrink(synth.WORKLOADS["c3"], N=333, M=3, d_model=128, attn=synth.AttnShape(Hq=6, Hkv=3, d=40)),
+}
+
+
+@pytest.mark.parametrize("name", list(MAMBA_CASES))
+def test_score_mamba_parity(name):
+    w = MAMBA_CASES[name]
+    _say("score_mamba %s N=%d M=%d %s" % (name, w.N, w.M, w.dtype))
+    t = _mamba_case(w)
+    N = w.N
+    got = strd.score_mamba(t["B"][:N].contiguous(), t["C"][N:].contiguous(), t["dt"][:N].contiguous())
+    want = oracle.score_mamba(synth.np64(t["B"][:N]), synth.np64(t["C"][N:]), synth.np64(t["dt"][:N]))
+    assert_close(got.cpu().numpy(), want, TOL[synth.torch_dtype(w.dtype)], "score_mamba " + name)
+    K = max(1, w.K)
+    idx = strd.select_topk(got, K).cpu().numpy()
+    assert_topk_equivalent(idx, want, K, TOL[synth.torch_dtype(w.dtype)])
+
+
+@pytest.mark.parametrize("name", list(ATTN_CASES))
+def test_score_attn_parity(name):
+    w = ATTN_CASES[name]
+    _say("score_attn %s N=%d M=%d %s" % (name, w.N, w.M, w.dtype))
+    t = _attn_case(w)
+    N = w.N
+    got = strd.score_attn(t["q"][N:].contiguous(), t["k"][:N].contiguous())
+    want = oracle.score_attn(synth.np64(t["q"][N:]), synth.np64(t["k"][:N]))
+    tol = TOL[synth.torch_dtype(w.dtype)]
+    assert_close(got.cpu().numpy(), want, tol, "score_attn " + name)
+    assert abs(float(got.double().sum()) - 1.0) < tol
+    K = max(1, w.K)
+    idx = strd.select_topk(got, K).cpu().numpy()
+    assert_topk_equivalent(idx, want, K, tol)
+
+
+# ------------------------------------------------------------------ mixers -----------------
+@pytest.mark.parametrize("name,T,extras", [("c1", 1056, False), ("c1", 544, True), ("c2-short", 300, True),
+                                           ("c2-short", 1537, False), ("odd", 130, True), ("c1", 1, True),
+                                           ("c1", 0, False)])
+def test_ssd_prefill_parity(name, T, extras):
+    w = MAMBA_CASES[name]
+    s = w.mamba
+    _say("ssd_prefill %s T=%d extras=%s %s" % (name, T, extras, w.dtype))
+    t = _mamba_case(w, seed=T)
+    x, dt, B, C = (t[k][:T].contiguous() for k in ("x", "dt", "B", "C"))
+    g = torch.Generator(device=DEV).manual_seed(5)
+    D = torch.randn(s.H, generator=g, device=DEV) if extras else None
+    S_in = torch.randn(s.H, s.P, s.n, generator=g, device=DEV) if extras else None
+    y, S_out = strd.ssd_prefill(x, dt, t["A"], B, C, D, S_in, chunk=s.chunk)
+    yw, Sw = oracle.ssd_seq(synth.np64(x), synth.np64(dt), synth.np64(t["A"]), synth.np64(B), synth.np64(C),
+                            None if D is None else synth.np64(D), None if S_in is None else synth.np64(S_in))
+    tol = TOL[synth.torch_dtype(w.dtype)]
+    assert_close(synth.np64(y), yw, tol, "ssd y")
+    assert_close(synth.np64(S_out), Sw, tol, "ssd S_out")
+
+
+def test_ssd_prefill_split_call_continues_the_scan():
+    w = MAMBA_CASES["c2-short"]
+    _say("ssd_prefill split call")
+    t = _mamba_case(w, seed=11)
+    T, cut = 700, 293
+    x, dt, B, C = (t[k][:T].contiguous() for k in ("x", "dt", "B", "C"))
+    y, S = strd.ssd_prefill(x, dt, t["A"], B, C, chunk=256)
+    ya, Sa = strd.ssd_prefill(x[:cut].contiguous(), dt[:cut].contiguous(), t["A"], B[:cut].contiguous(),
+                              C[:cut].contiguous(), chunk=256)
+    yb, Sb = strd.ssd_prefill(x[cut:].contiguous(), dt[cut:].contiguous(), t["A"], B[cut:].contiguous(),
+                              C[cut:].contiguous(), S_in=Sa, chunk=256)
+    tol = TOL[torch.bfloat16]
+    assert_close(synth.np64(torch.cat([ya, yb])), synth.np64(y), tol, "split y")
+    assert_close(synth.np64(Sb), synth.np64(S), tol, "split S")
+
+
+@pytest.mark.parametrize("name,T", [("c1", 1056), ("c1", 544), ("c3-short", 333), ("c3-short", 1537), ("odd", 100),
+                                    ("c1", 1), ("c1", 0)])
+def test_attn_prefill_parity(name, T):
+    w = ATTN_CASES[name]
+    _say("attn_prefill %s T=%d %s" % (name, T, w.dtype))
+    t = _attn_case(w, seed=T)
+    q, k, v = (t[n][:T].contiguous() for n in ("q", "k", "v"))
+    o = strd.attn_prefill(q, k, v)
+    want = oracle.attn(synth.np64(q), synth.np64(k), synth.np64(v))
+    assert_close(synth.np64(o), want, TOL[synth.torch_dtype(w.dtype)], "attn o")
+
+
+# ------------------------------------------------------------------ whole reduced layer ----
+def _reduced_mamba_layer_dev(t, N, M, K, chunk):
+    s = strd.score_mamba(t["B"][:N].contiguous(), t["C"][N:].contiguous(), t["dt"][:N].contiguous())
+    idx = strd.select_topk(s, K)
+    xs = strd.compact(t["x"], idx, N, M)
+    Bs = strd.compact(t["B"], idx, N, M)
+    Cs = strd.compact(t["C"], idx, N, M)
+    dts, pos = strd.compact(t["dt"], idx, N, M, want_pos=True)
+    y, S = strd.ssd_prefill(xs, dts, t["A"], Bs, Cs, chunk=chunk)
+    return s, idx, pos, y, S
+
+
+def test_reduced_mamba_layer_tiny_pair_matches_oracle_chain():
+    w = synth.WORKLOADS["c1"]
+    _say("reduced mamba layer c1")
+    t = _mamba_case(w)
+    N, M, K = w.N, w.M, w.K
+    s, idx, pos, y, S = _reduced_mamba_layer_dev(t, N, M, K, w.mamba.chunk)
+    s_ref = oracle.score_mamba(synth.np64(t["B"][:N]), synth.np64(t["C"][N:]), synth.np64(t["dt"][:N]))
+    assert_close(s.cpu().numpy(), s_ref, 1e-4, "score")
+    swaps = assert_topk_equivalent(idx.cpu().numpy(), s_ref, K, 1e-4)
+    # the mixer is checked on the device's own selection (identical to the oracle's unless a near-tie swapped)
+    idx_np = idx.cpu().numpy()
+    xs, pos_ref = oracle.compact(synth.np64(t["x"]), idx_np, N, M)
+    np.testing.assert_array_equal(pos.cpu().numpy(), pos_ref)
+    yw, Sw = oracle.ssd_seq(xs, oracle.compact(synth.np64(t["dt"]), idx_np, N, M)[0], synth.np64(t["A"]),
+                            oracle.compact(synth.np64(t["B"]), idx_np, N, M)[0],
+                            oracle.compact(synth.np64(t["C"]), idx_np, N, M)[0])
+    assert_close(synth.np64(y), yw, 1e-4, "reduced y")
+    assert_close(synth.np64(S), Sw, 1e-4, "reduced S")
+    _say("near-tie swaps vs oracle: %d" % swaps)
+
+
+def test_reduced_attention_layer_tiny_pair_matches_oracle_chain():
+    w = synth.WORKLOADS["c1"]
+    _say("reduced attention layer c1")
+    t = _attn_case(w)
+    N, M, K = w.N, w.M, w.K
+    s = strd.score_attn(t["q"][N:].contiguous(), t["k"][:N].contiguous())
+    idx = strd.select_topk(s, K)
+    qs, ks, vs = (strd.compact(t[n], idx, N, M) for n in ("q", "k", "v"))
+    o = strd.attn_prefill(qs, ks, vs)
+    s_ref = oracle.score_attn(synth.np64(t["q"][N:]), synth.np64(t["k"][:N]))
+    assert_close(s.cpu().numpy(), s_ref, 1e-4, "score")
+    assert_topk_equivalent(idx.cpu().numpy(), s_ref, K, 1e-4)
+    idx_np = idx.cpu().numpy()
+    want = oracle.attn(*(oracle.compact(synth.np64(t[n]), idx_np, N, M)[0] for n in ("q", "k", "v")))
+    assert_close(synth.np64(o), want, 1e-4, "reduced o")
+
+
+def test_full_budget_reproduces_the_unreduced_layer_on_device():
+    w = synth.WORKLOADS["c1"]
+    _say("100% budget identity c1")
+    t = _mamba_case(w)
+    N, M = w.N, w.M
+    s, idx, pos, y, S = _reduced_mamba_layer_dev(t, N, M, N, w.mamba.chunk)
+    assert torch.equal(idx.cpu(), torch.arange(N, dtype=torch.int32))
+    assert torch.equal(pos.cpu(), torch.arange(N + M, dtype=torch.int32))
+    y_full, S_full = strd.ssd_prefill(t["x"], t["dt"], t["A"], t["B"], t["C"], chunk=w.mamba.chunk)
+    assert torch.equal(y, y_full) and torch.equal(S, S_full)
+
+
+# ------------------------------------------------------------------ error behaviour --------
+def test_invalid_arguments_are_refused_without_launching():
+    _say("error paths")
+    s = torch.rand(100, device=DEV)
+    with pytest.raises(strd.StrdError):
+        strd.select_topk(s, 0)
+    with pytest.raises(strd.StrdError):
+        strd.select_topk(s, 101)
+    q = torch.randn(4, 3, 8, device=DEV)
+    k = torch.randn(9, 2, 8, device=DEV)
+    with pytest.raises(strd.StrdError):
+        strd.score_attn(q, k)          # 3 query heads over 2 kv heads
+    torch.cuda.synchronize()

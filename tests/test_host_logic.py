@@ -1,0 +1,95 @@
+"""CPU-only checks of the host side: the C ABI library loads and exports every symbol the
+header declares, the schedule helpers reproduce the paper's printed arithmetic, and the input
+generator is deterministic."""
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_00198_amd as strd
+from paper_2603_00198_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "strd.h")).read()
+    declared = set(re.findall(r"\b(strd_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found"
+    L = strd.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), "libstrd.so does not export " + name
+    assert declared == set(binding.exported_symbols())
+    assert L.strd_version() >= 1000
+    assert b"STRD_OK" in L.strd_status_string(0)
+
+
+def _golden_schedules(golden_dir):
+    rows = []
+    for line in open(os.path.join(golden_dir, "schedule_step_decay.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, comp, spec = line.split(None, 2)
+            alpha = np.zeros(62)
+            for part in spec.split(";"):
+                rng, val = part.split("=")
+                lo, hi = (int(v) for v in rng.split(":"))
+                alpha[lo:hi + 1] = float(val)
+            rows.append((name, float(comp), alpha))
+    return rows
+
+
+def test_step_decay_tables_reproduce_the_printed_compression(golden_dir):
+    # App. "Reduction Schedule Configurations": Comp.% is the mean retention over the 62 layers,
+    # with alpha relative to the original token count.
+    N0 = 36864                                   # 256 frames x 144 tokens per frame
+    for name, comp, alpha in _golden_schedules(golden_dir):
+        K = strd.schedule_budgets(list(alpha), N0, K_min=144)
+        assert len(K) == 62 and all(a >= b for a, b in zip(K, K[1:]))
+        assert 100.0 * np.mean(K) / N0 == pytest.approx(comp, abs=0.06), name
+
+
+def test_budgets_floor_clamp_and_monotone():
+    assert strd.schedule_budgets([1, 1, .75, .75, .5, .5, .25, .25], 32768) == \
+        [32768, 32768, 24576, 24576, 16384, 16384, 8192, 8192]
+    assert strd.schedule_budgets([0.15], 36864) == [5529]           # floor(5529.6)
+    assert strd.schedule_budgets([0.001, 0.5], 1000, K_min=144) == [144, 144]   # never grows back
+    assert strd.schedule_budgets([0.5], 100, K_min=144) == [100]    # a single image is left whole
+    with pytest.raises(strd.StrdError):
+        strd.schedule_budgets([1.5], 10)
+
+
+def test_sigmoid_schedule_shape():
+    a = strd.schedule_sigmoid(62, 1.0, 0.125, 20.0, 0.24)
+    assert a[0] == pytest.approx(0.125 + 0.875 / (1 + np.exp(-20 * 0.24)))
+    assert all(x > y for x, y in zip(a, a[1:]))
+    assert a[-1] == pytest.approx(0.125, abs=1e-4)
+    mid = 0.24 * 62
+    lo, hi = int(np.floor(mid)), int(np.ceil(mid))
+    assert a[lo] >= (1.0 + 0.125) / 2 >= a[hi]
+
+
+def test_speedup_arithmetic_of_the_headline_claim(golden_dir):
+    vals = {}
+    for line in open(os.path.join(golden_dir, "ttft_25pct.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            vals[k] = float(v)
+    ratios = [vals["baseline"] / v for k, v in vals.items() if k != "baseline"]
+    assert min(ratios) == pytest.approx(3.8, abs=0.05) and max(ratios) == pytest.approx(4.2, abs=0.06)
+
+
+def test_synthetic_inputs_are_seeded_and_shaped():
+    w = synth.shrink(synth.WORKLOADS["c5"], N=1024, M=16, d_model=64)
+    h1, h2 = synth.hidden_states(w), synth.hidden_states(w)
+    assert torch.equal(h1, h2) and h1.shape == (1040, 64)
+    t = synth.mamba_inputs(w, h1)
+    assert t["x"].shape == (1040, 128, 64) and t["x"].dtype == torch.bfloat16
+    assert t["B"].shape == (1040, 8, 128) and (t["dt"] > 0).all() and (t["A"] < 0).all()
+    a = synth.attn_inputs(w, h1)
+    assert a["q"].shape == (1040, 32, 128) and a["k"].shape == (1040, 8, 128)
+    # outlier rows exist and frames share a component
+    norms = h1[:1024].norm(dim=1)
+    assert (norms > 4 * norms.median()).float().mean() > 0.02
+    assert synth.WORKLOADS["c2"].K == 2048 and synth.WORKLOADS["c3"].K == 8192
