@@ -1,0 +1,384 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-reduced prefill of one hybrid layer on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic long-video-shaped sequence:
+score -> select_topk -> compact (every mixer input + the hidden states) -> mixer on the K + M
+survivors, all enqueued on one HIP stream without host synchronisation.  Inputs are resident
+in HBM before the timed region.  One JSON line is printed (see the design doc for the fields).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4m|c4a|c5m|c5a]
+                  [--budget 0.25] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+PAPER_CONTEXT = "paper: 3.8-4.2x LLM-stage prefill speed-up at ~25% budget, whole 12B hybrid, 1x A100, 36864 vision tokens"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--budget", type=float, default=0.25)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-attention-extra", action="store_true",
+                    help="skip the attention-layer figures appended to the default (c2) line")
+    return ap.parse_args()
+
+
+WORKLOADS = {           # name -> (synth workload, layer kind)
+    "c2": ("c2", "mamba"), "c3": ("c3", "attn"), "c4m": ("c4", "mamba"), "c4a": ("c4", "attn"),
+    "c5m": ("c5", "mamba"), "c5a": ("c5", "attn"),
+}
+
+
+class EventPairs:
+    """HIP event pairs recorded on torch's current stream (the stream the library launches on)."""
+
+    def __init__(self, torch):
+        self.torch, self.pairs = torch, []
+
+    def wrap(self, fn):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        out = fn()
+        b.record()
+        self.pairs.append((a, b))
+        return out
+
+    def mean_ms(self):
+        return sum(a.elapsed_time(b) for a, b in self.pairs) / max(len(self.pairs), 1)
+
+
+def time_loop(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_events(torch, fn, iters=20, warmup=3):
+    for _ in range(warmup):
+        fn()
+    ev = EventPairs(torch)
+    for _ in range(iters):
+        ev.wrap(fn)
+    torch.cuda.synchronize()
+    return ev.mean_ms()
+
+
+class MambaLayer:
+    kind = "mamba"
+
+    def __init__(self, torch, strd, synth, w, dev):
+        self.torch, self.strd, self.w = torch, strd, w
+        s = w.mamba
+        self.s = s
+        N, M, K = w.N, w.M, w.K
+        hidden = synth.hidden_states(w, dev)
+        t = synth.mamba_inputs(w, hidden)
+        self.hidden = hidden.to(synth.torch_dtype(w.dtype))
+        self.t = t
+        self.Bv = t["B"][:N].contiguous(); self.Ct = t["C"][N:].contiguous(); self.dtv = t["dt"][:N].contiguous()
+        e = lambda *shape, dtype=self.hidden.dtype: torch.empty(*shape, dtype=dtype, device=dev)
+        self.scores = e(N, dtype=torch.float32)
+        self.idx = e(K, dtype=torch.int32)
+        Tr = K + M
+        self.o = {"x": e(Tr, s.H, s.P), "B": e(Tr, s.G, s.n), "C": e(Tr, s.G, s.n),
+                  "dt": e(Tr, s.H, dtype=torch.float32), "hidden": e(Tr, w.d_model)}
+        self.y_red = e(Tr, s.H, s.P)
+        self.y_full = e(w.T, s.H, s.P)
+        lib = strd.lib()
+        io = 1 if w.dtype == "bf16" else 0
+        nb = max(lib.strd_score_mamba_workspace(M, N, s.H, s.G, s.n, io),
+                 lib.strd_ssd_prefill_workspace(w.T, s.H, s.P, s.G, s.n, s.chunk, io), 16)
+        self.ws = e(nb, dtype=torch.uint8)
+        self.mixer_ev = None
+
+    def score(self):
+        self.strd.score_mamba(self.Bv, self.Ct, self.dtv, out=self.scores, ws=self.ws)
+
+    def select(self):
+        self.strd.select_topk(self.scores, self.w.K, out=self.idx)
+
+    def compact(self):
+        N, M = self.w.N, self.w.M
+        for k in ("x", "B", "C", "dt"):
+            self.strd.compact(self.t[k], self.idx, N, M, out=self.o[k])
+        self.strd.compact(self.hidden, self.idx, N, M, out=self.o["hidden"])
+
+    def mixer_reduced(self):
+        o = self.o
+        self.strd.ssd_prefill(o["x"], o["dt"], self.t["A"], o["B"], o["C"], chunk=self.s.chunk, want_state=False,
+                              out=self.y_red, ws=self.ws)
+
+    def mixer_full(self):
+        t = self.t
+        self.strd.ssd_prefill(t["x"], t["dt"], t["A"], t["B"], t["C"], chunk=self.s.chunk, want_state=False,
+                              out=self.y_full, ws=self.ws)
+
+    def step(self):
+        self.score(); self.select(); self.compact()
+        if self.mixer_ev is not None:
+            self.mixer_ev.wrap(self.mixer_reduced)
+        else:
+            self.mixer_reduced()
+
+    # algorithmic HBM bytes / flops of the mixer on T tokens
+    def mixer_bytes(self, T):
+        s, eb = self.s, self.hidden.element_size()
+        return T * (2 * s.H * s.P * eb + 2 * s.G * s.n * eb + 4 * s.H)
+
+    def mixer_flops(self, T):
+        s = self.s
+        Q = s.chunk
+        return T * (s.H * (Q * s.P + 4 * s.n * s.P) + s.G * Q * s.n)   # causal count
+
+    def compact_bytes(self):
+        w, s, eb = self.w, self.s, self.hidden.element_size()
+        row = (s.H * s.P + 2 * s.G * s.n + w.d_model) * eb + 4 * s.H
+        return 2 * (w.K + w.M) * row + 4 * w.K * 5
+
+    mixer_name, mixer_bound = "ssd_prefill", "hbm"
+
+
+class AttnLayer:
+    kind = "attn"
+
+    def __init__(self, torch, strd, synth, w, dev):
+        self.torch, self.strd, self.w = torch, strd, w
+        s = w.attn
+        self.s = s
+        N, M, K = w.N, w.M, w.K
+        hidden = synth.hidden_states(w, dev)
+        self.t = synth.attn_inputs(w, hidden)
+        self.hidden = hidden.to(synth.torch_dtype(w.dtype))
+        self.qt = self.t["q"][N:].contiguous(); self.kv = self.t["k"][:N].contiguous()
+        e = lambda *shape, dtype=self.hidden.dtype: torch.empty(*shape, dtype=dtype, device=dev)
+        self.scores = e(N, dtype=torch.float32)
+        self.idx = e(K, dtype=torch.int32)
+        Tr = K + M
+        self.o = {"q": e(Tr, s.Hq, s.d), "k": e(Tr, s.Hkv, s.d), "v": e(Tr, s.Hkv, s.d), "hidden": e(Tr, w.d_model)}
+        self.o_red = e(Tr, s.Hq, s.d)
+        self.o_full = e(w.T, s.Hq, s.d)
+        lib = strd.lib()
+        io = 1 if w.dtype == "bf16" else 0
+        nb = max(lib.strd_score_attn_workspace(M, N, s.Hq, s.Hkv, s.d, io),
+                 lib.strd_attn_prefill_workspace(w.T, s.Hq, s.Hkv, s.d, io), 16)
+        self.ws = e(nb, dtype=torch.uint8)
+        self.mixer_ev = None
+
+    def score(self):
+        self.strd.score_attn(self.qt, self.kv, out=self.scores, ws=self.ws)
+
+    def select(self):
+        self.strd.select_topk(self.scores, self.w.K, out=self.idx)
+
+    def compact(self):
+        N, M = self.w.N, self.w.M
+        for k in ("q", "k", "v"):
+            self.strd.compact(self.t[k], self.idx, N, M, out=self.o[k])
+        self.strd.compact(self.hidden, self.idx, N, M, out=self.o["hidden"])
+
+    def mixer_reduced(self):
+        o = self.o
+        self.strd.attn_prefill(o["q"], o["k"], o["v"], out=self.o_red, ws=self.ws)
+
+    def mixer_full(self):
+        t = self.t
+        self.strd.attn_prefill(t["q"], t["k"], t["v"], out=self.o_full, ws=self.ws)
+
+    def step(self):
+        self.score(); self.select(); self.compact()
+        if self.mixer_ev is not None:
+            self.mixer_ev.wrap(self.mixer_reduced)
+        else:
+            self.mixer_reduced()
+
+    def mixer_bytes(self, T):
+        s, eb = self.s, self.hidden.element_size()
+        return T * (2 * s.Hq * s.d + 2 * s.Hkv * s.d) * eb
+
+    def mixer_flops(self, T):
+        s = self.s
+        return 2.0 * T * T * s.d * s.Hq          # causal: half of 4 T^2 d Hq
+
+    def compact_bytes(self):
+        w, s, eb = self.w, self.s, self.hidden.element_size()
+        row = (s.Hq * s.d + 2 * s.Hkv * s.d + w.d_model) * eb
+        return 2 * (w.K + w.M) * row + 4 * w.K * 4
+
+    mixer_name, mixer_bound = "attn_prefill", "mfma"
+
+
+def cpu_baseline_mamba(layer, synth):
+    """The fp64 oracle, as it stands, on the same reduced Mamba-2 layer (all of it)."""
+    import numpy as np
+    import oracle
+    w, t = layer.w, layer.t
+    N, M, K = w.N, w.M, w.K
+    f = synth.np64
+    Bv, Ct, dtv = f(t["B"][:N]), f(t["C"][N:]), f(t["dt"][:N])
+    full = {k: f(t[k]) for k in ("x", "B", "C", "dt")}
+    hid = layer.hidden.cpu().view(layer.torch.int16).numpy() if w.dtype == "bf16" else layer.hidden.cpu().numpy()
+    A = f(t["A"])
+    oracle.select_topk(np.zeros(4), 2)          # load the library outside the timed region
+    t0 = time.perf_counter()
+    s = oracle.score_mamba(Bv, Ct, dtv)
+    idx = oracle.select_topk(s, K)
+    red = {k: oracle.compact(v, idx, N, M)[0] for k, v in full.items()}
+    oracle.compact(hid, idx, N, M)
+    oracle.ssd_seq(red["x"], red["dt"], A, red["B"], red["C"])
+    dt = time.perf_counter() - t0
+    return {"value": (N + M) / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "the whole reduced layer of this workload (all %d vision + %d text tokens, all heads), "
+                      "fp64, %.1f s" % (N, M, dt)}
+
+
+def cpu_baseline_attn(layer, synth, rows=48, txt_rows=4):
+    """Oracle on a bounded sample: scores from a subset of text rows, attention for a subset of
+    query rows of the compacted sequence; time extrapolated linearly to the whole layer."""
+    import numpy as np
+    import oracle
+    w, t = layer.w, layer.t
+    N, M, K = w.N, w.M, w.K
+    f = synth.np64
+    oracle.select_topk(np.zeros(4), 2)
+    q_txt, k_vis = f(t["q"][N:N + txt_rows]), f(t["k"][:N])
+    t0 = time.perf_counter()
+    s = oracle.score_attn(q_txt, k_vis)
+    t_score = (time.perf_counter() - t0) * (M / txt_rows)
+    t0 = time.perf_counter()
+    idx = oracle.select_topk(s, K)
+    red = {k: oracle.compact(f(t[k]), idx, N, M)[0] for k in ("q", "k", "v")}
+    t_sel = time.perf_counter() - t0
+    Tr = K + M
+    pick = np.linspace(0, Tr - 1, rows).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.attn(red["q"], red["k"], red["v"], rows=pick)
+    t_attn = (time.perf_counter() - t0) * (Tr * (Tr + 1) / 2) / float((pick.astype(np.float64) + 1).sum())
+    tot = t_score + t_sel + t_attn
+    return {"value": (N + M) / tot, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "extrapolated: scores from %d of %d text rows, attention for %d of %d query rows "
+                      "(scaled by causal work); est. %.0f s for the whole layer" % (txt_rows, M, rows, Tr, tot)}
+
+
+def measure(torch, strd, synth, name, budget, steps, warmup, dev):
+    from dataclasses import replace
+    wname, kind = WORKLOADS[name]
+    w = replace(synth.WORKLOADS[wname], budget=budget)
+    layer = (MambaLayer if kind == "mamba" else AttnLayer)(torch, strd, synth, w, dev)
+    # whole reduced step, with the mixer bracketed by its own event pair inside the timed region
+    for _ in range(warmup):
+        layer.step()
+    torch.cuda.synchronize()
+    layer.mixer_ev = EventPairs(torch)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        layer.step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    ms_mixer = layer.mixer_ev.mean_ms()
+    layer.mixer_ev = None
+    calls = {
+        "score_us": 1e3 * time_events(torch, layer.score),
+        "select_topk_us": 1e3 * time_events(torch, layer.select),
+        "compact_us": 1e3 * time_events(torch, layer.compact),
+        "mixer_reduced_us": 1e3 * ms_mixer,
+    }
+    full_iters = max(3, min(20, int(200.0 / max(ms_mixer * (w.T / (w.K + w.M)), 1e-3))))
+    ms_full = time_events(torch, layer.mixer_full, iters=full_iters, warmup=2)
+    calls["mixer_full_us"] = 1e3 * ms_full
+    Tr = w.K + w.M
+    sel_compact_gbs = (layer.compact_bytes() + 4 * w.N) / ((calls["select_topk_us"] + calls["compact_us"]) * 1e-6) / 1e9
+    if layer.mixer_bound == "hbm":
+        ach = layer.mixer_bytes(Tr) / (ms_mixer * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": layer.mixer_name, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                "mfma_tflops": layer.mixer_flops(Tr) / (ms_mixer * 1e-3) / 1e12,
+                "mfma_frac": layer.mixer_flops(Tr) / (ms_mixer * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    else:
+        ach = layer.mixer_flops(Tr) / (ms_mixer * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": layer.mixer_name, "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    res = {
+        "layer": kind, "workload": name, "N": w.N, "M": w.M, "K": w.K, "budget": budget,
+        "ms_per_step": ms_step, "tokens_per_s": w.T / (ms_step * 1e-3),
+        "retained_tokens_per_s": Tr / (ms_step * 1e-3), "speedup_vs_full": ms_full / ms_step,
+        "calls": calls, "select_plus_compact_GBps": sel_compact_gbs,
+        "select_plus_compact_frac_of_hbm": sel_compact_gbs / HBM_PEAK_GBS, "roofline": roof,
+    }
+    return res, layer
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path uses no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_00198_amd as strd
+    from paper_2603_00198_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    name = args.workload
+    res, layer = measure(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)
+    w = layer.w
+    s = w.mamba if layer.kind == "mamba" else w.attn
+    line = {
+        "metric": "retained-token prefill tokens/s per layer at 25% budget; speedup vs full prefill",
+        "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: single %s layer, %d vision + %d text tokens, budget %.0f%% (K=%d), batch 1, %s"
+                               % (name, "Mamba-2" if layer.kind == "mamba" else "attention", w.N, w.M,
+                                  100 * args.budget, w.K, repr(s)),
+                   "tokens_counted": "input tokens N+M per reduced-layer step (score+select+compact+mixer)",
+                   "parallelism": "1 GPU"},
+        "speedup_vs_full": res["speedup_vs_full"], "retained_tokens_per_s": res["retained_tokens_per_s"],
+        "calls_us": res["calls"], "select_plus_compact_GBps": res["select_plus_compact_GBps"],
+        "select_plus_compact_frac_of_hbm": res["select_plus_compact_frac_of_hbm"],
+        "roofline": res["roofline"], "context": PAPER_CONTEXT,
+    }
+    if name == "c2" and not args.no_attention_extra:
+        del layer
+        torch.cuda.empty_cache()
+        extra, alayer = measure(torch, strd, synth, "c3", args.budget, max(3, args.steps // 10),
+                                max(1, args.warmup // 5), dev)
+        line["attention_layer"] = extra
+        del alayer
+        torch.cuda.empty_cache()
+        layer = None
+    if not args.no_cpu_baseline:
+        if layer is None:
+            from dataclasses import replace
+            layer = MambaLayer(torch, strd, synth, replace(synth.WORKLOADS["c2"], budget=args.budget), dev)
+        line["cpu_baseline"] = cpu_baseline_mamba(layer, synth) if layer.kind == "mamba" \
+            else cpu_baseline_attn(layer, synth)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
