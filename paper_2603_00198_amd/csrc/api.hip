@@ -96,6 +96,8 @@ int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void 
     if (T > 0 && (!x || !dt || !B || !C || !y)) return STRD_EINVAL;
     const size_t need = strd_ssd_prefill_workspace(T, H, P, G, n, chunk, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    if (ssd_mfma_supported(T, H, P, G, n, io))
+        return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, n, as_stream(stream));
     if (!ssd_general_supported(n)) return STRD_EUNSUPPORTED;
     return ssd_general(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, n, io, as_stream(stream));
 }

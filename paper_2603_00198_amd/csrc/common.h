@@ -48,6 +48,11 @@ bool ssd_general_supported(int n);
 int ssd_general(const void *x, const float *dt, const float *A, const void *B, const void *C,
                 const float *D, const float *S_in, void *y, float *S_out, int T, int H, int P, int G,
                 int n, strd_dtype io, hipStream_t st);
+// bf16 matrix-core paths
+bool ssd_mfma_supported(int T, int H, int P, int G, int n, strd_dtype io);
+int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
+             const float *S_in, void *y, float *S_out, int T, int H, int P, int G, int n, hipStream_t st);
+
 bool attn_general_supported(int d);
 int attn_general(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d,
                  float scale, strd_dtype io, hipStream_t st);

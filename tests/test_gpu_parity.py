@@ -94,6 +94,8 @@ MAMBA_CASES = {
     "c2-short": synth.shrink(synth.WORKLOADS["c2"], N=1500, M=37, d_model=512),
     "odd": synth.shrink(synth.WORKLOADS["c2"], N=700, M=5, d_model=128,
                         mamba=synth.MambaShape(H=6, P=24, n=40, G=3, chunk=64)),
+    "n64": synth.shrink(synth.WORKLOADS["c2"], N=700, M=5, d_model=128,
+                        mamba=synth.MambaShape(H=6, P=96, n=64, G=2, chunk=128)),
 }
 ATTN_CASES = {
     "c1": synth.WORKLOADS["c1"],
@@ -135,7 +137,9 @@ def test_score_attn_parity(name):
 # ------------------------------------------------------------------ mixers -----------------
 @pytest.mark.parametrize("name,T,extras", [("c1", 1056, False), ("c1", 544, True), ("c2-short", 300, True),
                                            ("c2-short", 1537, False), ("odd", 130, True), ("c1", 1, True),
-                                           ("c1", 0, False)])
+                                           ("c1", 0, False), ("c2-short", 64, True), ("c2-short", 65, False),
+                                           ("c2-short", 1, True), ("c2-short", 0, True), ("n64", 200, True),
+                                           ("n64", 705, False)])
 def test_ssd_prefill_parity(name, T, extras):
     w = MAMBA_CASES[name]
     s = w.mamba
