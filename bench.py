@@ -121,9 +121,9 @@ class MambaLayer:
 
     def compact(self):
         N, M = self.w.N, self.w.M
-        for k in ("x", "B", "C", "dt"):
-            self.strd.compact(self.t[k], self.idx, N, M, out=self.o[k])
-        self.strd.compact(self.hidden, self.idx, N, M, out=self.o["hidden"])
+        keys = ("x", "B", "C", "dt")
+        self.strd.compact_batch([self.t[k] for k in keys] + [self.hidden], self.idx, N, M,
+                                outs=[self.o[k] for k in keys] + [self.o["hidden"]])
 
     def mixer_reduced(self):
         o = self.o
@@ -194,9 +194,9 @@ class AttnLayer:
 
     def compact(self):
         N, M = self.w.N, self.w.M
-        for k in ("q", "k", "v"):
-            self.strd.compact(self.t[k], self.idx, N, M, out=self.o[k])
-        self.strd.compact(self.hidden, self.idx, N, M, out=self.o["hidden"])
+        keys = ("q", "k", "v")
+        self.strd.compact_batch([self.t[k] for k in keys] + [self.hidden], self.idx, N, M,
+                                outs=[self.o[k] for k in keys] + [self.o["hidden"]])
 
     def mixer_reduced(self):
         o = self.o

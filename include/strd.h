@@ -110,6 +110,19 @@ int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, 
 int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, int K,
                  int64_t row_bytes, const int32_t *pos_in, int32_t *pos_out, void *stream);
 
+/* compact_batch -- the same gather for up to STRD_COMPACT_MAX tensors that share one index
+ * list (a reducing layer compacts every mixer input and the hidden states), in one launch.
+ *   items [host] [n_items] {src [dev], dst [dev], row_bytes}; read before the call returns
+ * Every item obeys the rules of strd_compact; n_items may be 0 when only pos_out is wanted. */
+#define STRD_COMPACT_MAX 8
+typedef struct {
+    const void *src;
+    void *dst;
+    int64_t row_bytes;
+} strd_compact_item;
+int strd_compact_batch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M,
+                       int K, const int32_t *pos_in, int32_t *pos_out, void *stream);
+
 /* ---------------------------------------------------------------------------
  * ssd_prefill -- Mamba-2 mixer over T tokens (Eqs. "ssm_state_update",
  * "ssm_output"), per head h with group g(h):

@@ -4,11 +4,11 @@ The work is done by hand-written HIP kernels behind the C ABI declared in
 ``include/strd.h``; this package is the thin binding (argument marshalling only).
 """
 from .binding import (  # noqa: F401
-    LIB_PATH, StrdError, attn_prefill, compact, lib, schedule_budgets, schedule_sigmoid,
+    LIB_PATH, StrdError, attn_prefill, compact, compact_batch, lib, schedule_budgets, schedule_sigmoid,
     score_attn, score_mamba, select_topk, ssd_prefill,
 )
 
 __all__ = [
-    "LIB_PATH", "StrdError", "lib", "score_attn", "score_mamba", "select_topk", "compact",
+    "LIB_PATH", "StrdError", "lib", "score_attn", "score_mamba", "select_topk", "compact", "compact_batch",
     "ssd_prefill", "attn_prefill", "schedule_budgets", "schedule_sigmoid",
 ]

@@ -28,6 +28,7 @@ _SIGNATURES = {
     "strd_select_topk_workspace": (_sz, [_int, _int]),
     "strd_select_topk": (_int, [_vp, _int, _int, _vp, _vp, _sz, _vp]),
     "strd_compact": (_int, [_vp, _vp, _vp, _int, _int, _int, _i64, _vp, _vp, _vp]),
+    "strd_compact_batch": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp]),
     "strd_ssd_prefill_workspace": (_sz, [_int] * 6 + [_int]),
     "strd_ssd_prefill": (_int, [_vp] * 9 + [_int] * 6 + [_int, _vp, _sz, _vp]),
     "strd_attn_prefill_workspace": (_sz, [_int] * 4 + [_int]),
@@ -183,6 +184,33 @@ def compact(src: Optional[torch.Tensor], idx: torch.Tensor, N: int, M: int,
     if pos_out is not None:
         return dst, pos_out
     return dst
+
+
+class _CompactItem(ctypes.Structure):
+    _fields_ = [("src", _vp), ("dst", _vp), ("row_bytes", _i64)]
+
+
+def compact_batch(srcs: Sequence[torch.Tensor], idx: torch.Tensor, N: int, M: int,
+                  pos_in: Optional[torch.Tensor] = None, want_pos: bool = False,
+                  outs: Optional[Sequence[torch.Tensor]] = None):
+    """One-launch gather of several [N+M, ...] tensors by the same idx; returns (dsts, pos_out or None)."""
+    _dev(idx, pos_in, *srcs)
+    if idx.dtype != torch.int32:
+        raise StrdError("idx must be int32")
+    K = idx.shape[0]
+    if outs is None:
+        outs = [torch.empty((K + M,) + tuple(t.shape[1:]), dtype=t.dtype, device=t.device) for t in srcs]
+    _dev(*outs)
+    items = (_CompactItem * max(len(srcs), 1))()
+    for i, (t, o) in enumerate(zip(srcs, outs)):
+        if t.shape[0] != N + M or o.shape[0] != K + M or o.dtype != t.dtype or o.shape[1:] != t.shape[1:]:
+            raise StrdError("compact_batch: tensor %d has the wrong shape" % i)
+        items[i].src, items[i].dst = t.data_ptr(), o.data_ptr()
+        items[i].row_bytes = int(torch.Size(t.shape[1:]).numel()) * t.element_size()
+    pos_out = torch.empty(K + M, dtype=torch.int32, device=idx.device) if (want_pos or pos_in is not None) else None
+    _check(lib().strd_compact_batch(ctypes.cast(items, _vp), len(srcs), _ptr(idx), N, M, K, _ptr(pos_in),
+                                    _ptr(pos_out), _stream()), "compact_batch")
+    return list(outs), pos_out
 
 
 def ssd_prefill(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,

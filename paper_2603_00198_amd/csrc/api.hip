@@ -57,6 +57,8 @@ int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, 
         return STRD_EINVAL;
     const size_t need = strd_score_mamba_workspace(M, N, H, G, n, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    if (score_mamba_mfma_supported(M, N, H, G, n, io))
+        return score_mamba_mfma(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, as_stream(stream));
     return score_mamba_general(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, io, as_stream(stream));
 }
 
@@ -73,14 +75,22 @@ int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, 
 }
 
 // ------------------------------------------------------------------ compact ----------------
+int strd_compact_batch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
+                       const int32_t *pos_in, int32_t *pos_out, void *stream) {
+    if (N < 0 || M < 0 || K < 0 || K > N || (K > 0 && !idx)) return STRD_EINVAL;
+    if (n_items < 0 || n_items > STRD_COMPACT_MAX || (n_items > 0 && !items)) return STRD_EINVAL;
+    if (n_items == 0 && !pos_out) return STRD_EINVAL;
+    for (int i = 0; i < n_items; ++i)
+        if (!items[i].src || !items[i].dst || items[i].row_bytes <= 0 || items[i].row_bytes % 4) return STRD_EINVAL;
+    if ((long long)K + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+    return compact_launch(items, n_items, idx, N, M, K, pos_in, pos_out, as_stream(stream));
+}
+
 int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, int K, int64_t row_bytes,
                  const int32_t *pos_in, int32_t *pos_out, void *stream) {
-    if (N < 0 || M < 0 || K < 0 || K > N || (K > 0 && !idx)) return STRD_EINVAL;
     if ((src == nullptr) != (dst == nullptr)) return STRD_EINVAL;
-    if (src && (row_bytes <= 0 || row_bytes % 4)) return STRD_EINVAL;
-    if (!src && !pos_out) return STRD_EINVAL;
-    if ((long long)K + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
-    return compact_launch(src, idx, dst, N, M, K, row_bytes, pos_in, pos_out, as_stream(stream));
+    strd_compact_item it = {src, dst, row_bytes};
+    return strd_compact_batch(&it, src ? 1 : 0, idx, N, M, K, pos_in, pos_out, stream);
 }
 
 // ------------------------------------------------------------------ ssd_prefill ------------

@@ -34,8 +34,8 @@ __host__ __forceinline__ int xcd_grid(int n) { return (n + kXcd - 1) / kXcd * kX
 inline int launch_status() { return hipGetLastError() == hipSuccess ? STRD_OK : STRD_EHIP; }
 
 // ---- entry points of the individual kernel files (all enqueue on `s`, return strd_status) ----
-int compact_launch(const void *src, const int32_t *idx, void *dst, int N, int M, int K,
-                   int64_t row_bytes, const int32_t *pos_in, int32_t *pos_out, hipStream_t s);
+int compact_launch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
+                   const int32_t *pos_in, int32_t *pos_out, hipStream_t s);
 int select_topk_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s);
 
 // general SIMT kernels: any shape, fp32 or bf16 I/O, fp32 arithmetic
@@ -49,6 +49,9 @@ int ssd_general(const void *x, const float *dt, const float *A, const void *B, c
                 const float *D, const float *S_in, void *y, float *S_out, int T, int H, int P, int G,
                 int n, strd_dtype io, hipStream_t st);
 // bf16 matrix-core paths
+bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
+int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
+                     hipStream_t st);
 bool ssd_mfma_supported(int T, int H, int P, int G, int n, strd_dtype io);
 int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
              const float *S_in, void *y, float *S_out, int T, int H, int P, int G, int n, hipStream_t st);

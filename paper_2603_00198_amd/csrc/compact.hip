@@ -1,7 +1,10 @@
-// compact: order-preserving row gather of one per-token tensor (paper Sec. 3.1, token
-// selection: retained vision tokens continue, the text tail is kept whole).
+// compact: order-preserving row gather of per-token tensors (paper Sec. 3.1, token selection:
+// retained vision tokens continue, the text tail is kept whole).
 // Pure HBM-bound copy: every lane moves 16-byte vectors, the loads of a thread are issued
-// before its stores, consecutive lanes touch consecutive vectors of a row.
+// before its stores, consecutive lanes touch consecutive vectors of a row.  Up to
+// STRD_COMPACT_MAX tensors that share one index list are gathered by a single launch
+// (blockIdx.y selects the tensor), which matters because a reduced layer compacts 4-5 tensors
+// of a few tens of MB each and a launch costs about as much as moving 20 MB.
 #include "common.h"
 
 namespace strd {
@@ -10,15 +13,27 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 
-// One workgroup copies `rows_per_block` consecutive destination rows.  Vec is uint4 (rows a
-// multiple of 16 bytes) or uint32_t.
+struct Item {
+    const void *src;
+    void *dst;
+    int vec_per_row;     // row length in vectors
+    int rows_per_block;  // whole rows handled by one workgroup
+    int vec16;           // 1: 16-byte vectors, 0: 4-byte vectors
+    int identity;        // 1: write the source row number itself (position map without pos_in)
+};
+struct Batch {
+    Item item[STRD_COMPACT_MAX + 1];
+};
+
 template <typename Vec>
-__global__ __launch_bounds__(kThreads) void compact_rows_kernel(
-    const Vec *__restrict__ src, const int32_t *__restrict__ idx, Vec *__restrict__ dst, int N, int K,
-    int rows_out, int vec_per_row, int rows_per_block) {
-    const int row0 = blockIdx.x * rows_per_block;
-    const int nrows = min(rows_per_block, rows_out - row0);
-    const int total = nrows * vec_per_row;
+__device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restrict__ idx, int N, int K, int rows_out) {
+    const Vec *__restrict__ src = reinterpret_cast<const Vec *>(it.src);
+    Vec *__restrict__ dst = reinterpret_cast<Vec *>(it.dst);
+    const int vpr = it.vec_per_row;
+    const int row0 = blockIdx.x * it.rows_per_block;
+    if (row0 >= rows_out) return;
+    const int nrows = min(it.rows_per_block, rows_out - row0);
+    const int total = nrows * vpr;
     for (int e0 = threadIdx.x; e0 < total; e0 += kThreads * kUnroll) {
         Vec v[kUnroll];
         size_t off[kUnroll];
@@ -26,12 +41,12 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
         for (int u = 0; u < kUnroll; ++u) {
             const int e = e0 + u * kThreads;
             if (e < total) {
-                const int rl = e / vec_per_row;
-                const int c = e - rl * vec_per_row;
+                const int rl = e / vpr;
+                const int c = e - rl * vpr;
                 const int r = row0 + rl;
                 const int sr = (r < K) ? idx[r] : (N + (r - K));
-                v[u] = src[(size_t)sr * vec_per_row + c];
-                off[u] = (size_t)r * vec_per_row + c;
+                v[u] = src[(size_t)sr * vpr + c];
+                off[u] = (size_t)r * vpr + c;
             }
         }
 #pragma unroll
@@ -40,44 +55,57 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
     }
 }
 
-__global__ __launch_bounds__(kThreads) void compact_pos_kernel(const int32_t *__restrict__ idx,
-                                                               const int32_t *__restrict__ pos_in,
-                                                               int32_t *__restrict__ pos_out, int N,
-                                                               int K, int rows_out) {
-    const int r = blockIdx.x * kThreads + threadIdx.x;
-    if (r >= rows_out) return;
-    const int sr = (r < K) ? idx[r] : (N + (r - K));
-    pos_out[r] = pos_in ? pos_in[sr] : sr;
+__global__ __launch_bounds__(kThreads) void compact_kernel(Batch b, const int32_t *__restrict__ idx, int N, int K,
+                                                           int rows_out) {
+    const Item &it = b.item[blockIdx.y];
+    if (it.identity) {
+        const int r = blockIdx.x * kThreads + threadIdx.x;
+        if (r < rows_out) reinterpret_cast<int32_t *>(it.dst)[r] = (r < K) ? idx[r] : (N + (r - K));
+    } else if (it.vec16) {
+        copy_rows<uint4>(it, idx, N, K, rows_out);
+    } else {
+        copy_rows<uint32_t>(it, idx, N, K, rows_out);
+    }
 }
 
 }  // namespace
 
-int compact_launch(const void *src, const int32_t *idx, void *dst, int N, int M, int K,
-                   int64_t row_bytes, const int32_t *pos_in, int32_t *pos_out, hipStream_t s) {
+int compact_launch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
+                   const int32_t *pos_in, int32_t *pos_out, hipStream_t s) {
     const int rows_out = K + M;
     if (rows_out == 0) return STRD_OK;
-    if (src && dst) {
-        const bool v16 = (row_bytes % 16 == 0) && ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0);
-        const int64_t vpr64 = v16 ? row_bytes / 16 : row_bytes / 4;
-        if (vpr64 > (1 << 26)) return STRD_EUNSUPPORTED;
-        const int vpr = (int)vpr64;
+    Batch b;
+    int n = 0, grid_x = 1;
+    for (int i = 0; i < n_items; ++i) {
+        const strd_compact_item &ci = items[i];
+        Item it;
+        it.src = ci.src;
+        it.dst = ci.dst;
+        it.identity = 0;
+        it.vec16 = (ci.row_bytes % 16 == 0) && ((uintptr_t)ci.src % 16 == 0) && ((uintptr_t)ci.dst % 16 == 0);
+        const int64_t vpr = it.vec16 ? ci.row_bytes / 16 : ci.row_bytes / 4;
+        if (vpr > (1 << 26)) return STRD_EUNSUPPORTED;
+        it.vec_per_row = (int)vpr;
         // about 8 vectors per thread per workgroup, whole rows only
-        int rpb = (kThreads * 8) / vpr;
-        if (rpb < 1) rpb = 1;
-        const int grid = ceil_div(rows_out, rpb);
-        if (v16)
-            compact_rows_kernel<uint4><<<grid, kThreads, 0, s>>>((const uint4 *)src, idx, (uint4 *)dst, N, K,
-                                                                 rows_out, vpr, rpb);
-        else
-            compact_rows_kernel<uint32_t><<<grid, kThreads, 0, s>>>((const uint32_t *)src, idx,
-                                                                    (uint32_t *)dst, N, K, rows_out, vpr, rpb);
-        if (launch_status() != STRD_OK) return STRD_EHIP;
+        it.rows_per_block = (kThreads * 8) / it.vec_per_row;
+        if (it.rows_per_block < 1) it.rows_per_block = 1;
+        grid_x = max(grid_x, ceil_div(rows_out, it.rows_per_block));
+        b.item[n++] = it;
     }
     if (pos_out) {
-        compact_pos_kernel<<<ceil_div(rows_out, kThreads), kThreads, 0, s>>>(idx, pos_in, pos_out, N, K, rows_out);
-        if (launch_status() != STRD_OK) return STRD_EHIP;
+        Item it;
+        it.src = pos_in;
+        it.dst = pos_out;
+        it.identity = pos_in ? 0 : 1;
+        it.vec16 = 0;
+        it.vec_per_row = 1;
+        it.rows_per_block = kThreads * 8;
+        grid_x = max(grid_x, ceil_div(rows_out, pos_in ? it.rows_per_block : kThreads));
+        b.item[n++] = it;
     }
-    return STRD_OK;
+    if (n == 0) return STRD_OK;
+    compact_kernel<<<dim3(grid_x, n), kThreads, 0, s>>>(b, idx, N, K, rows_out);
+    return launch_status();
 }
 
 }  // namespace strd

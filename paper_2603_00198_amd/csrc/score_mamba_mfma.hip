@@ -1,0 +1,178 @@
+// score_mamba on bf16 matrix cores: Decoupled Content Alignment (paper Eq. "ssm_importance")
+//     s_i = 1/(M*H) * sum_g (sum_{h in g} dt_i^h) * sum_m | b_i^g . c_m^g |
+// The |b.c| table is an [M x N] contraction over the state dimension per group, which is never
+// materialised: a wave keeps the b fragments of its 32*CT vision tokens in registers (B operand,
+// tokens on the accumulator columns), streams the text rows c_m of the group through LDS as the
+// A operand, and folds |acc| into one running sum per lane, so the reduction over text rows
+// costs no cross-lane traffic until the single lane-half exchange at the end of a group.  The
+// sum over groups stays inside the lane, in group order: no atomics, bit-reproducible.
+//
+// One workgroup = 4 waves = 128*CT consecutive tokens, all groups.  The text tile (128 rows
+// of one group) is double-buffered in LDS and shared by the 4 waves; the next tile and the
+// next group's b fragments are prefetched into registers while the current tile is consumed.
+// HBM traffic is one pass over B_vis and dt_vis; C_txt (M*G*n*2 bytes) is re-read per
+// workgroup from L2.
+#include "common.h"
+
+namespace strd {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int kMC = 128;  // text rows per LDS tile
+
+template <int NS>
+struct Tile {
+    static constexpr int kPitch = NS + 8;  // bf16 elements per LDS row
+    bf16_t c[2][kMC][kPitch];
+};
+
+template <int NS, int CT>
+__global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t *__restrict__ Bv,
+                                                                    const bf16_t *__restrict__ Ct,
+                                                                    const float *__restrict__ dtv,
+                                                                    float *__restrict__ s, int M, int N, int H, int G) {
+    constexpr int KS = NS / 16;                 // k-steps of v_mfma_f32_32x32x16_bf16
+    constexpr int VR = NS / 8;                  // 16-byte vectors per text row
+    constexpr int VPT = kMC * VR / kThreads;    // staged vectors per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Tile<NS> &lds = *reinterpret_cast<Tile<NS> *>(smem_raw);
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int hpg = H / G;
+    const int nmc = (M + kMC - 1) / kMC, nchunk = G * nmc;
+    const int tok0 = blockIdx.x * (128 * CT) + w * (32 * CT);
+    int tok[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) tok[ct] = min(tok0 + 32 * ct + lc, N - 1);  // tail lanes repeat the last token
+
+    // text-tile staging (global -> registers -> LDS); rows past M are zero
+    uint4 stage[VPT];
+    auto stage_load = [&](int chunk) {
+        const int g = chunk / nmc, m0 = (chunk % nmc) * kMC;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
+            const int m = min(m0 + r, M - 1);
+            const uint4 val = *reinterpret_cast<const uint4 *>(Ct + ((size_t)m * G + g) * NS + cv * 8);
+            stage[i] = (m0 + r < M) ? val : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto stage_store = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
+            *reinterpret_cast<uint4 *>(&lds.c[b][r][cv * 8]) = stage[i];
+        }
+    };
+    // b fragments of group g for this wave's tokens: lane = token column, 8 consecutive k
+    auto load_b = [&](bf16x8 (&dst)[CT][KS], int g) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                dst[ct][ks] = *reinterpret_cast<const bf16x8 *>(Bv + ((size_t)tok[ct] * G + g) * NS + 16 * ks + 8 * half);
+    };
+
+    bf16x8 bcur[CT][KS], bnext[CT][KS];
+    load_b(bcur, 0);
+    stage_load(0);
+    stage_store(0);
+    __syncthreads();
+
+    float total[CT], part[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) total[ct] = part[ct] = 0.f;
+
+    for (int chunk = 0; chunk < nchunk; ++chunk) {
+        const int g = chunk / nmc, mc = chunk % nmc, cur = chunk & 1;
+        // prefetch (clamped, so the loop body is free of conditional loads)
+        stage_load(min(chunk + 1, nchunk - 1));
+        if (mc == 0) load_b(bnext, min(g + 1, G - 1));
+
+        // |c_m . b_i| for the 128 text rows of this tile, 32 at a time
+#pragma unroll
+        for (int mt = 0; mt < kMC / 32; ++mt) {
+            f32x16 acc[CT];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[ct][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lds.c[cur][32 * mt + lc][16 * ks + 8 * half]);
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bcur[ct][ks], acc[ct], 0, 0, 0);
+            }
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                float t = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t += fabsf(acc[ct][i]);
+                part[ct] += t;
+            }
+        }
+
+        stage_store(cur ^ 1);
+        if (mc == nmc - 1) {
+            // end of a group: weight by the summed dt of the group's heads
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                float dts = 0.f;
+                for (int j = half; j < hpg; j += 2) dts += dtv[(size_t)tok[ct] * H + g * hpg + j];
+                dts += __shfl_xor(dts, 32, kWave);
+                const float col = part[ct] + __shfl_xor(part[ct], 32, kWave);
+                total[ct] += dts * col;
+                part[ct] = 0.f;
+            }
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) bcur[ct][ks] = bnext[ct][ks];
+        }
+        __syncthreads();
+    }
+
+    const float norm = 1.f / ((float)M * (float)H);
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int t = tok0 + 32 * ct + lc;
+        if (half == 0 && t < N) s[t] = total[ct] * norm;
+    }
+}
+
+template <int NS, int CT>
+int launch(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, hipStream_t st) {
+    const size_t smem = sizeof(Tile<NS>);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return STRD_EHIP;
+        configured = true;
+    }
+    const int grid = ceil_div(N, 128 * CT);
+    score_mamba_mfma_kernel<NS, CT><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, dt, s, M, N, H, G);
+    return launch_status();
+}
+
+}  // namespace
+
+bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io) {
+    (void)M; (void)H; (void)G;
+    return io == STRD_BF16 && (n == 64 || n == 128) && N >= 1;
+}
+
+int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
+                     hipStream_t st) {
+    // wide token tiles once there are enough of them to fill 256 CUs; narrow ones otherwise
+    const bool wide = N >= 256 * 256;
+    if (n == 128) return wide ? launch<128, 2>(B, C, dt, s, M, N, H, G, st) : launch<128, 1>(B, C, dt, s, M, N, H, G, st);
+    if (n == 64) return wide ? launch<64, 2>(B, C, dt, s, M, N, H, G, st) : launch<64, 1>(B, C, dt, s, M, N, H, G, st);
+    return STRD_EUNSUPPORTED;
+}
+
+}  // namespace strd

@@ -43,6 +43,24 @@ def test_compact_bit_exact(N, M, K, row_elems, dtype):
     np.testing.assert_array_equal(pos_id.cpu().numpy(), oracle.compact(raw, idx.numpy(), N, M)[1])
 
 
+def test_compact_batch_bit_exact():
+    _say("compact_batch 5 tensors + positions")
+    N, M, K = 3000, 70, 811
+    g = torch.Generator().manual_seed(1)
+    shapes = [((64, 32), torch.bfloat16), ((8, 16), torch.bfloat16), ((24,), torch.float32), ((130,), torch.bfloat16),
+              ((4096,), torch.bfloat16)]
+    srcs = [torch.randn((N + M,) + shp, generator=g).to(dt) for shp, dt in shapes]
+    idx = torch.sort(torch.randperm(N, generator=g)[:K]).values.to(torch.int32)
+    pos_in = torch.randperm(5 * (N + M), generator=g)[: N + M].to(torch.int32)
+    outs, pos = strd.compact_batch([t.to(DEV) for t in srcs], idx.to(DEV), N, M, pos_in=pos_in.to(DEV))
+    for t, o in zip(srcs, outs):
+        raw = t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()
+        want, want_pos = oracle.compact(raw, idx.numpy(), N, M, pos_in=pos_in.numpy())
+        got = o.cpu().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()
+        np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(pos.cpu().numpy(), want_pos)
+
+
 # ------------------------------------------------------------------ select_topk ------------
 def _topk_case(scores, K):
     got = strd.select_topk(torch.from_numpy(scores).to(DEV), K).cpu().numpy()
