@@ -30,8 +30,8 @@ int strd_version(void) { return 1000; }
 
 // ------------------------------------------------------------------ score_attn -------------
 size_t strd_score_attn_workspace(int M, int N, int Hq, int Hkv, int d, strd_dtype io) {
-    (void)N; (void)Hkv; (void)d; (void)io;
-    if (M < 1 || Hq < 1) return 0;
+    if (M < 1 || N < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv) return 0;
+    if (score_attn_mfma_supported(M, N, Hq, Hkv, d, io)) return score_attn_mfma_ws(M, N, Hq, Hkv);
     return score_attn_general_ws(M, Hq);
 }
 
@@ -42,6 +42,8 @@ int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, 
     if ((long long)M * Hq > (1 << 30)) return STRD_EUNSUPPORTED;
     const size_t need = strd_score_attn_workspace(M, N, Hq, Hkv, d, io);
     if (!ws || ws_bytes < need) return STRD_EWORKSPACE;
+    if (score_attn_mfma_supported(M, N, Hq, Hkv, d, io))
+        return score_attn_mfma(q_txt, k_vis, scores, M, N, Hq, Hkv, d, scale, ws, as_stream(stream));
     return score_attn_general(q_txt, k_vis, scores, M, N, Hq, Hkv, d, scale, io, ws, as_stream(stream));
 }
 

@@ -49,6 +49,10 @@ int ssd_general(const void *x, const float *dt, const float *A, const void *B, c
                 const float *D, const float *S_in, void *y, float *S_out, int T, int H, int P, int G,
                 int n, strd_dtype io, hipStream_t st);
 // bf16 matrix-core paths
+bool score_attn_mfma_supported(int M, int N, int Hq, int Hkv, int d, strd_dtype io);
+size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv);
+int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
+                    hipStream_t st);
 bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
                      hipStream_t st);

@@ -1,0 +1,354 @@
+// score_attn on bf16 matrix cores: text-to-vision attention importance (paper Sec. 3.1,
+// "Attention Layers")
+//     s_i = 1/(M*Hq) * sum_{m,h} softmax_i( scale * q_m^h . k_i^{kv(h)} ),  softmax over the N keys.
+// The [M*Hq x N] probability table is never stored; it is produced twice, tile by tile:
+//   pass 1 (stats)   per query row: running max and sum of 2^z over a slice of the keys,
+//   combine          per query row: log2-sum-exp over the slices,
+//   pass 2 (colsum)  per key: sum over the query rows of 2^(z - lse),
+//   reduce           sum over kv heads, times 1/(M*Hq).
+// with z = q.k * scale * log2(e).  Both passes compute the tile transposed, Z^T[key, query]
+// (A operand = key rows, B operand = query rows, v_mfma_f32_32x32x16_bf16), so a lane holds one
+// query column and 16 keys: the per-query softmax state of pass 1 and the per-query lse of
+// pass 2 are one scalar per lane.  In pass 1 a wave keeps its query fragments in registers and
+// streams keys through LDS; in pass 2 a wave keeps its key fragments in registers, streams the
+// query rows of its kv head through LDS and accumulates 2^(z-lse) per (lane, key) over all
+// query tiles before a single butterfly reduction over the 32 lanes.  All reductions run in a
+// fixed order: the scores are bit-reproducible.
+#include "common.h"
+
+namespace strd {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int kRows = 128;  // rows (keys in pass 1, queries in pass 2) per LDS tile
+constexpr int kTW = 2;      // 32-wide register tiles per wave (queries in pass 1, keys in pass 2)
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int D>
+struct Tile {
+    static constexpr int kPitch = D + 8;
+    bf16_t t[2][kRows][kPitch];
+    float lse[2][kRows];
+};
+
+__device__ __forceinline__ float ex2(float v) { return __builtin_amdgcn_exp2f(v); }
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 v;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = 0.f;
+    return v;
+}
+
+// Query row r of kv head kvh (r = m * rep + j) lives at q[(m * Hq + kvh * rep + j) * D].
+__device__ __forceinline__ size_t qrow_index(int r, int rep, int Hq, int kvh) {
+    return (size_t)(r / rep) * Hq + kvh * rep + r % rep;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 1: grid = row blocks (fastest) x kv heads x key slices
+template <int D>
+__global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+                                                              float *__restrict__ pmax, float *__restrict__ psum, int M,
+                                                              int N, int Hq, int Hkv, float scale2, int nrb,
+                                                              int keys_per_slice) {
+    constexpr int KS = D / 16, VR = D / 8, VPT = kRows * VR / kThreads;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int rep = Hq / Hkv, R = M * rep;
+    const int rb = blockIdx.x % nrb, kvh = (blockIdx.x / nrb) % Hkv, sl = blockIdx.x / (nrb * Hkv);
+    const int key0 = sl * keys_per_slice, key1 = min(N, key0 + keys_per_slice);
+    const int nchunk = (key1 - key0 + kRows - 1) / kRows;
+
+    // this wave's query fragments (B operand: lane = query column)
+    bf16x8 bq[kTW][KS];
+    int row[kTW];
+#pragma unroll
+    for (int qt = 0; qt < kTW; ++qt) {
+        row[qt] = rb * (4 * 32 * kTW) + w * (32 * kTW) + 32 * qt + lc;
+        const bf16_t *qp = q + qrow_index(min(row[qt], R - 1), rep, Hq, kvh) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bq[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks + 8 * half);
+    }
+
+    uint4 stage[VPT];
+    auto stage_load = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
+            const int key = min(key0 + chunk * kRows + r, N - 1);
+            stage[i] = *reinterpret_cast<const uint4 *>(k + ((size_t)key * Hkv + kvh) * D + cv * 8);
+        }
+    };
+    auto stage_store = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
+            *reinterpret_cast<uint4 *>(&lds.t[b][r][cv * 8]) = stage[i];
+        }
+    };
+
+    float run_m[kTW], run_s[kTW];
+#pragma unroll
+    for (int qt = 0; qt < kTW; ++qt) { run_m[qt] = -INFINITY; run_s[qt] = 0.f; }
+
+    stage_load(0);
+    stage_store(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < nchunk; ++chunk) {
+        const int cur = chunk & 1;
+        stage_load(min(chunk + 1, nchunk - 1));
+        const int kbase = key0 + chunk * kRows;
+#pragma unroll
+        for (int kt = 0; kt < kRows / 32; ++kt) {
+            if (kbase + 32 * kt < key1) {  // uniform: skip tiles wholly past the slice
+                f32x16 acc[kTW];
+#pragma unroll
+                for (int qt = 0; qt < kTW; ++qt) acc[qt] = zero16();
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lds.t[cur][32 * kt + lc][16 * ks + 8 * half]);
+#pragma unroll
+                    for (int qt = 0; qt < kTW; ++qt) acc[qt] = mfma32(a, bq[qt][ks], acc[qt]);
+                }
+                const bool partial = kbase + 32 * kt + 32 > key1;
+#pragma unroll
+                for (int qt = 0; qt < kTW; ++qt) {
+                    float z[16], tmax = -INFINITY;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        z[i] = acc[qt][i] * scale2;
+                        if (partial && kbase + 32 * kt + 8 * (i / 4) + 4 * half + (i % 4) >= key1) z[i] = -INFINITY;
+                        tmax = fmaxf(tmax, z[i]);
+                    }
+                    const float nm = fmaxf(run_m[qt], tmax);
+                    const float ref = (nm == -INFINITY) ? 0.f : nm;
+                    float ts = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) ts += ex2(z[i] - ref);
+                    run_s[qt] = run_s[qt] * ex2(run_m[qt] - ref) + ts;
+                    run_m[qt] = nm;
+                }
+            }
+        }
+        stage_store(cur ^ 1);
+        __syncthreads();
+    }
+    // merge the two lane halves (disjoint keys of the same query) and publish
+#pragma unroll
+    for (int qt = 0; qt < kTW; ++qt) {
+        const float om = __shfl_xor(run_m[qt], 32, kWave), os = __shfl_xor(run_s[qt], 32, kWave);
+        const float nm = fmaxf(run_m[qt], om);
+        const float ref = (nm == -INFINITY) ? 0.f : nm;
+        const float tot = run_s[qt] * ex2(run_m[qt] - ref) + os * ex2(om - ref);
+        if (half == 0 && row[qt] < R) {
+            const size_t o = (size_t)sl * M * Hq + qrow_index(row[qt], rep, Hq, kvh);
+            pmax[o] = nm;
+            psum[o] = tot;
+        }
+    }
+}
+
+// combine: lse2[row] = log2 sum over slices; one thread per query row
+__global__ __launch_bounds__(kThreads) void attn_lse_kernel(const float *__restrict__ pmax, const float *__restrict__ psum,
+                                                            float *__restrict__ lse2, int rows, int nslice) {
+    const int r = blockIdx.x * kThreads + threadIdx.x;
+    if (r >= rows) return;
+    float m = -INFINITY;
+    for (int s = 0; s < nslice; ++s) m = fmaxf(m, pmax[(size_t)s * rows + r]);
+    float tot = 0.f;
+    for (int s = 0; s < nslice; ++s) {
+        const float pm = pmax[(size_t)s * rows + r];
+        if (pm != -INFINITY) tot += psum[(size_t)s * rows + r] * ex2(pm - m);
+    }
+    lse2[r] = m + __log2f(tot);
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 2: grid = kv heads (fastest) x key blocks
+template <int D>
+__global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+                                                               const float *__restrict__ lse2, float *__restrict__ part,
+                                                               int M, int N, int Hq, int Hkv, float scale2) {
+    constexpr int KS = D / 16, VR = D / 8, VPT = kRows * VR / kThreads;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int rep = Hq / Hkv, R = M * rep;
+    const int kvh = blockIdx.x % Hkv, kb = blockIdx.x / Hkv;
+    const int nchunk = (R + kRows - 1) / kRows;
+
+    // this wave's key fragments (A operand: lane = key row)
+    bf16x8 ak[kTW][KS];
+    const int kbase = kb * (4 * 32 * kTW) + w * (32 * kTW);
+#pragma unroll
+    for (int kt = 0; kt < kTW; ++kt) {
+        const bf16_t *kp = k + ((size_t)min(kbase + 32 * kt + lc, N - 1) * Hkv + kvh) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) ak[kt][ks] = *reinterpret_cast<const bf16x8 *>(kp + 16 * ks + 8 * half);
+    }
+
+    uint4 stage[VPT];
+    float stage_lse = 0.f;
+    auto stage_load = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
+            const int rr = min(chunk * kRows + r, R - 1);
+            stage[i] = *reinterpret_cast<const uint4 *>(q + qrow_index(rr, rep, Hq, kvh) * D + cv * 8);
+        }
+        if (tid < kRows) {
+            const int rr = chunk * kRows + tid;
+            // rows past the end get lse = +inf, so their probabilities are exactly 0
+            stage_lse = (rr < R) ? lse2[qrow_index(rr, rep, Hq, kvh)] : INFINITY;
+        }
+    };
+    auto stage_store = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
+            *reinterpret_cast<uint4 *>(&lds.t[b][r][cv * 8]) = stage[i];
+        }
+        if (tid < kRows) lds.lse[b][tid] = stage_lse;
+    };
+
+    float col[kTW * 16];
+#pragma unroll
+    for (int j = 0; j < kTW * 16; ++j) col[j] = 0.f;
+
+    stage_load(0);
+    stage_store(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < nchunk; ++chunk) {
+        const int cur = chunk & 1;
+        stage_load(min(chunk + 1, nchunk - 1));
+#pragma unroll
+        for (int qt = 0; qt < kRows / 32; ++qt) {
+            if (chunk * kRows + 32 * qt < R) {  // uniform: skip query tiles wholly past the end
+                const float lse = lds.lse[cur][32 * qt + lc];
+                f32x16 acc[kTW];
+#pragma unroll
+                for (int kt = 0; kt < kTW; ++kt) acc[kt] = zero16();
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(&lds.t[cur][32 * qt + lc][16 * ks + 8 * half]);
+#pragma unroll
+                    for (int kt = 0; kt < kTW; ++kt) acc[kt] = mfma32(ak[kt][ks], b, acc[kt]);
+                }
+#pragma unroll
+                for (int kt = 0; kt < kTW; ++kt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) col[kt * 16 + i] += ex2(fmaf(acc[kt][i], scale2, -lse));
+            }
+        }
+        stage_store(cur ^ 1);
+        __syncthreads();
+    }
+
+    // butterfly over the 32 query lanes of each half: afterwards lane lc holds the total of
+    // register lc (= key tile lc / 16, accumulator row lc % 16)
+    static_assert(kTW == 2, "the butterfly below reduces 32 registers over 32 lanes");
+#pragma unroll
+    for (int step = 0; step < 5; ++step) {
+        const int mask = 16 >> step, cnt = 16 >> step;
+        const bool up = (lc & mask) != 0;
+#pragma unroll
+        for (int j = 0; j < cnt; ++j) {
+            const float send = up ? col[j] : col[j + cnt];
+            const float keep = up ? col[j + cnt] : col[j];
+            col[j] = keep + __shfl_xor(send, mask, kWave);
+        }
+    }
+    const int kt = lc >> 4, i = lc & 15;
+    const int key = kbase + 32 * kt + 8 * (i / 4) + 4 * half + (i % 4);
+    if (key < N) part[(size_t)kvh * N + key] = col[0];
+}
+
+__global__ __launch_bounds__(kThreads) void attn_score_reduce_kernel(const float *__restrict__ part, float *__restrict__ s,
+                                                                     int N, int Hkv, float norm) {
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N) return;
+    float t = 0.f;
+    for (int h = 0; h < Hkv; ++h) t += part[(size_t)h * N + i];
+    s[i] = t * norm;
+}
+
+struct Plan {
+    int nrb, nslice, keys_per_slice;
+    size_t off_pmax, off_psum, off_lse, off_part, total;
+};
+
+Plan make_plan(int M, int N, int Hq, int Hkv) {
+    Plan p;
+    const int R = M * (Hq / Hkv);
+    p.nrb = ceil_div(R, 4 * 32 * kTW);
+    // enough key slices to give the chip a few waves of workgroups, at least one LDS tile each
+    int want = ceil_div(1024, p.nrb * Hkv);
+    const int max_slices = ceil_div(N, kRows);
+    if (want > max_slices) want = max_slices;
+    if (want < 1) want = 1;
+    p.keys_per_slice = ceil_div(ceil_div(N, want), kRows) * kRows;
+    p.nslice = ceil_div(N, p.keys_per_slice);
+    const size_t rows = (size_t)M * Hq;
+    size_t o = 0;
+    p.off_pmax = o; o += align_up(rows * p.nslice * sizeof(float), 256);
+    p.off_psum = o; o += align_up(rows * p.nslice * sizeof(float), 256);
+    p.off_lse = o;  o += align_up(rows * sizeof(float), 256);
+    p.off_part = o; o += align_up((size_t)Hkv * N * sizeof(float), 256);
+    p.total = o;
+    return p;
+}
+
+template <int D>
+int run(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, float scale, void *ws, hipStream_t st) {
+    const Plan p = make_plan(M, N, Hq, Hkv);
+    const size_t smem = sizeof(Tile<D>);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_stats_kernel<D>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_colsum_kernel<D>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return STRD_EHIP;
+        configured = true;
+    }
+    char *base = (char *)ws;
+    float *pmax = (float *)(base + p.off_pmax), *psum = (float *)(base + p.off_psum);
+    float *lse2 = (float *)(base + p.off_lse), *part = (float *)(base + p.off_part);
+    const float scale2 = scale * kLog2e;
+    const int rows = M * Hq;
+    attn_stats_kernel<D><<<p.nrb * Hkv * p.nslice, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, pmax, psum, M,
+                                                                         N, Hq, Hkv, scale2, p.nrb, p.keys_per_slice);
+    attn_lse_kernel<<<ceil_div(rows, kThreads), kThreads, 0, st>>>(pmax, psum, lse2, rows, p.nslice);
+    const int nkb = ceil_div(N, 4 * 32 * kTW);
+    attn_colsum_kernel<D><<<nkb * Hkv, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, lse2, part, M, N, Hq,
+                                                            Hkv, scale2);
+    attn_score_reduce_kernel<<<ceil_div(N, kThreads), kThreads, 0, st>>>(part, s, N, Hkv, 1.f / ((float)M * (float)Hq));
+    return launch_status();
+}
+
+}  // namespace
+
+bool score_attn_mfma_supported(int M, int N, int Hq, int Hkv, int d, strd_dtype io) {
+    if (io != STRD_BF16 || (d != 64 && d != 128)) return false;
+    const long long blocks1 = (long long)ceil_div(M * (Hq / Hkv), 4 * 32 * kTW) * Hkv * ceil_div(N, kRows);
+    const long long blocks2 = (long long)ceil_div(N, 4 * 32 * kTW) * Hkv;
+    return blocks1 < (1LL << 30) && blocks2 < (1LL << 30) && (long long)M * Hq < (1LL << 30);
+}
+
+size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv) { return make_plan(M, N, Hq, Hkv).total; }
+
+int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
+                    hipStream_t st) {
+    if (d == 128) return run<128>(q, k, s, M, N, Hq, Hkv, scale, ws, st);
+    if (d == 64) return run<64>(q, k, s, M, N, Hq, Hkv, scale, ws, st);
+    return STRD_EUNSUPPORTED;
+}
+
+}  // namespace strd

@@ -119,6 +119,8 @@ ATTN_CASES = {
     "c1": synth.WORKLOADS["c1"],
     "c3-short": synth.shrink(synth.WORKLOADS["c3"], N=1500, M=37, d_model=512),
     "odd": synth.shrink(synth.WORKLOADS["c3"], N=333, M=3, d_model=128, attn=synth.AttnShape(Hq=6, Hkv=3, d=40)),
+    "d64": synth.shrink(synth.WORKLOADS["c3"], N=700, M=5, d_model=128, attn=synth.AttnShape(Hq=6, Hkv=2, d=64)),
+    "c3-mid": synth.shrink(synth.WORKLOADS["c3"], N=5000, M=100, d_model=256),
 }
 
 
@@ -192,7 +194,7 @@ def test_ssd_prefill_split_call_continues_the_scan():
 
 
 @pytest.mark.parametrize("name,T", [("c1", 1056), ("c1", 544), ("c3-short", 333), ("c3-short", 1537), ("odd", 100),
-                                    ("c1", 1), ("c1", 0)])
+                                    ("c1", 1), ("c1", 0), ("d64", 200), ("d64", 705)])
 def test_attn_prefill_parity(name, T):
     w = ATTN_CASES[name]
     _say("attn_prefill %s T=%d %s" % (name, T, w.dtype))
