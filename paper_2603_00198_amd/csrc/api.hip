@@ -126,6 +126,7 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
     if (T > 0 && (!q || !k || !v || !o)) return STRD_EINVAL;
     const size_t need = strd_attn_prefill_workspace(T, Hq, Hkv, d, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    if (attn_mfma_supported(T, Hq, Hkv, d, io)) return attn_mfma(q, k, v, o, T, Hq, Hkv, d, scale, as_stream(stream));
     if (!attn_general_supported(d)) return STRD_EUNSUPPORTED;
     return attn_general(q, k, v, o, T, Hq, Hkv, d, scale, io, as_stream(stream));
 }

@@ -49,6 +49,9 @@ int ssd_general(const void *x, const float *dt, const float *A, const void *B, c
                 const float *D, const float *S_in, void *y, float *S_out, int T, int H, int P, int G,
                 int n, strd_dtype io, hipStream_t st);
 // bf16 matrix-core paths
+bool attn_mfma_supported(int T, int Hq, int Hkv, int d, strd_dtype io);
+int attn_mfma(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d, float scale,
+              hipStream_t st);
 bool score_attn_mfma_supported(int M, int N, int Hq, int Hkv, int d, strd_dtype io);
 size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv);
 int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
