@@ -34,6 +34,10 @@ def parse_args():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--budget", type=float, default=0.25)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile", action="store_true",
+                    help="for rocprofv3: only the warm-up and the timed reduced steps, then one plain copy of "
+                         "known size (256 MiB through the compact kernel with the identity index list) that "
+                         "calibrates the FETCH_SIZE / WRITE_SIZE counters; prints the byte counts")
     ap.add_argument("--no-attention-extra", action="store_true",
                     help="skip the attention-layer figures appended to the default (c2) line")
     return ap.parse_args()
@@ -281,6 +285,30 @@ def cpu_baseline_attn(layer, synth, rows=48, txt_rows=4):
                       "(scaled by causal work); est. %.0f s for the whole layer" % (txt_rows, M, rows, Tr, tot)}
 
 
+def profile_run(torch, strd, synth, name, budget, steps, warmup, dev):
+    from dataclasses import replace
+    wname, kind = WORKLOADS[name]
+    w = replace(synth.WORKLOADS[wname], budget=budget)
+    layer = (MambaLayer if kind == "mamba" else AttnLayer)(torch, strd, synth, w, dev)
+    for _ in range(warmup + steps):
+        layer.step()
+    torch.cuda.synchronize()
+    rows, row_elems = 16384, 8192                       # 16384 rows x 16 KiB = 256 MiB
+    src = torch.empty(rows, row_elems, dtype=torch.bfloat16, device=dev).normal_()
+    dst = torch.empty_like(src)
+    ident = torch.arange(rows, dtype=torch.int32, device=dev)
+    for _ in range(5):
+        strd.compact(src, ident, rows, 0, out=dst)
+    torch.cuda.synchronize()
+    Tr = w.K + w.M
+    print(json.dumps({"profile": name, "steps": warmup + steps, "mixer_kernel": layer.mixer_name,
+                      "mixer_algorithmic_bytes_per_launch": layer.mixer_bytes(Tr),
+                      "compact_algorithmic_bytes_per_launch": layer.compact_bytes(),
+                      "calibration_copy": {"kernel": "compact_kernel", "launches": 5,
+                                           "read_bytes_per_launch": rows * row_elems * 2 + rows * 4,
+                                           "write_bytes_per_launch": rows * row_elems * 2}}))
+
+
 def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     from dataclasses import replace
     wname, kind = WORKLOADS[name]
@@ -344,6 +372,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     name = args.workload
+    if args.profile:
+        profile_run(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)
+        return
     res, layer = measure(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)
     w = layer.w
     s = w.mamba if layer.kind == "mamba" else w.attn
