@@ -11,7 +11,7 @@
 // already laid out as the B operand of the second product (8 consecutive accumulator registers
 // = the 8 contraction slots of a lane; V is read with the matching key permutation).
 // K and V stream through LDS in 64-key chunks, double-buffered, shared by the 4 waves; the
-// next chunk is prefetched into registers during the current one.  Workgroups are issued
+// next chunk is copied global -> LDS asynchronously (no register staging) during the current one.  Workgroups are issued
 // longest-first (last query block first), heads of one kv group adjacent.
 #include "common.h"
 
@@ -30,30 +30,25 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 template <int D>
 struct Tile {
-    static constexpr int kPitch = D + 8;
-    bf16_t k[2][kKC][kPitch];
-    bf16_t v[2][kKC][kPitch];
+    using A = AsyncTile<kKC, D / 8, kThreads / kWave>;
+    static constexpr int kPitch = A::kPitch;
+    struct alignas(16) Half {
+        bf16_t e[A::kBytes / 2];
+        __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitch + c; }
+    };
+    Half k[2], v[2];
 };
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
-// Transposing LDS read: within 16 lanes, lane r passes &tile[k0 + r/4][c0 + 4*(r%4)] and
-// receives tile[k0..k0+3][c0 + r].
-__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t *p) {
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
-    return __builtin_bit_cast(bf16x4, v);
-}
-__device__ __forceinline__ bf16x8 cat(bf16x4 lo, bf16x4 hi) {
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
 
 template <int D>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                              const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
                                                              int Hq, int Hkv, float scale2, int nqb) {
-    constexpr int KS = D / 16, DT = D / 32, VR = D / 8, VPT = kKC * VR / kThreads;
+    constexpr int KS = D / 16, DT = D / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
@@ -72,22 +67,17 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
         for (int ks = 0; ks < KS; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks + 8 * half);
     }
 
-    uint4 sk[VPT], sv[VPT];
-    auto stage_load = [&](int chunk) {
+    // K / V chunks go global -> LDS directly; this lane's slots of a tile are fixed
+    using AT = typename Tile<D>::A;
+    int st_row[AT::kIssues], st_col[AT::kIssues];
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int e = tid + i * kThreads, r = e / VR, cv = e % VR;
-            const size_t off = ((size_t)min(chunk * kKC + r, T - 1) * Hkv + kvh) * D + cv * 8;
-            sk[i] = *reinterpret_cast<const uint4 *>(k + off);
-            sv[i] = *reinterpret_cast<const uint4 *>(v + off);
-        }
-    };
-    auto stage_store = [&](int b) {
+    for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
+    auto stage = [&](int chunk, int b) {
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int e = tid + i * kThreads, r = e / VR, cv = e % VR;
-            *reinterpret_cast<uint4 *>(&lds.k[b][r][cv * 8]) = sk[i];
-            *reinterpret_cast<uint4 *>(&lds.v[b][r][cv * 8]) = sv[i];
+        for (int i = 0; i < AT::kIssues; ++i) {
+            const size_t off = ((size_t)min(chunk * kKC + st_row[i], T - 1) * Hkv + kvh) * D + st_col[i] * 8;
+            AT::issue(k + off, &lds.k[b], w, i);
+            AT::issue(v + off, &lds.v[b], w, i);
         }
     };
 
@@ -102,12 +92,12 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
     const int vb = lane >> 4, vr = lane & 15;
     const int v_krow = 4 * (vb >> 1) + (vr >> 2), v_col = 16 * (vb & 1) + 4 * (vr & 3);
 
-    stage_load(0);
-    stage_store(0);
+    stage(0, 0);
+    async_tile_wait();
     __syncthreads();
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int cur = chunk & 1;
-        stage_load(min(chunk + 1, nchunk - 1));
+        stage(min(chunk + 1, nchunk - 1), cur ^ 1);
 #pragma unroll
         for (int kt = 0; kt < kKC / 32; ++kt) {
             const int kb = chunk * kKC + 32 * kt;
@@ -117,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
                 for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lds.k[cur][32 * kt + lc][16 * ks + 8 * half]);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds.k[cur].at(32 * kt + lc, 16 * ks + 8 * half));
                     sacc = mfma32(a, bq[ks], sacc);
                 }
                 const bool diag = kb + 31 > wq0;  // some (key, query) pair of the tile is masked
@@ -150,16 +140,20 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
                 l_run += ps;
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    const bf16_t *vp = &lds.v[cur][32 * kt + 16 * ks2 + v_krow][v_col];
+                    const bf16_t *vp = lds.v[cur].at(32 * kt + 16 * ks2 + v_krow, v_col);
+                    constexpr int kHi = 8 * Tile<D>::kPitch * 2;  // byte offset of the second 4 keys of a slot group
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        const bf16x8 vf = cat(lds_read_tr(vp + 32 * dt), lds_read_tr(vp + 32 * dt + 8 * Tile<D>::kPitch));
-                        oacc[dt] = mfma32(vf, pf[ks2], oacc[dt]);
+                    for (int dp = 0; dp < DT; dp += 4) {
+                        strd_s16x4 r[8];
+                        lds_read_tr8<0, kHi, 64, 64 + kHi, 128, 128 + kHi, 192, 192 + kHi>(vp + 32 * dp, r);
+#pragma unroll
+                        for (int dd = 0; dd < 4; ++dd)
+                            if (dp + dd < DT) oacc[dp + dd] = mfma32(tr_pair(r[2 * dd], r[2 * dd + 1]), pf[ks2], oacc[dp + dd]);
                     }
                 }
             }
         }
-        stage_store(cur ^ 1);
+        async_tile_wait();
         __syncthreads();
     }
 

@@ -31,6 +31,75 @@ __device__ __forceinline__ int xcd_swizzle(int b, int n) {
 }
 __host__ __forceinline__ int xcd_grid(int n) { return (n + kXcd - 1) / kXcd * kXcd; }
 
+// ---- asynchronous global -> LDS tile copy (no VGPR staging) ---------------------------------
+// A tile is ROWS rows of VR 16-byte vectors, stored in LDS with one pad vector per row (pitch
+// VR + 1 vectors, which keeps 16-byte row reads and transposing reads off each other's banks).
+// global_load_lds writes lane l of a wave to (uniform LDS base) + 16 * l, so the tile is filled
+// slot by slot: slot s = row * (VR + 1) + cv; pad slots (cv == VR) re-read the row's last vector.
+// Slots are dealt to the NW waves of the workgroup 64 at a time; the tile's LDS footprint is
+// rounded up to whole 64-slot groups per wave (kBytes), the surplus slots re-read the last row.
+template <int ROWS, int VR, int NW>
+struct AsyncTile {
+    static constexpr int kVP = VR + 1;                                  // vectors per LDS row
+    static constexpr int kPitch = kVP * 8;                              // bf16 elements per LDS row
+    static constexpr int kSlots = ROWS * kVP;
+    static constexpr int kIssues = (kSlots + 64 * NW - 1) / (64 * NW);  // instructions per wave
+    static constexpr int kBytes = kIssues * NW * 64 * 16;
+
+    // Row and vector of the slot this lane fills with its i-th instruction.
+    __device__ static __forceinline__ void slot(int wave, int lane, int i, int &row, int &cv) {
+        const int s = (i * NW + wave) * 64 + lane;
+        row = min(s / kVP, ROWS - 1);
+        cv = min(s % kVP, VR - 1);
+    }
+    // Issue this lane's i-th copy: 16 bytes from `src` to its slot of the tile at `lds_tile`.
+    __device__ static __forceinline__ void issue(const void *src, void *lds_tile, int wave, int i) {
+        char *dst = reinterpret_cast<char *>(lds_tile) + (i * NW + wave) * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    }
+};
+// Wait until every copy this wave issued has landed (call before the barrier that publishes).
+__device__ __forceinline__ void async_tile_wait() { __builtin_amdgcn_s_waitcnt(0); }
+
+// ---- transposing LDS reads (ds_read_b64_tr_b16) ----------------------------------------------
+// Within each group of 16 lanes, lane r passes the address of element [k0 + r/4][c0 + 4*(r%4)] of
+// a row-major bf16 tile and receives [k0..k0+3][c0 + r]: four consecutive rows of one column,
+// which is what an MFMA operand needs when the contraction index runs along the tile's rows.
+// The reads are issued from inline assembly, eight at a time with one wait: the compiler's own
+// builtin carries no memory operand, so every use of it would wait for all outstanding
+// asynchronous global -> LDS copies and serialise the prefetch.
+typedef short strd_s16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 strd_bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 strd_bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t lds_offset(const void *p) {
+    return (uint32_t)(size_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+// r[i] = transposed read at byte offset Oi from p.
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ void lds_read_tr8(const void *p, strd_s16x4 (&r)[8]) {
+    const uint32_t a = lds_offset(p);
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %8 offset:%9\n\t"
+        "ds_read_b64_tr_b16 %1, %8 offset:%10\n\t"
+        "ds_read_b64_tr_b16 %2, %8 offset:%11\n\t"
+        "ds_read_b64_tr_b16 %3, %8 offset:%12\n\t"
+        "ds_read_b64_tr_b16 %4, %8 offset:%13\n\t"
+        "ds_read_b64_tr_b16 %5, %8 offset:%14\n\t"
+        "ds_read_b64_tr_b16 %6, %8 offset:%15\n\t"
+        "ds_read_b64_tr_b16 %7, %8 offset:%16\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
+        : "v"(a), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
+        : "memory");
+}
+__device__ __forceinline__ strd_bf16x8 tr_pair(strd_s16x4 lo, strd_s16x4 hi) {
+    return __builtin_shufflevector(__builtin_bit_cast(strd_bf16x4, lo), __builtin_bit_cast(strd_bf16x4, hi), 0, 1, 2, 3,
+                                   4, 5, 6, 7);
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? STRD_OK : STRD_EHIP; }
 
 // ---- entry points of the individual kernel files (all enqueue on `s`, return strd_status) ----
