@@ -29,8 +29,13 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 template <int D>
 struct Tile {
-    static constexpr int kPitch = D + 8;
-    bf16_t t[2][kRows][kPitch];
+    using A = AsyncTile<kRows, D / 8, kThreads / kWave>;
+    static constexpr int kPitch = A::kPitch;
+    struct alignas(16) Buf {
+        bf16_t e[A::kBytes / 2];
+        __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitch + c; }
+    };
+    Buf t[2];
     float lse[2][kRows];
 };
 
@@ -57,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
                                                               float *__restrict__ pmax, float *__restrict__ psum, int M,
                                                               int N, int Hq, int Hkv, float scale2, int nrb,
                                                               int keys_per_slice) {
-    constexpr int KS = D / 16, VR = D / 8, VPT = kRows * VR / kThreads;
+    constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
@@ -77,20 +82,16 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
         for (int ks = 0; ks < KS; ++ks) bq[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks + 8 * half);
     }
 
-    uint4 stage[VPT];
-    auto stage_load = [&](int chunk) {
+    // key tiles go global -> LDS directly; this lane's slots of a tile are fixed
+    using AT = typename Tile<D>::A;
+    int st_row[AT::kIssues], st_col[AT::kIssues];
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
-            const int key = min(key0 + chunk * kRows + r, N - 1);
-            stage[i] = *reinterpret_cast<const uint4 *>(k + ((size_t)key * Hkv + kvh) * D + cv * 8);
-        }
-    };
-    auto stage_store = [&](int b) {
+    for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
+    auto stage = [&](int chunk, int b) {
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
-            *reinterpret_cast<uint4 *>(&lds.t[b][r][cv * 8]) = stage[i];
+        for (int i = 0; i < AT::kIssues; ++i) {
+            const int key = min(key0 + chunk * kRows + st_row[i], N - 1);
+            AT::issue(k + ((size_t)key * Hkv + kvh) * D + st_col[i] * 8, &lds.t[b], w, i);
         }
     };
 
@@ -98,12 +99,12 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
 #pragma unroll
     for (int qt = 0; qt < kTW; ++qt) { run_m[qt] = -INFINITY; run_s[qt] = 0.f; }
 
-    stage_load(0);
-    stage_store(0);
+    stage(0, 0);
+    async_tile_wait();
     __syncthreads();
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int cur = chunk & 1;
-        stage_load(min(chunk + 1, nchunk - 1));
+        stage(min(chunk + 1, nchunk - 1), cur ^ 1);
         const int kbase = key0 + chunk * kRows;
 #pragma unroll
         for (int kt = 0; kt < kRows / 32; ++kt) {
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
                 for (int qt = 0; qt < kTW; ++qt) acc[qt] = zero16();
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lds.t[cur][32 * kt + lc][16 * ks + 8 * half]);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * kt + lc, 16 * ks + 8 * half));
 #pragma unroll
                     for (int qt = 0; qt < kTW; ++qt) acc[qt] = mfma32(a, bq[qt][ks], acc[qt]);
                 }
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
                 }
             }
         }
-        stage_store(cur ^ 1);
+        async_tile_wait();
         __syncthreads();
     }
     // merge the two lane halves (disjoint keys of the same query) and publish
@@ -176,7 +177,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                                const float *__restrict__ lse2, float *__restrict__ part,
                                                                int M, int N, int Hq, int Hkv, float scale2) {
-    constexpr int KS = D / 16, VR = D / 8, VPT = kRows * VR / kThreads;
+    constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
@@ -194,14 +195,17 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
         for (int ks = 0; ks < KS; ++ks) ak[kt][ks] = *reinterpret_cast<const bf16x8 *>(kp + 16 * ks + 8 * half);
     }
 
-    uint4 stage[VPT];
-    float stage_lse = 0.f;
-    auto stage_load = [&](int chunk) {
+    // query tiles go global -> LDS directly; the lse of the tile's rows goes through a register
+    using AT = typename Tile<D>::A;
+    int st_row[AT::kIssues], st_col[AT::kIssues];
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
-            const int rr = min(chunk * kRows + r, R - 1);
-            stage[i] = *reinterpret_cast<const uint4 *>(q + qrow_index(rr, rep, Hq, kvh) * D + cv * 8);
+    for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
+    float stage_lse = 0.f;
+    auto stage = [&](int chunk, int b) {
+#pragma unroll
+        for (int i = 0; i < AT::kIssues; ++i) {
+            const int rr = min(chunk * kRows + st_row[i], R - 1);
+            AT::issue(q + qrow_index(rr, rep, Hq, kvh) * D + st_col[i] * 8, &lds.t[b], w, i);
         }
         if (tid < kRows) {
             const int rr = chunk * kRows + tid;
@@ -209,12 +213,7 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
             stage_lse = (rr < R) ? lse2[qrow_index(rr, rep, Hq, kvh)] : INFINITY;
         }
     };
-    auto stage_store = [&](int b) {
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
-            *reinterpret_cast<uint4 *>(&lds.t[b][r][cv * 8]) = stage[i];
-        }
+    auto stage_lse_store = [&](int b) {
         if (tid < kRows) lds.lse[b][tid] = stage_lse;
     };
 
@@ -222,12 +221,13 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
 #pragma unroll
     for (int j = 0; j < kTW * 16; ++j) col[j] = 0.f;
 
-    stage_load(0);
-    stage_store(0);
+    stage(0, 0);
+    stage_lse_store(0);
+    async_tile_wait();
     __syncthreads();
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int cur = chunk & 1;
-        stage_load(min(chunk + 1, nchunk - 1));
+        stage(min(chunk + 1, nchunk - 1), cur ^ 1);
 #pragma unroll
         for (int qt = 0; qt < kRows / 32; ++qt) {
             if (chunk * kRows + 32 * qt < R) {  // uniform: skip query tiles wholly past the end
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
                 for (int kt = 0; kt < kTW; ++kt) acc[kt] = zero16();
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(&lds.t[cur][32 * qt + lc][16 * ks + 8 * half]);
+                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * qt + lc, 16 * ks + 8 * half));
 #pragma unroll
                     for (int kt = 0; kt < kTW; ++kt) acc[kt] = mfma32(ak[kt][ks], b, acc[kt]);
                 }
@@ -247,7 +247,8 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
                     for (int i = 0; i < 16; ++i) col[kt * 16 + i] += ex2(fmaf(acc[kt][i], scale2, -lse));
             }
         }
-        stage_store(cur ^ 1);
+        stage_lse_store(cur ^ 1);
+        async_tile_wait();
         __syncthreads();
     }
 

@@ -9,7 +9,8 @@
 //
 // One workgroup = 4 waves = 128*CT consecutive tokens, all groups.  The text tile (128 rows
 // of one group) is double-buffered in LDS and shared by the 4 waves; the next tile and the
-// next group's b fragments are prefetched into registers while the current tile is consumed.
+// next group's b fragments are prefetched (tile: asynchronous global -> LDS copy, fragments:
+// registers) while the current tile is consumed.
 // HBM traffic is one pass over B_vis and dt_vis; C_txt (M*G*n*2 bytes) is re-read per
 // workgroup from L2.
 #include "common.h"
@@ -25,8 +26,13 @@ constexpr int kMC = 128;  // text rows per LDS tile
 
 template <int NS>
 struct Tile {
-    static constexpr int kPitch = NS + 8;  // bf16 elements per LDS row
-    bf16_t c[2][kMC][kPitch];
+    using A = AsyncTile<kMC, NS / 8, kThreads / kWave>;
+    static constexpr int kPitch = A::kPitch;  // bf16 elements per LDS row
+    struct alignas(16) Buf {
+        bf16_t e[A::kBytes / 2];
+        __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitch + c; }
+    };
+    Buf c[2];
 };
 
 template <int NS, int CT>
@@ -34,9 +40,7 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
                                                                     const bf16_t *__restrict__ Ct,
                                                                     const float *__restrict__ dtv,
                                                                     float *__restrict__ s, int M, int N, int H, int G) {
-    constexpr int KS = NS / 16;                 // k-steps of v_mfma_f32_32x32x16_bf16
-    constexpr int VR = NS / 8;                  // 16-byte vectors per text row
-    constexpr int VPT = kMC * VR / kThreads;    // staged vectors per thread
+    constexpr int KS = NS / 16;  // k-steps of v_mfma_f32_32x32x16_bf16
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<NS> &lds = *reinterpret_cast<Tile<NS> *>(smem_raw);
 
@@ -48,23 +52,18 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) tok[ct] = min(tok0 + 32 * ct + lc, N - 1);  // tail lanes repeat the last token
 
-    // text-tile staging (global -> registers -> LDS); rows past M are zero
-    uint4 stage[VPT];
-    auto stage_load = [&](int chunk) {
+    // text tiles go global -> LDS directly; rows past M re-read the last row and are skipped
+    // (whole 32-row tiles) or masked (the ragged tile) when the products are folded
+    using AT = typename Tile<NS>::A;
+    int st_row[AT::kIssues], st_col[AT::kIssues];
+#pragma unroll
+    for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
+    auto stage = [&](int chunk, int b) {
         const int g = chunk / nmc, m0 = (chunk % nmc) * kMC;
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
-            const int m = min(m0 + r, M - 1);
-            const uint4 val = *reinterpret_cast<const uint4 *>(Ct + ((size_t)m * G + g) * NS + cv * 8);
-            stage[i] = (m0 + r < M) ? val : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto stage_store = [&](int b) {
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = tid + i * kThreads, r = v / VR, cv = v % VR;
-            *reinterpret_cast<uint4 *>(&lds.c[b][r][cv * 8]) = stage[i];
+        for (int i = 0; i < AT::kIssues; ++i) {
+            const int m = min(m0 + st_row[i], M - 1);
+            AT::issue(Ct + ((size_t)m * G + g) * NS + st_col[i] * 8, &lds.c[b], w, i);
         }
     };
     // b fragments of group g for this wave's tokens: lane = token column, 8 consecutive k
@@ -78,8 +77,8 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 
     bf16x8 bcur[CT][KS], bnext[CT][KS];
     load_b(bcur, 0);
-    stage_load(0);
-    stage_store(0);
+    stage(0, 0);
+    async_tile_wait();
     __syncthreads();
 
     float total[CT], part[CT];
@@ -89,12 +88,14 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int g = chunk / nmc, mc = chunk % nmc, cur = chunk & 1;
         // prefetch (clamped, so the loop body is free of conditional loads)
-        stage_load(min(chunk + 1, nchunk - 1));
+        stage(min(chunk + 1, nchunk - 1), cur ^ 1);
         if (mc == 0) load_b(bnext, min(g + 1, G - 1));
+        const int mrows = M - mc * kMC;  // valid text rows of this tile (may exceed kMC)
 
         // |c_m . b_i| for the 128 text rows of this tile, 32 at a time
 #pragma unroll
         for (int mt = 0; mt < kMC / 32; ++mt) {
+            if (32 * mt >= mrows) continue;  // uniform: tile wholly past the last text row
             f32x16 acc[CT];
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct)
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
                 for (int i = 0; i < 16; ++i) acc[ct][i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lds.c[cur][32 * mt + lc][16 * ks + 8 * half]);
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds.c[cur].at(32 * mt + lc, 16 * ks + 8 * half));
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
                     acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bcur[ct][ks], acc[ct], 0, 0, 0);
@@ -110,13 +111,18 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 float t = 0.f;
+                if (32 * mt + 32 <= mrows) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) t += fabsf(acc[ct][i]);
+                    for (int i = 0; i < 16; ++i) t += fabsf(acc[ct][i]);
+                } else {  // ragged tile: accumulator row i of this lane is text row 8*(i/4) + 4*half + i%4
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        t += (32 * mt + 8 * (i / 4) + 4 * half + (i % 4) < mrows) ? fabsf(acc[ct][i]) : 0.f;
+                }
                 part[ct] += t;
             }
         }
 
-        stage_store(cur ^ 1);
         if (mc == nmc - 1) {
             // end of a group: weight by the summed dt of the group's heads
 #pragma unroll
@@ -133,6 +139,7 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) bcur[ct][ks] = bnext[ct][ks];
         }
+        async_tile_wait();
         __syncthreads();
     }
 
