@@ -73,6 +73,7 @@ size_t strd_select_topk_workspace(int N, int K) {
 int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes, void *stream) {
     (void)ws; (void)ws_bytes;
     if (!scores || !idx || N < 1 || K < 1 || K > N) return STRD_EINVAL;
+    if (N > (1 << 30)) return STRD_EUNSUPPORTED;
     return select_topk_launch(scores, N, K, idx, as_stream(stream));
 }
 

@@ -5,8 +5,15 @@
 // N is at most a few hundred thousand (<= 512 KB of scores), so the problem is latency-bound:
 // one 1024-lane workgroup does an MSB radix select on the order-preserving integer image of
 // the floats (11 + 11 + 10 bits, histogram in LDS), which yields the exact K-th value and how
-// many of its duplicates to keep, then one ordered pass (ballot-free packed prefix sums) writes
-// the surviving indices.  No global atomics, no scratch memory, bit-exact and deterministic.
+// many of its duplicates to keep, then one ordered pass (packed prefix sums) writes the
+// surviving indices.  Each lane owns 4 consecutive scores of every 4096-score tile; up to
+// 32768 scores the keys are read from memory once and stay in registers for all four passes,
+// beyond that they are re-read in batches of 8 tiles with all loads of a batch in flight
+// together.  Importance scores cluster (a near-uniform attention score puts every key into a
+// handful of exponent bins) and same-address LDS atomics serialise, so every bin has 16 copies,
+// one per lane modulo 16, in adjacent LDS words (different banks); the copies are summed when a
+// bin is picked.  The ordered pass scans 8 tiles per barrier.  No global atomics, no scratch
+// memory, bit-exact and deterministic.
 #include "common.h"
 
 namespace strd {
@@ -15,134 +22,257 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kBins = 2048;
+constexpr int kTile = kThreads * 4;  // scores per tile
+constexpr int kBatch = 8;            // tiles loaded together when streaming / scanned per barrier
+constexpr int kCopies = 16;          // copies of every histogram bin
 
 // Monotone map float -> uint32 (larger float = larger key); -0.0 is folded onto +0.0.
+// Every real float maps above 0, the key given to the slots past the end of the array.
 __device__ __forceinline__ uint32_t order_key(float f) {
     uint32_t b = __float_as_uint(f);
     if (b == 0x80000000u) b = 0u;
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Exclusive prefix sum of one value per thread over the workgroup; `total` gets the sum.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_sums, uint32_t &total) {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    uint32_t inc = v;
+// Keys of the 4 scores this lane owns in tile `t` (0 past the end).
+__device__ __forceinline__ void load_tile(const float *__restrict__ scores, int N, int t, uint32_t (&key)[4]) {
+    const int i0 = t * kTile + threadIdx.x * 4;
+    if (i0 + 3 < N) {
+        const float4 v = *reinterpret_cast<const float4 *>(scores + i0);
+        key[0] = order_key(v.x); key[1] = order_key(v.y); key[2] = order_key(v.z); key[3] = order_key(v.w);
+    } else {
 #pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t up = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += up;
+        for (int u = 0; u < 4; ++u) key[u] = (i0 + u < N) ? order_key(scores[i0 + u]) : 0u;
     }
-    __syncthreads();  // wave_sums may still be read from the previous call
-    if (lane == kWave - 1) wave_sums[wave] = inc;
+}
+
+// hist[bin] += 1 in this lane's copy of the bin.
+__device__ __forceinline__ void hist_add(uint32_t *hist, uint32_t bin, bool valid) {
+    if (valid) atomicAdd(&hist[bin * kCopies + (threadIdx.x & (kCopies - 1))], 1u);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS round trips):
+// Kogge-Stone inside each row of 16 lanes, then the row totals are broadcast forward.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+#define STRD_DPP_ADD(ctrl, row_mask) \
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, row_mask, 0xF, true)
+    STRD_DPP_ADD(0x111, 0xF);  // row_shr:1
+    STRD_DPP_ADD(0x112, 0xF);  // row_shr:2
+    STRD_DPP_ADD(0x114, 0xF);  // row_shr:4
+    STRD_DPP_ADD(0x118, 0xF);  // row_shr:8
+    STRD_DPP_ADD(0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+    STRD_DPP_ADD(0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+#undef STRD_DPP_ADD
+    return v;
+}
+
+// Cross-wave step of up to kBatch workgroup scans that share one pair of barriers.  Before the
+// call every wave has stored the inclusive total of scan b in sums[b][wave].  The first 16*kBatch
+// threads turn each row of 16 wave totals into exclusive offsets with a DPP row scan (a row of
+// 16 lanes is exactly one scan) and append the grand total as element [b][kWaves].
+struct ScanScratch {
+    uint32_t sums[kBatch][kWaves];
+    uint32_t base[kBatch][kWaves + 1];
+};
+__device__ __forceinline__ void finish_scans(ScanScratch &sc) {
     __syncthreads();
-    uint32_t base = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t s = wave_sums[w];
-        if (w < wave) base += s;
-        tot += s;
+    if (threadIdx.x < kBatch * kWaves) {
+        const int b = threadIdx.x / kWaves, w = threadIdx.x % kWaves;
+        const uint32_t v = sc.sums[b][w];
+        uint32_t inc = v;
+#define STRD_DPP_ADD(ctrl) inc += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)inc, ctrl, 0xF, 0xF, true)
+        STRD_DPP_ADD(0x111);
+        STRD_DPP_ADD(0x112);
+        STRD_DPP_ADD(0x114);
+        STRD_DPP_ADD(0x118);
+#undef STRD_DPP_ADD
+        sc.base[b][w] = inc - v;
+        if (w == kWaves - 1) sc.base[b][kWaves] = inc;
     }
-    total = tot;
-    return base + inc - v;
+    __syncthreads();
 }
 
 // After a histogram pass: find the bin (scanning from the top) that holds the k-th largest key
-// and reduce k to its rank inside that bin.  All threads return the same (bin, k).
-__device__ __forceinline__ void pick_bin(const uint32_t *hist, uint32_t *wave_sums, uint32_t *shared2,
-                                         uint32_t &k, uint32_t &bin) {
-    const int d0 = kBins - 1 - 2 * threadIdx.x, d1 = d0 - 1;  // two bins per thread, descending
-    const uint32_t c0 = hist[d0], c1 = hist[d1];
-    uint32_t total;
-    const uint32_t above = block_exclusive_scan(c0 + c1, wave_sums, total);
-    if (above < k && k <= above + c0) {
-        shared2[0] = (uint32_t)d0;
-        shared2[1] = k - above;
-    } else if (above + c0 < k && k <= above + c0 + c1) {
-        shared2[0] = (uint32_t)d1;
-        shared2[1] = k - above - c0;
+// and reduce k to its rank inside that bin.  All threads return the same (bin, k).  Thread t owns
+// bins 2047 - t and 1023 - t, so neighbouring threads read neighbouring 64-byte groups of copies.
+__device__ __forceinline__ void pick_bin(const uint32_t *hist, ScanScratch &sc, uint32_t *found, uint32_t &k,
+                                         uint32_t &bin) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int d_hi = kBins - 1 - threadIdx.x, d_lo = d_hi - kThreads;
+    uint32_t c_hi = 0, c_lo = 0;
+#pragma unroll
+    for (int c = 0; c < kCopies; c += 4) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(&hist[d_hi * kCopies + c]);
+        const uint4 b = *reinterpret_cast<const uint4 *>(&hist[d_lo * kCopies + c]);
+        c_hi += a.x + a.y + a.z + a.w;
+        c_lo += b.x + b.y + b.z + b.w;
+    }
+    const uint32_t i_hi = wave_inclusive_scan(c_hi), i_lo = wave_inclusive_scan(c_lo);
+    if (lane == kWave - 1) {
+        sc.sums[0][wave] = i_hi;
+        sc.sums[1][wave] = i_lo;
+    }
+    finish_scans(sc);
+    // keys in higher bins than this thread's: all upper-half bins come before any lower-half bin
+    const uint32_t above_hi = sc.base[0][wave] + i_hi - c_hi;
+    const uint32_t above_lo = sc.base[0][kWaves] + sc.base[1][wave] + i_lo - c_lo;
+    if (above_hi < k && k <= above_hi + c_hi) {
+        found[0] = (uint32_t)d_hi;
+        found[1] = k - above_hi;
+    } else if (above_lo < k && k <= above_lo + c_lo) {
+        found[0] = (uint32_t)d_lo;
+        found[1] = k - above_lo;
     }
     __syncthreads();
-    bin = shared2[0];
-    k = shared2[1];
-    __syncthreads();
+    bin = found[0];
+    k = found[1];
 }
 
+// TILES > 0: N <= TILES * kTile and every key stays in registers.  TILES == 0: streaming.
+template <int TILES>
 __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__restrict__ scores, int N, int K,
                                                                int32_t *__restrict__ idx) {
-    __shared__ uint32_t hist[kBins];
-    __shared__ uint32_t wave_sums[kWaves];
-    __shared__ uint32_t shared2[2];
+    extern __shared__ __attribute__((aligned(16))) uint32_t hist[];  // [kBins][kCopies]
+    __shared__ ScanScratch scan;
+    __shared__ uint32_t found[3][2];         // (bin, rank inside the bin) of each pass
     const int tid = threadIdx.x;
+    const int ntiles = (N + kTile - 1) / kTile;
+    auto zero_hist = [&]() {
+        for (int b = tid * 4; b < kBins * kCopies; b += kThreads * 4)
+            *reinterpret_cast<uint4 *>(&hist[b]) = make_uint4(0, 0, 0, 0);
+    };
+    zero_hist();
+
+    constexpr int kHeld = TILES > 0 ? TILES : 1;
+    uint32_t held[kHeld][4];
+    if (TILES > 0) {
+#pragma unroll
+        for (int t = 0; t < kHeld; ++t) load_tile(scores, N, t, held[t]);
+    }
+    // Visit every key this lane owns; f is inlined into both variants.
+    auto for_each_key = [&](auto &&f) {
+        if (TILES > 0) {
+#pragma unroll
+            for (int t = 0; t < kHeld; ++t)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) f(held[t][u]);
+        } else {
+            for (int t0 = 0; t0 < ntiles; t0 += kBatch) {
+                uint32_t key[kBatch][4];
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) load_tile(scores, N, t0 + b, key[b]);  // past-the-end tiles give 0
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) f(key[b][u]);
+            }
+        }
+    };
+    __syncthreads();
 
     // ---- radix select: exact key of the K-th largest score --------------------------------
     uint32_t k = (uint32_t)K, prefix = 0, bin;
-    // pass 0: top 11 bits
-    for (int b = tid; b < kBins; b += kThreads) hist[b] = 0;
+    for_each_key([&](uint32_t key) { hist_add(hist, key >> 21, true); });  // pass 0: top 11 bits
     __syncthreads();
-    for (int i = tid; i < N; i += kThreads) atomicAdd(&hist[order_key(scores[i]) >> 21], 1u);
-    __syncthreads();
-    pick_bin(hist, wave_sums, shared2, k, bin);
+    pick_bin(hist, scan, found[0], k, bin);
     prefix = bin << 21;
-    // pass 1: middle 11 bits of the keys that share the top 11
-    for (int b = tid; b < kBins; b += kThreads) hist[b] = 0;
+    zero_hist();  // every lane has read its bins before the barrier inside pick_bin
     __syncthreads();
-    for (int i = tid; i < N; i += kThreads) {
-        const uint32_t key = order_key(scores[i]);
-        if ((key >> 21) == (prefix >> 21)) atomicAdd(&hist[(key >> 10) & 0x7FFu], 1u);
-    }
+    for_each_key([&](uint32_t key) {  // pass 1: middle 11 bits of the keys that share the top 11
+        hist_add(hist, (key >> 10) & 0x7FFu, (key >> 21) == (prefix >> 21));
+    });
     __syncthreads();
-    pick_bin(hist, wave_sums, shared2, k, bin);
+    pick_bin(hist, scan, found[1], k, bin);
     prefix |= bin << 10;
-    // pass 2: low 10 bits
-    for (int b = tid; b < kBins; b += kThreads) hist[b] = 0;
+    zero_hist();
     __syncthreads();
-    for (int i = tid; i < N; i += kThreads) {
-        const uint32_t key = order_key(scores[i]);
-        if ((key >> 10) == (prefix >> 10)) atomicAdd(&hist[key & 0x3FFu], 1u);
-    }
+    for_each_key([&](uint32_t key) {  // pass 2: low 10 bits
+        hist_add(hist, key & 0x3FFu, (key >> 10) == (prefix >> 10));
+    });
     __syncthreads();
-    pick_bin(hist, wave_sums, shared2, k, bin);
-    const uint32_t thresh = prefix | bin;  // key of the K-th largest score
+    pick_bin(hist, scan, found[2], k, bin);
+    const uint32_t thresh = prefix | bin;  // key of the K-th largest score (a real score: > 0)
     const uint32_t keep_eq = k;            // how many keys == thresh survive (the first ones)
 
-    // ---- ordered write-out: 4 consecutive scores per thread per tile ------------------------
-    uint32_t out_base = 0, eq_base = 0;    // survivors / duplicates of thresh seen in earlier tiles
-    for (int t0 = 0; t0 < N; t0 += kThreads * 4) {
-        const int i0 = t0 + tid * 4;
-        uint32_t key[4];
-        uint32_t cnt = 0;  // low 16 bits: keys > thresh, high 16 bits: keys == thresh
+    // ---- ordered write-out: kBatch tiles per barrier ----------------------------------------
+    uint32_t out_base = 0, eq_base = 0;  // survivors / duplicates of thresh seen in earlier tiles
+    auto emit_batch = [&](int t0, const uint32_t (&key)[kBatch][4], int ntile) {
+        const int lane = tid & (kWave - 1), wave = tid / kWave;
+        uint32_t cnt[kBatch], inc[kBatch];  // low 16 bits: keys > thresh, high 16 bits: keys == thresh
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            key[u] = (i0 + u < N) ? order_key(scores[i0 + u]) : 0u;
-            const bool in = i0 + u < N;
-            cnt += (in && key[u] > thresh) ? 1u : 0u;
-            cnt += (in && key[u] == thresh) ? 0x10000u : 0u;
+        for (int b = 0; b < kBatch; ++b) {
+            cnt[b] = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                cnt[b] += (key[b][u] > thresh ? 1u : 0u) + (key[b][u] == thresh ? 0x10000u : 0u);
+            inc[b] = wave_inclusive_scan(cnt[b]);
+            if (lane == kWave - 1) scan.sums[b][wave] = inc[b];
         }
-        uint32_t total;
-        const uint32_t ex = block_exclusive_scan(cnt, wave_sums, total);
-        uint32_t gt_before = ex & 0xFFFFu, eq_before = eq_base + (ex >> 16);
+        finish_scans(scan);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (i0 + u < N) {
-                const bool gt = key[u] > thresh, eq = key[u] == thresh;
-                if (gt || (eq && eq_before < keep_eq)) {
-                    const uint32_t eq_kept = min(eq_before, keep_eq) - min(eq_base, keep_eq);
-                    idx[out_base + gt_before + eq_kept] = i0 + u;
+        for (int b = 0; b < kBatch; ++b) {
+            if (b < ntile) {  // uniform
+                const uint32_t total = scan.base[b][kWaves];
+                const uint32_t ex = scan.base[b][wave] + inc[b] - cnt[b];
+                const int i0 = (t0 + b) * kTile + tid * 4;
+                uint32_t gt_before = ex & 0xFFFFu, eq_before = eq_base + (ex >> 16);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const bool gt = key[b][u] > thresh, eq = key[b][u] == thresh;
+                    if (gt || (eq && eq_before < keep_eq)) {
+                        const uint32_t eq_kept = min(eq_before, keep_eq) - min(eq_base, keep_eq);
+                        idx[out_base + gt_before + eq_kept] = i0 + u;
+                    }
+                    gt_before += gt ? 1u : 0u;
+                    eq_before += eq ? 1u : 0u;
                 }
-                gt_before += gt ? 1u : 0u;
-                eq_before += eq ? 1u : 0u;
+                const uint32_t eq_tile = total >> 16;
+                out_base += (total & 0xFFFFu) + (min(eq_base + eq_tile, keep_eq) - min(eq_base, keep_eq));
+                eq_base += eq_tile;
             }
         }
-        const uint32_t eq_tile = total >> 16;
-        out_base += (total & 0xFFFFu) + (min(eq_base + eq_tile, keep_eq) - min(eq_base, keep_eq));
-        eq_base += eq_tile;
+    };
+    if (TILES > 0) {
+        uint32_t key[kBatch][4];
+#pragma unroll
+        for (int t0 = 0; t0 < kHeld; t0 += kBatch) {
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) key[b][u] = (t0 + b < kHeld) ? held[t0 + b < kHeld ? t0 + b : 0][u] : 0u;
+            emit_batch(t0, key, min(kBatch, ntiles - t0));
+        }
+    } else {
+        for (int t0 = 0; t0 < ntiles; t0 += kBatch) {
+            uint32_t key[kBatch][4];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) load_tile(scores, N, t0 + b, key[b]);
+            emit_batch(t0, key, min(kBatch, ntiles - t0));
+        }
     }
 }
 
 }  // namespace
 
 int select_topk_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s) {
-    select_topk_kernel<<<1, kThreads, 0, s>>>(scores, N, K, idx);
+    const size_t smem = (size_t)kBins * kCopies * sizeof(uint32_t);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return STRD_EHIP;
+        configured = true;
+    }
+    if (N <= 2 * kTile)
+        select_topk_kernel<2><<<1, kThreads, smem, s>>>(scores, N, K, idx);
+    else if (N <= 8 * kTile)
+        select_topk_kernel<8><<<1, kThreads, smem, s>>>(scores, N, K, idx);
+    else
+        select_topk_kernel<0><<<1, kThreads, smem, s>>>(scores, N, K, idx);
     return launch_status();
 }
 
