@@ -32,15 +32,15 @@ __device__ __forceinline__ int xcd_swizzle(int b, int n) {
 __host__ __forceinline__ int xcd_grid(int n) { return (n + kXcd - 1) / kXcd * kXcd; }
 
 // ---- asynchronous global -> LDS tile copy (no VGPR staging) ---------------------------------
-// A tile is ROWS rows of VR 16-byte vectors, stored in LDS with one pad vector per row (pitch
-// VR + 1 vectors, which keeps 16-byte row reads and transposing reads off each other's banks).
+// A tile is ROWS rows of VR 16-byte vectors, stored in LDS with PAD pad vectors per row (pitch
+// VR + PAD vectors, which keeps 16-byte row reads and transposing reads off each other's banks).
 // global_load_lds writes lane l of a wave to (uniform LDS base) + 16 * l, so the tile is filled
-// slot by slot: slot s = row * (VR + 1) + cv; pad slots (cv == VR) re-read the row's last vector.
+// slot by slot: slot s = row * (VR + PAD) + cv; pad slots (cv >= VR) re-read the row's last vector.
 // Slots are dealt to the NW waves of the workgroup 64 at a time; the tile's LDS footprint is
 // rounded up to whole 64-slot groups per wave (kBytes), the surplus slots re-read the last row.
-template <int ROWS, int VR, int NW>
+template <int ROWS, int VR, int NW, int PAD = 1>
 struct AsyncTile {
-    static constexpr int kVP = VR + 1;                                  // vectors per LDS row
+    static constexpr int kVP = VR + PAD;                                // vectors per LDS row
     static constexpr int kPitch = kVP * 8;                              // bf16 elements per LDS row
     static constexpr int kSlots = ROWS * kVP;
     static constexpr int kIssues = (kSlots + 64 * NW - 1) / (64 * NW);  // instructions per wave
@@ -98,6 +98,27 @@ __device__ __forceinline__ void lds_read_tr8(const void *p, strd_s16x4 (&r)[8]) 
 __device__ __forceinline__ strd_bf16x8 tr_pair(strd_s16x4 lo, strd_s16x4 hi) {
     return __builtin_shufflevector(__builtin_bit_cast(strd_bf16x4, lo), __builtin_bit_cast(strd_bf16x4, hi), 0, 1, 2, 3,
                                    4, 5, 6, 7);
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory,
+// which on gfx9 means waiting for every outstanding vector-memory operation of the wave -- all
+// the asynchronous copies requested steps ahead and every global store still in flight.  Here
+// the wave's own LDS reads and writes are drained (lgkmcnt) and the waves meet; copies are
+// waited for explicitly, by count, where their data is needed.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Inclusive prefix sum of a float over the 64 lanes of a wave with DPP moves (no LDS round trip).
+__device__ __forceinline__ float wave_inclusive_scan_f32(float v) {
+#define STRD_DPP_FADD(ctrl, row_mask) \
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, row_mask, 0xF, true))
+    STRD_DPP_FADD(0x111, 0xF);  // row_shr:1
+    STRD_DPP_FADD(0x112, 0xF);  // row_shr:2
+    STRD_DPP_FADD(0x114, 0xF);  // row_shr:4
+    STRD_DPP_FADD(0x118, 0xF);  // row_shr:8
+    STRD_DPP_FADD(0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+    STRD_DPP_FADD(0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+#undef STRD_DPP_FADD
+    return v;
 }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? STRD_OK : STRD_EHIP; }

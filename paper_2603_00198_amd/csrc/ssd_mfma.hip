@@ -17,12 +17,18 @@
 // their token-major LDS tiles with the transposing LDS read (ds_read_b64_tr_b16).
 //
 // Roles.  Waves 0-3 ("output waves") compute (a)-(d), wave w for tokens 16w..16w+15 of the
-// step.  Waves 4-7 ("state waves") each own a quarter of the state rows for (e), and between
-// them stage the next step's tiles global -> registers -> LDS, including the weighted copy
-// w_j x_j and the scan of dt*A.  The two roles share each SIMD, so the state waves' memory
-// latency hides behind the output waves' arithmetic.  LDS tiles and the bf16 state copy are
-// double-buffered: one workgroup barrier per step.  Rows past T are staged as copies of the
-// last row with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.
+// step; causality makes wave 3 do four times the (a)-(c) work of wave 0.  Waves 4-7 ("state
+// waves") own the state rows for (e) in the opposite proportion (3, 2, 2, 1 sixteenths-of-n
+// tiles when n = 128), because wave 4+i shares a SIMD with wave i.
+//
+// Memory.  Every input reaches LDS by asynchronous global -> LDS copies issued by waves 4 and 5,
+// far enough ahead to cover HBM latency with only one workgroup per CU: x three steps ahead
+// (ring of 4), dt seven steps ahead (ring of 8), the B and C tiles two steps ahead (ring of 3;
+// they are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 turns dt of the
+// next step into the scan l_t, dt_t and the state weights w_t one step ahead.  The bf16 state copy
+// is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the last row
+// with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.  Each wave runs a
+// straight-line specialisation (compile-time trip counts).
 #include "common.h"
 
 namespace strd {
@@ -30,51 +36,59 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 64;         // tokens per step
 constexpr int kPB = 32;        // channels of the head per workgroup
 constexpr int kThreads = 512;  // 4 output waves + 4 state waves
-constexpr int kStage = 256;    // threads that stage tiles (the state waves)
-constexpr int kXPitch = 48;    // bf16 elements per row of the x tiles (32 used)
 constexpr float kLog2e = 1.4426950408889634f;
+
+constexpr int kXRing = 4;   // x tiles in LDS (requested kXRing - 1 steps ahead)
+constexpr int kDtRing = 8;  // dt rows in LDS (requested kDtRing - 1 steps ahead)
 
 template <int NS>
 struct Lds {
-    static constexpr int kCP = NS + 16;  // bf16 elements per row of the B / C tiles
-    static constexpr int kSP = NS + 8;   // bf16 elements per row of the state copy
-    struct Buf {
-        bf16_t c[kQ][kCP];
-        bf16_t b[kQ][kCP];
-        bf16_t x[kQ][kXPitch];
-        bf16_t xw[kQ][kXPitch];  // w_j * x_j
-        float ell[kQ];           // inclusive cumulative sum of dt*A*log2(e) inside the step
-        float dtv[kQ];           // dt (0 past the end of the sequence)
+    using BC = AsyncTile<kQ, NS / 8, 2, 2>;   // B / C tile, filled by 2 waves, 2 pad vectors per row
+    using XT = AsyncTile<kQ, kPB / 8, 2, 2>;  // x tile of the slab
+    static constexpr int kCP = BC::kPitch;    // bf16 elements per row of the B / C tiles
+    static constexpr int kXP = XT::kPitch;    // bf16 elements per row of the x tiles
+    static constexpr int kSP = NS + 8;        // bf16 elements per row of the state copy
+    struct alignas(16) TileBC {
+        bf16_t c[BC::kBytes / 2];
+        bf16_t b[BC::kBytes / 2];
     };
-    Buf buf[2];
+    struct alignas(16) TileX {
+        bf16_t x[XT::kBytes / 2];
+    };
+    struct alignas(16) Meta {
+        float ell[kQ];  // inclusive cumulative sum of dt*A*log2(e) inside the step
+        float dtv[kQ];  // dt (0 past the end of the sequence)
+        float wv[kQ];   // dt_j * 2^(l_Q - l_j)
+    };
+    TileBC bc[3];
+    TileX xr[kXRing];
+    float dt[kDtRing][kQ];
+    Meta meta[2];
     bf16_t s[2][kPB][kSP];  // state before the step, [p][n]
 };
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-
-// Transposing LDS read.  Within each group of 16 lanes, lane r must pass the address of
-// element [k0 + r/4][c0 + 4*(r%4)] of a row-major bf16 tile; it receives [k0..k0+3][c0 + r].
-__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t *p) {
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
-    return __builtin_bit_cast(bf16x4, v);
-}
-
-__device__ __forceinline__ bf16x8 cat(bf16x4 lo, bf16x4 hi) {
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
-__device__ __forceinline__ uint4 ld16(const void *base, uint32_t byte_off) {
-    return *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(base) + byte_off);
+// The four token-contracted fragments of an x tile (pr = token half, pt = channel half).
+// Token slots of a fragment: s < 4 is token 32*pr + 4*lb + s, s >= 4 adds 16.
+template <int PITCH>
+__device__ __forceinline__ void read_x_frags(const bf16_t *xt, int lr, int lb, bf16x8 (&xf)[2][2]) {
+    constexpr int R = PITCH * 2;  // row pitch in bytes
+    strd_s16x4 r[8];
+    lds_read_tr8<0, 16 * R, 32, 16 * R + 32, 32 * R, 48 * R, 32 * R + 32, 48 * R + 32>(
+        xt + (4 * lb + (lr >> 2)) * PITCH + 4 * (lr & 3), r);
+    xf[0][0] = tr_pair(r[0], r[1]);
+    xf[0][1] = tr_pair(r[2], r[3]);
+    xf[1][0] = tr_pair(r[4], r[5]);
+    xf[1][1] = tr_pair(r[6], r[7]);
 }
 
 // Output wave W of a workgroup: steps (a)-(d) for tokens 16W..16W+15 of every step.
@@ -88,17 +102,32 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     const int tcol = 16 * W + lr;  // this lane's token inside the step
     bf16_t *yp = y + ((size_t)tcol * H + h) * P + p0 + 4 * lb;
     const size_t y_step = (size_t)kQ * H * P;
-    __syncthreads();  // pairs with the state waves' barrier after the first commit
+    __syncthreads();  // the two barriers of the state waves' prologue: copies landed,
+    __syncthreads();  // then the scan of step 0 is published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
-        typename L::Buf &bf = lds.buf[cur];
+        typename L::Meta &bf = lds.meta[cur];
+        typename L::TileBC &tb = lds.bc[step % 3];
+        const bf16_t *xt = lds.xr[step % kXRing].x;
         const float el_t = bf.ell[tcol];
 
         // c_t fragments: B operand of (a) and of (d)
         bf16x8 cf[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) cf[ks] = *reinterpret_cast<const bf16x8 *>(&bf.c[tcol][32 * ks + 8 * lb]);
+        for (int ks = 0; ks < KS; ++ks) cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
+
+        // (d) first: it only needs the state copy, so it overlaps the (a) -> (b) -> (c) chain
+        f32x4 yin[2];
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt) {
+            yin[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 sf = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
+                yin[pt] = mfma16(sf, cf[ks], yin[pt]);
+            }
+        }
 
         // (a): G^T tiles for key blocks jt <= W (independent accumulators)
         f32x4 acc[W + 1];
@@ -108,7 +137,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int jt = 0; jt <= W; ++jt) {
-                const bf16x8 bfr = *reinterpret_cast<const bf16x8 *>(&bf.b[16 * jt + lr][32 * ks + 8 * lb]);
+                const bf16x8 bfr = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
                 acc[jt] = mfma16(bfr, cf[ks], acc[jt]);
             }
         // (b): decay, dt and causal mask; pack pairs of key blocks as B operands of (c)
@@ -128,25 +157,18 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
             }
         }
 
-        // (c) intra-step part and (d) carried-state part of Y^T[p, t]
-        f32x4 yacc[2], yin[2];
+        // (c) intra-step part of Y^T[p, t]
+        bf16x8 xf[2][2];
+        read_x_frags<L::kXP>(xt, lr, lb, xf);
+        f32x4 yacc[2];
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             yacc[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            yin[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr)
-                if (2 * pr <= W) {
-                    // token slots of a fragment: s < 4 is token 32*pr + 4*lb + s, s >= 4 adds 16
-                    const bf16_t *a0 = &bf.x[32 * pr + 4 * lb + (lr >> 2)][16 * pt + 4 * (lr & 3)];
-                    const bf16x8 xf = cat(lds_read_tr(a0), lds_read_tr(a0 + 16 * kXPitch));
-                    yacc[pt] = mfma16(xf, cat(m4[2 * pr], m4[2 * pr + 1]), yacc[pt]);
-                }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 sf = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
-                yin[pt] = mfma16(sf, cf[ks], yin[pt]);
-            }
+                if (2 * pr <= W)
+                    yacc[pt] = mfma16(xf[pr][pt],
+                                      __builtin_shufflevector(m4[2 * pr], m4[2 * pr + 1], 0, 1, 2, 3, 4, 5, 6, 7), yacc[pt]);
         }
         const float carry = fast_exp2(el_t);
         if (step * kQ + tcol < T) {
@@ -154,7 +176,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
             for (int pt = 0; pt < 2; ++pt) {
                 bf16x4 out;
                 if (D) {
-                    const bf16x4 xv = *reinterpret_cast<const bf16x4 *>(&bf.x[tcol][16 * pt + 4 * lb]);
+                    const bf16x4 xv = *reinterpret_cast<const bf16x4 *>(&xt[tcol * L::kXP + 16 * pt + 4 * lb]);
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i] + Dh * (float)xv[i]);
@@ -166,7 +188,191 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
             }
         }
         yp += y_step;
-        __syncthreads();
+        lds_barrier();  // the y stores stay in flight
+    }
+}
+
+// State wave SW: owns NT 16-row tiles of the state starting at tile T0, stages x / dt (all
+// state waves) and issues the B / C tile copies (SW < 2).
+template <int NS, int SW>
+__device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
+                                           const float *__restrict__ A, const bf16_t *__restrict__ B,
+                                           const bf16_t *__restrict__ C, const float *__restrict__ S_in,
+                                           float *__restrict__ S_out, int T, int H, int P, int G, int h, int p0, int g,
+                                           int nsteps) {
+    using L = Lds<NS>;
+    using BC = typename L::BC;
+    // state tiles per wave, in the opposite proportion to the causal work of the output wave
+    // on the same SIMD (n = 128: 3, 2, 2, 1 of 8 tiles; n = 64: one tile each)
+    constexpr int NT = NS == 128 ? (SW == 0 ? 3 : SW == 3 ? 1 : 2) : 1;
+    constexpr int T0 = NS == 128 ? (SW == 0 ? 0 : SW == 1 ? 3 : SW == 2 ? 5 : 7) : SW;
+    using XT = typename L::XT;
+    const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
+    const float Al2 = A[h] * kLog2e;
+
+    // ---- asynchronous copies (waves SW < 2): byte offsets at the next step to request, per-step
+    // strides and end-of-sequence clamps (rows past T re-read the last row)
+    const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
+    uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues], off_x[XT::kIssues], lim_x[XT::kIssues];
+    uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
+    const uint32_t lim_dt = (uint32_t)(T - 1) * dt_row + (uint32_t)h * 4;
+    if (SW < 2) {
+#pragma unroll
+        for (int i = 0; i < BC::kIssues; ++i) {
+            int r, cv;
+            BC::slot(SW, lane, i, r, cv);
+            const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
+            off_bc[i] = (uint32_t)r * bc_row + col;
+            lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
+        }
+#pragma unroll
+        for (int i = 0; i < XT::kIssues; ++i) {
+            int r, cv;
+            XT::slot(SW, lane, i, r, cv);
+            const uint32_t col = ((uint32_t)h * P + p0 + cv * 8) * 2;
+            off_x[i] = (uint32_t)r * x_row + col;
+            lim_x[i] = (uint32_t)(T - 1) * x_row + col;
+        }
+    }
+    // each call requests the next not yet requested step of its stream into ring slot b
+    auto request_bc = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < BC::kIssues; ++i) {
+            const uint32_t o = min(off_bc[i], lim_bc[i]);
+            BC::issue(reinterpret_cast<const char *>(C) + o, lds.bc[b].c, SW, i);
+            BC::issue(reinterpret_cast<const char *>(B) + o, lds.bc[b].b, SW, i);
+            off_bc[i] += kQ * bc_row;
+        }
+    };
+    auto request_x = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < XT::kIssues; ++i) {
+            XT::issue(reinterpret_cast<const char *>(x) + min(off_x[i], lim_x[i]), lds.xr[b].x, SW, i);
+            off_x[i] += kQ * x_row;
+        }
+    };
+    auto request_dt = [&](int b) {  // wave SW == 0 only: 64 lanes x 4 bytes
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + min(off_dt, lim_dt)),
+            (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
+        off_dt += kQ * dt_row;
+    };
+    // copies issued per step by this wave; everything older has landed once at most that many are
+    // outstanding (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
+    // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+    constexpr int kNewest = SW < 2 ? 2 * BC::kIssues + XT::kIssues + (SW == 0 ? 1 : 0) : 0;
+    static_assert(kNewest < 64, "vmcnt has 6 bits");
+    constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
+
+    // scan of dt*A of `step` from the dt ring into meta[step & 1] (wave SW == 3: lane = token)
+    auto make_meta = [&](int step) {
+        const float raw = lds.dt[step % kDtRing][lane];
+        const float dv = (step * kQ + lane < T) ? raw : 0.f;
+        const float inc = wave_inclusive_scan_f32(dv * Al2);
+        const float lq = __shfl(inc, kWave - 1, kWave);
+        typename L::Meta &m = lds.meta[step & 1];
+        m.ell[lane] = inc;
+        m.dtv[lane] = dv;
+        m.wv[lane] = dv * fast_exp2(lq - inc);
+    };
+
+    // state: fp32 master in registers ([n rows][p cols] tiles), bf16 copy in LDS
+    f32x4 sacc[NT][2];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt) {
+            const int n0 = (T0 + nt) * 16 + lb * 4, pp = pt * 16 + lr;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (S_in) v = *reinterpret_cast<const f32x4 *>(S_in + ((size_t)h * P + p0 + pp) * NS + n0);
+            sacc[nt][pt] = v;
+            bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+            *reinterpret_cast<bf16x4 *>(&lds.s[0][pp][n0]) = sv;
+        }
+    // prologue: fill the rings up to their look-ahead, then the meta data of step 0
+    if (SW < 2) {
+#pragma unroll
+        for (int i = 0; i < kXRing - 1; ++i) request_x(i);
+        if (SW == 0) {
+#pragma unroll
+            for (int i = 0; i < kDtRing - 1; ++i) request_dt(i);
+        }
+        request_bc(0);
+        request_bc(1);
+        async_tile_wait();
+    }
+    __syncthreads();
+    if (SW == 3) make_meta(0);
+    __syncthreads();
+
+    for (int step = 0; step < nsteps; ++step) {
+        const int cur = step & 1;
+        typename L::Meta &bf = lds.meta[cur];
+        typename L::TileBC &tb = lds.bc[step % 3];
+        if (SW < 2) {  // every target slot was last read in step - 1
+            request_x((step + kXRing - 1) % kXRing);
+            if (SW == 0) request_dt((step + kDtRing - 1) % kDtRing);
+            request_bc((step + 2) % 3);
+        }
+        if (SW == 3) make_meta(step + 1);  // dt of step + 1 landed at least one barrier ago
+
+        // (e) for the rows this wave owns: weight the x fragments by w_j, then S^T += b^T (w x)
+        const float decay_q = fast_exp2(bf.ell[kQ - 1]);
+        bf16x8 xf[2][2];
+        read_x_frags<L::kXP>(lds.xr[step % kXRing].x, lr, lb, xf);
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+            const f32x4 w_lo = *reinterpret_cast<const f32x4 *>(&bf.wv[32 * pr + 4 * lb]);
+            const f32x4 w_hi = *reinterpret_cast<const f32x4 *>(&bf.wv[32 * pr + 16 + 4 * lb]);
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xf[pr][pt][i] = (bf16_t)((float)xf[pr][pt][i] * w_lo[i]);
+                    xf[pr][pt][4 + i] = (bf16_t)((float)xf[pr][pt][4 + i] * w_hi[i]);
+                }
+        }
+#pragma unroll
+        for (int n2 = 0; n2 < NT; n2 += 2) {
+            // b^T fragments of two state tiles: [tile][token half], second tile only if owned
+            constexpr int R = L::kCP * 2;
+            strd_s16x4 r[8];
+            lds_read_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
+                &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], r);
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                if (n2 + d < NT) {
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt) sacc[n2 + d][pt] *= decay_q;
+#pragma unroll
+                    for (int pr = 0; pr < 2; ++pr) {
+                        const bf16x8 bt = tr_pair(r[4 * d + 2 * pr], r[4 * d + 2 * pr + 1]);
+#pragma unroll
+                        for (int pt = 0; pt < 2; ++pt) sacc[n2 + d][pt] = mfma16(bt, xf[pr][pt], sacc[n2 + d][pt]);
+                    }
+                }
+            }
+        }
+        // publish the new state copy
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt) {
+                const f32x4 v = sacc[nt][pt];
+                bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                *reinterpret_cast<bf16x4 *>(&lds.s[cur ^ 1][pt * 16 + lr][(T0 + nt) * 16 + lb * 4]) = sv;
+            }
+        if (SW < 2) __builtin_amdgcn_s_waitcnt(kWaitOlder);  // all copies issued in earlier steps have landed
+        lds_barrier();  // this step's copies stay in flight
+    }
+
+    if (S_out) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+                *reinterpret_cast<f32x4 *>(S_out + ((size_t)h * P + p0 + pt * 16 + lr) * NS + (T0 + nt) * 16 + lb * 4) =
+                    sacc[nt][pt];
     }
 }
 
@@ -176,10 +382,6 @@ __global__ __launch_bounds__(kThreads) void ssd_mfma_kernel(
     const bf16_t *__restrict__ B, const bf16_t *__restrict__ C, const float *__restrict__ D,
     const float *__restrict__ S_in, bf16_t *__restrict__ y, float *__restrict__ S_out, int T, int H, int P, int G,
     int nunits) {
-    constexpr int KS = NS / 32;            // k-steps over the state dimension
-    constexpr int NT = NS / 64;            // 16-row state tiles owned by one state wave
-    constexpr int VR = NS / 8;             // 16-byte vectors per B / C row
-    constexpr int VPT = kQ * VR / kStage;  // B (or C) vectors staged per staging thread
     using L = Lds<NS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     L &lds = *reinterpret_cast<L *>(smem_raw);
@@ -188,166 +390,16 @@ __global__ __launch_bounds__(kThreads) void ssd_mfma_kernel(
     if (unit >= nunits) return;
     const int nslab = P / kPB;
     const int h = unit / nslab, p0 = (unit % nslab) * kPB, g = h / (H / G);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lr = lane & 15, lb = lane >> 4;
     const int nsteps = (T + kQ - 1) / kQ;
-
-    if (w >= 4) {
-        // =========================== state waves ===========================================
-        const int sw = w - 4, st = tid - kStage;
-        const int nbase = sw * (NS / 4);  // first state row of this wave
-        const float Al2 = A[h] * kLog2e;
-
-        // byte offsets of this thread's staging vectors at step 0, their per-step stride and
-        // their value at the last row of the sequence (rows past T re-read that row)
-        const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
-        uint32_t off_bc[VPT], lim_bc[VPT];
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int v = st + i * kStage, r = v / VR, cv = v % VR;
-            const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
-            off_bc[i] = (uint32_t)r * bc_row + col;
-            lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
-        }
-        const uint32_t x_col = ((uint32_t)h * P + p0 + (st & 3) * 8) * 2;
-        uint32_t off_x = (uint32_t)(st >> 2) * x_row + x_col;
-        const uint32_t lim_x = (uint32_t)(T - 1) * x_row + x_col;
-        uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
-        const uint32_t lim_dt = (uint32_t)(T - 1) * dt_row + (uint32_t)h * 4;
-
-        // two register sets: a step's tiles are requested two steps before they are needed
-        struct Regs {
-            uint4 pc[VPT], pb[VPT], px;
-            float pdt;
-        };
-        auto prefetch = [&](Regs &rg, int step) {
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                const uint32_t o = min(off_bc[i], lim_bc[i]);
-                rg.pc[i] = ld16(C, o);
-                rg.pb[i] = ld16(B, o);
-                off_bc[i] += kQ * bc_row;
-            }
-            rg.px = ld16(x, min(off_x, lim_x));
-            off_x += kQ * x_row;
-            const float dv = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(dt) + min(off_dt, lim_dt));
-            rg.pdt = (step * kQ + lane < T) ? dv : 0.f;
-            off_dt += kQ * dt_row;
-        };
-        auto commit = [&](const Regs &rg, int b) {
-            typename L::Buf &bf = lds.buf[b];
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                const int v = st + i * kStage, r = v / VR, cv = v % VR;
-                *reinterpret_cast<uint4 *>(&bf.c[r][cv * 8]) = rg.pc[i];
-                *reinterpret_cast<uint4 *>(&bf.b[r][cv * 8]) = rg.pb[i];
-            }
-            // scan of dt*A over the step (every state wave does it: lane = token)
-            float inc = rg.pdt * Al2;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const float up = __shfl_up(inc, o, kWave);
-                if (lane >= o) inc += up;
-            }
-            const float lq = __shfl(inc, kWave - 1, kWave);
-            const float wv = rg.pdt * fast_exp2(lq - inc);
-            if (sw == 0) {
-                bf.ell[lane] = inc;
-                bf.dtv[lane] = rg.pdt;
-            }
-            // x tile and its weighted copy; this thread holds 8 channels of row st / 4
-            const float wrow = __shfl(wv, 16 * sw + (lane >> 2), kWave);
-            const bf16x8 xv = __builtin_bit_cast(bf16x8, rg.px);
-            bf16x8 xs;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[e] * wrow);
-            *reinterpret_cast<uint4 *>(&bf.x[st >> 2][(st & 3) * 8]) = rg.px;
-            *reinterpret_cast<bf16x8 *>(&bf.xw[st >> 2][(st & 3) * 8]) = xs;
-        };
-        Regs ra, rb;
-
-        // state: fp32 master in registers ([n rows][p cols] tiles), bf16 copy in LDS
-        f32x4 sacc[NT][2];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt) {
-                const int n0 = nbase + nt * 16 + lb * 4, pp = pt * 16 + lr;
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (S_in) v = *reinterpret_cast<const f32x4 *>(S_in + ((size_t)h * P + p0 + pp) * NS + n0);
-                sacc[nt][pt] = v;
-                bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-                *reinterpret_cast<bf16x4 *>(&lds.s[0][pp][n0]) = sv;
-            }
-        // prefetches past the end re-read the last row (offsets are clamped) and are never
-        // consumed, so the loop body has no conditional loads or LDS writes
-        prefetch(ra, 0);
-        commit(ra, 0);
-        prefetch(ra, 1);
-        __syncthreads();
-
-        // one step; `held` carries the tiles of step + 1, `next` receives those of step + 2
-        auto do_step = [&](int step, Regs &held, Regs &next) {
-            const int cur = step & 1;
-            typename L::Buf &bf = lds.buf[cur];
-            prefetch(next, step + 2);
-
-            // (e): token slots of a fragment: s < 4 is token 32*pr + 4*lb + s, s >= 4 adds 16
-            const float decay_q = fast_exp2(bf.ell[kQ - 1]);
-            bf16x8 xf[2][2];
-#pragma unroll
-            for (int pr = 0; pr < 2; ++pr)
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt) {
-                    const bf16_t *a0 = &bf.xw[32 * pr + 4 * lb + (lr >> 2)][16 * pt + 4 * (lr & 3)];
-                    xf[pr][pt] = cat(lds_read_tr(a0), lds_read_tr(a0 + 16 * kXPitch));
-                }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] *= decay_q;
-#pragma unroll
-                for (int pr = 0; pr < 2; ++pr) {
-                    const bf16_t *a0 = &bf.b[32 * pr + 4 * lb + (lr >> 2)][nbase + 16 * nt + 4 * (lr & 3)];
-                    const bf16x8 bt = cat(lds_read_tr(a0), lds_read_tr(a0 + 16 * L::kCP));
-#pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] = mfma16(bt, xf[pr][pt], sacc[nt][pt]);
-                }
-            }
-            // publish the new state copy and the next step's tiles into the other buffers
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt) {
-                    const f32x4 v = sacc[nt][pt];
-                    bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-                    *reinterpret_cast<bf16x4 *>(&lds.s[cur ^ 1][pt * 16 + lr][nbase + nt * 16 + lb * 4]) = sv;
-                }
-            commit(held, cur ^ 1);
-            __syncthreads();
-        };
-        for (int step = 0; step < nsteps; step += 2) {
-            do_step(step, ra, rb);
-            if (step + 1 < nsteps) do_step(step + 1, rb, ra);
-        }
-
-        if (S_out) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
-                    *reinterpret_cast<f32x4 *>(S_out + ((size_t)h * P + p0 + pt * 16 + lr) * NS + nbase + nt * 16 +
-                                               lb * 4) = sacc[nt][pt];
-        }
-    } else {
-        // =========================== output waves ==========================================
-        // one straight-line specialisation per wave, so that the causal trip counts are
-        // compile-time constants and the independent MFMA chains can be interleaved
-        switch (w) {
-            case 0: output_wave<NS, 0>(lds, D, y, T, H, P, h, p0, nsteps); break;
-            case 1: output_wave<NS, 1>(lds, D, y, T, H, P, h, p0, nsteps); break;
-            case 2: output_wave<NS, 2>(lds, D, y, T, H, P, h, p0, nsteps); break;
-            default: output_wave<NS, 3>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        }
+    switch (threadIdx.x >> 6) {
+        case 0: output_wave<NS, 0>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 1: output_wave<NS, 1>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 2: output_wave<NS, 2>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 3: output_wave<NS, 3>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 4: state_wave<NS, 0>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
+        case 5: state_wave<NS, 1>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
+        case 6: state_wave<NS, 2>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
+        default: state_wave<NS, 3>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
     }
 }
 
@@ -375,8 +427,8 @@ bool ssd_mfma_supported(int T, int H, int P, int G, int n, strd_dtype io) {
     // staging uses 32-bit byte offsets from the tensor bases
     const unsigned long long lim = 1ull << 32;
     return io == STRD_BF16 && T >= 1 && (n == 64 || n == 128) && P % kPB == 0 &&
-           (long long)H * (P / kPB) < (1 << 24) && (unsigned long long)(T + kQ) * H * P * 2 < lim &&
-           (unsigned long long)(T + kQ) * G * n * 2 < lim && (unsigned long long)(T + kQ) * H * 4 < lim;
+           (long long)H * (P / kPB) < (1 << 24) && (unsigned long long)(T + 2 * kQ) * H * P * 2 < lim &&
+           (unsigned long long)(T + 2 * kQ) * G * n * 2 < lim && (unsigned long long)(T + 2 * kQ) * H * 4 < lim;
 }
 
 int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
