@@ -21,11 +21,12 @@
 // waves") own the state rows for (e) in the opposite proportion (3, 2, 2, 1 sixteenths-of-n
 // tiles when n = 128), because wave 4+i shares a SIMD with wave i.
 //
-// Memory.  Every input reaches LDS by asynchronous global -> LDS copies issued by waves 4 and 5,
-// far enough ahead to cover HBM latency with only one workgroup per CU: x three steps ahead
-// (ring of 4), dt seven steps ahead (ring of 8), the B and C tiles two steps ahead (ring of 3;
-// they are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 turns dt of the
-// next step into the scan l_t, dt_t and the state weights w_t one step ahead.  The bf16 state copy
+// Memory.  Every input reaches LDS by asynchronous global -> LDS copies (B and C: waves 4 and 5;
+// x and dt: wave 7), far enough ahead to cover HBM latency with only one workgroup per CU: x three steps ahead
+// (ring of 4), dt three steps ahead (ring of 4), the B and C tiles two steps ahead (ring of 3;
+// they are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 (the lightest)
+// turns dt of the next step into the scan l_t, the key factors of (b) and the weighted copy
+// w_j x_j one step ahead.  The bf16 state copy
 // is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the last row
 // with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.  Each wave runs a
 // straight-line specialisation (compile-time trip counts).
@@ -44,12 +45,12 @@ constexpr int kThreads = 512;  // 4 output waves + 4 state waves
 constexpr float kLog2e = 1.4426950408889634f;
 
 constexpr int kXRing = 4;   // x tiles in LDS (requested kXRing - 1 steps ahead)
-constexpr int kDtRing = 8;  // dt rows in LDS (requested kDtRing - 1 steps ahead)
+constexpr int kDtRing = 4;  // dt rows in LDS (requested kDtRing - 1 steps ahead)
 
 template <int NS>
 struct Lds {
     using BC = AsyncTile<kQ, NS / 8, 2, 2>;   // B / C tile, filled by 2 waves, 2 pad vectors per row
-    using XT = AsyncTile<kQ, kPB / 8, 2, 2>;  // x tile of the slab
+    using XT = AsyncTile<kQ, kPB / 8, 1, 1>;  // x tile of the slab, filled by one wave, 1 pad vector per row
     static constexpr int kCP = BC::kPitch;    // bf16 elements per row of the B / C tiles
     static constexpr int kXP = XT::kPitch;    // bf16 elements per row of the x tiles
     static constexpr int kSP = NS + 8;        // bf16 elements per row of the state copy
@@ -61,9 +62,10 @@ struct Lds {
         bf16_t x[XT::kBytes / 2];
     };
     struct alignas(16) Meta {
-        float ell[kQ];  // inclusive cumulative sum of dt*A*log2(e) inside the step
-        float dtv[kQ];  // dt (0 past the end of the sequence)
-        float wv[kQ];   // dt_j * 2^(l_Q - l_j)
+        float ell[kQ];      // inclusive cumulative sum of dt*A*log2(e) inside the step
+        float dtv[kQ];      // dt (0 past the end of the sequence)
+        float fw[3][kQ];    // fw[W-1][j] = dt_j * 2^(l_{16W-1} - l_j), j < 16W: key factor for query block W
+        bf16_t xw[kQ][kPB + 8];   // w_j * x_j, w_j = dt_j * 2^(l_Q - l_j): B operand of the state update
     };
     TileBC bc[3];
     TileX xr[kXRing];
@@ -71,6 +73,8 @@ struct Lds {
     Meta meta[2];
     bf16_t s[2][kPB][kSP];  // state before the step, [p][n]
 };
+
+static_assert(sizeof(Lds<128>) <= 160 * 1024, "one workgroup must fit the 160 KB of LDS of a CU");
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -102,8 +106,8 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     const int tcol = 16 * W + lr;  // this lane's token inside the step
     bf16_t *yp = y + ((size_t)tcol * H + h) * P + p0 + 4 * lb;
     const size_t y_step = (size_t)kQ * H * P;
-    __syncthreads();  // the two barriers of the state waves' prologue: copies landed,
-    __syncthreads();  // then the scan of step 0 is published
+    __syncthreads();  // the two barriers of the state waves' prologue: first copies landed,
+    __syncthreads();  // scan of step 0 published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
@@ -140,19 +144,25 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
                 const bf16x8 bfr = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
                 acc[jt] = mfma16(bfr, cf[ks], acc[jt]);
             }
-        // (b): decay, dt and causal mask; pack pairs of key blocks as B operands of (c)
+        // (b): decay, dt and causal mask; pack pairs of key blocks as B operands of (c).
+        // Blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan
+        // at the last token before this wave's block (both exponents <= 0); diagonal block: direct.
         bf16x4 m4[4];
+        const float e_ref = W > 0 ? fast_exp2(el_t - bf.ell[W > 0 ? 16 * W - 1 : 0]) : 0.f;
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
             m4[jt] = bf16x4{(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
-            if (jt <= W) {
+            if (jt < W) {
+                const f32x4 f_j = *reinterpret_cast<const f32x4 *>(&bf.fw[W > 0 ? W - 1 : 0][16 * jt + 4 * lb]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) m4[jt][i] = (bf16_t)(acc[jt < W ? jt : W][i] * e_ref * f_j[i]);
+            } else if (jt == W) {
                 const f32x4 el_j = *reinterpret_cast<const f32x4 *>(&bf.ell[16 * jt + 4 * lb]);
                 const f32x4 dt_j = *reinterpret_cast<const f32x4 *>(&bf.dtv[16 * jt + 4 * lb]);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float val = acc[jt < W ? jt : W][i] * fast_exp2(el_t - el_j[i]) * dt_j[i];
-                    // only the diagonal block needs the causal mask
-                    m4[jt][i] = (bf16_t)((jt < W || 4 * lb + i <= lr) ? val : 0.f);
+                    const float val = acc[W][i] * fast_exp2(el_t - el_j[i]) * dt_j[i];
+                    m4[jt][i] = (bf16_t)((4 * lb + i <= lr) ? val : 0.f);  // causal mask
                 }
             }
         }
@@ -210,8 +220,9 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
     const float Al2 = A[h] * kLog2e;
 
-    // ---- asynchronous copies (waves SW < 2): byte offsets at the next step to request, per-step
-    // strides and end-of-sequence clamps (rows past T re-read the last row)
+    // ---- asynchronous copies: waves SW < 2 fetch the B / C tiles, wave SW == 3 fetches x and dt
+    // (it is their first consumer).  Byte offsets at the next step to request, per-step strides
+    // and end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes them inert).
     const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
     uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues], off_x[XT::kIssues], lim_x[XT::kIssues];
     uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
@@ -225,10 +236,12 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
             off_bc[i] = (uint32_t)r * bc_row + col;
             lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
         }
+    }
+    if (SW == 3) {
 #pragma unroll
         for (int i = 0; i < XT::kIssues; ++i) {
             int r, cv;
-            XT::slot(SW, lane, i, r, cv);
+            XT::slot(0, lane, i, r, cv);
             const uint32_t col = ((uint32_t)h * P + p0 + cv * 8) * 2;
             off_x[i] = (uint32_t)r * x_row + col;
             lim_x[i] = (uint32_t)(T - 1) * x_row + col;
@@ -247,20 +260,21 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     auto request_x = [&](int b) {
 #pragma unroll
         for (int i = 0; i < XT::kIssues; ++i) {
-            XT::issue(reinterpret_cast<const char *>(x) + min(off_x[i], lim_x[i]), lds.xr[b].x, SW, i);
+            XT::issue(reinterpret_cast<const char *>(x) + min(off_x[i], lim_x[i]), lds.xr[b].x, 0, i);
             off_x[i] += kQ * x_row;
         }
     };
-    auto request_dt = [&](int b) {  // wave SW == 0 only: 64 lanes x 4 bytes
+    auto request_dt = [&](int b) {  // 64 lanes x 4 bytes
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + min(off_dt, lim_dt)),
             (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
         off_dt += kQ * dt_row;
     };
-    // copies issued per step by this wave; everything older has landed once at most that many are
+    // Copies a wave issues per step; everything older has landed once at most that many are
     // outstanding (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
     // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-    constexpr int kNewest = SW < 2 ? 2 * BC::kIssues + XT::kIssues + (SW == 0 ? 1 : 0) : 0;
+    // (wave 3 consumes x one step before the others, so it lets two steps' worth stay in flight)
+    constexpr int kNewest = SW < 2 ? 2 * BC::kIssues : SW == 3 ? 2 * (XT::kIssues + 1) : 0;
     static_assert(kNewest < 64, "vmcnt has 6 bits");
     constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
 
@@ -273,7 +287,22 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
         typename L::Meta &m = lds.meta[step & 1];
         m.ell[lane] = inc;
         m.dtv[lane] = dv;
-        m.wv[lane] = dv * fast_exp2(lq - inc);
+#pragma unroll
+        for (int wq = 1; wq < 4; ++wq) {  // only tokens j < 16 * wq are read; the exponent is <= 0 for them
+            const float lref = __shfl(inc, 16 * wq - 1, kWave);
+            m.fw[wq - 1][lane] = dv * fast_exp2(fminf(lref - inc, 0.f));
+        }
+        // weighted copy of the x row of this lane's token
+        const float wv = dv * fast_exp2(lq - inc);
+        const bf16_t *xrow = lds.xr[step % kXRing].x + lane * L::kXP;
+#pragma unroll
+        for (int c = 0; c < kPB; c += 8) {
+            const bf16x8 xv = *reinterpret_cast<const bf16x8 *>(xrow + c);
+            bf16x8 xs;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[e] * wv);
+            *reinterpret_cast<bf16x8 *>(&m.xw[lane][c]) = xs;
+        }
     };
 
     // state: fp32 master in registers ([n rows][p cols] tiles), bf16 copy in LDS
@@ -291,14 +320,15 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
         }
     // prologue: fill the rings up to their look-ahead, then the meta data of step 0
     if (SW < 2) {
-#pragma unroll
-        for (int i = 0; i < kXRing - 1; ++i) request_x(i);
-        if (SW == 0) {
-#pragma unroll
-            for (int i = 0; i < kDtRing - 1; ++i) request_dt(i);
-        }
         request_bc(0);
         request_bc(1);
+        async_tile_wait();
+    }
+    if (SW == 3) {
+#pragma unroll
+        for (int i = 0; i < kXRing - 1; ++i) request_x(i);
+#pragma unroll
+        for (int i = 0; i < kDtRing - 1; ++i) request_dt(i);
         async_tile_wait();
     }
     __syncthreads();
@@ -309,29 +339,16 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
         const int cur = step & 1;
         typename L::Meta &bf = lds.meta[cur];
         typename L::TileBC &tb = lds.bc[step % 3];
-        if (SW < 2) {  // every target slot was last read in step - 1
-            request_x((step + kXRing - 1) % kXRing);
-            if (SW == 0) request_dt((step + kDtRing - 1) % kDtRing);
-            request_bc((step + 2) % 3);
+        if (SW < 2) request_bc((step + 2) % 3);  // that slot was last read in step - 1
+        if (SW == 3) {
+            request_x((step + kXRing - 1) % kXRing);  // slot last read in step - 1
+            request_dt((step + kDtRing - 1) % kDtRing);
         }
-        if (SW == 3) make_meta(step + 1);  // dt of step + 1 landed at least one barrier ago
 
-        // (e) for the rows this wave owns: weight the x fragments by w_j, then S^T += b^T (w x)
+        // (e) for the rows this wave owns: S^T = 2^(l_Q) S^T + b^T (w x)
         const float decay_q = fast_exp2(bf.ell[kQ - 1]);
         bf16x8 xf[2][2];
-        read_x_frags<L::kXP>(lds.xr[step % kXRing].x, lr, lb, xf);
-#pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-            const f32x4 w_lo = *reinterpret_cast<const f32x4 *>(&bf.wv[32 * pr + 4 * lb]);
-            const f32x4 w_hi = *reinterpret_cast<const f32x4 *>(&bf.wv[32 * pr + 16 + 4 * lb]);
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    xf[pr][pt][i] = (bf16_t)((float)xf[pr][pt][i] * w_lo[i]);
-                    xf[pr][pt][4 + i] = (bf16_t)((float)xf[pr][pt][4 + i] * w_hi[i]);
-                }
-        }
+        read_x_frags<kPB + 8>(&bf.xw[0][0], lr, lb, xf);
 #pragma unroll
         for (int n2 = 0; n2 < NT; n2 += 2) {
             // b^T fragments of two state tiles: [tile][token half], second tile only if owned
@@ -362,7 +379,11 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
                 bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                 *reinterpret_cast<bf16x4 *>(&lds.s[cur ^ 1][pt * 16 + lr][(T0 + nt) * 16 + lb * 4]) = sv;
             }
-        if (SW < 2) __builtin_amdgcn_s_waitcnt(kWaitOlder);  // all copies issued in earlier steps have landed
+        if (SW < 2) __builtin_amdgcn_s_waitcnt(kWaitOlder);  // the B / C copies issued in earlier steps have landed
+        if (SW == 3) {
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);  // x and dt of step + 1 (requested in earlier steps) have landed
+            make_meta(step + 1);                     // last thing in the step: the copy had two steps to arrive
+        }
         lds_barrier();  // this step's copies stay in flight
     }
 
