@@ -1,0 +1,158 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: whatever the
+fp64 oracle can afford is compared in full (scores, indices, gathers), the mixers on sampled
+heads / query rows computed one by one, plus properties that hold at any size.  Needs a GPU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_00198_amd as strd
+from paper_2603_00198_amd import synth
+from util import TOL, assert_close, assert_topk_equivalent
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+f = synth.np64
+TOLB = TOL[torch.bfloat16]
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _reduced_mamba(w, t, hidden):
+    N, M, K = w.N, w.M, w.K
+    s = strd.score_mamba(t["B"][:N].contiguous(), t["C"][N:].contiguous(), t["dt"][:N].contiguous())
+    idx = strd.select_topk(s, K)
+    keys = ("x", "B", "C", "dt")
+    outs, pos = strd.compact_batch([t[k] for k in keys] + [hidden], idx, N, M, want_pos=True)
+    red = dict(zip(keys + ("hidden",), outs))
+    y, S = strd.ssd_prefill(red["x"], red["dt"], t["A"], red["B"], red["C"], chunk=w.mamba.chunk)
+    return s, idx, pos, red, y, S
+
+
+def _check_ssd_heads(x, dt, A, B, C, y, S, heads, G, what):
+    """Oracle recurrence for a few heads at full length."""
+    H = x.shape[1]
+    hpg = H // G
+    for h in heads:
+        g = h // hpg
+        y_ref, S_ref = oracle.ssd_seq(f(x[:, h:h + 1]), f(dt[:, h:h + 1]), f(A[h:h + 1]), f(B[:, g:g + 1]),
+                                      f(C[:, g:g + 1]))
+        assert_close(f(y[:, h:h + 1]), y_ref, TOLB, "%s y head %d" % (what, h))
+        if S is not None:
+            assert_close(f(S[h:h + 1]), S_ref, TOLB, "%s state head %d" % (what, h))
+
+
+def test_c2_reduced_mamba_layer_full_size():
+    w = synth.WORKLOADS["c2"]
+    _say("c2 full size: N=%d M=%d K=%d" % (w.N, w.M, w.K))
+    hidden = synth.hidden_states(w, DEV)
+    t = synth.mamba_inputs(w, hidden)
+    hb = hidden.to(torch.bfloat16)
+    N, M, K = w.N, w.M, w.K
+    s, idx, pos, red, y, S = _reduced_mamba(w, t, hb)
+    s_ref = oracle.score_mamba(f(t["B"][:N]), f(t["C"][N:]), f(t["dt"][:N]))
+    assert_close(s.cpu().numpy(), s_ref, TOLB, "scores")
+    swaps = assert_topk_equivalent(idx.cpu().numpy(), s_ref, K, TOLB)
+    _say("near-tie swaps vs oracle: %d of %d" % (swaps, K))
+    # select on the oracle's exact scores (rounded to fp32) is bit-exact
+    s32 = torch.from_numpy(s_ref.astype(np.float32)).to(DEV)
+    np.testing.assert_array_equal(strd.select_topk(s32, K).cpu().numpy(),
+                                  oracle.select_topk(s_ref.astype(np.float32).astype(np.float64), K))
+    i_np = idx.cpu().numpy()
+    for k in ("x", "B", "C", "hidden"):
+        src = (hb if k == "hidden" else t[k]).view(torch.int16).cpu().numpy()
+        np.testing.assert_array_equal(red[k].view(torch.int16).cpu().numpy(), oracle.compact(src, i_np, N, M)[0])
+    np.testing.assert_array_equal(red["dt"].cpu().numpy(), oracle.compact(t["dt"].cpu().numpy(), i_np, N, M)[0])
+    np.testing.assert_array_equal(pos.cpu().numpy(), np.concatenate([i_np, np.arange(N, N + M)]))
+    heads = [0, 17, 34, 51, 68, 85, 102, 127]       # one per group
+    _check_ssd_heads(red["x"], red["dt"], t["A"], red["B"], red["C"], y, S, heads, w.mamba.G, "reduced")
+    # the unreduced layer (the denominator of the speed-up) on two heads
+    y_full, S_full = strd.ssd_prefill(t["x"], t["dt"], t["A"], t["B"], t["C"], chunk=w.mamba.chunk)
+    _check_ssd_heads(t["x"], t["dt"], t["A"], t["B"], t["C"], y_full, S_full, [5, 120], w.mamba.G, "full")
+    assert torch.isfinite(y_full.float()).all()
+
+
+def test_c3_reduced_attention_layer_full_size():
+    w = synth.WORKLOADS["c3"]
+    _say("c3 full size: N=%d M=%d K=%d" % (w.N, w.M, w.K))
+    hidden = synth.hidden_states(w, DEV)
+    t = synth.attn_inputs(w, hidden)
+    N, M, K = w.N, w.M, w.K
+    s = strd.score_attn(t["q"][N:].contiguous(), t["k"][:N].contiguous())
+    idx = strd.select_topk(s, K)
+    (qs, ks, vs), _ = strd.compact_batch([t["q"], t["k"], t["v"]], idx, N, M)
+    o = strd.attn_prefill(qs, ks, vs)
+    assert abs(float(s.double().sum()) - 1.0) < 1e-3 and float(s.min()) >= 0.0
+    _say("oracle scores (about 70 G multiply-adds in fp64) ...")
+    s_ref = oracle.score_attn(f(t["q"][N:]), f(t["k"][:N]))
+    assert_close(s.cpu().numpy(), s_ref, TOLB, "scores")
+    swaps = assert_topk_equivalent(idx.cpu().numpy(), s_ref, K, TOLB)
+    _say("near-tie swaps vs oracle: %d of %d" % (swaps, K))
+    i_np = idx.cpu().numpy()
+    np.testing.assert_array_equal(ks.view(torch.int16).cpu().numpy(),
+                                  oracle.compact(t["k"].view(torch.int16).cpu().numpy(), i_np, N, M)[0])
+    Tr = K + M
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, 129, Tr - 1, Tr - 2, K - 1, K, K + 1],
+                                     np.random.default_rng(0).integers(0, Tr, 10)])).astype(np.int32)
+    o_ref = oracle.attn(f(qs), f(ks), f(vs), rows=rows)
+    assert_close(f(o[torch.from_numpy(rows).long().to(DEV)]), o_ref, TOLB, "reduced attention rows")
+    # the unreduced layer on a few rows
+    o_full = strd.attn_prefill(t["q"], t["k"], t["v"])
+    rows = np.array([0, 200, 4095, 4096, 20000, N + M - 1], np.int32)
+    o_ref = oracle.attn(f(t["q"]), f(t["k"]), f(t["v"]), rows=rows)
+    assert_close(f(o_full[torch.from_numpy(rows).long().to(DEV)]), o_ref, TOLB, "full attention rows")
+
+
+@pytest.mark.parametrize("budget", [0.10, 0.25, 0.50])
+def test_c5_long_video_mamba_layer_sampled(budget):
+    w = synth.shrink(synth.WORKLOADS["c5"], N=131072, M=512, budget=budget)
+    _say("c5 long video mamba: N=%d M=%d K=%d" % (w.N, w.M, w.K))
+    hidden = synth.hidden_states(w, DEV)
+    t = synth.mamba_inputs(w, hidden)
+    hb = hidden.to(torch.bfloat16)
+    del hidden
+    N, M, K = w.N, w.M, w.K
+    s, idx, pos, red, y, S = _reduced_mamba(w, t, hb)
+    # scores of sampled tokens, one by one (a token's score needs only its own row)
+    pick = np.sort(np.random.default_rng(1).choice(N, 192, replace=False))
+    pt = torch.from_numpy(pick).long().to(DEV)
+    s_ref = oracle.score_mamba(f(t["B"][:N][pt]), f(t["C"][N:]), f(t["dt"][:N][pt]))
+    assert_close(s[pt].cpu().numpy(), s_ref, TOLB, "sampled scores")
+    # selection: valid, ascending, consistent with a threshold on the device scores
+    i_np = idx.cpu().numpy()
+    s_np = s.cpu().numpy()
+    assert i_np.shape == (K,) and (np.diff(i_np) > 0).all() and i_np[0] >= 0 and i_np[-1] < N
+    np.testing.assert_array_equal(i_np, oracle.select_topk(s_np.astype(np.float64), K))
+    np.testing.assert_array_equal(red["B"].view(torch.int16).cpu().numpy(),
+                                  oracle.compact(t["B"].view(torch.int16).cpu().numpy(), i_np, N, M)[0])
+    np.testing.assert_array_equal(red["hidden"][::97].view(torch.int16).cpu().numpy(),
+                                  hb[torch.from_numpy(np.concatenate([i_np, np.arange(N, N + M)])[::97]).long().to(DEV)]
+                                  .view(torch.int16).cpu().numpy())
+    _check_ssd_heads(red["x"], red["dt"], t["A"], red["B"], red["C"], y, S, [3, 77], w.mamba.G, "reduced")
+
+
+def test_c5_long_video_attention_layer_sampled():
+    w = synth.shrink(synth.WORKLOADS["c5"], N=131072, M=512, budget=0.25)
+    _say("c5 long video attention: N=%d M=%d K=%d" % (w.N, w.M, w.K))
+    hidden = synth.hidden_states(w, DEV)
+    t = synth.attn_inputs(w, hidden)
+    del hidden
+    N, M, K = w.N, w.M, w.K
+    s = strd.score_attn(t["q"][N:].contiguous(), t["k"][:N].contiguous())
+    # properties that hold at any size: a probability vector; independent of the key order
+    assert abs(float(s.double().sum()) - 1.0) < 1e-3 and float(s.min()) >= 0.0
+    # exact values on a key subset whose softmax normaliser the oracle can afford: restrict both sides to 2048 keys
+    sub = torch.from_numpy(np.sort(np.random.default_rng(2).choice(N, 2048, replace=False))).long().to(DEV)
+    s_sub = strd.score_attn(t["q"][N:].contiguous(), t["k"][:N][sub].contiguous())
+    assert_close(s_sub.cpu().numpy(), oracle.score_attn(f(t["q"][N:]), f(t["k"][:N][sub])), TOLB, "subset scores")
+    idx = strd.select_topk(s, K)
+    i_np = idx.cpu().numpy()
+    np.testing.assert_array_equal(i_np, oracle.select_topk(s.cpu().numpy().astype(np.float64), K))
+    (qs, ks, vs), _ = strd.compact_batch([t["q"], t["k"], t["v"]], idx, N, M)
+    o = strd.attn_prefill(qs, ks, vs)
+    Tr = K + M
+    rows = np.array([0, 127, 128, 5000, K - 1, K, Tr - 1], np.int32)
+    o_ref = oracle.attn(f(qs), f(ks), f(vs), rows=rows)
+    assert_close(f(o[torch.from_numpy(rows).long().to(DEV)]), o_ref, TOLB, "reduced attention rows")
