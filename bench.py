@@ -326,6 +326,28 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     ms_step = (time.perf_counter() - t0) * 1e3 / steps
     ms_mixer = layer.mixer_ev.mean_ms()
     layer.mixer_ev = None
+    # the same step captured once into a HIP graph and replayed (no per-launch host work)
+    ms_graph = None
+    try:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            layer.step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                layer.step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / steps
+    except Exception as exc:  # graph capture is an extra figure, never the headline
+        print("bench.py: graph replay skipped: %s" % exc, file=sys.stderr)
     calls = {
         "score_us": 1e3 * time_events(torch, layer.score),
         "select_topk_us": 1e3 * time_events(torch, layer.select),
@@ -349,7 +371,7 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
                 "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
     res = {
         "layer": kind, "workload": name, "N": w.N, "M": w.M, "K": w.K, "budget": budget,
-        "ms_per_step": ms_step, "tokens_per_s": w.T / (ms_step * 1e-3),
+        "ms_per_step": ms_step, "graph_replay_ms_per_step": ms_graph, "tokens_per_s": w.T / (ms_step * 1e-3),
         "retained_tokens_per_s": Tr / (ms_step * 1e-3), "speedup_vs_full": ms_full / ms_step,
         "calls": calls, "select_plus_compact_GBps": sel_compact_gbs,
         "select_plus_compact_frac_of_hbm": sel_compact_gbs / HBM_PEAK_GBS, "roofline": roof,
@@ -389,6 +411,7 @@ def main():
                    "tokens_counted": "input tokens N+M per reduced-layer step (score+select+compact+mixer)",
                    "parallelism": "1 GPU"},
         "speedup_vs_full": res["speedup_vs_full"], "retained_tokens_per_s": res["retained_tokens_per_s"],
+        "graph_replay_ms_per_step": res["graph_replay_ms_per_step"],
         "calls_us": res["calls"], "select_plus_compact_GBps": res["select_plus_compact_GBps"],
         "select_plus_compact_frac_of_hbm": res["select_plus_compact_frac_of_hbm"],
         "roofline": res["roofline"], "context": PAPER_CONTEXT,

@@ -49,8 +49,8 @@ int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, 
 
 // ------------------------------------------------------------------ score_mamba ------------
 size_t strd_score_mamba_workspace(int M, int N, int H, int G, int n, strd_dtype io) {
-    (void)M; (void)N; (void)H; (void)G; (void)n; (void)io;
-    return 0;
+    if (M < 1 || N < 1 || H < 1 || G < 1 || H % G) return 0;
+    return score_mamba_mfma_supported(M, N, H, G, n, io) ? score_mamba_mfma_ws(N, G) : 0;
 }
 
 int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, float *scores, int M, int N,
@@ -60,7 +60,7 @@ int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, 
     const size_t need = strd_score_mamba_workspace(M, N, H, G, n, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
     if (score_mamba_mfma_supported(M, N, H, G, n, io))
-        return score_mamba_mfma(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, as_stream(stream));
+        return score_mamba_mfma(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, ws, as_stream(stream));
     return score_mamba_general(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, io, as_stream(stream));
 }
 

@@ -72,12 +72,22 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
     int st_row[AT::kIssues], st_col[AT::kIssues];
 #pragma unroll
     for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
-    auto stage = [&](int chunk, int b) {
+    // 32-bit byte offsets (shared by K and V) of the next chunk to request; rows past T re-read row T - 1
+    const uint32_t kv_row = (uint32_t)Hkv * D * 2;
+    uint32_t st_off[AT::kIssues], st_lim[AT::kIssues];
+#pragma unroll
+    for (int i = 0; i < AT::kIssues; ++i) {
+        const uint32_t col = ((uint32_t)kvh * D + st_col[i] * 8) * 2;
+        st_off[i] = (uint32_t)st_row[i] * kv_row + col;
+        st_lim[i] = (uint32_t)(T - 1) * kv_row + col;
+    }
+    auto stage = [&](int b) {  // requests the next chunk in sequence
 #pragma unroll
         for (int i = 0; i < AT::kIssues; ++i) {
-            const size_t off = ((size_t)min(chunk * kKC + st_row[i], T - 1) * Hkv + kvh) * D + st_col[i] * 8;
-            AT::issue(k + off, &lds.k[b], w, i);
-            AT::issue(v + off, &lds.v[b], w, i);
+            const uint32_t off = min(st_off[i], st_lim[i]);
+            AT::issue(reinterpret_cast<const char *>(k) + off, &lds.k[b], w, i);
+            AT::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], w, i);
+            st_off[i] += kKC * kv_row;
         }
     };
 
@@ -86,18 +96,18 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane half's share of the row sum
+    float m_run = -INFINITY, m_neg = 0.f, l_run = 0.f;  // l_run: this lane half's share of the row sum
 
     // lane-dependent parts of the transposed V read
     const int vb = lane >> 4, vr = lane & 15;
     const int v_krow = 4 * (vb >> 1) + (vr >> 2), v_col = 16 * (vb & 1) + 4 * (vr & 3);
 
-    stage(0, 0);
+    stage(0);
     async_tile_wait();
     __syncthreads();
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int cur = chunk & 1;
-        stage(min(chunk + 1, nchunk - 1), cur ^ 1);
+        stage(cur ^ 1);  // chunk + 1 (past the last chunk: clamped rows, never read)
 #pragma unroll
         for (int kt = 0; kt < kKC / 32; ++kt) {
             const int kb = chunk * kKC + 32 * kt;
@@ -111,29 +121,31 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
                     sacc = mfma32(a, bq[ks], sacc);
                 }
                 const bool diag = kb + 31 > wq0;  // some (key, query) pair of the tile is masked
-                float z[16], tm = -INFINITY;
+                float tm = -INFINITY;             // max of this lane half's 16 raw scores
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    z[i] = sacc[i] * scale2;
-                    if (diag && kb + 8 * (i / 4) + 4 * half + (i % 4) > tq) z[i] = -INFINITY;
-                    tm = fmaxf(tm, z[i]);
+                    if (diag && kb + 8 * (i / 4) + 4 * half + (i % 4) > tq) sacc[i] = -INFINITY;
+                    tm = fmaxf(tm, sacc[i]);
                 }
-                tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
-                const float nm = fmaxf(m_run, tm);  // finite: key 0 is visible to every query
-                if (__any(nm > m_run)) {
-                    const float corr = ex2(m_run - nm);
+                // m_run (raw units) is common to both lane halves of a query; it only has to move, and
+                // the halves only have to talk, when some lane of the wave sees a larger score
+                if (__any(tm > m_run)) {
+                    tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
+                    const float nm = fmaxf(m_run, tm);  // finite: key 0 is visible to every query
+                    const float corr = ex2((m_run - nm) * scale2);
                     l_run *= corr;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) oacc[dt][i] *= corr;
                     m_run = nm;
+                    m_neg = -nm * scale2;
                 }
                 float ps = 0.f;
                 bf16x8 pf[2];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float p = ex2(z[i] - m_run);
+                    const float p = ex2(fmaf(sacc[i], scale2, m_neg));  // 2^((s - m) * scale * log2 e)
                     ps += p;
                     pf[i >> 3][i & 7] = (bf16_t)p;
                 }
@@ -192,8 +204,9 @@ int launch(const void *q, const void *k, const void *v, void *o, int T, int Hq, 
 }  // namespace
 
 bool attn_mfma_supported(int T, int Hq, int Hkv, int d, strd_dtype io) {
-    (void)Hkv;
-    return io == STRD_BF16 && T >= 1 && (d == 64 || d == 128) && (long long)ceil_div(T, kBM) * Hq < (1LL << 30);
+    // staging uses 32-bit byte offsets into K and V
+    return io == STRD_BF16 && T >= 1 && (d == 64 || d == 128) && (long long)ceil_div(T, kBM) * Hq < (1LL << 30) &&
+           (unsigned long long)(T + 2 * kKC) * Hkv * d * 2 < (1ull << 32);
 }
 
 int attn_mfma(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d, float scale,

@@ -36,15 +36,15 @@ __host__ __forceinline__ int xcd_grid(int n) { return (n + kXcd - 1) / kXcd * kX
 // VR + PAD vectors, which keeps 16-byte row reads and transposing reads off each other's banks).
 // global_load_lds writes lane l of a wave to (uniform LDS base) + 16 * l, so the tile is filled
 // slot by slot: slot s = row * (VR + PAD) + cv; pad slots (cv >= VR) re-read the row's last vector.
-// Slots are dealt to the NW waves of the workgroup 64 at a time; the tile's LDS footprint is
-// rounded up to whole 64-slot groups per wave (kBytes), the surplus slots re-read the last row.
+// Slots are dealt to the NW waves of the workgroup 64 at a time; lanes whose slot lies past the
+// end of the tile copy nothing, so the tile occupies exactly ROWS * (VR + PAD) * 16 bytes.
 template <int ROWS, int VR, int NW, int PAD = 1>
 struct AsyncTile {
     static constexpr int kVP = VR + PAD;                                // vectors per LDS row
     static constexpr int kPitch = kVP * 8;                              // bf16 elements per LDS row
     static constexpr int kSlots = ROWS * kVP;
     static constexpr int kIssues = (kSlots + 64 * NW - 1) / (64 * NW);  // instructions per wave
-    static constexpr int kBytes = kIssues * NW * 64 * 16;
+    static constexpr int kBytes = kSlots * 16;
 
     // Row and vector of the slot this lane fills with its i-th instruction.
     __device__ static __forceinline__ void slot(int wave, int lane, int i, int &row, int &cv) {
@@ -55,8 +55,10 @@ struct AsyncTile {
     // Issue this lane's i-th copy: 16 bytes from `src` to its slot of the tile at `lds_tile`.
     __device__ static __forceinline__ void issue(const void *src, void *lds_tile, int wave, int i) {
         char *dst = reinterpret_cast<char *>(lds_tile) + (i * NW + wave) * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        const int s = (i * NW + wave) * 64 + (int)(threadIdx.x & 63);
+        if ((i + 1) * NW * 64 <= kSlots || s < kSlots)  // only the last round can run past the tile
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     }
 };
 // Wait until every copy this wave issued has landed (call before the barrier that publishes).
@@ -147,8 +149,9 @@ size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv);
 int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
                     hipStream_t st);
 bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
+size_t score_mamba_mfma_ws(int N, int G);
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
-                     hipStream_t st);
+                     void *ws, hipStream_t st);
 bool ssd_mfma_supported(int T, int H, int P, int G, int n, strd_dtype io);
 int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
              const float *S_in, void *y, float *S_out, int T, int H, int P, int G, int n, hipStream_t st);

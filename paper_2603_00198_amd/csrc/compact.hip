@@ -1,7 +1,7 @@
 // compact: order-preserving row gather of per-token tensors (paper Sec. 3.1, token selection:
 // retained vision tokens continue, the text tail is kept whole).
-// Pure HBM-bound copy: every lane moves 16-byte vectors, the loads of a thread are issued
-// before its stores, consecutive lanes touch consecutive vectors of a row.  Up to
+// Pure HBM-bound copy: every lane moves 16-byte vectors (non-temporal loads, cached stores), the
+// loads of a thread are issued before its stores, consecutive lanes touch consecutive vectors of a row.  Up to
 // STRD_COMPACT_MAX tensors that share one index list are gathered by a single launch
 // (blockIdx.y selects the tensor), which matters because a reduced layer compacts 4-5 tensors
 // of a few tens of MB each and a launch costs about as much as moving 20 MB.
@@ -12,6 +12,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 struct Item {
     const void *src;
@@ -45,13 +46,13 @@ __device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restr
                 const int c = e - rl * vpr;
                 const int r = row0 + rl;
                 const int sr = (r < K) ? idx[r] : (N + (r - K));
-                v[u] = src[(size_t)sr * vpr + c];
+                v[u] = __builtin_nontemporal_load(src + (size_t)sr * vpr + c);  // streamed once: keep it out of L2
                 off[u] = (size_t)r * vpr + c;
             }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            if (e0 + u * kThreads < total) dst[off[u]] = v[u];
+            if (e0 + u * kThreads < total) dst[off[u]] = v[u];  // cached: the mixer reads it next
     }
 }
 
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(Batch b, const int32_
         const int r = blockIdx.x * kThreads + threadIdx.x;
         if (r < rows_out) reinterpret_cast<int32_t *>(it.dst)[r] = (r < K) ? idx[r] : (N + (r - K));
     } else if (it.vec16) {
-        copy_rows<uint4>(it, idx, N, K, rows_out);
+        copy_rows<u32x4>(it, idx, N, K, rows_out);
     } else {
         copy_rows<uint32_t>(it, idx, N, K, rows_out);
     }

@@ -4,15 +4,15 @@
 // materialised: a wave keeps the b fragments of its 32*CT vision tokens in registers (B operand,
 // tokens on the accumulator columns), streams the text rows c_m of the group through LDS as the
 // A operand, and folds |acc| into one running sum per lane, so the reduction over text rows
-// costs no cross-lane traffic until the single lane-half exchange at the end of a group.  The
-// sum over groups stays inside the lane, in group order: no atomics, bit-reproducible.
+// costs no cross-lane traffic until a single lane-half exchange at the end.
 //
-// One workgroup = 4 waves = 128*CT consecutive tokens, all groups.  The text tile (128 rows
-// of one group) is double-buffered in LDS and shared by the 4 waves; the next tile and the
-// next group's b fragments are prefetched (tile: asynchronous global -> LDS copy, fragments:
-// registers) while the current tile is consumed.
-// HBM traffic is one pass over B_vis and dt_vis; C_txt (M*G*n*2 bytes) is re-read per
-// workgroup from L2.
+// Kernel 1: one workgroup = 4 waves = 128*CT consecutive tokens of ONE group (grid = token
+// tiles x groups, so even 8192 tokens give 512 workgroups); the text tile (128 rows) is
+// double-buffered in LDS, filled by asynchronous global -> LDS copies, shared by the 4 waves.
+// It writes a[g][i] = sum_m |b_i^g . c_m^g|.  Kernel 2: 16 lanes per token sum dt_i^h * a[g(h)][i]
+// over the heads and scale.
+// No atomics, fixed summation order: bit-reproducible.  HBM traffic is one pass over B_vis and
+// dt_vis; C_txt (M*n*2 bytes per group) is re-read per workgroup from L2.
 #include "common.h"
 
 namespace strd {
@@ -38,19 +38,15 @@ struct Tile {
 template <int NS, int CT>
 __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t *__restrict__ Bv,
                                                                     const bf16_t *__restrict__ Ct,
-                                                                    const float *__restrict__ dtv,
-                                                                    float *__restrict__ s, int M, int N, int H, int G) {
+                                                                    float *__restrict__ part, int M, int N, int G) {
     constexpr int KS = NS / 16;  // k-steps of v_mfma_f32_32x32x16_bf16
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<NS> &lds = *reinterpret_cast<Tile<NS> *>(smem_raw);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
-    const int hpg = H / G;
-    const int nmc = (M + kMC - 1) / kMC, nchunk = G * nmc;
+    const int g = blockIdx.y;
+    const int nmc = (M + kMC - 1) / kMC;
     const int tok0 = blockIdx.x * (128 * CT) + w * (32 * CT);
-    int tok[CT];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) tok[ct] = min(tok0 + 32 * ct + lc, N - 1);  // tail lanes repeat the last token
 
     // text tiles go global -> LDS directly; rows past M re-read the last row and are skipped
     // (whole 32-row tiles) or masked (the ragged tile) when the products are folded
@@ -58,41 +54,34 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
     int st_row[AT::kIssues], st_col[AT::kIssues];
 #pragma unroll
     for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
-    auto stage = [&](int chunk, int b) {
-        const int g = chunk / nmc, m0 = (chunk % nmc) * kMC;
+    auto stage = [&](int mc, int b) {
 #pragma unroll
         for (int i = 0; i < AT::kIssues; ++i) {
-            const int m = min(m0 + st_row[i], M - 1);
+            const int m = min(mc * kMC + st_row[i], M - 1);
             AT::issue(Ct + ((size_t)m * G + g) * NS + st_col[i] * 8, &lds.c[b], w, i);
         }
     };
-    // b fragments of group g for this wave's tokens: lane = token column, 8 consecutive k
-    auto load_b = [&](bf16x8 (&dst)[CT][KS], int g) {
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                dst[ct][ks] = *reinterpret_cast<const bf16x8 *>(Bv + ((size_t)tok[ct] * G + g) * NS + 16 * ks + 8 * half);
-    };
-
-    bf16x8 bcur[CT][KS], bnext[CT][KS];
-    load_b(bcur, 0);
     stage(0, 0);
+
+    // b fragments of this wave's tokens: lane = token column, 8 consecutive k (tail lanes repeat the last token)
+    bf16x8 bfr[CT][KS];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const bf16_t *bp = Bv + ((size_t)min(tok0 + 32 * ct + lc, N - 1) * G + g) * NS + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bfr[ct][ks] = *reinterpret_cast<const bf16x8 *>(bp + 16 * ks);
+    }
     async_tile_wait();
     __syncthreads();
 
-    float total[CT], part[CT];
+    float part_sum[CT];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) total[ct] = part[ct] = 0.f;
+    for (int ct = 0; ct < CT; ++ct) part_sum[ct] = 0.f;
 
-    for (int chunk = 0; chunk < nchunk; ++chunk) {
-        const int g = chunk / nmc, mc = chunk % nmc, cur = chunk & 1;
-        // prefetch (clamped, so the loop body is free of conditional loads)
-        stage(min(chunk + 1, nchunk - 1), cur ^ 1);
-        if (mc == 0) load_b(bnext, min(g + 1, G - 1));
-        const int mrows = M - mc * kMC;  // valid text rows of this tile (may exceed kMC)
-
-        // |c_m . b_i| for the 128 text rows of this tile, 32 at a time
+    for (int mc = 0; mc < nmc; ++mc) {
+        const int cur = mc & 1;
+        if (mc + 1 < nmc) stage(mc + 1, cur ^ 1);  // uniform
+        const int mrows = M - mc * kMC;            // valid text rows of this tile (may exceed kMC)
 #pragma unroll
         for (int mt = 0; mt < kMC / 32; ++mt) {
             if (32 * mt >= mrows) continue;  // uniform: tile wholly past the last text row
@@ -106,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
                 const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds.c[cur].at(32 * mt + lc, 16 * ks + 8 * half));
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
-                    acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bcur[ct][ks], acc[ct], 0, 0, 0);
+                    acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfr[ct][ks], acc[ct], 0, 0, 0);
             }
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
@@ -119,40 +108,41 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
                     for (int i = 0; i < 16; ++i)
                         t += (32 * mt + 8 * (i / 4) + 4 * half + (i % 4) < mrows) ? fabsf(acc[ct][i]) : 0.f;
                 }
-                part[ct] += t;
+                part_sum[ct] += t;
             }
-        }
-
-        if (mc == nmc - 1) {
-            // end of a group: weight by the summed dt of the group's heads
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                float dts = 0.f;
-                for (int j = half; j < hpg; j += 2) dts += dtv[(size_t)tok[ct] * H + g * hpg + j];
-                dts += __shfl_xor(dts, 32, kWave);
-                const float col = part[ct] + __shfl_xor(part[ct], 32, kWave);
-                total[ct] += dts * col;
-                part[ct] = 0.f;
-            }
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) bcur[ct][ks] = bnext[ct][ks];
         }
         async_tile_wait();
         __syncthreads();
     }
-
-    const float norm = 1.f / ((float)M * (float)H);
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
+        const float col = part_sum[ct] + __shfl_xor(part_sum[ct], 32, kWave);
         const int t = tok0 + 32 * ct + lc;
-        if (half == 0 && t < N) s[t] = total[ct] * norm;
+        if (half == 0 && t < N) part[(size_t)g * N + t] = col;
     }
 }
 
+// s_i = 1/(M*H) * sum_h dt_i^h * a[g(h)][i].  16 adjacent lanes share a token and read its dt
+// row in 64-byte pieces (coalesced); their partial sums meet in a fixed butterfly order.
+__global__ __launch_bounds__(kThreads) void score_mamba_reduce_kernel(const float *__restrict__ part,
+                                                                      const float *__restrict__ dtv,
+                                                                      float *__restrict__ s, int N, int H, int G,
+                                                                      float norm) {
+    const int i = blockIdx.x * (kThreads / 16) + threadIdx.x / 16, j = threadIdx.x & 15;
+    const int hpg = H / G;
+    float tot = 0.f;
+    if (i < N) {
+        const float *dr = dtv + (size_t)i * H;
+        for (int h = j; h < H; h += 16) tot = fmaf(dr[h], part[(size_t)(h / hpg) * N + i], tot);
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) tot += __shfl_xor(tot, o, kWave);
+    if (i < N && j == 0) s[i] = tot * norm;
+}
+
 template <int NS, int CT>
-int launch(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, hipStream_t st) {
+int launch(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, void *ws,
+           hipStream_t st) {
     const size_t smem = sizeof(Tile<NS>);
     static bool configured = false;
     if (!configured) {
@@ -161,24 +151,31 @@ int launch(const void *B, const void *C, const float *dt, float *s, int M, int N
             return STRD_EHIP;
         configured = true;
     }
-    const int grid = ceil_div(N, 128 * CT);
-    score_mamba_mfma_kernel<NS, CT><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, dt, s, M, N, H, G);
+    float *part = (float *)ws;
+    const dim3 grid(ceil_div(N, 128 * CT), G);
+    score_mamba_mfma_kernel<NS, CT><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, part, M, N, G);
+    score_mamba_reduce_kernel<<<ceil_div(N, kThreads / 16), kThreads, 0, st>>>(part, dt, s, N, H, G,
+                                                                          1.f / ((float)M * (float)H));
     return launch_status();
 }
 
 }  // namespace
 
 bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io) {
-    (void)M; (void)H; (void)G;
-    return io == STRD_BF16 && (n == 64 || n == 128) && N >= 1;
+    (void)M; (void)H;
+    return io == STRD_BF16 && (n == 64 || n == 128) && N >= 1 && G <= 65535;
 }
 
+size_t score_mamba_mfma_ws(int N, int G) { return align_up((size_t)G * N * sizeof(float), 256); }
+
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
-                     hipStream_t st) {
-    // wide token tiles once there are enough of them to fill 256 CUs; narrow ones otherwise
-    const bool wide = N >= 256 * 256;
-    if (n == 128) return wide ? launch<128, 2>(B, C, dt, s, M, N, H, G, st) : launch<128, 1>(B, C, dt, s, M, N, H, G, st);
-    if (n == 64) return wide ? launch<64, 2>(B, C, dt, s, M, N, H, G, st) : launch<64, 1>(B, C, dt, s, M, N, H, G, st);
+                     void *ws, hipStream_t st) {
+    // wide token tiles once there are enough of them to fill 256 CUs several times over
+    const bool wide = (long long)N * G >= 256LL * 256 * 8;
+    if (n == 128)
+        return wide ? launch<128, 2>(B, C, dt, s, M, N, H, G, ws, st) : launch<128, 1>(B, C, dt, s, M, N, H, G, ws, st);
+    if (n == 64)
+        return wide ? launch<64, 2>(B, C, dt, s, M, N, H, G, ws, st) : launch<64, 1>(B, C, dt, s, M, N, H, G, ws, st);
     return STRD_EUNSUPPORTED;
 }
 
