@@ -106,8 +106,7 @@ class MambaLayer:
         self.scores = e(N, dtype=torch.float32)
         self.idx = e(K, dtype=torch.int32)
         Tr = K + M
-        self.o = {"x": e(Tr, s.H, s.P), "B": e(Tr, s.G, s.n), "C": e(Tr, s.G, s.n),
-                  "dt": e(Tr, s.H, dtype=torch.float32), "hidden": e(Tr, w.d_model)}
+        self.o = {"hidden": e(Tr, w.d_model)}
         self.y_red = e(Tr, s.H, s.P)
         self.y_full = e(w.T, s.H, s.P)
         lib = strd.lib()
@@ -125,14 +124,13 @@ class MambaLayer:
 
     def compact(self):
         N, M = self.w.N, self.w.M
-        keys = ("x", "B", "C", "dt")
-        self.strd.compact_batch([self.t[k] for k in keys] + [self.hidden], self.idx, N, M,
-                                outs=[self.o[k] for k in keys] + [self.o["hidden"]])
+        # the scan reads its inputs through the index list, so only the residual stream moves
+        self.strd.compact_batch([self.hidden], self.idx, N, M, outs=[self.o["hidden"]])
 
     def mixer_reduced(self):
-        o = self.o
-        self.strd.ssd_prefill(o["x"], o["dt"], self.t["A"], o["B"], o["C"], chunk=self.s.chunk, want_state=False,
-                              out=self.y_red, ws=self.ws)
+        t = self.t
+        self.strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], self.idx, self.w.N, self.w.M,
+                                     chunk=self.s.chunk, want_state=False, out=self.y_red)
 
     def mixer_full(self):
         t = self.t
@@ -158,8 +156,8 @@ class MambaLayer:
 
     def compact_bytes(self):
         w, s, eb = self.w, self.s, self.hidden.element_size()
-        row = (s.H * s.P + 2 * s.G * s.n + w.d_model) * eb + 4 * s.H
-        return 2 * (w.K + w.M) * row + 4 * w.K * 5
+        row = w.d_model * eb
+        return 2 * (w.K + w.M) * row + 4 * w.K
 
     mixer_name, mixer_bound = "ssd_prefill", "hbm"
 

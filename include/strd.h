@@ -142,6 +142,18 @@ int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void 
                      int G, int n, int chunk, strd_dtype io, void *ws, size_t ws_bytes,
                      void *stream);
 
+/* ssd_prefill_gather -- ssd_prefill on the K + M surviving tokens WITHOUT a compacted copy of
+ * the mixer inputs: token t of the scan is row idx[t] (t < K) or N + (t - K) of the
+ * uncompacted x, dt, B, C (N + M rows each).  Equal, bit for bit, to compacting the four
+ * tensors with strd_compact and calling strd_ssd_prefill, minus that HBM round trip.
+ *   idx [dev] [K] int32, ascending, each in [0, N)     y [dev] [K+M, H, P] (dense)
+ * Only shapes the matrix-core kernel covers (bf16, n in {64, 128}, P % 32 == 0, K + M >= 1);
+ * anything else gives STRD_EUNSUPPORTED (compact, then call strd_ssd_prefill). */
+int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, const void *B, const void *C,
+                            const float *D, const float *S_in, const int32_t *idx, void *y, float *S_out,
+                            int N, int M, int K, int H, int P, int G, int n, int chunk, strd_dtype io,
+                            void *ws, size_t ws_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------
  * attn_prefill -- causal softmax attention with grouped-query heads over T tokens
  * (App. "Attention via Kernel Functions", first equation):

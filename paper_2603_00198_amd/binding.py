@@ -31,6 +31,7 @@ _SIGNATURES = {
     "strd_compact_batch": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp]),
     "strd_ssd_prefill_workspace": (_sz, [_int] * 6 + [_int]),
     "strd_ssd_prefill": (_int, [_vp] * 9 + [_int] * 6 + [_int, _vp, _sz, _vp]),
+    "strd_ssd_prefill_gather": (_int, [_vp] * 10 + [_int] * 8 + [_int, _vp, _sz, _vp]),
     "strd_attn_prefill_workspace": (_sz, [_int] * 4 + [_int]),
     "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
     "strd_schedule_budgets": (_int, [_vp, _int, _int, _int, _vp]),
@@ -236,6 +237,28 @@ def ssd_prefill(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Ten
     _check(lib().strd_ssd_prefill(_ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(S_in), _ptr(y),
                                   _ptr(S_out), T, H, P, G, n, chunk, io, _ptr(ws),
                                   0 if ws is None else ws.numel(), _stream()), "ssd_prefill")
+    return y, S_out
+
+
+def ssd_prefill_gather(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,
+                       idx: torch.Tensor, N: int, M: int, D: Optional[torch.Tensor] = None,
+                       S_in: Optional[torch.Tensor] = None, chunk: int = 256, want_state: bool = True,
+                       out: Optional[torch.Tensor] = None):
+    """Mamba-2 scan over rows idx (vision) + the M text rows of the uncompacted inputs [N+M, ...]."""
+    _dev(x, dt, A, B, C, D, S_in, idx, out)
+    Ttot, H, P = x.shape
+    G, n = B.shape[1:]
+    K = idx.shape[0]
+    if Ttot != N + M or dt.shape != (Ttot, H) or A.shape != (H,) or B.shape != (Ttot, G, n) or C.shape != (Ttot, G, n) \
+            or dt.dtype != torch.float32 or A.dtype != torch.float32 or B.dtype != x.dtype or C.dtype != x.dtype \
+            or idx.dtype != torch.int32:
+        raise StrdError("ssd_prefill_gather: inconsistent shapes or dtypes")
+    io = _io(x)
+    y = out if out is not None else torch.empty((K + M, H, P), dtype=x.dtype, device=x.device)
+    S_out = torch.empty(H, P, n, dtype=torch.float32, device=x.device) if want_state else None
+    _check(lib().strd_ssd_prefill_gather(_ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(S_in), _ptr(idx),
+                                         _ptr(y), _ptr(S_out), N, M, K, H, P, G, n, chunk, io, None, 0, _stream()),
+           "ssd_prefill_gather")
     return y, S_out
 
 

@@ -109,10 +109,30 @@ int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void 
     if (T > 0 && (!x || !dt || !B || !C || !y)) return STRD_EINVAL;
     const size_t need = strd_ssd_prefill_workspace(T, H, P, G, n, chunk, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
-    if (ssd_mfma_supported(T, H, P, G, n, io))
-        return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, n, as_stream(stream));
+    if (ssd_mfma_supported(T, T, H, P, G, n, io))
+        return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, nullptr, 0, 0, T, H, P, G, n, as_stream(stream));
     if (!ssd_general_supported(n)) return STRD_EUNSUPPORTED;
     return ssd_general(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, n, io, as_stream(stream));
+}
+
+int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, const void *B, const void *C,
+                            const float *D, const float *S_in, const int32_t *idx, void *y, float *S_out, int N, int M,
+                            int K, int H, int P, int G, int n, int chunk, strd_dtype io, void *ws, size_t ws_bytes,
+                            void *stream) {
+    (void)ws; (void)ws_bytes;
+    if (N < 0 || M < 0 || K < 0 || K > N || H < 1 || P < 1 || G < 1 || n < 1 || H % G || chunk < 1 || !io_ok(io) || !A)
+        return STRD_EINVAL;
+    const long long T = (long long)K + M;
+    if (T > 0 && (!x || !dt || !B || !C || !y || (K > 0 && !idx))) return STRD_EINVAL;
+    if (T == 0 || (long long)N + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+    if (!ssd_mfma_supported((int)T, N + M, H, P, G, n, io)) return STRD_EUNSUPPORTED;
+    if (K == 0) {  // only the text rows survive: a dense scan over the tail of the tensors
+        const size_t es = 2;
+        return ssd_mfma((const char *)x + (size_t)N * H * P * es, dt + (size_t)N * H, A,
+                        (const char *)B + (size_t)N * G * n * es, (const char *)C + (size_t)N * G * n * es, D, S_in, y,
+                        S_out, nullptr, 0, 0, (int)T, H, P, G, n, as_stream(stream));
+    }
+    return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, idx, N, K, (int)T, H, P, G, n, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ attn_prefill -----------

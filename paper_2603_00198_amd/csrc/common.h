@@ -152,9 +152,10 @@ bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io
 size_t score_mamba_mfma_ws(int N, int G);
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
                      void *ws, hipStream_t st);
-bool ssd_mfma_supported(int T, int H, int P, int G, int n, strd_dtype io);
+bool ssd_mfma_supported(int T, int rows, int H, int P, int G, int n, strd_dtype io);
 int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
-             const float *S_in, void *y, float *S_out, int T, int H, int P, int G, int n, hipStream_t st);
+             const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G,
+             int n, hipStream_t st);
 
 bool attn_general_supported(int d);
 int attn_general(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d,

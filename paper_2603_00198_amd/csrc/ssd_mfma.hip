@@ -70,6 +70,7 @@ struct Lds {
     TileBC bc[3];
     TileX xr[kXRing];
     float dt[kDtRing][kQ];
+    uint32_t rowtab[4][kQ];  // gather mode: source row of every token of steps q, q % 4 = slot
     Meta meta[2];
     bf16_t s[2][kPB][kSP];  // state before the step, [p][n]
 };
@@ -96,7 +97,7 @@ __device__ __forceinline__ void read_x_frags(const bf16_t *xt, int lr, int lb, b
 }
 
 // Output wave W of a workgroup: steps (a)-(d) for tokens 16W..16W+15 of every step.
-template <int NS, int W>
+template <int NS, int W, bool GATHER>
 __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restrict__ D, bf16_t *__restrict__ y, int T,
                                             int H, int P, int h, int p0, int nsteps) {
     constexpr int KS = NS / 32;
@@ -106,8 +107,9 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     const int tcol = 16 * W + lr;  // this lane's token inside the step
     bf16_t *yp = y + ((size_t)tcol * H + h) * P + p0 + 4 * lb;
     const size_t y_step = (size_t)kQ * H * P;
-    __syncthreads();  // the two barriers of the state waves' prologue: first copies landed,
-    __syncthreads();  // scan of step 0 published
+    if (GATHER) __syncthreads();  // the barriers of the state waves' prologue: (row tables written,)
+    __syncthreads();              // first copies landed,
+    __syncthreads();              // scan of step 0 published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
@@ -204,12 +206,14 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 
 // State wave SW: owns NT 16-row tiles of the state starting at tile T0, stages x / dt (all
 // state waves) and issues the B / C tile copies (SW < 2).
-template <int NS, int SW>
+// GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
+// kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy.
+template <int NS, int SW, bool GATHER>
 __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
                                            const float *__restrict__ A, const bf16_t *__restrict__ B,
                                            const bf16_t *__restrict__ C, const float *__restrict__ S_in,
-                                           float *__restrict__ S_out, int T, int H, int P, int G, int h, int p0, int g,
-                                           int nsteps) {
+                                           float *__restrict__ S_out, const int32_t *__restrict__ idx, int N, int K,
+                                           int T, int H, int P, int G, int h, int p0, int g, int nsteps) {
     using L = Lds<NS>;
     using BC = typename L::BC;
     // state tiles per wave, in the opposite proportion to the causal work of the output wave
@@ -224,26 +228,30 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     // (it is their first consumer).  Byte offsets at the next step to request, per-step strides
     // and end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes them inert).
     const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
+    // dense mode: running offsets; gather mode: (row in the step, column offset) per copy and the
+    // number of the next step to request, the row itself comes from the row table
     uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues], off_x[XT::kIssues], lim_x[XT::kIssues];
+    int row_bc[BC::kIssues], row_x[XT::kIssues];
     uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
     const uint32_t lim_dt = (uint32_t)(T - 1) * dt_row + (uint32_t)h * 4;
+    int next_bc = 0, next_x = 0, next_dt = 0;
     if (SW < 2) {
 #pragma unroll
         for (int i = 0; i < BC::kIssues; ++i) {
-            int r, cv;
-            BC::slot(SW, lane, i, r, cv);
+            int cv;
+            BC::slot(SW, lane, i, row_bc[i], cv);
             const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
-            off_bc[i] = (uint32_t)r * bc_row + col;
+            off_bc[i] = GATHER ? col : (uint32_t)row_bc[i] * bc_row + col;
             lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
         }
     }
     if (SW == 3) {
 #pragma unroll
         for (int i = 0; i < XT::kIssues; ++i) {
-            int r, cv;
-            XT::slot(0, lane, i, r, cv);
+            int cv;
+            XT::slot(0, lane, i, row_x[i], cv);
             const uint32_t col = ((uint32_t)h * P + p0 + cv * 8) * 2;
-            off_x[i] = (uint32_t)r * x_row + col;
+            off_x[i] = GATHER ? col : (uint32_t)row_x[i] * x_row + col;
             lim_x[i] = (uint32_t)(T - 1) * x_row + col;
         }
     }
@@ -251,25 +259,40 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     auto request_bc = [&](int b) {
 #pragma unroll
         for (int i = 0; i < BC::kIssues; ++i) {
-            const uint32_t o = min(off_bc[i], lim_bc[i]);
+            const uint32_t o = GATHER ? lds.rowtab[next_bc & 3][row_bc[i]] * bc_row + off_bc[i] : min(off_bc[i], lim_bc[i]);
             BC::issue(reinterpret_cast<const char *>(C) + o, lds.bc[b].c, SW, i);
             BC::issue(reinterpret_cast<const char *>(B) + o, lds.bc[b].b, SW, i);
-            off_bc[i] += kQ * bc_row;
+            if (!GATHER) off_bc[i] += kQ * bc_row;
         }
+        ++next_bc;
     };
     auto request_x = [&](int b) {
 #pragma unroll
         for (int i = 0; i < XT::kIssues; ++i) {
-            XT::issue(reinterpret_cast<const char *>(x) + min(off_x[i], lim_x[i]), lds.xr[b].x, 0, i);
-            off_x[i] += kQ * x_row;
+            const uint32_t o = GATHER ? lds.rowtab[next_x & 3][row_x[i]] * x_row + off_x[i] : min(off_x[i], lim_x[i]);
+            XT::issue(reinterpret_cast<const char *>(x) + o, lds.xr[b].x, 0, i);
+            if (!GATHER) off_x[i] += kQ * x_row;
         }
+        ++next_x;
     };
     auto request_dt = [&](int b) {  // 64 lanes x 4 bytes
+        const uint32_t o = GATHER ? lds.rowtab[next_dt & 3][lane] * dt_row + (uint32_t)h * 4 : min(off_dt, lim_dt);
         __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + min(off_dt, lim_dt)),
+            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + o),
             (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
         off_dt += kQ * dt_row;
+        ++next_dt;
     };
+    // gather mode, wave SW == 2 (it issues no copies, so its own loads disturb nobody's count of
+    // outstanding copies): source rows of the tokens of `step`, tokens past T repeat the last one
+    // (an index outside [0, N) is clamped into the tensors instead of faulting).  The load runs one
+    // step ahead of the store so that its latency never sits inside a step.
+    const uint32_t last_row = (uint32_t)(N + (T - K) - 1);
+    auto load_row = [&](int step) -> uint32_t {
+        const int t = min(step * kQ + lane, T - 1);
+        return min((uint32_t)(t < K ? idx[t] : N + (t - K)), last_row);
+    };
+    uint32_t row_ahead = 0;
     // Copies a wave issues per step; everything older has landed once at most that many are
     // outstanding (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
     // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
@@ -318,7 +341,16 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
             bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
             *reinterpret_cast<bf16x4 *>(&lds.s[0][pp][n0]) = sv;
         }
-    // prologue: fill the rings up to their look-ahead, then the meta data of step 0
+    // prologue: (row tables of the first steps,) fill the rings up to their look-ahead, then the
+    // meta data of step 0
+    if (GATHER) {
+        if (SW == 2) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
+            row_ahead = load_row(4);
+        }
+        __syncthreads();
+    }
     if (SW < 2) {
         request_bc(0);
         request_bc(1);
@@ -384,6 +416,12 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
             __builtin_amdgcn_s_waitcnt(kWaitOlder);  // x and dt of step + 1 (requested in earlier steps) have landed
             make_meta(step + 1);                     // last thing in the step: the copy had two steps to arrive
         }
+        if (GATHER && SW == 2) {
+            // rows of step + 4: read from step + 1 (x, dt) and step + 2 (B, C) on; the slot held the
+            // rows of this step, last read two steps ago
+            lds.rowtab[step & 3][lane] = row_ahead;
+            row_ahead = load_row(step + 5);
+        }
         lds_barrier();  // this step's copies stay in flight
     }
 
@@ -397,12 +435,12 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     }
 }
 
-template <int NS>
+template <int NS, bool GATHER>
 __global__ __launch_bounds__(kThreads) void ssd_mfma_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ dt, const float *__restrict__ A,
     const bf16_t *__restrict__ B, const bf16_t *__restrict__ C, const float *__restrict__ D,
-    const float *__restrict__ S_in, bf16_t *__restrict__ y, float *__restrict__ S_out, int T, int H, int P, int G,
-    int nunits) {
+    const float *__restrict__ S_in, bf16_t *__restrict__ y, float *__restrict__ S_out,
+    const int32_t *__restrict__ idx, int N, int K, int T, int H, int P, int G, int nunits) {
     using L = Lds<NS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     L &lds = *reinterpret_cast<L *>(smem_raw);
@@ -413,49 +451,56 @@ __global__ __launch_bounds__(kThreads) void ssd_mfma_kernel(
     const int h = unit / nslab, p0 = (unit % nslab) * kPB, g = h / (H / G);
     const int nsteps = (T + kQ - 1) / kQ;
     switch (threadIdx.x >> 6) {
-        case 0: output_wave<NS, 0>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        case 1: output_wave<NS, 1>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        case 2: output_wave<NS, 2>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        case 3: output_wave<NS, 3>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        case 4: state_wave<NS, 0>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
-        case 5: state_wave<NS, 1>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
-        case 6: state_wave<NS, 2>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
-        default: state_wave<NS, 3>(lds, x, dt, A, B, C, S_in, S_out, T, H, P, G, h, p0, g, nsteps); break;
+        case 0: output_wave<NS, 0, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 1: output_wave<NS, 1, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 2: output_wave<NS, 2, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 3: output_wave<NS, 3, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
+        case 4: state_wave<NS, 0, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
+        case 5: state_wave<NS, 1, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
+        case 6: state_wave<NS, 2, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
+        default: state_wave<NS, 3, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
     }
 }
 
-template <int NS>
+template <int NS, bool GATHER>
 int launch(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
-           const float *S_in, void *y, float *S_out, int T, int H, int P, int G, hipStream_t st) {
+           const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G,
+           hipStream_t st) {
     const int nunits = H * (P / kPB);
     const size_t smem = sizeof(Lds<NS>);
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&ssd_mfma_kernel<NS>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&ssd_mfma_kernel<NS, GATHER>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return STRD_EHIP;
         configured = true;
     }
-    ssd_mfma_kernel<NS><<<xcd_grid(nunits), kThreads, smem, st>>>(
-        (const bf16_t *)x, dt, A, (const bf16_t *)B, (const bf16_t *)C, D, S_in, (bf16_t *)y, S_out, T, H, P, G,
-        nunits);
+    ssd_mfma_kernel<NS, GATHER><<<xcd_grid(nunits), kThreads, smem, st>>>(
+        (const bf16_t *)x, dt, A, (const bf16_t *)B, (const bf16_t *)C, D, S_in, (bf16_t *)y, S_out, idx, N, K, T, H, P,
+        G, nunits);
     return launch_status();
 }
 
 }  // namespace
 
-bool ssd_mfma_supported(int T, int H, int P, int G, int n, strd_dtype io) {
+// `rows` = number of rows of the source tensors (T for the dense call, N + M for the gather call)
+bool ssd_mfma_supported(int T, int rows, int H, int P, int G, int n, strd_dtype io) {
     // staging uses 32-bit byte offsets from the tensor bases
-    const unsigned long long lim = 1ull << 32;
+    const unsigned long long lim = 1ull << 32, r = (unsigned long long)(rows > T ? rows : T) + 2 * kQ;
     return io == STRD_BF16 && T >= 1 && (n == 64 || n == 128) && P % kPB == 0 &&
-           (long long)H * (P / kPB) < (1 << 24) && (unsigned long long)(T + 2 * kQ) * H * P * 2 < lim &&
-           (unsigned long long)(T + 2 * kQ) * G * n * 2 < lim && (unsigned long long)(T + 2 * kQ) * H * 4 < lim;
+           (long long)H * (P / kPB) < (1 << 24) && r * H * P * 2 < lim && r * G * n * 2 < lim && r * H * 4 < lim;
 }
 
 int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
-             const float *S_in, void *y, float *S_out, int T, int H, int P, int G, int n, hipStream_t st) {
-    if (n == 128) return launch<128>(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, st);
-    if (n == 64) return launch<64>(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, st);
+             const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G,
+             int n, hipStream_t st) {
+    if (idx) {
+        if (n == 128) return launch<128, true>(x, dt, A, B, C, D, S_in, y, S_out, idx, N, K, T, H, P, G, st);
+        if (n == 64) return launch<64, true>(x, dt, A, B, C, D, S_in, y, S_out, idx, N, K, T, H, P, G, st);
+    } else {
+        if (n == 128) return launch<128, false>(x, dt, A, B, C, D, S_in, y, S_out, nullptr, 0, 0, T, H, P, G, st);
+        if (n == 64) return launch<64, false>(x, dt, A, B, C, D, S_in, y, S_out, nullptr, 0, 0, T, H, P, G, st);
+    }
     return STRD_EUNSUPPORTED;
 }
 

@@ -193,6 +193,39 @@ def test_ssd_prefill_split_call_continues_the_scan():
     assert_close(synth.np64(Sb), synth.np64(S), tol, "split S")
 
 
+@pytest.mark.parametrize("name,K,extras", [("c2-short", 375, True), ("c2-short", 1, False), ("c2-short", 0, True),
+                                           ("c2-short", 1500, False), ("c2-short", 283, False), ("n64", 130, True)])
+def test_ssd_prefill_gather_equals_compact_then_scan(name, K, extras):
+    w = MAMBA_CASES[name]
+    s = w.mamba
+    N, M = w.N, w.M
+    _say("ssd_prefill_gather %s N=%d M=%d K=%d" % (name, N, M, K))
+    t = _mamba_case(w, seed=K + 3)
+    g = torch.Generator(device=DEV).manual_seed(9)
+    idx = torch.randperm(N, generator=g, device=DEV)[:K].sort().values.to(torch.int32)
+    D = torch.randn(s.H, generator=g, device=DEV) if extras else None
+    S_in = torch.randn(s.H, s.P, s.n, generator=g, device=DEV) if extras else None
+    y, S = strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], idx, N, M, D, S_in, chunk=s.chunk)
+    xs, dts, Bs, Cs = (strd.compact(t[k], idx, N, M) for k in ("x", "dt", "B", "C"))
+    y2, S2 = strd.ssd_prefill(xs, dts, t["A"], Bs, Cs, D, S_in, chunk=s.chunk)
+    assert torch.equal(y, y2) and torch.equal(S, S2)  # same arithmetic on the same rows: bit for bit
+    idx_np = idx.cpu().numpy()
+    yw, Sw = oracle.ssd_seq(*(oracle.compact(synth.np64(t[k]), idx_np, N, M)[0] for k in ("x", "dt")),
+                            synth.np64(t["A"]), *(oracle.compact(synth.np64(t[k]), idx_np, N, M)[0] for k in ("B", "C")),
+                            None if D is None else synth.np64(D), None if S_in is None else synth.np64(S_in))
+    tol = TOL[torch.bfloat16]
+    assert_close(synth.np64(y), yw, tol, "gather y")
+    assert_close(synth.np64(S), Sw, tol, "gather S_out")
+
+
+def test_ssd_prefill_gather_refuses_what_the_matrix_core_kernel_does_not_cover():
+    w = synth.WORKLOADS["c1"]  # fp32 I/O
+    t = _mamba_case(w)
+    idx = torch.arange(10, device=DEV, dtype=torch.int32)
+    with pytest.raises(strd.StrdError):
+        strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], idx, w.N, w.M)
+
+
 @pytest.mark.parametrize("name,T", [("c1", 1056), ("c1", 544), ("c3-short", 333), ("c3-short", 1537), ("odd", 100),
                                     ("c1", 1), ("c1", 0), ("d64", 200), ("d64", 705)])
 def test_attn_prefill_parity(name, T):
