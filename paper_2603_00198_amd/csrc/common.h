@@ -97,6 +97,33 @@ __device__ __forceinline__ void lds_read_tr8(const void *p, strd_s16x4 (&r)[8]) 
         : "v"(a), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
         : "memory");
 }
+// The same eight reads without the wait: the results may be used only after lds_settle8() on
+// the same registers.  Splitting issue and wait lets a wave put all the LDS reads of a step in
+// flight at once instead of paying one LDS round trip per group of reads.
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ void lds_issue_tr8(const void *p, strd_s16x4 (&r)[8]) {
+    const uint32_t a = lds_offset(p);
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %8 offset:%9\n\t"
+        "ds_read_b64_tr_b16 %1, %8 offset:%10\n\t"
+        "ds_read_b64_tr_b16 %2, %8 offset:%11\n\t"
+        "ds_read_b64_tr_b16 %3, %8 offset:%12\n\t"
+        "ds_read_b64_tr_b16 %4, %8 offset:%13\n\t"
+        "ds_read_b64_tr_b16 %5, %8 offset:%14\n\t"
+        "ds_read_b64_tr_b16 %6, %8 offset:%15\n\t"
+        "ds_read_b64_tr_b16 %7, %8 offset:%16"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
+        : "v"(a), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
+        : "memory");
+}
+// Wait for every LDS operation of the wave; the registers pass through the statement so that no
+// use of them can be scheduled before it.
+__device__ __forceinline__ void lds_settle8(strd_s16x4 (&r)[8]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+                 :
+                 : "memory");
+}
 __device__ __forceinline__ strd_bf16x8 tr_pair(strd_s16x4 lo, strd_s16x4 hi) {
     return __builtin_shufflevector(__builtin_bit_cast(strd_bf16x4, lo), __builtin_bit_cast(strd_bf16x4, hi), 0, 1, 2, 3,
                                    4, 5, 6, 7);

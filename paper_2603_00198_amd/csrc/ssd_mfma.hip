@@ -25,8 +25,8 @@
 // x and dt: wave 7), far enough ahead to cover HBM latency with only one workgroup per CU: x three steps ahead
 // (ring of 4), dt three steps ahead (ring of 4), the B and C tiles two steps ahead (ring of 3;
 // they are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 (the lightest)
-// turns dt of the next step into the scan l_t, the key factors of (b) and the weighted copy
-// w_j x_j one step ahead.  The bf16 state copy
+// turns dt into the scan l_t and the key factors of (b) two steps ahead, wave 6 (the next
+// lightest) makes the weighted copy w_j x_j one step ahead.  The bf16 state copy
 // is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the last row
 // with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.  Each wave runs a
 // straight-line specialisation (compile-time trip counts).
@@ -61,17 +61,21 @@ struct Lds {
     struct alignas(16) TileX {
         bf16_t x[XT::kBytes / 2];
     };
-    struct alignas(16) Meta {
-        float ell[kQ];      // inclusive cumulative sum of dt*A*log2(e) inside the step
-        float dtv[kQ];      // dt (0 past the end of the sequence)
-        float fw[3][kQ];    // fw[W-1][j] = dt_j * 2^(l_{16W-1} - l_j), j < 16W: key factor for query block W
-        bf16_t xw[kQ][kPB + 8];   // w_j * x_j, w_j = dt_j * 2^(l_Q - l_j): B operand of the state update
+    struct alignas(16) Scan {
+        float ell[kQ];  // inclusive cumulative sum of dt*A*log2(e) inside the step
+        float dtv[kQ];  // dt (0 past the end of the sequence)
+        float fw[96];   // key factors of query block W = 1..3 at fw_at(W): dt_j * 2^(l_{16W-1} - l_j), j < 16W
     };
+    struct alignas(16) Xw {
+        bf16_t v[kQ][kPB + 8];  // w_j * x_j, w_j = dt_j * 2^(l_Q - l_j): B operand of the state update
+    };
+    static constexpr int fw_at(int W) { return W <= 1 ? 0 : W == 2 ? 16 : 48; }
     TileBC bc[3];
     TileX xr[kXRing];
     float dt[kDtRing][kQ];
     uint32_t rowtab[4][kQ];  // gather mode: source row of every token of steps q, q % 4 = slot
-    Meta meta[2];
+    Scan scan[3];  // made two steps ahead
+    Xw xw[2];      // made one step ahead
     bf16_t s[2][kPB][kSP];  // state before the step, [p][n]
 };
 
@@ -81,15 +85,22 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+// value of lane `l` (compile-time constant) in every lane, through a scalar register
+__device__ __forceinline__ float read_lane_f32(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
 
 // The four token-contracted fragments of an x tile (pr = token half, pt = channel half).
 // Token slots of a fragment: s < 4 is token 32*pr + 4*lb + s, s >= 4 adds 16.
+// Issued early (issue_x_frags), usable after take_x_frags.
 template <int PITCH>
-__device__ __forceinline__ void read_x_frags(const bf16_t *xt, int lr, int lb, bf16x8 (&xf)[2][2]) {
+__device__ __forceinline__ void issue_x_frags(const bf16_t *xt, int lr, int lb, strd_s16x4 (&r)[8]) {
     constexpr int R = PITCH * 2;  // row pitch in bytes
-    strd_s16x4 r[8];
-    lds_read_tr8<0, 16 * R, 32, 16 * R + 32, 32 * R, 48 * R, 32 * R + 32, 48 * R + 32>(
+    lds_issue_tr8<0, 16 * R, 32, 16 * R + 32, 32 * R, 48 * R, 32 * R + 32, 48 * R + 32>(
         xt + (4 * lb + (lr >> 2)) * PITCH + 4 * (lr & 3), r);
+}
+__device__ __forceinline__ void take_x_frags(strd_s16x4 (&r)[8], bf16x8 (&xf)[2][2]) {
+    lds_settle8(r);
     xf[0][0] = tr_pair(r[0], r[1]);
     xf[0][1] = tr_pair(r[2], r[3]);
     xf[1][0] = tr_pair(r[4], r[5]);
@@ -109,32 +120,49 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     const size_t y_step = (size_t)kQ * H * P;
     if (GATHER) __syncthreads();  // the barriers of the state waves' prologue: (row tables written,)
     __syncthreads();              // first copies landed,
-    __syncthreads();              // scan of step 0 published
+    __syncthreads();              // scans of steps 0 and 1 published,
+    __syncthreads();              // weighted x of step 0 published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
-        typename L::Meta &bf = lds.meta[cur];
+        typename L::Scan &bf = lds.scan[step % 3];
         typename L::TileBC &tb = lds.bc[step % 3];
         const bf16_t *xt = lds.xr[step % kXRing].x;
+        strd_s16x4 xr8[8];
+        issue_x_frags<L::kXP>(xt, lr, lb, xr8);  // x^T fragments for (c), in flight during (d), (a), (b)
+        // Every LDS read of the step is issued here, before any arithmetic: after the barrier all
+        // eight waves hit the LDS at once and a round trip is long, so the wave pays one, not one
+        // per phase.
         const float el_t = bf.ell[tcol];
-
-        // c_t fragments: B operand of (a) and of (d)
-        bf16x8 cf[KS];
+        const float el_ref = bf.ell[W > 0 ? 16 * W - 1 : 0];
+        f32x4 f_j[W > 0 ? W : 1];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
+        for (int jt = 0; jt < W; ++jt) f_j[jt] = *reinterpret_cast<const f32x4 *>(&bf.fw[L::fw_at(W) + 16 * jt + 4 * lb]);
+        const f32x4 el_j = *reinterpret_cast<const f32x4 *>(&bf.ell[16 * W + 4 * lb]);
+        const f32x4 dt_j = *reinterpret_cast<const f32x4 *>(&bf.dtv[16 * W + 4 * lb]);
+        bf16x8 cf[KS], sf[2][KS], bfr[W + 1][KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {  // c_t fragments: B operand of (a) and of (d)
+            cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+                sf[pt][ks] = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int jt = 0; jt <= W; ++jt)
+                bfr[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
+        __builtin_amdgcn_sched_barrier(0);  // nothing moves across: loads above, arithmetic below
 
-        // (d) first: it only needs the state copy, so it overlaps the (a) -> (b) -> (c) chain
+        // (d): inter-step part from the state copy
         f32x4 yin[2];
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             yin[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 sf = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
-                yin[pt] = mfma16(sf, cf[ks], yin[pt]);
-            }
+            for (int ks = 0; ks < KS; ++ks) yin[pt] = mfma16(sf[pt][ks], cf[ks], yin[pt]);
         }
-
         // (a): G^T tiles for key blocks jt <= W (independent accumulators)
         f32x4 acc[W + 1];
 #pragma unroll
@@ -142,25 +170,19 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int jt = 0; jt <= W; ++jt) {
-                const bf16x8 bfr = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
-                acc[jt] = mfma16(bfr, cf[ks], acc[jt]);
-            }
+            for (int jt = 0; jt <= W; ++jt) acc[jt] = mfma16(bfr[jt][ks], cf[ks], acc[jt]);
         // (b): decay, dt and causal mask; pack pairs of key blocks as B operands of (c).
         // Blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan
         // at the last token before this wave's block (both exponents <= 0); diagonal block: direct.
         bf16x4 m4[4];
-        const float e_ref = W > 0 ? fast_exp2(el_t - bf.ell[W > 0 ? 16 * W - 1 : 0]) : 0.f;
+        const float e_ref = W > 0 ? fast_exp2(el_t - el_ref) : 0.f;
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
             m4[jt] = bf16x4{(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
             if (jt < W) {
-                const f32x4 f_j = *reinterpret_cast<const f32x4 *>(&bf.fw[W > 0 ? W - 1 : 0][16 * jt + 4 * lb]);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) m4[jt][i] = (bf16_t)(acc[jt < W ? jt : W][i] * e_ref * f_j[i]);
+                for (int i = 0; i < 4; ++i) m4[jt][i] = (bf16_t)(acc[jt < W ? jt : W][i] * e_ref * f_j[jt < W ? jt : 0][i]);
             } else if (jt == W) {
-                const f32x4 el_j = *reinterpret_cast<const f32x4 *>(&bf.ell[16 * jt + 4 * lb]);
-                const f32x4 dt_j = *reinterpret_cast<const f32x4 *>(&bf.dtv[16 * jt + 4 * lb]);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float val = acc[W][i] * fast_exp2(el_t - el_j[i]) * dt_j[i];
@@ -171,7 +193,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 
         // (c) intra-step part of Y^T[p, t]
         bf16x8 xf[2][2];
-        read_x_frags<L::kXP>(xt, lr, lb, xf);
+        take_x_frags(xr8, xf);
         f32x4 yacc[2];
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
@@ -296,35 +318,39 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     // Copies a wave issues per step; everything older has landed once at most that many are
     // outstanding (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
     // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-    // (wave 3 consumes x one step before the others, so it lets two steps' worth stay in flight)
-    constexpr int kNewest = SW < 2 ? 2 * BC::kIssues : SW == 3 ? 2 * (XT::kIssues + 1) : 0;
+    constexpr int kNewest = SW < 2 ? 2 * BC::kIssues : SW == 3 ? XT::kIssues + 1 : 0;
     static_assert(kNewest < 64, "vmcnt has 6 bits");
     constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
 
-    // scan of dt*A of `step` from the dt ring into meta[step & 1] (wave SW == 3: lane = token)
-    auto make_meta = [&](int step) {
+    // wave SW == 3, lane = token: scan of dt*A of `step` from the dt ring and the key factors
+    auto make_scan = [&](int step) {
         const float raw = lds.dt[step % kDtRing][lane];
         const float dv = (step * kQ + lane < T) ? raw : 0.f;
         const float inc = wave_inclusive_scan_f32(dv * Al2);
-        const float lq = __shfl(inc, kWave - 1, kWave);
-        typename L::Meta &m = lds.meta[step & 1];
+        typename L::Scan &m = lds.scan[step % 3];
         m.ell[lane] = inc;
         m.dtv[lane] = dv;
 #pragma unroll
         for (int wq = 1; wq < 4; ++wq) {  // only tokens j < 16 * wq are read; the exponent is <= 0 for them
-            const float lref = __shfl(inc, 16 * wq - 1, kWave);
-            m.fw[wq - 1][lane] = dv * fast_exp2(fminf(lref - inc, 0.f));
+            const float lref = read_lane_f32(inc, 16 * wq - 1);
+            if (lane < 16 * wq) m.fw[L::fw_at(wq) + lane] = dv * fast_exp2(lref - inc);
         }
-        // weighted copy of the x row of this lane's token
-        const float wv = dv * fast_exp2(lq - inc);
+    };
+    // wave SW == 2, lane = token: weighted copy of the x row of the token (x tile and scan of
+    // `step` were published by the barrier of an earlier step)
+    auto make_xw = [&](int step) {
         const bf16_t *xrow = lds.xr[step % kXRing].x + lane * L::kXP;
+        bf16x8 xv[kPB / 8];
 #pragma unroll
-        for (int c = 0; c < kPB; c += 8) {
-            const bf16x8 xv = *reinterpret_cast<const bf16x8 *>(xrow + c);
+        for (int c = 0; c < kPB / 8; ++c) xv[c] = *reinterpret_cast<const bf16x8 *>(xrow + 8 * c);
+        const typename L::Scan &m = lds.scan[step % 3];
+        const float wv = m.dtv[lane] * fast_exp2(m.ell[kQ - 1] - m.ell[lane]);
+#pragma unroll
+        for (int c = 0; c < kPB / 8; ++c) {
             bf16x8 xs;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[e] * wv);
-            *reinterpret_cast<bf16x8 *>(&m.xw[lane][c]) = xs;
+            for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[c][e] * wv);
+            *reinterpret_cast<bf16x8 *>(&lds.xw[step & 1].v[lane][8 * c]) = xs;
         }
     };
 
@@ -364,12 +390,17 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
         async_tile_wait();
     }
     __syncthreads();
-    if (SW == 3) make_meta(0);
+    if (SW == 3) {
+        make_scan(0);
+        make_scan(1);
+    }
+    __syncthreads();
+    if (SW == 2) make_xw(0);
     __syncthreads();
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
-        typename L::Meta &bf = lds.meta[cur];
+        typename L::Scan &bf = lds.scan[step % 3];
         typename L::TileBC &tb = lds.bc[step % 3];
         if (SW < 2) request_bc((step + 2) % 3);  // that slot was last read in step - 1
         if (SW == 3) {
@@ -378,16 +409,23 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
         }
 
         // (e) for the rows this wave owns: S^T = 2^(l_Q) S^T + b^T (w x)
-        const float decay_q = fast_exp2(bf.ell[kQ - 1]);
-        bf16x8 xf[2][2];
-        read_x_frags<kPB + 8>(&bf.xw[0][0], lr, lb, xf);
+        // all LDS reads of the step go out together: weighted x, then b^T of every owned tile pair
+        // ([tile][token half], second tile of a pair only used if owned), then the step's decay
+        strd_s16x4 xr8[8], br8[(NT + 1) / 2][8];
+        issue_x_frags<kPB + 8>(&lds.xw[cur].v[0][0], lr, lb, xr8);
 #pragma unroll
         for (int n2 = 0; n2 < NT; n2 += 2) {
-            // b^T fragments of two state tiles: [tile][token half], second tile only if owned
             constexpr int R = L::kCP * 2;
-            strd_s16x4 r[8];
-            lds_read_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
-                &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], r);
+            lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
+                &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], br8[n2 / 2]);
+        }
+        const float decay_q = fast_exp2(bf.ell[kQ - 1]);
+        bf16x8 xf[2][2];
+        take_x_frags(xr8, xf);
+#pragma unroll
+        for (int n2 = 0; n2 < NT; n2 += 2) {
+            strd_s16x4(&r)[8] = br8[n2 / 2];
+            lds_settle8(r);
 #pragma unroll
             for (int d = 0; d < 2; ++d) {
                 if (n2 + d < NT) {
@@ -413,9 +451,10 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
             }
         if (SW < 2) __builtin_amdgcn_s_waitcnt(kWaitOlder);  // the B / C copies issued in earlier steps have landed
         if (SW == 3) {
-            __builtin_amdgcn_s_waitcnt(kWaitOlder);  // x and dt of step + 1 (requested in earlier steps) have landed
-            make_meta(step + 1);                     // last thing in the step: the copy had two steps to arrive
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);  // x and dt up to step + 2 (requested in earlier steps) have landed
+            make_scan(step + 2);                     // last thing in the step
         }
+        if (SW == 2) make_xw(step + 1);  // x of step + 1 was waited for by wave SW == 3 before the last barrier
         if (GATHER && SW == 2) {
             // rows of step + 4: read from step + 1 (x, dt) and step + 2 (B, C) on; the slot held the
             // rows of this step, last read two steps ago
@@ -436,7 +475,7 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
 }
 
 template <int NS, bool GATHER>
-__global__ __launch_bounds__(kThreads) void ssd_mfma_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void ssd_mfma_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ dt, const float *__restrict__ A,
     const bf16_t *__restrict__ B, const bf16_t *__restrict__ C, const float *__restrict__ D,
     const float *__restrict__ S_in, bf16_t *__restrict__ y, float *__restrict__ S_out,
