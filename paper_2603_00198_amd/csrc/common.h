@@ -38,7 +38,9 @@ __host__ __forceinline__ int xcd_grid(int n) { return (n + kXcd - 1) / kXcd * kX
 // slot by slot: slot s = row * (VR + PAD) + cv; pad slots (cv >= VR) re-read the row's last vector.
 // Slots are dealt to the NW waves of the workgroup 64 at a time; lanes whose slot lies past the
 // end of the tile copy nothing, so the tile occupies exactly ROWS * (VR + PAD) * 16 bytes.
-template <int ROWS, int VR, int NW, int PAD = 1>
+// SKIP_PAD: lanes on pad slots copy nothing either (the pad bytes stay unwritten and must never
+// be read into a result), which saves PAD / (VR + PAD) of the copy traffic.
+template <int ROWS, int VR, int NW, int PAD = 1, bool SKIP_PAD = false>
 struct AsyncTile {
     static constexpr int kVP = VR + PAD;                                // vectors per LDS row
     static constexpr int kPitch = kVP * 8;                              // bf16 elements per LDS row
@@ -56,7 +58,8 @@ struct AsyncTile {
     __device__ static __forceinline__ void issue(const void *src, void *lds_tile, int wave, int i) {
         char *dst = reinterpret_cast<char *>(lds_tile) + (i * NW + wave) * 1024;
         const int s = (i * NW + wave) * 64 + (int)(threadIdx.x & 63);
-        if ((i + 1) * NW * 64 <= kSlots || s < kSlots)  // only the last round can run past the tile
+        if (((i + 1) * NW * 64 <= kSlots || s < kSlots) &&  // only the last round can run past the tile
+            (!SKIP_PAD || s % kVP < VR))
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     }

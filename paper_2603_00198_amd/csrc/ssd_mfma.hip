@@ -23,8 +23,11 @@
 //
 // Memory.  Every input reaches LDS by asynchronous global -> LDS copies (B and C: waves 4 and 5;
 // x and dt: wave 7), far enough ahead to cover HBM latency with only one workgroup per CU: x three steps ahead
-// (ring of 4), dt three steps ahead (ring of 4), the B and C tiles two steps ahead (ring of 3;
-// they are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 (the lightest)
+// (ring of 4), dt three steps ahead (ring of 4), the B and C tiles three steps ahead (ring of 3:
+// a tile has landed two steps before its step, is read into registers during the step before
+// its step -- every wave fetches its B / C / x operands in the tail of the previous step and the
+// output waves compute (a) there -- and its slot is refilled during its own step; the tiles
+// are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 (the lightest)
 // turns dt into the scan l_t and the key factors of (b) two steps ahead, wave 6 (the next
 // lightest) makes the weighted copy w_j x_j one step ahead.  The bf16 state copy
 // is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the last row
@@ -41,16 +44,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 64;         // tokens per step
 constexpr int kPB = 32;        // channels of the head per workgroup
-constexpr int kThreads = 512;  // 4 output waves + 4 state waves
+constexpr int kThreads = 640;  // 4 output waves + 4 state waves + 2 copy waves
 constexpr float kLog2e = 1.4426950408889634f;
 
 constexpr int kXRing = 4;   // x tiles in LDS (requested kXRing - 1 steps ahead)
-constexpr int kDtRing = 4;  // dt rows in LDS (requested kDtRing - 1 steps ahead)
+constexpr int kDtRing = 5;  // dt rows in LDS (requested kDtRing - 1 steps ahead)
 
 template <int NS>
 struct Lds {
-    using BC = AsyncTile<kQ, NS / 8, 2, 2>;   // B / C tile, filled by 2 waves, 2 pad vectors per row
-    using XT = AsyncTile<kQ, kPB / 8, 1, 1>;  // x tile of the slab, filled by one wave, 1 pad vector per row
+    using BC = AsyncTile<kQ, NS / 8, 2, 2, true>;   // B / C tile, filled by two waves, 2 pad vectors per row
+    using XT = AsyncTile<kQ, kPB / 8, 1, 1, true>;  // x tile of the slab, filled by one wave, 1 pad vector per row
     static constexpr int kCP = BC::kPitch;    // bf16 elements per row of the B / C tiles
     static constexpr int kXP = XT::kPitch;    // bf16 elements per row of the x tiles
     static constexpr int kSP = NS + 8;        // bf16 elements per row of the state copy
@@ -118,21 +121,46 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     const int tcol = 16 * W + lr;  // this lane's token inside the step
     bf16_t *yp = y + ((size_t)tcol * H + h) * P + p0 + 4 * lb;
     const size_t y_step = (size_t)kQ * H * P;
-    if (GATHER) __syncthreads();  // the barriers of the state waves' prologue: (row tables written,)
+    // Operands that come from the B / C / x tiles alone are fetched one step early, in the tail
+    // of the previous step when the LDS is quiet, and (a) is computed there too: carried from
+    // step to step are c_t (for (d)), G^T and the x^T fragments of the coming step.
+    bf16x8 cf[KS], xf[2][2];
+    f32x4 acc[W + 1];
+    auto fetch = [&](int q) {
+        typename L::TileBC &tb = lds.bc[q % 3];
+        strd_s16x4 xr8[8];
+        issue_x_frags<L::kXP>(lds.xr[q % kXRing].x, lr, lb, xr8);
+        bf16x8 bfr[W + 1][KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int jt = 0; jt <= W; ++jt)
+                bfr[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
+        __builtin_amdgcn_sched_barrier(0);  // nothing moves across: loads above, arithmetic below
+        // (a): G^T tiles for key blocks jt <= W (independent accumulators)
+#pragma unroll
+        for (int jt = 0; jt <= W; ++jt) acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int jt = 0; jt <= W; ++jt) acc[jt] = mfma16(bfr[jt][ks], cf[ks], acc[jt]);
+        take_x_frags(xr8, xf);
+    };
+
+    if (GATHER) __syncthreads();  // the barriers of the prologue: (row tables written,)
     __syncthreads();              // first copies landed,
+    fetch(0);
     __syncthreads();              // scans of steps 0 and 1 published,
     __syncthreads();              // weighted x of step 0 published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
         typename L::Scan &bf = lds.scan[step % 3];
-        typename L::TileBC &tb = lds.bc[step % 3];
-        const bf16_t *xt = lds.xr[step % kXRing].x;
-        strd_s16x4 xr8[8];
-        issue_x_frags<L::kXP>(xt, lr, lb, xr8);  // x^T fragments for (c), in flight during (d), (a), (b)
-        // Every LDS read of the step is issued here, before any arithmetic: after the barrier all
-        // eight waves hit the LDS at once and a round trip is long, so the wave pays one, not one
-        // per phase.
+        // What depends on the previous step (state copy, scan) is read here, all of it before any
+        // arithmetic: after the barrier all eight waves hit the LDS at once and a round trip is
+        // long, so the wave pays one, not one per phase.
         const float el_t = bf.ell[tcol];
         const float el_ref = bf.ell[W > 0 ? 16 * W - 1 : 0];
         f32x4 f_j[W > 0 ? W : 1];
@@ -140,20 +168,13 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
         for (int jt = 0; jt < W; ++jt) f_j[jt] = *reinterpret_cast<const f32x4 *>(&bf.fw[L::fw_at(W) + 16 * jt + 4 * lb]);
         const f32x4 el_j = *reinterpret_cast<const f32x4 *>(&bf.ell[16 * W + 4 * lb]);
         const f32x4 dt_j = *reinterpret_cast<const f32x4 *>(&bf.dtv[16 * W + 4 * lb]);
-        bf16x8 cf[KS], sf[2][KS], bfr[W + 1][KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {  // c_t fragments: B operand of (a) and of (d)
-            cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-                sf[pt][ks] = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
-        }
+        bf16x8 sf[2][KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int jt = 0; jt <= W; ++jt)
-                bfr[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
-        __builtin_amdgcn_sched_barrier(0);  // nothing moves across: loads above, arithmetic below
+            for (int pt = 0; pt < 2; ++pt)
+                sf[pt][ks] = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
+        __builtin_amdgcn_sched_barrier(0);
 
         // (d): inter-step part from the state copy
         f32x4 yin[2];
@@ -163,14 +184,6 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) yin[pt] = mfma16(sf[pt][ks], cf[ks], yin[pt]);
         }
-        // (a): G^T tiles for key blocks jt <= W (independent accumulators)
-        f32x4 acc[W + 1];
-#pragma unroll
-        for (int jt = 0; jt <= W; ++jt) acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int jt = 0; jt <= W; ++jt) acc[jt] = mfma16(bfr[jt][ks], cf[ks], acc[jt]);
         // (b): decay, dt and causal mask; pack pairs of key blocks as B operands of (c).
         // Blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan
         // at the last token before this wave's block (both exponents <= 0); diagonal block: direct.
@@ -190,10 +203,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
                 }
             }
         }
-
         // (c) intra-step part of Y^T[p, t]
-        bf16x8 xf[2][2];
-        take_x_frags(xr8, xf);
         f32x4 yacc[2];
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
@@ -206,6 +216,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
         }
         const float carry = fast_exp2(el_t);
         if (step * kQ + tcol < T) {
+            const bf16_t *xt = lds.xr[step % kXRing].x;
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt) {
                 bf16x4 out;
@@ -222,90 +233,26 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
             }
         }
         yp += y_step;
-        lds_barrier();  // the y stores stay in flight
+        fetch(step + 1);  // its tiles were published by the barrier that ended the previous step
+        lds_barrier();    // the y stores stay in flight
     }
 }
 
-// State wave SW: owns NT 16-row tiles of the state starting at tile T0, stages x / dt (all
-// state waves) and issues the B / C tile copies (SW < 2).
-// GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
-// kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy.
+// State wave SW: owns NT 16-row tiles of the state starting at tile T0 and does (e) for them;
+// SW == 3 also makes the scans, SW == 2 the weighted x and, in gather mode, the row tables.
 template <int NS, int SW, bool GATHER>
-__device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
-                                           const float *__restrict__ A, const bf16_t *__restrict__ B,
-                                           const bf16_t *__restrict__ C, const float *__restrict__ S_in,
+__device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict__ A, const float *__restrict__ S_in,
                                            float *__restrict__ S_out, const int32_t *__restrict__ idx, int N, int K,
-                                           int T, int H, int P, int G, int h, int p0, int g, int nsteps) {
+                                           int T, int P, int h, int p0, int nsteps) {
     using L = Lds<NS>;
-    using BC = typename L::BC;
     // state tiles per wave, in the opposite proportion to the causal work of the output wave
     // on the same SIMD (n = 128: 3, 2, 2, 1 of 8 tiles; n = 64: one tile each)
     constexpr int NT = NS == 128 ? (SW == 0 ? 3 : SW == 3 ? 1 : 2) : 1;
     constexpr int T0 = NS == 128 ? (SW == 0 ? 0 : SW == 1 ? 3 : SW == 2 ? 5 : 7) : SW;
-    using XT = typename L::XT;
     const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
     const float Al2 = A[h] * kLog2e;
 
-    // ---- asynchronous copies: waves SW < 2 fetch the B / C tiles, wave SW == 3 fetches x and dt
-    // (it is their first consumer).  Byte offsets at the next step to request, per-step strides
-    // and end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes them inert).
-    const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
-    // dense mode: running offsets; gather mode: (row in the step, column offset) per copy and the
-    // number of the next step to request, the row itself comes from the row table
-    uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues], off_x[XT::kIssues], lim_x[XT::kIssues];
-    int row_bc[BC::kIssues], row_x[XT::kIssues];
-    uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
-    const uint32_t lim_dt = (uint32_t)(T - 1) * dt_row + (uint32_t)h * 4;
-    int next_bc = 0, next_x = 0, next_dt = 0;
-    if (SW < 2) {
-#pragma unroll
-        for (int i = 0; i < BC::kIssues; ++i) {
-            int cv;
-            BC::slot(SW, lane, i, row_bc[i], cv);
-            const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
-            off_bc[i] = GATHER ? col : (uint32_t)row_bc[i] * bc_row + col;
-            lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
-        }
-    }
-    if (SW == 3) {
-#pragma unroll
-        for (int i = 0; i < XT::kIssues; ++i) {
-            int cv;
-            XT::slot(0, lane, i, row_x[i], cv);
-            const uint32_t col = ((uint32_t)h * P + p0 + cv * 8) * 2;
-            off_x[i] = GATHER ? col : (uint32_t)row_x[i] * x_row + col;
-            lim_x[i] = (uint32_t)(T - 1) * x_row + col;
-        }
-    }
-    // each call requests the next not yet requested step of its stream into ring slot b
-    auto request_bc = [&](int b) {
-#pragma unroll
-        for (int i = 0; i < BC::kIssues; ++i) {
-            const uint32_t o = GATHER ? lds.rowtab[next_bc & 3][row_bc[i]] * bc_row + off_bc[i] : min(off_bc[i], lim_bc[i]);
-            BC::issue(reinterpret_cast<const char *>(C) + o, lds.bc[b].c, SW, i);
-            BC::issue(reinterpret_cast<const char *>(B) + o, lds.bc[b].b, SW, i);
-            if (!GATHER) off_bc[i] += kQ * bc_row;
-        }
-        ++next_bc;
-    };
-    auto request_x = [&](int b) {
-#pragma unroll
-        for (int i = 0; i < XT::kIssues; ++i) {
-            const uint32_t o = GATHER ? lds.rowtab[next_x & 3][row_x[i]] * x_row + off_x[i] : min(off_x[i], lim_x[i]);
-            XT::issue(reinterpret_cast<const char *>(x) + o, lds.xr[b].x, 0, i);
-            if (!GATHER) off_x[i] += kQ * x_row;
-        }
-        ++next_x;
-    };
-    auto request_dt = [&](int b) {  // 64 lanes x 4 bytes
-        const uint32_t o = GATHER ? lds.rowtab[next_dt & 3][lane] * dt_row + (uint32_t)h * 4 : min(off_dt, lim_dt);
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + o),
-            (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
-        off_dt += kQ * dt_row;
-        ++next_dt;
-    };
-    // gather mode, wave SW == 2 (it issues no copies, so its own loads disturb nobody's count of
+    // gather mode, wave SW == 2 (it issues no copies, so its loads disturb nobody's count of
     // outstanding copies): source rows of the tokens of `step`, tokens past T repeat the last one
     // (an index outside [0, N) is clamped into the tensors instead of faulting).  The load runs one
     // step ahead of the store so that its latency never sits inside a step.
@@ -315,13 +262,6 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
         return min((uint32_t)(t < K ? idx[t] : N + (t - K)), last_row);
     };
     uint32_t row_ahead = 0;
-    // Copies a wave issues per step; everything older has landed once at most that many are
-    // outstanding (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
-    // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-    constexpr int kNewest = SW < 2 ? 2 * BC::kIssues : SW == 3 ? XT::kIssues + 1 : 0;
-    static_assert(kNewest < 64, "vmcnt has 6 bits");
-    constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
-
     // wave SW == 3, lane = token: scan of dt*A of `step` from the dt ring and the key factors
     auto make_scan = [&](int step) {
         const float raw = lds.dt[step % kDtRing][lane];
@@ -367,29 +307,46 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
             bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
             *reinterpret_cast<bf16x4 *>(&lds.s[0][pp][n0]) = sv;
         }
-    // prologue: (row tables of the first steps,) fill the rings up to their look-ahead, then the
-    // meta data of step 0
+    // b^T fragments of the owned state tiles ([tile][token half]) are read from the B tile one
+    // step early, in the tail of the previous step, like the output waves' tile operands
+    bf16x8 bt[NT][2];
+    auto fetch_b = [&](int q) {
+        typename L::TileBC &tb = lds.bc[q % 3];
+        strd_s16x4 br8[(NT + 1) / 2][8];
+#pragma unroll
+        for (int n2 = 0; n2 < NT; n2 += 2) {  // two tiles per group of reads, the second only used if owned
+            constexpr int R = L::kCP * 2;
+            lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
+                &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], br8[n2 / 2]);
+        }
+#pragma unroll
+        for (int n2 = 0; n2 < NT; n2 += 2) {
+            lds_settle8(br8[n2 / 2]);
+#pragma unroll
+            for (int d = 0; d < 2; ++d)
+                if (n2 + d < NT) {
+#pragma unroll
+                    for (int pr = 0; pr < 2; ++pr)
+                        bt[n2 + d][pr] = tr_pair(br8[n2 / 2][4 * d + 2 * pr], br8[n2 / 2][4 * d + 2 * pr + 1]);
+                }
+        }
+    };
+
+    // prologue, in step with the copy waves: (row tables 0..3 |) first copies landed | scans 0
+    // and 1 (, row table 4) | weighted x 0
     if (GATHER) {
         if (SW == 2) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
-            row_ahead = load_row(4);
         }
         __syncthreads();
     }
-    if (SW < 2) {
-        request_bc(0);
-        request_bc(1);
-        async_tile_wait();
-    }
-    if (SW == 3) {
-#pragma unroll
-        for (int i = 0; i < kXRing - 1; ++i) request_x(i);
-#pragma unroll
-        for (int i = 0; i < kDtRing - 1; ++i) request_dt(i);
-        async_tile_wait();
-    }
     __syncthreads();
+    if (GATHER && SW == 2) {  // the prologue's requests have read table 0
+        lds.rowtab[0][lane] = load_row(4);
+        row_ahead = load_row(5);
+    }
+    fetch_b(0);
     if (SW == 3) {
         make_scan(0);
         make_scan(1);
@@ -401,44 +358,20 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
         typename L::Scan &bf = lds.scan[step % 3];
-        typename L::TileBC &tb = lds.bc[step % 3];
-        if (SW < 2) request_bc((step + 2) % 3);  // that slot was last read in step - 1
-        if (SW == 3) {
-            request_x((step + kXRing - 1) % kXRing);  // slot last read in step - 1
-            request_dt((step + kDtRing - 1) % kDtRing);
-        }
-
         // (e) for the rows this wave owns: S^T = 2^(l_Q) S^T + b^T (w x)
-        // all LDS reads of the step go out together: weighted x, then b^T of every owned tile pair
-        // ([tile][token half], second tile of a pair only used if owned), then the step's decay
-        strd_s16x4 xr8[8], br8[(NT + 1) / 2][8];
+        strd_s16x4 xr8[8];
         issue_x_frags<kPB + 8>(&lds.xw[cur].v[0][0], lr, lb, xr8);
-#pragma unroll
-        for (int n2 = 0; n2 < NT; n2 += 2) {
-            constexpr int R = L::kCP * 2;
-            lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
-                &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], br8[n2 / 2]);
-        }
         const float decay_q = fast_exp2(bf.ell[kQ - 1]);
         bf16x8 xf[2][2];
         take_x_frags(xr8, xf);
 #pragma unroll
-        for (int n2 = 0; n2 < NT; n2 += 2) {
-            strd_s16x4(&r)[8] = br8[n2 / 2];
-            lds_settle8(r);
+        for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-            for (int d = 0; d < 2; ++d) {
-                if (n2 + d < NT) {
+            for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] *= decay_q;
 #pragma unroll
-                    for (int pt = 0; pt < 2; ++pt) sacc[n2 + d][pt] *= decay_q;
+            for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-                    for (int pr = 0; pr < 2; ++pr) {
-                        const bf16x8 bt = tr_pair(r[4 * d + 2 * pr], r[4 * d + 2 * pr + 1]);
-#pragma unroll
-                        for (int pt = 0; pt < 2; ++pt) sacc[n2 + d][pt] = mfma16(bt, xf[pr][pt], sacc[n2 + d][pt]);
-                    }
-                }
-            }
+                for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] = mfma16(bt[nt][pr], xf[pr][pt], sacc[nt][pt]);
         }
         // publish the new state copy
 #pragma unroll
@@ -449,19 +382,17 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
                 bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                 *reinterpret_cast<bf16x4 *>(&lds.s[cur ^ 1][pt * 16 + lr][(T0 + nt) * 16 + lb * 4]) = sv;
             }
-        if (SW < 2) __builtin_amdgcn_s_waitcnt(kWaitOlder);  // the B / C copies issued in earlier steps have landed
-        if (SW == 3) {
-            __builtin_amdgcn_s_waitcnt(kWaitOlder);  // x and dt up to step + 2 (requested in earlier steps) have landed
-            make_scan(step + 2);                     // last thing in the step
-        }
-        if (SW == 2) make_xw(step + 1);  // x of step + 1 was waited for by wave SW == 3 before the last barrier
+        fetch_b(step + 1);  // its tile was published by the barrier that ended the previous step
+        // dt up to step + 2 and x up to step + 1 landed before the barrier that ended the previous step
+        if (SW == 3) make_scan(step + 2);
+        if (SW == 2) make_xw(step + 1);
         if (GATHER && SW == 2) {
-            // rows of step + 4: read from step + 1 (x, dt) and step + 2 (B, C) on; the slot held the
-            // rows of this step, last read two steps ago
-            lds.rowtab[step & 3][lane] = row_ahead;
-            row_ahead = load_row(step + 5);
+            // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
+            // rows of step + 1, last used two steps ago
+            lds.rowtab[(step + 1) & 3][lane] = row_ahead;
+            row_ahead = load_row(step + 6);
         }
-        lds_barrier();  // this step's copies stay in flight
+        lds_barrier();
     }
 
     if (S_out) {
@@ -474,8 +405,113 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const bf16_t *__restric
     }
 }
 
+// Copy waves: every input reaches LDS through their asynchronous global -> LDS copies (B and C:
+// half a tile each; x and dt: copy wave 0).  They run ahead of the consumers by a fixed number
+// of steps and block on the copy path instead of them.
+// GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
+// kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy;
+// the rows of a step come from a table that state wave 2 keeps five steps ahead.
+template <int NS, int CW, bool GATHER>
+__device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
+                                          const bf16_t *__restrict__ B, const bf16_t *__restrict__ C,
+                                          int T, int H, int P, int G, int h, int p0, int g, int nsteps) {
+    using L = Lds<NS>;
+    using BC = typename L::BC;
+    using XT = typename L::XT;
+    const int lane = threadIdx.x & 63;
+    // Byte offsets (32 bits) of this lane's copies at the next step to request, per-step strides and
+    // end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes them inert).
+    const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
+    // dense mode: running offsets; gather mode: (row in the step, column offset) per copy and the
+    // number of the next step to request, the row itself comes from the row table
+    uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues], off_x[XT::kIssues], lim_x[XT::kIssues];
+    int row_bc[BC::kIssues], row_x[XT::kIssues];
+    uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
+    const uint32_t lim_dt = (uint32_t)(T - 1) * dt_row + (uint32_t)h * 4;
+    int next_bc = 0, next_x = 0, next_dt = 0;
+#pragma unroll
+    for (int i = 0; i < BC::kIssues; ++i) {
+        int cv;
+        BC::slot(CW, lane, i, row_bc[i], cv);
+        const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
+        off_bc[i] = GATHER ? col : (uint32_t)row_bc[i] * bc_row + col;
+        lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
+    }
+#pragma unroll
+    for (int i = 0; i < XT::kIssues; ++i) {
+        int cv;
+        XT::slot(0, lane, i, row_x[i], cv);
+        const uint32_t col = ((uint32_t)h * P + p0 + cv * 8) * 2;
+        off_x[i] = GATHER ? col : (uint32_t)row_x[i] * x_row + col;
+        lim_x[i] = (uint32_t)(T - 1) * x_row + col;
+    }
+    // each call requests the next not yet requested step of its stream into ring slot b
+    auto request_bc = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < BC::kIssues; ++i) {
+            const uint32_t o = GATHER ? lds.rowtab[next_bc & 3][row_bc[i]] * bc_row + off_bc[i] : min(off_bc[i], lim_bc[i]);
+            BC::issue(reinterpret_cast<const char *>(C) + o, lds.bc[b].c, CW, i);
+            BC::issue(reinterpret_cast<const char *>(B) + o, lds.bc[b].b, CW, i);
+            if (!GATHER) off_bc[i] += kQ * bc_row;
+        }
+        ++next_bc;
+    };
+    auto request_x = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < XT::kIssues; ++i) {
+            const uint32_t o = GATHER ? lds.rowtab[next_x & 3][row_x[i]] * x_row + off_x[i] : min(off_x[i], lim_x[i]);
+            XT::issue(reinterpret_cast<const char *>(x) + o, lds.xr[b].x, 0, i);
+            if (!GATHER) off_x[i] += kQ * x_row;
+        }
+        ++next_x;
+    };
+    auto request_dt = [&](int b) {  // 64 lanes x 4 bytes
+        const uint32_t o = GATHER ? lds.rowtab[next_dt & 3][lane] * dt_row + (uint32_t)h * 4 : min(off_dt, lim_dt);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + o),
+            (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
+        off_dt += kQ * dt_row;
+        ++next_dt;
+    };
+    // Copies issued per step; everything older has landed once at most that many are outstanding
+    // (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
+    // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+    constexpr int kNewest = 2 * BC::kIssues + (CW == 0 ? XT::kIssues + 1 : 0);
+    static_assert(kNewest < 64, "vmcnt has 6 bits");
+    constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
+
+    // prologue: fill the rings up to their look-ahead (B / C and x: steps 0..2, dt: steps 0..3)
+    if (GATHER) __syncthreads();  // row tables of steps 0..3 written
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (q < 3) {
+            request_bc(q);
+            if (CW == 0) request_x(q);
+        }
+        if (CW == 0) request_dt(q);
+    }
+    async_tile_wait();
+    __syncthreads();  // first copies landed
+    __syncthreads();  // (scans of steps 0 and 1)
+    __syncthreads();  // (weighted x of step 0)
+
+    for (int step = 0; step < nsteps; ++step) {
+        if (step + 3 < nsteps) {  // uniform; nothing past the last step is requested
+            request_bc(step % 3);                        // tile step + 3; the slot's tile (step) was read in step - 1
+            if (CW == 0) {
+                request_x((step + kXRing - 1) % kXRing);     // x of step + 3; slot last read in step - 1
+                request_dt((step + kDtRing - 1) % kDtRing);  // dt of step + 4; slot last read in step - 3
+            }
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);      // everything requested in earlier steps has landed
+        } else {
+            async_tile_wait();
+        }
+        lds_barrier();  // publishes it; this step's copies stay in flight
+    }
+}
+
 template <int NS, bool GATHER>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void ssd_mfma_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 3))) void ssd_mfma_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ dt, const float *__restrict__ A,
     const bf16_t *__restrict__ B, const bf16_t *__restrict__ C, const float *__restrict__ D,
     const float *__restrict__ S_in, bf16_t *__restrict__ y, float *__restrict__ S_out,
@@ -494,10 +530,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         case 1: output_wave<NS, 1, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
         case 2: output_wave<NS, 2, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
         case 3: output_wave<NS, 3, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        case 4: state_wave<NS, 0, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
-        case 5: state_wave<NS, 1, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
-        case 6: state_wave<NS, 2, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
-        default: state_wave<NS, 3, GATHER>(lds, x, dt, A, B, C, S_in, S_out, idx, N, K, T, H, P, G, h, p0, g, nsteps); break;
+        case 4: state_wave<NS, 0, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
+        case 5: state_wave<NS, 1, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
+        case 6: state_wave<NS, 2, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
+        case 7: state_wave<NS, 3, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
+        case 8: copy_wave<NS, 0, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
+        default: copy_wave<NS, 1, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
     }
 }
 
