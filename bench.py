@@ -110,7 +110,9 @@ class MambaLayer:
         self.scores = e(N, dtype=torch.float32)
         self.idx = e(K, dtype=torch.int32)
         Tr = K + M
-        self.o = {"hidden": e(Tr, w.d_model)}
+        self.o = {"x": e(Tr, s.H, s.P), "B": e(Tr, s.G, s.n), "C": e(Tr, s.G, s.n),
+                  "dt": e(Tr, s.H, dtype=torch.float32), "hidden": e(Tr, w.d_model)}
+        self.fused = False   # True: ssd_prefill_gather reads x, dt, B, C through idx; only hidden is compacted
         self.y_red = e(Tr, s.H, s.P)
         self.y_full = e(w.T, s.H, s.P)
         lib = strd.lib()
@@ -128,13 +130,21 @@ class MambaLayer:
 
     def compact(self):
         N, M = self.w.N, self.w.M
-        # the scan reads its inputs through the index list, so only the residual stream moves
-        self.strd.compact_batch([self.hidden], self.idx, N, M, outs=[self.o["hidden"]])
+        if self.fused:   # the scan reads its inputs through the index list, so only the residual stream moves
+            self.strd.compact_batch([self.hidden], self.idx, N, M, outs=[self.o["hidden"]])
+            return
+        keys = ("x", "B", "C", "dt")
+        self.strd.compact_batch([self.t[k] for k in keys] + [self.hidden], self.idx, N, M,
+                                outs=[self.o[k] for k in keys] + [self.o["hidden"]])
 
     def mixer_reduced(self):
-        t = self.t
-        self.strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], self.idx, self.w.N, self.w.M,
-                                     chunk=self.s.chunk, want_state=False, out=self.y_red)
+        t, o = self.t, self.o
+        if self.fused:
+            self.strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], self.idx, self.w.N, self.w.M,
+                                         chunk=self.s.chunk, want_state=False, out=self.y_red)
+        else:
+            self.strd.ssd_prefill(o["x"], o["dt"], t["A"], o["B"], o["C"], chunk=self.s.chunk, want_state=False,
+                                  out=self.y_red, ws=self.ws)
 
     def mixer_full(self):
         t = self.t
@@ -160,8 +170,8 @@ class MambaLayer:
 
     def compact_bytes(self):
         w, s, eb = self.w, self.s, self.hidden.element_size()
-        row = w.d_model * eb
-        return 2 * (w.K + w.M) * row + 4 * w.K
+        row = w.d_model * eb if self.fused else (s.H * s.P + 2 * s.G * s.n + w.d_model) * eb + 4 * s.H
+        return 2 * (w.K + w.M) * row + 4 * w.K * (1 if self.fused else 5)
 
     mixer_name, mixer_bound = "ssd_prefill", "hbm"
 
@@ -374,6 +384,22 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         roof = {"bound": "mfma", "kernel": layer.mixer_name, "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((name, budget))}
+    fused = None
+    if kind == "mamba":   # variant: the scan gathers its inputs itself (same y, bit for bit; see tests)
+        layer.fused = True
+        for _ in range(warmup):
+            layer.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            layer.step()
+        torch.cuda.synchronize()
+        ms_fused = (time.perf_counter() - t0) * 1e3 / steps
+        fused = {"ms_per_step": ms_fused, "tokens_per_s": w.T / (ms_fused * 1e-3), "speedup_vs_full": ms_full / ms_fused,
+                 "compact_us": 1e3 * time_events(torch, layer.compact),
+                 "mixer_reduced_us": 1e3 * time_events(torch, layer.mixer_reduced),
+                 "note": "ssd_prefill_gather reads x, dt, B, C through idx; only the residual stream is compacted"}
+        layer.fused = False
     res = {
         "layer": kind, "workload": name, "N": w.N, "M": w.M, "K": w.K, "budget": budget,
         "ms_per_step": ms_step, "graph_replay_ms_per_step": ms_graph, "tokens_per_s": w.T / (ms_step * 1e-3),
@@ -381,6 +407,8 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         "calls": calls, "select_plus_compact_GBps": sel_compact_gbs,
         "select_plus_compact_frac_of_hbm": sel_compact_gbs / HBM_PEAK_GBS, "roofline": roof,
     }
+    if fused:
+        res["gather_fused_variant"] = fused
     return res, layer
 
 
@@ -421,6 +449,8 @@ def main():
         "select_plus_compact_frac_of_hbm": res["select_plus_compact_frac_of_hbm"],
         "roofline": res["roofline"], "context": PAPER_CONTEXT,
     }
+    if "gather_fused_variant" in res:
+        line["gather_fused_variant"] = res["gather_fused_variant"]
     if name == "c2" and not args.no_attention_extra:
         del layer
         torch.cuda.empty_cache()
