@@ -120,10 +120,15 @@ class MambaLayer:
         nb = max(lib.strd_score_mamba_workspace(M, N, s.H, s.G, s.n, io),
                  lib.strd_ssd_prefill_workspace(w.T, s.H, s.P, s.G, s.n, s.chunk, io), 16)
         self.ws = e(nb, dtype=torch.uint8)
+        self.ws_full = e(max(lib.strd_score_mamba_full_workspace(M, N, s.H, s.G, s.n, io), 16), dtype=torch.uint8)
+        self.scores_full = e(N, dtype=torch.float32)
         self.mixer_ev = None
 
     def score(self):
         self.strd.score_mamba(self.Bv, self.Ct, self.dtv, out=self.scores, ws=self.ws)
+
+    def score_full(self):   # the Full Mamba Dynamic score (ablation row), not part of the step
+        self.strd.score_mamba_full(self.Bv, self.Ct, self.t["dt"], self.t["A"], out=self.scores_full, ws=self.ws_full)
 
     def select(self):
         self.strd.select_topk(self.scores, self.w.K, out=self.idx)
@@ -400,6 +405,7 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
                  "mixer_reduced_us": 1e3 * time_events(torch, layer.mixer_reduced),
                  "note": "ssd_prefill_gather reads x, dt, B, C through idx; only the residual stream is compacted"}
         layer.fused = False
+        fused["score_mamba_full_us"] = 1e3 * time_events(torch, layer.score_full)
     res = {
         "layer": kind, "workload": name, "N": w.N, "M": w.M, "K": w.K, "budget": budget,
         "ms_per_step": ms_step, "graph_replay_ms_per_step": ms_graph, "tokens_per_s": w.T / (ms_step * 1e-3),
@@ -451,6 +457,9 @@ def main():
     }
     if "gather_fused_variant" in res:
         line["gather_fused_variant"] = res["gather_fused_variant"]
+        line["next_rows"] = {"score_mamba_full_us": line["gather_fused_variant"].pop("score_mamba_full_us"),
+                             "note": "Full Mamba Dynamic score (decayed |w_tj|) on the same inputs; an ablation "
+                                     "row, not part of the timed step"}
     if name == "c2" and not args.no_attention_extra:
         del layer
         torch.cuda.empty_cache()

@@ -84,6 +84,23 @@ int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, 
                      void *stream);
 
 /* ---------------------------------------------------------------------------
+ * score_mamba_full -- the Full Mamba Dynamic score (|w_{t,j}| of Eq. "ssm_weight"),
+ * which the decay-free score above is ablated against: every term carries the
+ * decay of the recurrence from vision token i to text row m,
+ *     s_i = 1/(M*H) * sum_{m,h} dt_i^h * | b_i^{g(h)} . c_m^{g(h)} | * prod_{u=i+1}^{N+m} exp(dt_u^h * A^h).
+ * With A = 0 it equals score_mamba.
+ *   B_vis  [dev] [N, G, n]      C_txt [dev] [M, G, n]
+ *   dt_all [dev] [N+M, H] fp32  steps of every token, vision rows first (the decay runs through
+ *                               the later vision tokens and the text rows up to m)
+ *   A      [dev] [H] fp32 (< 0) scores [dev] [N] fp32 output
+ * Requires M,N >= 1, H % G == 0; the workspace is always needed.  Deterministic.
+ * ------------------------------------------------------------------------- */
+size_t strd_score_mamba_full_workspace(int M, int N, int H, int G, int n, strd_dtype io);
+int strd_score_mamba_full(const void *B_vis, const void *C_txt, const float *dt_all, const float *A,
+                          float *scores, int M, int N, int H, int G, int n, strd_dtype io, void *ws,
+                          size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * select_topk -- keep the K highest-scoring vision tokens, in temporal order
  * (Sec. 3.1 "Token Selection").  Ties at the K-th score go to the lowest index.
  *   scores [dev] [N] fp32, finite and >= 0 (both score kinds are); -0.0 counts as 0

@@ -84,15 +84,22 @@ def score_mamba(B_vis, C_txt, dt_vis):
     return s
 
 
-def score_mamba_full(B_all, C_all, dt_all, A, N):
-    """Full Mamba Dynamic score |w_{t,j}| averaged over text rows and heads."""
+def score_mamba_full(B_all, C_all, dt_all, A, N, rows=None):
+    """Full Mamba Dynamic score |w_{t,j}| averaged over text rows and heads (optionally only for
+    the vision tokens listed in rows)."""
     B, C, dt, A = _f64(B_all), _f64(C_all), _f64(dt_all), _f64(A)
     T, G, n = B.shape
     M = T - N
     H = dt.shape[1]
-    s = np.empty(N, np.float64)
-    _check(_load().oracle_score_mamba_full(_p(B), _p(C), _p(dt), _p(A), _p(s), M, N, H, G, n),
-           "score_mamba_full")
+    if rows is None:
+        s = np.empty(N, np.float64)
+        _check(_load().oracle_score_mamba_full(_p(B), _p(C), _p(dt), _p(A), _p(s), M, N, H, G, n),
+               "score_mamba_full")
+        return s
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    s = np.empty(rows.shape[0], np.float64)
+    _check(_load().oracle_score_mamba_full_rows(_p(B), _p(C), _p(dt), _p(A), _p(s), M, N, H, G, n, _p(rows),
+                                                int(rows.shape[0])), "score_mamba_full_rows")
     return s
 
 

@@ -120,13 +120,20 @@ int oracle_score_mamba(const double *Bv, const double *Ct, const double *dtv,
 /* Ball: [N+M,G,n] (only vision rows read)  Call: [N+M,G,n] (only text */
 /* rows read)  dt: [N+M,H]  A: [H]  s: [N]                             */
 /* ------------------------------------------------------------------ */
-int oracle_score_mamba_full(const double *Ball, const double *Call, const double *dt,
-                            const double *A, double *s, int M, int N, int H, int G, int n)
+/* rows: optional list of nrows vision tokens to score (s then has nrows     */
+/* entries, in that order); NULL = all N tokens.                           */
+int oracle_score_mamba_full_rows(const double *Ball, const double *Call, const double *dt,
+                                 const double *A, double *s, int M, int N, int H, int G, int n,
+                                 const int32_t *rows, int nrows)
 {
     if (M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G) return -1;
     const int hpg = H / G;
-#pragma omp parallel for schedule(static)
-    for (int i = 0; i < N; ++i) {
+    const int cnt = rows ? nrows : N;
+    for (int r = 0; r < cnt; ++r)
+        if (rows && (rows[r] < 0 || rows[r] >= N)) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < cnt; ++r) {
+        const int i = rows ? rows[r] : r;
         double tot = 0.0;
         for (int m = 0; m < M; ++m) {
             const int t = N + m;
@@ -141,9 +148,15 @@ int oracle_score_mamba_full(const double *Ball, const double *Call, const double
                 tot += fabs(decay * dot);
             }
         }
-        s[i] = tot / ((double)M * (double)H);
+        s[r] = tot / ((double)M * (double)H);
     }
     return 0;
+}
+
+int oracle_score_mamba_full(const double *Ball, const double *Call, const double *dt,
+                            const double *A, double *s, int M, int N, int H, int G, int n)
+{
+    return oracle_score_mamba_full_rows(Ball, Call, dt, A, s, M, N, H, G, n, NULL, 0);
 }
 
 /* ------------------------------------------------------------------ */

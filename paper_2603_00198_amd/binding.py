@@ -25,6 +25,8 @@ _SIGNATURES = {
     "strd_score_attn": (_int, [_vp, _vp, _vp] + [_int] * 5 + [_f32, _int, _vp, _sz, _vp]),
     "strd_score_mamba_workspace": (_sz, [_int] * 5 + [_int]),
     "strd_score_mamba": (_int, [_vp, _vp, _vp, _vp] + [_int] * 5 + [_int, _vp, _sz, _vp]),
+    "strd_score_mamba_full_workspace": (_sz, [_int] * 5 + [_int]),
+    "strd_score_mamba_full": (_int, [_vp] * 5 + [_int] * 5 + [_int, _vp, _sz, _vp]),
     "strd_select_topk_workspace": (_sz, [_int, _int]),
     "strd_select_topk": (_int, [_vp, _int, _int, _vp, _vp, _sz, _vp]),
     "strd_compact": (_int, [_vp, _vp, _vp, _int, _int, _int, _i64, _vp, _vp, _vp]),
@@ -140,6 +142,28 @@ def score_mamba(B_vis: torch.Tensor, C_txt: torch.Tensor, dt_vis: torch.Tensor,
         ws, _ = _ws(need, B_vis)
     _check(lib().strd_score_mamba(_ptr(B_vis), _ptr(C_txt), _ptr(dt_vis), _ptr(out), M, N, H, G, n, io,
                                   _ptr(ws), 0 if ws is None else ws.numel(), _stream()), "score_mamba")
+    return out
+
+
+def score_mamba_full(B_vis: torch.Tensor, C_txt: torch.Tensor, dt_all: torch.Tensor, A: torch.Tensor,
+                     out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Full Mamba Dynamic score s[N] fp32 from vision b [N,G,n], text c [M,G,n], dt of all tokens
+    [N+M,H] (fp32, vision rows first) and A [H]."""
+    _dev(B_vis, C_txt, dt_all, A, out, ws)
+    N, G, n = B_vis.shape
+    M = C_txt.shape[0]
+    H = dt_all.shape[1]
+    if C_txt.shape[1:] != (G, n) or dt_all.shape[0] != N + M or dt_all.dtype != torch.float32 \
+            or A.shape != (H,) or A.dtype != torch.float32 or B_vis.dtype != C_txt.dtype:
+        raise StrdError("B/C/dt/A mismatch")
+    io = _io(B_vis)
+    if out is None:
+        out = torch.empty(N, dtype=torch.float32, device=B_vis.device)
+    need = lib().strd_score_mamba_full_workspace(M, N, H, G, n, io)
+    if ws is None:
+        ws, _ = _ws(need, B_vis)
+    _check(lib().strd_score_mamba_full(_ptr(B_vis), _ptr(C_txt), _ptr(dt_all), _ptr(A), _ptr(out), M, N, H, G, n, io,
+                                       _ptr(ws), 0 if ws is None else ws.numel(), _stream()), "score_mamba_full")
     return out
 
 

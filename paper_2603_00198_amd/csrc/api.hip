@@ -64,6 +64,21 @@ int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, 
     return score_mamba_general(B_vis, C_txt, dt_vis, scores, M, N, H, G, n, io, as_stream(stream));
 }
 
+size_t strd_score_mamba_full_workspace(int M, int N, int H, int G, int n, strd_dtype io) {
+    if (M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G) return 0;
+    return score_mamba_full_ws(M, N, H, G, n, io);
+}
+
+int strd_score_mamba_full(const void *B_vis, const void *C_txt, const float *dt_all, const float *A, float *scores,
+                          int M, int N, int H, int G, int n, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (!B_vis || !C_txt || !dt_all || !A || !scores || M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G || !io_ok(io))
+        return STRD_EINVAL;
+    if ((long long)N + M > 0x7FFFFFFFLL || H > 65535 * 256) return STRD_EUNSUPPORTED;
+    const size_t need = strd_score_mamba_full_workspace(M, N, H, G, n, io);
+    if (!ws || ws_bytes < need) return STRD_EWORKSPACE;
+    return score_mamba_full(B_vis, C_txt, dt_all, A, scores, M, N, H, G, n, io, ws, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ select_topk ------------
 size_t strd_select_topk_workspace(int N, int K) {
     (void)N; (void)K;

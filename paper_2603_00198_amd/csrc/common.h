@@ -178,6 +178,12 @@ bool score_attn_mfma_supported(int M, int N, int Hq, int Hkv, int d, strd_dtype 
 size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv);
 int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
                     hipStream_t st);
+bool score_mamba_full_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
+int score_mamba_full_mfma(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H,
+                          int G, int n, void *part_ws, hipStream_t st);
+size_t score_mamba_full_ws(int M, int N, int H, int G, int n, strd_dtype io);
+int score_mamba_full(const void *B, const void *C, const float *dt_all, const float *A, float *s, int M, int N, int H,
+                     int G, int n, strd_dtype io, void *ws, hipStream_t st);
 bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
 size_t score_mamba_mfma_ws(int N, int G);
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,

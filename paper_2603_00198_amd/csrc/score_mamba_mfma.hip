@@ -35,10 +35,19 @@ struct Tile {
     Buf c[2];
 };
 
-template <int NS, int CT>
+// FULL (the Full Mamba Dynamic score, |w_{t,j}| of paper Eq. "ssm_weight", Sec. "Why the Full Mamba Dynamic Fails"): every |b_i . c_m| is
+// weighted by sum_{h in g} u_i^h v_m^h, u_i^h = dt_i^h * decay from token i to the last vision
+// token, v_m^h = decay from there to text row m (both <= dt resp. 1, made by the prep kernels).
+// That weight table is itself a [text row x token] contraction over the <= 16 heads of the group,
+// in the accumulator layout of G^T, so it is one more MFMA per tile; u and v are split into
+// bf16 high and low parts (three products) to keep about 16 bits of them.
+template <int NS, int CT, bool FULL>
 __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t *__restrict__ Bv,
                                                                     const bf16_t *__restrict__ Ct,
-                                                                    float *__restrict__ part, int M, int N, int G) {
+                                                                    const float *__restrict__ U,
+                                                                    const float *__restrict__ V,
+                                                                    float *__restrict__ part, int M, int N, int G,
+                                                                    int H) {
     constexpr int KS = NS / 16;  // k-steps of v_mfma_f32_32x32x16_bf16
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<NS> &lds = *reinterpret_cast<Tile<NS> *>(smem_raw);
@@ -71,6 +80,21 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bfr[ct][ks] = *reinterpret_cast<const bf16x8 *>(bp + 16 * ks);
     }
+    // u fragments of this wave's tokens (B operand: lane = token column, k = head 8*half + j of the group)
+    const int hpg = FULL ? H / G : 0;
+    bf16x8 u_hi[CT], u_lo[CT];
+    if (FULL) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const float *up = U + (size_t)min(tok0 + 32 * ct + lc, N - 1) * H + g * hpg + 8 * half;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float u = (8 * half + j < hpg) ? up[j] : 0.f;
+                u_hi[ct][j] = (bf16_t)u;
+                u_lo[ct][j] = (bf16_t)(u - (float)u_hi[ct][j]);
+            }
+        }
+    }
     async_tile_wait();
     __syncthreads();
 
@@ -96,6 +120,32 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
                     acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfr[ct][ks], acc[ct], 0, 0, 0);
+            }
+            if (FULL) {
+                // v fragment of the tile's text rows (A operand: lane = text row, k = head); rows past M give 0
+                const int m = mc * kMC + 32 * mt + lc;
+                const float *vp = V + (size_t)min(m, M - 1) * H + g * hpg + 8 * half;
+                bf16x8 v_hi, v_lo;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float v = (m < M && 8 * half + j < hpg) ? vp[j] : 0.f;
+                    v_hi[j] = (bf16_t)v;
+                    v_lo[j] = (bf16_t)(v - (float)v_hi[j]);
+                }
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    f32x16 wt;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) wt[i] = 0.f;
+                    wt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_lo, u_hi[ct], wt, 0, 0, 0);
+                    wt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_hi, u_lo[ct], wt, 0, 0, 0);
+                    wt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_hi, u_hi[ct], wt, 0, 0, 0);
+                    float t = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) t = fmaf(fabsf(acc[ct][i]), wt[i], t);
+                    part_sum[ct] += t;
+                }
+                continue;
             }
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
@@ -140,20 +190,52 @@ __global__ __launch_bounds__(kThreads) void score_mamba_reduce_kernel(const floa
     if (i < N && j == 0) s[i] = tot * norm;
 }
 
+// Full score: the per-token factors are already inside the group partials.
+__global__ __launch_bounds__(kThreads) void score_mamba_full_reduce_kernel(const float *__restrict__ part,
+                                                                           float *__restrict__ s, int N, int G,
+                                                                           float norm) {
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N) return;
+    float tot = 0.f;
+    for (int g = 0; g < G; ++g) tot += part[(size_t)g * N + i];
+    s[i] = tot * norm;
+}
+
 template <int NS, int CT>
-int launch(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, void *ws,
-           hipStream_t st) {
+int launch_full(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H, int G,
+                void *ws, hipStream_t st) {
     const size_t smem = sizeof(Tile<NS>);
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return STRD_EHIP;
         configured = true;
     }
     float *part = (float *)ws;
     const dim3 grid(ceil_div(N, 128 * CT), G);
-    score_mamba_mfma_kernel<NS, CT><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, part, M, N, G);
+    score_mamba_mfma_kernel<NS, CT, true><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, U, V, part,
+                                                                        M, N, G, H);
+    score_mamba_full_reduce_kernel<<<ceil_div(N, kThreads), kThreads, 0, st>>>(part, s, N, G,
+                                                                             1.f / ((float)M * (float)H));
+    return launch_status();
+}
+
+template <int NS, int CT>
+int launch(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, void *ws,
+           hipStream_t st) {
+    const size_t smem = sizeof(Tile<NS>);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return STRD_EHIP;
+        configured = true;
+    }
+    float *part = (float *)ws;
+    const dim3 grid(ceil_div(N, 128 * CT), G);
+    score_mamba_mfma_kernel<NS, CT, false><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, nullptr,
+                                                                         nullptr, part, M, N, G, H);
     score_mamba_reduce_kernel<<<ceil_div(N, kThreads / 16), kThreads, 0, st>>>(part, dt, s, N, H, G,
                                                                           1.f / ((float)M * (float)H));
     return launch_status();
@@ -176,6 +258,18 @@ int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, in
         return wide ? launch<128, 2>(B, C, dt, s, M, N, H, G, ws, st) : launch<128, 1>(B, C, dt, s, M, N, H, G, ws, st);
     if (n == 64)
         return wide ? launch<64, 2>(B, C, dt, s, M, N, H, G, ws, st) : launch<64, 1>(B, C, dt, s, M, N, H, G, ws, st);
+    return STRD_EUNSUPPORTED;
+}
+
+// Full score on matrix cores: needs the heads of a group to fit one k = 16 product.
+bool score_mamba_full_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io) {
+    return score_mamba_mfma_supported(M, N, H, G, n, io) && H / G <= 16;
+}
+
+int score_mamba_full_mfma(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H,
+                          int G, int n, void *part_ws, hipStream_t st) {
+    if (n == 128) return launch_full<128, 1>(B, C, U, V, s, M, N, H, G, part_ws, st);
+    if (n == 64) return launch_full<64, 1>(B, C, U, V, s, M, N, H, G, part_ws, st);
     return STRD_EUNSUPPORTED;
 }
 

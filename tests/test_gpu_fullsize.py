@@ -68,6 +68,9 @@ def test_c2_reduced_mamba_layer_full_size():
     np.testing.assert_array_equal(pos.cpu().numpy(), np.concatenate([i_np, np.arange(N, N + M)]))
     heads = [0, 17, 34, 51, 68, 85, 102, 127]       # one per group
     _check_ssd_heads(red["x"], red["dt"], t["A"], red["B"], red["C"], y, S, heads, w.mamba.G, "reduced")
+    # the scan that gathers its inputs through idx gives the same bits without the compacted copies
+    y_g, S_g = strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], idx, N, M, chunk=w.mamba.chunk)
+    assert torch.equal(y_g, y) and torch.equal(S_g, S)
     # the unreduced layer (the denominator of the speed-up) on two heads
     y_full, S_full = strd.ssd_prefill(t["x"], t["dt"], t["A"], t["B"], t["C"], chunk=w.mamba.chunk)
     _check_ssd_heads(t["x"], t["dt"], t["A"], t["B"], t["C"], y_full, S_full, [5, 120], w.mamba.G, "full")
@@ -105,6 +108,29 @@ def test_c3_reduced_attention_layer_full_size():
     assert_close(f(o_full[torch.from_numpy(rows).long().to(DEV)]), o_ref, TOLB, "full attention rows")
 
 
+@pytest.mark.parametrize("a_scale", [1.0, 3e-4])
+def test_c2_full_dynamic_score_sampled(a_scale):
+    """The decayed score at c2 size on sampled tokens (each token's score is independent).  With the
+    workload's A only the last tokens are above fp32's range; A x 3e-4 keeps the whole sequence alive."""
+    w = synth.WORKLOADS["c2"]
+    _say("c2 full dynamic score: N=%d M=%d, A x %g" % (w.N, w.M, a_scale))
+    hidden = synth.hidden_states(w, DEV)
+    t = synth.mamba_inputs(w, hidden)
+    N = w.N
+    A = (t["A"] * a_scale).contiguous()
+    s = strd.score_mamba_full(t["B"][:N].contiguous(), t["C"][N:].contiguous(), t["dt"], A)
+    rng = np.random.default_rng(2)
+    pick = np.unique(np.concatenate([np.arange(N - 12, N), rng.choice(N - 12, 20, replace=False)])).astype(np.int32)
+    want = oracle.score_mamba_full(f(t["B"]), f(t["C"]), f(t["dt"]), f(A), N, rows=pick)
+    got = s.cpu().numpy()[pick]
+    assert np.isfinite(s.cpu().numpy()).all() and (s.cpu().numpy() >= 0).all()
+    # relative to the largest score of the sample (which contains the last tokens, the largest of all)
+    assert np.abs(got - want).max() <= TOLB * want.max()
+    if a_scale < 1:
+        assert (want > 1e-3 * want.max()).all()     # the sample is not vacuous: early tokens still count
+        assert (np.abs(got - want) <= TOLB * want).all()
+
+
 @pytest.mark.parametrize("budget", [0.10, 0.25, 0.50])
 def test_c5_long_video_mamba_layer_sampled(budget):
     w = synth.shrink(synth.WORKLOADS["c5"], N=131072, M=512, budget=budget)
@@ -131,6 +157,8 @@ def test_c5_long_video_mamba_layer_sampled(budget):
                                   hb[torch.from_numpy(np.concatenate([i_np, np.arange(N, N + M)])[::97]).long().to(DEV)]
                                   .view(torch.int16).cpu().numpy())
     _check_ssd_heads(red["x"], red["dt"], t["A"], red["B"], red["C"], y, S, [3, 77], w.mamba.G, "reduced")
+    y_g, S_g = strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], idx, N, M, chunk=w.mamba.chunk)
+    assert torch.equal(y_g, y) and torch.equal(S_g, S)
 
 
 def test_c5_long_video_attention_layer_sampled():

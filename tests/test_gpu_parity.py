@@ -138,6 +138,41 @@ def test_score_mamba_parity(name):
     assert_topk_equivalent(idx, want, K, TOL[synth.torch_dtype(w.dtype)])
 
 
+FULL_CASES = {
+    "c1": synth.WORKLOADS["c1"],                                                     # fp32, SIMT path
+    "n64": MAMBA_CASES["n64"],                                                       # 3 heads per group (padded k)
+    "odd": MAMBA_CASES["odd"],                                                       # bf16, SIMT path
+    "c2-tiny": synth.shrink(synth.WORKLOADS["c2"], N=600, M=20, d_model=256),        # 16 heads per group
+    "c2-ragged": synth.shrink(synth.WORKLOADS["c2"], N=300, M=37, d_model=256),      # ragged text tile
+}
+
+
+@pytest.mark.parametrize("a_scale", [1.0, 0.003])   # 0.003: the decay is mild over the whole sequence, every
+@pytest.mark.parametrize("name", list(FULL_CASES))  # block of the suffix sum matters, not only the last tokens
+def test_score_mamba_full_parity(name, a_scale):
+    w = FULL_CASES[name]
+    _say("score_mamba_full %s N=%d M=%d %s A x %g" % (name, w.N, w.M, w.dtype, a_scale))
+    t = _mamba_case(w, seed=3)
+    N = w.N
+    A = (t["A"] * a_scale).contiguous()
+    got = strd.score_mamba_full(t["B"][:N].contiguous(), t["C"][N:].contiguous(), t["dt"], A)
+    want = oracle.score_mamba_full(synth.np64(t["B"]), synth.np64(t["C"]), synth.np64(t["dt"]), synth.np64(A), N)
+    tol = TOL[synth.torch_dtype(w.dtype)]
+    assert_close(got.cpu().numpy(), want, tol, "score_mamba_full " + name)
+    K = max(1, w.K)
+    assert_topk_equivalent(strd.select_topk(got, K).cpu().numpy(), want, K, tol, band_of_max=True)
+
+
+def test_score_mamba_full_without_decay_is_the_decay_free_score():
+    w = FULL_CASES["c2-tiny"]
+    t = _mamba_case(w, seed=4)
+    N = w.N
+    Bv, Ct = t["B"][:N].contiguous(), t["C"][N:].contiguous()
+    full = strd.score_mamba_full(Bv, Ct, t["dt"], torch.zeros_like(t["A"]))
+    free = strd.score_mamba(Bv, Ct, t["dt"][:N].contiguous())
+    assert_close(full.cpu().numpy(), free.cpu().numpy().astype(np.float64), 1e-4, "A = 0")
+
+
 @pytest.mark.parametrize("name", list(ATTN_CASES))
 def test_score_attn_parity(name):
     w = ATTN_CASES[name]

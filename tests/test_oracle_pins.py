@@ -173,6 +173,8 @@ def test_score_mamba_full_is_impulse_response_of_the_recurrence():
         y, _ = oracle.ssd_seq(x, dt, A, B, C)
         want[j] = np.abs(y[N:, :, 0]).sum() / (M * H)
     np.testing.assert_allclose(oracle.score_mamba_full(B, C, dt, A, N), want, rtol=1e-12)
+    # the row-subset entry scores the listed tokens, in the listed order
+    np.testing.assert_allclose(oracle.score_mamba_full(B, C, dt, A, N, rows=[4, 0, 5]), want[[4, 0, 5]], rtol=1e-12)
 
 
 # ----------------------------------------------------- attention score ----

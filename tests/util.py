@@ -25,9 +25,12 @@ def assert_close(got, ref, tol, what=""):
     return emax, efro
 
 
-def assert_topk_equivalent(idx_dev, scores_ref, K, tol):
+def assert_topk_equivalent(idx_dev, scores_ref, K, tol, band_of_max=False):
     """The device selection may differ from the oracle's only in elements whose oracle score
-    lies within tol * (K-th score) of the K-th score; what is unique must match exactly."""
+    lies within tol * (K-th score) of the K-th score; what is unique must match exactly.
+    band_of_max: the band is tol * (largest score) instead -- for scores that span hundreds of
+    orders of magnitude (the decayed Mamba score), where the K-th score is far below what fp32
+    resolves and the score tolerance itself is relative to the largest score."""
     import oracle
     idx_dev = np.asarray(idx_dev)
     N = scores_ref.shape[0]
@@ -36,7 +39,7 @@ def assert_topk_equivalent(idx_dev, scores_ref, K, tol):
     assert (np.diff(idx_dev) > 0).all(), "indices must be strictly ascending"
     want = oracle.select_topk(scores_ref, K)
     kth = np.sort(scores_ref)[::-1][K - 1]
-    band = tol * max(abs(kth), 1e-300)
+    band = tol * max(abs(scores_ref.max() if band_of_max else kth), 1e-300)
     only_dev = np.setdiff1d(idx_dev, want)
     only_ref = np.setdiff1d(want, idx_dev)
     assert only_dev.size == only_ref.size
