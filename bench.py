@@ -42,6 +42,10 @@ def parse_args():
                     help="for rocprofv3: only the warm-up and the timed reduced steps, then one plain copy of "
                          "known size (256 MiB through the compact kernel with the identity index list) that "
                          "calibrates the FETCH_SIZE / WRITE_SIZE counters; prints the byte counts")
+    ap.add_argument("--stack-model", action="store_true",
+                    help="instead of the layer benchmark: measure the Mamba-2 and attention layer at every token "
+                         "count the paper's named schedules visit (c4 shapes) and print the modelled speed-up of "
+                         "the mixers of the 62-layer hybrid under each schedule")
     ap.add_argument("--no-attention-extra", action="store_true",
                     help="skip the attention-layer figures appended to the default (c2) line")
     return ap.parse_args()
@@ -328,6 +332,73 @@ def profile_run(torch, strd, synth, name, budget, steps, warmup, dev):
                                            "write_bytes_per_launch": rows * row_elems * 2}}))
 
 
+def stack_model(torch, strd, synth, dev):
+    """Modelled time of the mixers of the 62-layer hybrid under the paper's named schedules, from
+    per-layer times measured here at every (layer kind, token count) a schedule visits."""
+    from paper_2603_00198_amd.stack import model_stack_time
+    w = synth.WORKLOADS["c4"]
+    N0, M = w.N, w.M
+    hidden = synth.hidden_states(w, dev)
+    tm, ta = synth.mamba_inputs(w, hidden), synth.attn_inputs(w, hidden)
+    hb = hidden.to(torch.bfloat16)
+    del hidden
+    sm, sa = w.mamba, w.attn
+    types = strd.hybrid_layout()
+    mix_cache, red_cache = {}, {}
+
+    def rows(t, keys, n):      # the first n vision rows and the text rows of full-length tensors
+        return [torch.cat([t[k][:n], t[k][N0:]]).contiguous() for k in keys]
+
+    def mixer_time(kind, n):
+        if (kind, n) not in mix_cache:
+            if kind == "mamba":
+                x, dt, B, C = rows(tm, ("x", "dt", "B", "C"), n)
+                fn = lambda: strd.ssd_prefill(x, dt, tm["A"], B, C, chunk=sm.chunk, want_state=False)
+            else:
+                q, k, v = rows(ta, ("q", "k", "v"), n)
+                fn = lambda: strd.attn_prefill(q, k, v)
+            mix_cache[(kind, n)] = 1e-3 * time_events(torch, fn, iters=5 if kind == "attn" and n > 16384 else 10, warmup=2)
+        return mix_cache[(kind, n)]
+
+    def reduce_time(kind, n_in, k):
+        if (kind, n_in, k) not in red_cache:
+            if kind == "mamba":
+                x, dt, B, C = rows(tm, ("x", "dt", "B", "C"), n_in)
+                hid = torch.cat([hb[:n_in], hb[N0:]]).contiguous()
+                Bv, Ct, dtv = B[:n_in].contiguous(), C[n_in:].contiguous(), dt[:n_in].contiguous()
+
+                def fn():
+                    idx = strd.select_topk(strd.score_mamba(Bv, Ct, dtv), k)
+                    strd.compact_batch([x, B, C, dt, hid], idx, n_in, M)
+            else:
+                q, kk, v = rows(ta, ("q", "k", "v"), n_in)
+                hid = torch.cat([hb[:n_in], hb[N0:]]).contiguous()
+                qt, kv = q[n_in:].contiguous(), kk[:n_in].contiguous()
+
+                def fn():
+                    idx = strd.select_topk(strd.score_attn(qt, kv), k)
+                    strd.compact_batch([q, kk, v, hid], idx, n_in, M)
+            red_cache[(kind, n_in, k)] = 1e-3 * time_events(torch, fn, iters=10, warmup=2)
+        return red_cache[(kind, n_in, k)]
+
+    out = {}
+    for name in strd.NAMED_SCHEDULES:
+        alpha = strd.schedule_named(name)
+        K = strd.schedule_budgets(alpha, N0, K_min=0)
+        red, full = model_stack_time(types, K, N0, mixer_time, reduce_time)
+        out[name] = {"mean_retention": sum(K) / (len(K) * N0), "mixers_full_ms": 1e3 * full, "mixers_reduced_ms": 1e3 * red,
+                     "speedup": full / red}
+    print(json.dumps({
+        "stack_model": out, "N0": N0, "M": M, "layers": {"mamba": types.count(strd.LAYER_MAMBA),
+                                                          "attn": types.count(strd.LAYER_ATTN),
+                                                          "mlp_not_modelled": types.count(strd.LAYER_MLP)},
+        "layer_ms": {"%s@%d" % k: 1e3 * v for k, v in sorted(mix_cache.items())},
+        "note": "sum of measured per-layer times (mixer at each layer's token count + score/select/compact at the "
+                "reducing layers) over the 28 Mamba-2 and 6 attention layers of the 62-layer hybrid, c4 shapes; "
+                "MLP layers, projections and norms are outside this library and not in either sum",
+        "context": PAPER_CONTEXT}))
+
+
 def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     from dataclasses import replace
     wname, kind = WORKLOADS[name]
@@ -433,6 +504,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     name = args.workload
+    if args.stack_model:
+        stack_model(torch, strd, synth, dev)
+        return
     if args.profile:
         profile_run(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)
         return

@@ -200,6 +200,28 @@ int strd_schedule_budgets(const double *alpha, int L, int N0, int K_min, int32_t
 int strd_schedule_sigmoid(int L, double a_start, double a_end, double k, double x0,
                           double *alpha_out);
 
+/* Step-decay retention schedule (App. "Step Decay Schedule"): alpha_l = alpha[r] for the layers
+ * lo[r]..hi[r] (inclusive, 0-indexed; later ranges win), 1.0 elsewhere.
+ *   lo, hi [host] [nranges] ints   alpha [host] [nranges] doubles in [0,1]   alpha_out [host] [L] */
+int strd_schedule_step_decay(const int *lo, const int *hi, const double *alpha, int nranges, int L,
+                             double *alpha_out);
+
+/* Layer types of the 62-layer hybrid the schedules of the paper are written for (App. "Reduction
+ * Schedule Configurations"): attention at layers 7, 16, 25, 34, 43, 52; the other 56 layers
+ * alternate Mamba-2, MLP starting with Mamba-2 (28 + 28; the paper gives the counts, not the order).
+ *   type_out [host] [L] int32 of STRD_LAYER_*; a shorter or longer L follows the same rule. */
+enum { STRD_LAYER_MAMBA = 0, STRD_LAYER_MLP = 1, STRD_LAYER_ATTN = 2, STRD_HYBRID_LAYERS = 62 };
+int strd_hybrid_layout(int L, int32_t *type_out);
+
+/* The named schedules of the same table, as retention ratios for the STRD_HYBRID_LAYERS layers:
+ * "attn_only_1st_attn", "all_attn_25", "all_attn_35", "all_attn_50", "first_mamba",
+ * "second_mamba" (ranges as printed), "sigmoid_25", "sigmoid_35", "sigmoid_50" (k = 20, x0 = 0.11 /
+ * 0.24 / 0.41, 1.0 -> 0.125), "all_attn_1m", "all_attn_2m" (the table only says 0.32 -> 0.15 over
+ * the 6 attention layers plus 1 or 2 Mamba layers before each: taken as a linear fall over the
+ * reducing layers up to layer 33, held afterwards).  Unknown name: STRD_EINVAL.
+ *   alpha_out [host] [STRD_HYBRID_LAYERS] doubles */
+int strd_schedule_named(const char *name, double *alpha_out);
+
 #ifdef __cplusplus
 }
 #endif

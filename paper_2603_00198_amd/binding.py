@@ -38,6 +38,9 @@ _SIGNATURES = {
     "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
     "strd_schedule_budgets": (_int, [_vp, _int, _int, _int, _vp]),
     "strd_schedule_sigmoid": (_int, [_int, _c.c_double, _c.c_double, _c.c_double, _c.c_double, _vp]),
+    "strd_schedule_step_decay": (_int, [_vp, _vp, _vp, _int, _int, _vp]),
+    "strd_hybrid_layout": (_int, [_int, _vp]),
+    "strd_schedule_named": (_int, [_c.c_char_p, _vp]),
 }
 
 _lib = None
@@ -320,4 +323,36 @@ def schedule_sigmoid(L: int, a_start: float = 1.0, a_end: float = 0.125, k: floa
     """Sigmoid retention ratios alpha_l, l = 0..L-1 (host only)."""
     out = (ctypes.c_double * L)()
     _check(lib().strd_schedule_sigmoid(int(L), a_start, a_end, k, x0, ctypes.cast(out, _vp)), "schedule_sigmoid")
+    return list(out)
+
+
+HYBRID_LAYERS = 62
+LAYER_MAMBA, LAYER_MLP, LAYER_ATTN = 0, 1, 2
+NAMED_SCHEDULES = ("attn_only_1st_attn", "all_attn_25", "all_attn_35", "all_attn_50", "first_mamba", "second_mamba",
+                   "all_attn_1m", "all_attn_2m", "sigmoid_25", "sigmoid_35", "sigmoid_50")
+
+
+def schedule_step_decay(ranges: Sequence[Tuple[int, int, float]], L: int):
+    """alpha_l from (lo, hi, alpha) ranges (inclusive, later ranges win; 1.0 elsewhere)."""
+    n = len(ranges)
+    lo = (ctypes.c_int * n)(*[int(r[0]) for r in ranges])
+    hi = (ctypes.c_int * n)(*[int(r[1]) for r in ranges])
+    al = (ctypes.c_double * n)(*[float(r[2]) for r in ranges])
+    out = (ctypes.c_double * L)()
+    _check(lib().strd_schedule_step_decay(ctypes.cast(lo, _vp), ctypes.cast(hi, _vp), ctypes.cast(al, _vp), n, int(L),
+                                          ctypes.cast(out, _vp)), "schedule_step_decay")
+    return list(out)
+
+
+def hybrid_layout(L: int = HYBRID_LAYERS):
+    """Layer types (LAYER_MAMBA / LAYER_MLP / LAYER_ATTN) of the 62-layer hybrid of the paper's schedules."""
+    out = (ctypes.c_int32 * L)()
+    _check(lib().strd_hybrid_layout(int(L), ctypes.cast(out, _vp)), "hybrid_layout")
+    return list(out)
+
+
+def schedule_named(name: str):
+    """Retention ratios of one of NAMED_SCHEDULES for the 62 layers."""
+    out = (ctypes.c_double * HYBRID_LAYERS)()
+    _check(lib().strd_schedule_named(name.encode(), ctypes.cast(out, _vp)), "schedule_named(%s)" % name)
     return list(out)

@@ -2,6 +2,8 @@
 // Every entry point validates on the host, then enqueues kernels on the caller's stream.
 #include <math.h>
 
+#include <string.h>
+
 #include "common.h"
 
 using namespace strd;
@@ -191,6 +193,77 @@ int strd_schedule_sigmoid(int L, double a_start, double a_end, double k, double 
         alpha_out[l] = a_end + (a_start - a_end) / (1.0 + exp(-z));
     }
     return STRD_OK;
+}
+
+int strd_schedule_step_decay(const int *lo, const int *hi, const double *alpha, int nranges, int L,
+                             double *alpha_out) {
+    if (!alpha_out || L < 1 || nranges < 0 || (nranges && (!lo || !hi || !alpha))) return STRD_EINVAL;
+    for (int l = 0; l < L; ++l) alpha_out[l] = 1.0;
+    for (int r = 0; r < nranges; ++r) {
+        if (lo[r] < 0 || hi[r] < lo[r] || hi[r] >= L || !(alpha[r] >= 0.0 && alpha[r] <= 1.0)) return STRD_EINVAL;
+        for (int l = lo[r]; l <= hi[r]; ++l) alpha_out[l] = alpha[r];
+    }
+    return STRD_OK;
+}
+
+int strd_hybrid_layout(int L, int32_t *type_out) {
+    if (!type_out || L < 1) return STRD_EINVAL;
+    int other = 0;
+    for (int l = 0; l < L; ++l) {
+        if (l >= 7 && (l - 7) % 9 == 0 && l <= 52)
+            type_out[l] = STRD_LAYER_ATTN;
+        else
+            type_out[l] = (other++ % 2 == 0) ? STRD_LAYER_MAMBA : STRD_LAYER_MLP;
+    }
+    return STRD_OK;
+}
+
+int strd_schedule_named(const char *name, double *alpha_out) {
+    if (!name || !alpha_out) return STRD_EINVAL;
+    const int L = STRD_HYBRID_LAYERS;
+    struct Range { int lo, hi; double a; };
+    struct Named { const char *name; int n; Range r[7]; };
+    static const Named table[] = {
+        {"attn_only_1st_attn", 2, {{0, 6, 1.0}, {7, 61, 0.15}}},
+        {"all_attn_25", 4, {{0, 6, 1.0}, {7, 15, 0.25}, {16, 33, 0.20}, {34, 61, 0.10}}},
+        {"all_attn_35", 6, {{0, 6, 1.0}, {7, 15, 0.50}, {16, 24, 0.40}, {25, 33, 0.30}, {34, 42, 0.20}, {43, 61, 0.10}}},
+        {"all_attn_50", 7, {{0, 6, 1.0}, {7, 15, 0.65}, {16, 24, 0.60}, {25, 33, 0.50}, {34, 42, 0.40}, {43, 51, 0.30},
+                            {52, 61, 0.20}}},
+        {"first_mamba", 1, {{0, 61, 0.25}}},
+        {"second_mamba", 2, {{0, 0, 1.0}, {1, 61, 0.23}}},
+    };
+    for (const Named &t : table) {
+        if (strcmp(name, t.name)) continue;
+        int lo[7], hi[7];
+        double a[7];
+        for (int i = 0; i < t.n; ++i) { lo[i] = t.r[i].lo; hi[i] = t.r[i].hi; a[i] = t.r[i].a; }
+        return strd_schedule_step_decay(lo, hi, a, t.n, L, alpha_out);
+    }
+    if (!strcmp(name, "sigmoid_25")) return strd_schedule_sigmoid(L, 1.0, 0.125, 20.0, 0.11, alpha_out);
+    if (!strcmp(name, "sigmoid_35")) return strd_schedule_sigmoid(L, 1.0, 0.125, 20.0, 0.24, alpha_out);
+    if (!strcmp(name, "sigmoid_50")) return strd_schedule_sigmoid(L, 1.0, 0.125, 20.0, 0.41, alpha_out);
+    const int extra = !strcmp(name, "all_attn_1m") ? 1 : !strcmp(name, "all_attn_2m") ? 2 : 0;
+    if (extra) {
+        // the 6 attention layers reduce, and so do the first `extra` Mamba layers after layer 0 and
+        // after every attention layer (6 + 7 reducing layers for extra = 1); the ratio falls linearly
+        // from 0.32 at the first reducing layer to 0.15 at the last one up to layer 33, held from there on
+        int32_t type[STRD_HYBRID_LAYERS];
+        strd_hybrid_layout(L, type);
+        int red[STRD_HYBRID_LAYERS], nred = 0, want = extra;
+        for (int l = 1; l < L; ++l) {
+            if (type[l] == STRD_LAYER_ATTN) { red[nred++] = l; want = extra; }
+            else if (type[l] == STRD_LAYER_MAMBA && want > 0) { red[nred++] = l; --want; }
+        }
+        int last = 0;
+        while (last + 1 < nred && red[last + 1] <= 33) ++last;
+        for (int l = 0; l < L; ++l) alpha_out[l] = 1.0;
+        for (int i = 0; i < nred; ++i) {
+            const double a = i >= last ? 0.15 : 0.32 + (0.15 - 0.32) * (double)i / (double)last;
+            for (int l = red[i]; l < L; ++l) alpha_out[l] = a;
+        }
+        return STRD_OK;
+    }
+    return STRD_EINVAL;
 }
 
 }  // extern "C"

@@ -56,3 +56,26 @@ def run_stack(kinds: Sequence[str], layer_inputs: Sequence[Dict[str, torch.Tenso
         rec["pos"] = pos
         out.append(rec)
     return out
+
+
+def model_stack_time(types: Sequence[int], budgets: Sequence[int], N0: int, mixer_time, reduce_time):
+    """Time of the mixers of a hybrid stack under a schedule, from measured per-layer times.
+
+    types[l]: binding.LAYER_*; budgets[l]: vision tokens layer l runs on (schedule_budgets);
+    mixer_time(kind, n_vis) and reduce_time(kind, n_in, k): measured seconds of the layer mixer on
+    n_vis vision (+ text) tokens and of score + select + compact from n_in to k vision tokens, kind in
+    {"mamba", "attn"}.  A layer reduces when its budget is below what the previous layer left;
+    MLP layers cannot score, so their budget change is carried to the next Mamba / attention layer
+    (their own cost is not modelled: no MLP kernel is part of this library).
+    Returns (reduced_seconds, full_seconds)."""
+    n_cur, red, full = N0, 0.0, 0.0
+    for ty, k in zip(types, budgets):
+        if ty == strd.LAYER_MLP:
+            continue
+        kind = "attn" if ty == strd.LAYER_ATTN else "mamba"
+        if k < n_cur:
+            red += reduce_time(kind, n_cur, k)
+            n_cur = k
+        red += mixer_time(kind, n_cur)
+        full += mixer_time(kind, N0)
+    return red, full

@@ -70,6 +70,54 @@ def test_sigmoid_schedule_shape():
     assert a[lo] >= (1.0 + 0.125) / 2 >= a[hi]
 
 
+def test_named_schedules_match_the_printed_table(golden_dir):
+    names = {"attn_only_1st_attn", "all_attn_25", "all_attn_35", "all_attn_50", "first_mamba"}
+    seen = set()
+    for name, comp, alpha in _golden_schedules(golden_dir):
+        np.testing.assert_allclose(strd.schedule_named(name), alpha, rtol=0, atol=0)
+        seen.add(name)
+    assert seen == names
+    second = strd.schedule_named("second_mamba")
+    assert second[0] == 1.0 and set(second[1:]) == {0.23}
+    assert strd.schedule_named("sigmoid_35") == strd.schedule_sigmoid(62, 1.0, 0.125, 20.0, 0.24)
+    with pytest.raises(strd.StrdError):
+        strd.schedule_named("no_such_schedule")
+
+
+def test_step_decay_ranges_and_layout():
+    assert strd.schedule_step_decay([(0, 1, 1.0), (2, 4, 0.5), (4, 4, 0.25)], 6) == [1.0, 1.0, 0.5, 0.5, 0.25, 1.0]
+    with pytest.raises(strd.StrdError):
+        strd.schedule_step_decay([(3, 9, 0.5)], 6)
+    ty = strd.hybrid_layout()
+    assert [l for l, t in enumerate(ty) if t == strd.LAYER_ATTN] == [7, 16, 25, 34, 43, 52]
+    assert ty.count(strd.LAYER_MAMBA) == 28 and ty.count(strd.LAYER_MLP) == 28 and ty[0] == strd.LAYER_MAMBA
+
+
+def test_interleaved_schedules_reduce_at_attention_and_the_mamba_layers_between():
+    ty = strd.hybrid_layout()
+    for name, per_gap in (("all_attn_1m", 1), ("all_attn_2m", 2)):
+        a = strd.schedule_named(name)
+        assert a[0] == 1.0 and all(x >= y for x, y in zip(a, a[1:]))
+        drops = [l for l in range(1, 62) if a[l] < a[l - 1]]
+        assert all(ty[l] != strd.LAYER_MLP for l in drops)
+        assert a[drops[0]] == pytest.approx(0.32) and min(a) == pytest.approx(0.15)
+        assert all(a[l] == pytest.approx(0.15) for l in range(34, 62))
+        # every attention layer up to 33 reduces, and so do `per_gap` Mamba layers before each
+        assert {7, 16, 25} <= set(drops)
+        assert sum(ty[l] == strd.LAYER_MAMBA for l in drops if l < 7) == per_gap
+
+
+def test_stack_model_adds_up():
+    from paper_2603_00198_amd.stack import model_stack_time
+    ty = strd.hybrid_layout()
+    K = strd.schedule_budgets(strd.schedule_named("attn_only_1st_attn"), 1000)
+    mix = lambda kind, n: float(n) if kind == "mamba" else float(n) ** 2 / 1000
+    red, full = model_stack_time(ty, K, 1000, mix, lambda kind, n_in, k: 7.0)
+    assert full == 28 * 1000 + 6 * 1000
+    n_m_before = sum(t == strd.LAYER_MAMBA for t in ty[:7])
+    assert red == pytest.approx(7.0 + n_m_before * 1000 + (28 - n_m_before) * 150 + 6 * 150 ** 2 / 1000)
+
+
 def test_speedup_arithmetic_of_the_headline_claim(golden_dir):
     vals = {}
     for line in open(os.path.join(golden_dir, "ttft_25pct.txt")):
