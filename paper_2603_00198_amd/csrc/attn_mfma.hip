@@ -55,7 +55,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
     const int h = blockIdx.x % Hq, qb = nqb - 1 - blockIdx.x / Hq, kvh = h / (Hq / Hkv);
     const int t0 = qb * kBM;
     const int tq = t0 + 32 * w + lc;             // this lane's query position
-    const int wq0 = t0 + 32 * w;                 // first query of the wave
+    // first query of the wave, in a scalar register so that tests on it are real branches (the wave
+    // index comes from threadIdx, which the compiler cannot prove uniform)
+    const int wq0 = __builtin_amdgcn_readfirstlane(t0 + 32 * w);
     const int wmax = min(T - 1, wq0 + 31);       // last key any query of the wave may see
     const int nkeys = min(T, t0 + kBM);
     const int nchunk = (nkeys + kKC - 1) / kKC;
@@ -112,21 +114,35 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
         for (int kt = 0; kt < kKC / 32; ++kt) {
             const int kb = chunk * kKC + 32 * kt;
             if (kb <= wmax) {  // uniform per wave
+                // all key fragments of the tile first (one LDS round trip, not one per product)
+                bf16x8 kf[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    kf[ks] = *reinterpret_cast<const bf16x8 *>(lds.k[cur].at(32 * kt + lc, 16 * ks + 8 * half));
+                __builtin_amdgcn_sched_barrier(0);
                 f32x16 sacc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds.k[cur].at(32 * kt + lc, 16 * ks + 8 * half));
-                    sacc = mfma32(a, bq[ks], sacc);
-                }
-                const bool diag = kb + 31 > wq0;  // some (key, query) pair of the tile is masked
-                float tm = -INFINITY;             // max of this lane half's 16 raw scores
+                for (int ks = 0; ks < KS; ++ks) sacc = mfma32(kf[ks], bq[ks], sacc);
+                // the transposed V fragments of the tile are requested now and arrive during the softmax
+                constexpr int kHi = 8 * Tile<D>::kPitch * 2;  // byte offset of the second 4 keys of a slot group
+                strd_s16x4 vr8[2][(DT + 3) / 4][8];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    if (diag && kb + 8 * (i / 4) + 4 * half + (i % 4) > tq) sacc[i] = -INFINITY;
-                    tm = fmaxf(tm, sacc[i]);
+                for (int ks2 = 0; ks2 < 2; ++ks2) {
+                    const bf16_t *vp = lds.v[cur].at(32 * kt + 16 * ks2 + v_krow, v_col);
+#pragma unroll
+                    for (int dp = 0; dp < DT; dp += 4)
+                        lds_issue_tr8<0, kHi, 64, 64 + kHi, 128, 128 + kHi, 192, 192 + kHi>(vp + 32 * dp, vr8[ks2][dp / 4]);
                 }
+                if (kb + 31 > wq0) {  // uniform: some (key, query) pair of the tile is masked
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (kb + 8 * (i / 4) + 4 * half + (i % 4) > tq) sacc[i] = -INFINITY;
+                }
+                float tm = -INFINITY;  // max of this lane half's 16 raw scores
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tm = fmaxf(tm, sacc[i]);
                 // m_run (raw units) is common to both lane halves of a query; it only has to move, and
                 // the halves only have to talk, when some lane of the wave sees a larger score
                 if (__any(tm > m_run)) {
@@ -151,18 +167,15 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
                 }
                 l_run += ps;
 #pragma unroll
-                for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    const bf16_t *vp = lds.v[cur].at(32 * kt + 16 * ks2 + v_krow, v_col);
-                    constexpr int kHi = 8 * Tile<D>::kPitch * 2;  // byte offset of the second 4 keys of a slot group
+                for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
                     for (int dp = 0; dp < DT; dp += 4) {
-                        strd_s16x4 r[8];
-                        lds_read_tr8<0, kHi, 64, 64 + kHi, 128, 128 + kHi, 192, 192 + kHi>(vp + 32 * dp, r);
+                        strd_s16x4(&r)[8] = vr8[ks2][dp / 4];
+                        lds_settle8(r);
 #pragma unroll
                         for (int dd = 0; dd < 4; ++dd)
                             if (dp + dd < DT) oacc[dp + dd] = mfma32(tr_pair(r[2 * dd], r[2 * dd + 1]), pf[ks2], oacc[dp + dd]);
                     }
-                }
             }
         }
         async_tile_wait();
