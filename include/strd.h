@@ -59,7 +59,7 @@ int strd_version(void);
  *   q_txt  [dev] [M, Hq, d]   text-row queries (already projected / rotated)
  *   k_vis  [dev] [N, Hkv, d]  vision-row keys
  *   scores [dev] [N] fp32     output
- * Requires M,N >= 1, Hq % Hkv == 0.  Deterministic (fixed reduction order).
+ * Requires M,N >= 1, Hq % Hkv == 0, scale > 0.  Deterministic (fixed reduction order).
  * ------------------------------------------------------------------------- */
 size_t strd_score_attn_workspace(int M, int N, int Hq, int Hkv, int d, strd_dtype io);
 int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, int N, int Hq,

@@ -39,7 +39,8 @@ size_t strd_score_attn_workspace(int M, int N, int Hq, int Hkv, int d, strd_dtyp
 
 int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, int N, int Hq, int Hkv,
                     int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
-    if (!q_txt || !k_vis || !scores || M < 1 || N < 1 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io))
+    if (!q_txt || !k_vis || !scores || M < 1 || N < 1 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io) ||
+        !(scale > 0.f))
         return STRD_EINVAL;
     if ((long long)M * Hq > (1 << 30)) return STRD_EUNSUPPORTED;
     const size_t need = strd_score_attn_workspace(M, N, Hq, Hkv, d, io);

@@ -51,7 +51,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
     constexpr int KS = D / 16, DT = D / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int h = blockIdx.x % Hq, qb = nqb - 1 - blockIdx.x / Hq, kvh = h / (Hq / Hkv);
     const int t0 = qb * kBM;
     const int tq = t0 + 32 * w + lc;             // this lane's query position

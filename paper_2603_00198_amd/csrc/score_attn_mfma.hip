@@ -65,7 +65,8 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
     constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int rep = Hq / Hkv, R = M * rep;
     const int rb = blockIdx.x % nrb, kvh = (blockIdx.x / nrb) % Hkv, sl = blockIdx.x / (nrb * Hkv);
     const int key0 = sl * keys_per_slice, key1 = min(N, key0 + keys_per_slice);
@@ -112,27 +113,34 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
                 f32x16 acc[kTW];
 #pragma unroll
                 for (int qt = 0; qt < kTW; ++qt) acc[qt] = zero16();
+                // all key fragments of the tile first (one LDS round trip, not one per product)
+                bf16x8 kf[KS];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * kt + lc, 16 * ks + 8 * half));
+                for (int ks = 0; ks < KS; ++ks)
+                    kf[ks] = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * kt + lc, 16 * ks + 8 * half));
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int qt = 0; qt < kTW; ++qt) acc[qt] = mfma32(a, bq[qt][ks], acc[qt]);
-                }
-                const bool partial = kbase + 32 * kt + 32 > key1;
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int qt = 0; qt < kTW; ++qt) acc[qt] = mfma32(kf[ks], bq[qt][ks], acc[qt]);
+                const bool partial = kbase + 32 * kt + 32 > key1;  // uniform
 #pragma unroll
                 for (int qt = 0; qt < kTW; ++qt) {
-                    float z[16], tmax = -INFINITY;
+                    // running max in log2 units; the scale (> 0) commutes with the max and is folded
+                    // into the exponent's fma
+                    if (partial) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        z[i] = acc[qt][i] * scale2;
-                        if (partial && kbase + 32 * kt + 8 * (i / 4) + 4 * half + (i % 4) >= key1) z[i] = -INFINITY;
-                        tmax = fmaxf(tmax, z[i]);
+                        for (int i = 0; i < 16; ++i)
+                            if (kbase + 32 * kt + 8 * (i / 4) + 4 * half + (i % 4) >= key1) acc[qt][i] = -INFINITY;
                     }
-                    const float nm = fmaxf(run_m[qt], tmax);
+                    float tmax = -INFINITY;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[qt][i]);
+                    const float nm = fmaxf(run_m[qt], tmax * scale2);
                     const float ref = (nm == -INFINITY) ? 0.f : nm;
                     float ts = 0.f;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) ts += ex2(z[i] - ref);
+                    for (int i = 0; i < 16; ++i) ts += ex2(fmaf(acc[qt][i], scale2, -ref));
                     run_s[qt] = run_s[qt] * ex2(run_m[qt] - ref) + ts;
                     run_m[qt] = nm;
                 }
@@ -180,7 +188,8 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
     constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int rep = Hq / Hkv, R = M * rep;
     const int kvh = blockIdx.x % Hkv, kb = blockIdx.x / Hkv;
     const int nchunk = (R + kRows - 1) / kRows;
@@ -235,12 +244,15 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
                 f32x16 acc[kTW];
 #pragma unroll
                 for (int kt = 0; kt < kTW; ++kt) acc[kt] = zero16();
+                bf16x8 qf[KS];  // all query fragments of the tile first (one LDS round trip)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * qt + lc, 16 * ks + 8 * half));
+                for (int ks = 0; ks < KS; ++ks)
+                    qf[ks] = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * qt + lc, 16 * ks + 8 * half));
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int kt = 0; kt < kTW; ++kt) acc[kt] = mfma32(ak[kt][ks], b, acc[kt]);
-                }
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int kt = 0; kt < kTW; ++kt) acc[kt] = mfma32(ak[kt][ks], qf[ks], acc[kt]);
 #pragma unroll
                 for (int kt = 0; kt < kTW; ++kt)
 #pragma unroll

@@ -52,7 +52,8 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<NS> &lds = *reinterpret_cast<Tile<NS> *>(smem_raw);
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lc = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int g = blockIdx.y;
     const int nmc = (M + kMC - 1) / kMC;
     const int tok0 = blockIdx.x * (128 * CT) + w * (32 * CT);
