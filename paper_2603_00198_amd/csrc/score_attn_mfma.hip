@@ -164,25 +164,40 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
     }
 }
 
-// combine: lse2[row] = log2 sum over slices; one thread per query row
+// combine: lse2[row] = log2 sum over slices.  A workgroup takes 16 rows; thread (j, r) = (tid / 16,
+// tid % 16) folds slices j, j + 16, ... of row r (16 adjacent rows per load: coalesced), then the 16
+// partial (max, sum) pairs of a row meet in LDS in a fixed order.
 __global__ __launch_bounds__(kThreads) void attn_lse_kernel(const float *__restrict__ pmax, const float *__restrict__ psum,
                                                             float *__restrict__ lse2, int rows, int nslice) {
-    const int r = blockIdx.x * kThreads + threadIdx.x;
-    if (r >= rows) return;
-    float m = -INFINITY;
-    for (int s = 0; s < nslice; ++s) m = fmaxf(m, pmax[(size_t)s * rows + r]);
-    float tot = 0.f;
-    for (int s = 0; s < nslice; ++s) {
-        const float pm = pmax[(size_t)s * rows + r];
-        if (pm != -INFINITY) tot += psum[(size_t)s * rows + r] * ex2(pm - m);
+    __shared__ float sm[16][17], ss[16][17];
+    const int j = threadIdx.x >> 4, rr = threadIdx.x & 15;
+    const int r = min(blockIdx.x * 16 + rr, rows - 1);
+    float m = -INFINITY, tot = 0.f;
+    for (int s = j; s < nslice; s += 16) {  // online (max, sum) over this thread's slices
+        const float pm = pmax[(size_t)s * rows + r], ps = psum[(size_t)s * rows + r];
+        if (pm != -INFINITY) {
+            const float nm = fmaxf(m, pm);
+            tot = tot * ex2(m - nm) + ps * ex2(pm - nm);
+            m = nm;
+        }
     }
-    lse2[r] = m + __log2f(tot);
+    sm[j][rr] = m;
+    ss[j][rr] = tot;
+    __syncthreads();
+    if (j == 0 && blockIdx.x * 16 + rr < rows) {
+        float gm = -INFINITY;
+        for (int q = 0; q < 16; ++q) gm = fmaxf(gm, sm[q][rr]);
+        float t = 0.f;
+        for (int q = 0; q < 16; ++q)
+            if (sm[q][rr] != -INFINITY) t += ss[q][rr] * ex2(sm[q][rr] - gm);
+        lse2[r] = gm + __log2f(t);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // pass 2: grid = kv heads (fastest) x key blocks
 template <int D>
-__global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_colsum_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                                const float *__restrict__ lse2, float *__restrict__ part,
                                                                int M, int N, int Hq, int Hkv, float scale2) {
     constexpr int KS = D / 16;
@@ -210,11 +225,15 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
 #pragma unroll
     for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
     float stage_lse = 0.f;
+    // rows per kv head are usually a power of two: shift and mask instead of a division per copy
+    const int rep_shift = (rep & (rep - 1)) == 0 ? __builtin_ctz(rep) : -1;  // uniform
     auto stage = [&](int chunk, int b) {
 #pragma unroll
         for (int i = 0; i < AT::kIssues; ++i) {
             const int rr = min(chunk * kRows + st_row[i], R - 1);
-            AT::issue(q + qrow_index(rr, rep, Hq, kvh) * D + st_col[i] * 8, &lds.t[b], w, i);
+            const size_t qi = rep_shift >= 0 ? (size_t)(rr >> rep_shift) * Hq + kvh * rep + (rr & (rep - 1))
+                                             : qrow_index(rr, rep, Hq, kvh);
+            AT::issue(q + qi * D + st_col[i] * 8, &lds.t[b], w, i);
         }
         if (tid < kRows) {
             const int rr = chunk * kRows + tid;
@@ -237,26 +256,63 @@ __global__ __launch_bounds__(kThreads) void attn_colsum_kernel(const bf16_t *__r
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int cur = chunk & 1;
         stage(min(chunk + 1, nchunk - 1), cur ^ 1);
+        // Units of work: (query tile qt, key tile kt), 8 products each, then 16 exponentials folded
+        // into the column sums.  The products of the next unit are issued before the exponentials
+        // of the current one (two accumulators), so the matrix pipe works while the wave does its
+        // vector arithmetic.  Query tiles wholly past the end are skipped (uniform).
+        auto load_q = [&](int qt, bf16x8 (&qf)[KS]) {  // all fragments of a tile at once: one LDS round trip
 #pragma unroll
-        for (int qt = 0; qt < kRows / 32; ++qt) {
-            if (chunk * kRows + 32 * qt < R) {  // uniform: skip query tiles wholly past the end
+            for (int ks = 0; ks < KS; ++ks)
+                qf[ks] = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * qt + lc, 16 * ks + 8 * half));
+        };
+        auto products = [&](int kt, const bf16x8 (&qf)[KS]) {
+            f32x16 acc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = mfma32(ak[kt][ks], qf[ks], acc);
+            return acc;
+        };
+        auto fold = [&](int kt, const f32x16 &acc, float lse) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) col[kt * 16 + i] += ex2(fmaf(acc[i], scale2, -lse));
+        };
+        // ask the scheduler for one product, then six vector instructions (2 x fma, exp, add), eight times
+        auto interleave = [] {
+#pragma unroll
+            for (int i = 0; i < KS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one product
+                __builtin_amdgcn_sched_group_barrier(0x002, 16 / KS, 0);  // fma of the next elements
+                __builtin_amdgcn_sched_group_barrier(0x400, 16 / KS, 0);  // their exponentials
+                __builtin_amdgcn_sched_group_barrier(0x002, 16 / KS, 0);  // adds of the previous ones
+            }
+        };
+        static_assert(kTW == 2, "two key tiles per wave");
+        bf16x8 qf[KS];
+        if (chunk * kRows + kRows <= R) {  // uniform: every query tile of the chunk is real -- one straight block
+            load_q(0, qf);
+            float lse = lds.lse[cur][lc];
+            f32x16 acc0 = products(0, qf), acc1;
+#pragma unroll
+            for (int qt = 0; qt < kRows / 32; ++qt) {
+                acc1 = products(1, qf);  // last use of this tile's fragments
+                float lse_next = 0.f;
+                if (qt + 1 < kRows / 32) {
+                    load_q(qt + 1, qf);
+                    lse_next = lds.lse[cur][32 * (qt + 1) + lc];
+                }
+                fold(0, acc0, lse);
+                interleave();
+                if (qt + 1 < kRows / 32) acc0 = products(0, qf);
+                fold(1, acc1, lse);
+                if (qt + 1 < kRows / 32) interleave();
+                lse = lse_next;
+            }
+        } else {
+            for (int qt = 0; chunk * kRows + 32 * qt < R; ++qt) {  // ragged last chunk: tile by tile
+                load_q(qt, qf);
                 const float lse = lds.lse[cur][32 * qt + lc];
-                f32x16 acc[kTW];
-#pragma unroll
-                for (int kt = 0; kt < kTW; ++kt) acc[kt] = zero16();
-                bf16x8 qf[KS];  // all query fragments of the tile first (one LDS round trip)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    qf[ks] = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * qt + lc, 16 * ks + 8 * half));
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                    for (int kt = 0; kt < kTW; ++kt) acc[kt] = mfma32(ak[kt][ks], qf[ks], acc[kt]);
-#pragma unroll
-                for (int kt = 0; kt < kTW; ++kt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) col[kt * 16 + i] += ex2(fmaf(acc[kt][i], scale2, -lse));
+                const f32x16 acc0 = products(0, qf), acc1 = products(1, qf);
+                fold(0, acc0, lse);
+                fold(1, acc1, lse);
             }
         }
         stage_lse_store(cur ^ 1);
@@ -338,7 +394,7 @@ int run(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, f
     const int rows = M * Hq;
     attn_stats_kernel<D><<<p.nrb * Hkv * p.nslice, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, pmax, psum, M,
                                                                          N, Hq, Hkv, scale2, p.nrb, p.keys_per_slice);
-    attn_lse_kernel<<<ceil_div(rows, kThreads), kThreads, 0, st>>>(pmax, psum, lse2, rows, p.nslice);
+    attn_lse_kernel<<<ceil_div(rows, 16), kThreads, 0, st>>>(pmax, psum, lse2, rows, p.nslice);
     const int nkb = ceil_div(N, 4 * 32 * kTW);
     attn_colsum_kernel<D><<<nkb * Hkv, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, lse2, part, M, N, Hq,
                                                             Hkv, scale2);
