@@ -58,17 +58,20 @@ __device__ __forceinline__ size_t qrow_index(int r, int rep, int Hq, int kvh) {
 // ---------------------------------------------------------------------------------------------
 // pass 1: grid = row blocks (fastest) x kv heads x key slices
 template <int D>
-__global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_stats_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                               float *__restrict__ pmax, float *__restrict__ psum, int M,
                                                               int N, int Hq, int Hkv, float scale2, int nrb,
-                                                              int keys_per_slice) {
+                                                              int keys_per_slice, int nunits) {
     constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int rep = Hq / Hkv, R = M * rep;
-    const int rb = blockIdx.x % nrb, kvh = (blockIdx.x / nrb) % Hkv, sl = blockIdx.x / (nrb * Hkv);
+    // the row blocks of one (kv head, slice) stream the same keys: keep them on one XCD's L2
+    const int unit = xcd_swizzle(blockIdx.x, nunits);
+    if (unit >= nunits) return;
+    const int rb = unit % nrb, kvh = (unit / nrb) % Hkv, sl = unit / (nrb * Hkv);
     const int key0 = sl * keys_per_slice, key1 = min(N, key0 + keys_per_slice);
     const int nchunk = (key1 - key0 + kRows - 1) / kRows;
 
@@ -107,43 +110,71 @@ __global__ __launch_bounds__(kThreads) void attn_stats_kernel(const bf16_t *__re
         const int cur = chunk & 1;
         stage(min(chunk + 1, nchunk - 1), cur ^ 1);
         const int kbase = key0 + chunk * kRows;
+        // Units of work: (key tile kt, query tile qt): 8 products, then the online (max, sum) update
+        // with 16 exponentials.  In a full chunk the products of the next unit are issued with the
+        // vector arithmetic of the current one (two accumulators).
+        auto load_k = [&](int kt, bf16x8 (&kf)[KS]) {  // all fragments of a tile at once: one LDS round trip
 #pragma unroll
-        for (int kt = 0; kt < kRows / 32; ++kt) {
-            if (kbase + 32 * kt < key1) {  // uniform: skip tiles wholly past the slice
-                f32x16 acc[kTW];
+            for (int ks = 0; ks < KS; ++ks)
+                kf[ks] = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * kt + lc, 16 * ks + 8 * half));
+        };
+        auto products = [&](int qt, const bf16x8 (&kf)[KS]) {
+            f32x16 acc = zero16();
 #pragma unroll
-                for (int qt = 0; qt < kTW; ++qt) acc[qt] = zero16();
-                // all key fragments of the tile first (one LDS round trip, not one per product)
-                bf16x8 kf[KS];
+            for (int ks = 0; ks < KS; ++ks) acc = mfma32(kf[ks], bq[qt][ks], acc);
+            return acc;
+        };
+        // running max in log2 units; the scale (> 0) commutes with the max and is folded into the
+        // exponent's fma
+        auto fold = [&](int qt, const f32x16 &acc) {
+            float tmax = -INFINITY;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    kf[ks] = *reinterpret_cast<const bf16x8 *>(lds.t[cur].at(32 * kt + lc, 16 * ks + 8 * half));
-                __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+            const float nm = fmaxf(run_m[qt], tmax * scale2);
+            const float ref = (nm == -INFINITY) ? 0.f : nm;
+            float ts = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
+            for (int i = 0; i < 16; ++i) ts += ex2(fmaf(acc[i], scale2, -ref));
+            run_s[qt] = run_s[qt] * ex2(run_m[qt] - ref) + ts;
+            run_m[qt] = nm;
+        };
+        auto interleave = [] {  // per product: its share of the 16 fma / exp / add and of the 8 max3
 #pragma unroll
-                    for (int qt = 0; qt < kTW; ++qt) acc[qt] = mfma32(kf[ks], bq[qt][ks], acc[qt]);
-                const bool partial = kbase + 32 * kt + 32 > key1;  // uniform
+            for (int i = 0; i < KS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 24 / KS, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 16 / KS, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 16 / KS, 0);
+            }
+        };
+        static_assert(kTW == 2, "two query tiles per wave");
+        bf16x8 kf[KS];
+        if (kbase + kRows <= key1) {  // uniform: every key of the chunk belongs to the slice -- one straight block
+            load_k(0, kf);
+            f32x16 acc0 = products(0, kf), acc1;
 #pragma unroll
-                for (int qt = 0; qt < kTW; ++qt) {
-                    // running max in log2 units; the scale (> 0) commutes with the max and is folded
-                    // into the exponent's fma
-                    if (partial) {
+            for (int kt = 0; kt < kRows / 32; ++kt) {
+                acc1 = products(1, kf);  // last use of this tile's fragments
+                if (kt + 1 < kRows / 32) load_k(kt + 1, kf);
+                fold(0, acc0);
+                interleave();
+                if (kt + 1 < kRows / 32) acc0 = products(0, kf);
+                fold(1, acc1);
+                if (kt + 1 < kRows / 32) interleave();
+            }
+        } else {
+            for (int kt = 0; kbase + 32 * kt < key1; ++kt) {  // ragged last chunk: tile by tile, keys past the slice masked
+                load_k(kt, kf);
+                f32x16 acc[kTW] = {products(0, kf), products(1, kf)};
+                if (kbase + 32 * kt + 32 > key1) {
+#pragma unroll
+                    for (int qt = 0; qt < kTW; ++qt)
 #pragma unroll
                         for (int i = 0; i < 16; ++i)
                             if (kbase + 32 * kt + 8 * (i / 4) + 4 * half + (i % 4) >= key1) acc[qt][i] = -INFINITY;
-                    }
-                    float tmax = -INFINITY;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[qt][i]);
-                    const float nm = fmaxf(run_m[qt], tmax * scale2);
-                    const float ref = (nm == -INFINITY) ? 0.f : nm;
-                    float ts = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) ts += ex2(fmaf(acc[qt][i], scale2, -ref));
-                    run_s[qt] = run_s[qt] * ex2(run_m[qt] - ref) + ts;
-                    run_m[qt] = nm;
                 }
+                fold(0, acc[0]);
+                fold(1, acc[1]);
             }
         }
         async_tile_wait();
@@ -392,8 +423,9 @@ int run(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, f
     float *lse2 = (float *)(base + p.off_lse), *part = (float *)(base + p.off_part);
     const float scale2 = scale * kLog2e;
     const int rows = M * Hq;
-    attn_stats_kernel<D><<<p.nrb * Hkv * p.nslice, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, pmax, psum, M,
-                                                                         N, Hq, Hkv, scale2, p.nrb, p.keys_per_slice);
+    const int nunits = p.nrb * Hkv * p.nslice;
+    attn_stats_kernel<D><<<xcd_grid(nunits), kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, pmax, psum, M, N, Hq,
+                                                                   Hkv, scale2, p.nrb, p.keys_per_slice, nunits);
     attn_lse_kernel<<<ceil_div(rows, 16), kThreads, 0, st>>>(pmax, psum, lse2, rows, p.nslice);
     const int nkb = ceil_div(N, 4 * 32 * kTW);
     attn_colsum_kernel<D><<<nkb * Hkv, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, lse2, part, M, N, Hq,
