@@ -182,6 +182,10 @@ class MambaLayer:
         row = w.d_model * eb if self.fused else (s.H * s.P + 2 * s.G * s.n + w.d_model) * eb + 4 * s.H
         return 2 * (w.K + w.M) * row + 4 * w.K * (1 if self.fused else 5)
 
+    def score_work(self):   # (algorithmic bytes, flops) of score_mamba
+        w, s, eb = self.w, self.s, self.hidden.element_size()
+        return (w.N * (s.G * s.n * eb + 4 * s.H) + w.M * s.G * s.n * eb + 4 * w.N, 2.0 * w.M * w.N * s.n * s.G)
+
     mixer_name, mixer_bound = "ssd_prefill", "hbm"
 
 
@@ -251,6 +255,10 @@ class AttnLayer:
         row = (s.Hq * s.d + 2 * s.Hkv * s.d + w.d_model) * eb
         return 2 * (w.K + w.M) * row + 4 * w.K * 4
 
+    def score_work(self):   # (algorithmic bytes, flops by definition -- executed twice) of score_attn
+        w, s, eb = self.w, self.s, self.hidden.element_size()
+        return (w.N * s.Hkv * s.d * eb + w.M * s.Hq * s.d * eb + 4 * w.N, 2.0 * w.M * w.N * s.d * s.Hq)
+
     mixer_name, mixer_bound = "attn_prefill", "mfma"
 
 
@@ -278,6 +286,34 @@ def cpu_baseline_mamba(layer, synth):
     return {"value": (N + M) / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": "the whole reduced layer of this workload (all %d vision + %d text tokens, all heads), "
                       "fp64, mean of %d passes of %.2f s" % (N, M, reps, dt)}
+
+
+def cpu_single_thread_c1(torch, synth):
+    """The oracle on the whole tiny pair c1 (reduced Mamba-2 layer + reduced attention layer) with one thread."""
+    import subprocess
+    code = (
+        "import time, numpy as np, torch, oracle\n"
+        "from paper_2603_00198_amd import synth\n"
+        "w = synth.WORKLOADS['c1']; N, M, K = w.N, w.M, w.K; f = synth.np64\n"
+        "h = synth.hidden_states(w, 'cpu'); t = synth.mamba_inputs(w, h); a = synth.attn_inputs(w, h)\n"
+        "oracle.select_topk(np.zeros(4), 2)\n"
+        "t0 = time.perf_counter()\n"
+        "s = oracle.score_mamba(f(t['B'][:N]), f(t['C'][N:]), f(t['dt'][:N])); i = oracle.select_topk(s, K)\n"
+        "r = {k: oracle.compact(f(t[k]), i, N, M)[0] for k in ('x', 'dt', 'B', 'C')}\n"
+        "oracle.ssd_seq(r['x'], r['dt'], f(t['A']), r['B'], r['C'])\n"
+        "s = oracle.score_attn(f(a['q'][N:]), f(a['k'][:N])); i = oracle.select_topk(s, K)\n"
+        "r = {k: oracle.compact(f(a[k]), i, N, M)[0] for k in ('q', 'k', 'v')}\n"
+        "oracle.attn(r['q'], r['k'], r['v'])\n"
+        "print(time.perf_counter() - t0)\n")
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300,
+                         cwd=os.path.dirname(os.path.abspath(__file__)))
+    if out.returncode != 0:
+        return None
+    dt = float(out.stdout.strip().splitlines()[-1])
+    w = synth.WORKLOADS["c1"]
+    return {"value": 2 * (w.N + w.M) / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": "c1: reduced Mamba-2 layer + reduced attention layer, whole workload, one thread, %.2f s" % dt}
 
 
 def cpu_baseline_attn(layer, synth, rows=48, txt_rows=4):
@@ -460,6 +496,18 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         roof = {"bound": "mfma", "kernel": layer.mixer_name, "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((name, budget))}
+    # every call against both published peaks (algorithmic work / event-timed duration)
+    def fr(nbytes, flops, us):
+        return {"us": us, "GBps": nbytes / (us * 1e-6) / 1e9, "frac_hbm": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "TFLOPs": flops / (us * 1e-6) / 1e12, "frac_mfma": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    sb, sf = layer.score_work()
+    per_call = {
+        "score": fr(sb, sf, calls["score_us"]),
+        "select_topk": fr(4 * w.N + 4 * w.K, 0.0, calls["select_topk_us"]),
+        "compact": fr(layer.compact_bytes(), 0.0, calls["compact_us"]),
+        "mixer_reduced": fr(layer.mixer_bytes(Tr), layer.mixer_flops(Tr), calls["mixer_reduced_us"]),
+        "mixer_full": fr(layer.mixer_bytes(w.T), layer.mixer_flops(w.T), calls["mixer_full_us"]),
+    }
     fused = None
     if kind == "mamba":   # variant: the scan gathers its inputs itself (same y, bit for bit; see tests)
         layer.fused = True
@@ -483,6 +531,7 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         "retained_tokens_per_s": Tr / (ms_step * 1e-3), "speedup_vs_full": ms_full / ms_step,
         "calls": calls, "select_plus_compact_GBps": sel_compact_gbs,
         "select_plus_compact_frac_of_hbm": sel_compact_gbs / HBM_PEAK_GBS, "roofline": roof,
+        "per_call_roofline": per_call,
     }
     if fused:
         res["gather_fused_variant"] = fused
@@ -527,7 +576,7 @@ def main():
         "graph_replay_ms_per_step": res["graph_replay_ms_per_step"],
         "calls_us": res["calls"], "select_plus_compact_GBps": res["select_plus_compact_GBps"],
         "select_plus_compact_frac_of_hbm": res["select_plus_compact_frac_of_hbm"],
-        "roofline": res["roofline"], "context": PAPER_CONTEXT,
+        "roofline": res["roofline"], "per_call_roofline": res["per_call_roofline"], "context": PAPER_CONTEXT,
     }
     if "gather_fused_variant" in res:
         line["gather_fused_variant"] = res["gather_fused_variant"]
@@ -549,6 +598,7 @@ def main():
             layer = MambaLayer(torch, strd, synth, replace(synth.WORKLOADS["c2"], budget=args.budget), dev)
         line["cpu_baseline"] = cpu_baseline_mamba(layer, synth) if layer.kind == "mamba" \
             else cpu_baseline_attn(layer, synth)
+        line["cpu_baseline"]["single_thread_c1"] = cpu_single_thread_c1(torch, synth)
     print(json.dumps(line))
 
 
