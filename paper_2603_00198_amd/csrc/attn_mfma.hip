@@ -202,13 +202,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
 template <int D>
 int launch(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, float scale, hipStream_t st) {
     const size_t smem = sizeof(Tile<D>);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return STRD_EHIP;
-        configured = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_mfma_kernel<D>), smem))
+        return STRD_EHIP;
     const int nqb = ceil_div(T, kBM);
     attn_mfma_kernel<D><<<nqb * Hq, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
                                                           (bf16_t *)o, T, Hq, Hkv, scale * kLog2e, nqb);

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "strd.h"
 
 namespace strd {
@@ -151,6 +153,27 @@ __device__ __forceinline__ float wave_inclusive_scan_f32(float v) {
     STRD_DPP_FADD(0x143, 0xC);  // row_bcast:31 into rows 2 and 3
 #undef STRD_DPP_FADD
     return v;
+}
+
+// Kernels whose LDS tile exceeds the 64 KB default need the limit raised once per (kernel, device);
+// a process may drive several devices and call from several threads.
+inline bool allow_dynamic_lds(const void *kernel, size_t bytes) {
+    constexpr int kMaxDev = 64, kMaxFn = 64;
+    static std::mutex mu;
+    static const void *fn[kMaxFn];
+    static unsigned long long done[kMaxFn];  // bit d: configured on device d
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    int slot = -1;
+    for (int i = 0; i < kMaxFn; ++i) {
+        if (fn[i] == kernel) { slot = i; break; }
+        if (!fn[i]) { fn[i] = kernel; slot = i; break; }
+    }
+    if (slot >= 0 && (done[slot] >> dev & 1ull)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+    if (slot >= 0) done[slot] |= 1ull << dev;
+    return true;
 }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? STRD_OK : STRD_EHIP; }

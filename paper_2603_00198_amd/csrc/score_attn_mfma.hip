@@ -409,15 +409,9 @@ template <int D>
 int run(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, float scale, void *ws, hipStream_t st) {
     const Plan p = make_plan(M, N, Hq, Hkv);
     const size_t smem = sizeof(Tile<D>);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_stats_kernel<D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_colsum_kernel<D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return STRD_EHIP;
-        configured = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_stats_kernel<D>), smem) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&attn_colsum_kernel<D>), smem))
+        return STRD_EHIP;
     char *base = (char *)ws;
     float *pmax = (float *)(base + p.off_pmax), *psum = (float *)(base + p.off_psum);
     float *lse2 = (float *)(base + p.off_lse), *part = (float *)(base + p.off_part);

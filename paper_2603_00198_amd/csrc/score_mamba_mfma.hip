@@ -206,13 +206,8 @@ template <int NS, int CT>
 int launch_full(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H, int G,
                 void *ws, hipStream_t st) {
     const size_t smem = sizeof(Tile<NS>);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return STRD_EHIP;
-        configured = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT, true>), smem))
+        return STRD_EHIP;
     float *part = (float *)ws;
     const dim3 grid(ceil_div(N, 128 * CT), G);
     score_mamba_mfma_kernel<NS, CT, true><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, U, V, part,
@@ -226,13 +221,8 @@ template <int NS, int CT>
 int launch(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, void *ws,
            hipStream_t st) {
     const size_t smem = sizeof(Tile<NS>);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return STRD_EHIP;
-        configured = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, CT, false>), smem))
+        return STRD_EHIP;
     float *part = (float *)ws;
     const dim3 grid(ceil_div(N, 128 * CT), G);
     score_mamba_mfma_kernel<NS, CT, false><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, nullptr,

@@ -256,17 +256,10 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
 
 int select_topk_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s) {
     const size_t smem = (size_t)kBins * kCopies * sizeof(uint32_t);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&select_topk_kernel<0>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return STRD_EHIP;
-        configured = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<2>), smem) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<8>), smem) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<0>), smem))
+        return STRD_EHIP;
     if (N <= 2 * kTile)
         select_topk_kernel<2><<<1, kThreads, smem, s>>>(scores, N, K, idx);
     else if (N <= 8 * kTile)

@@ -545,13 +545,8 @@ int launch(const void *x, const float *dt, const float *A, const void *B, const 
            hipStream_t st) {
     const int nunits = H * (P / kPB);
     const size_t smem = sizeof(Lds<NS>);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&ssd_mfma_kernel<NS, GATHER>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return STRD_EHIP;
-        configured = true;
-    }
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&ssd_mfma_kernel<NS, GATHER>), smem))
+        return STRD_EHIP;
     ssd_mfma_kernel<NS, GATHER><<<xcd_grid(nunits), kThreads, smem, st>>>(
         (const bf16_t *)x, dt, A, (const bf16_t *)B, (const bf16_t *)C, D, S_in, (bf16_t *)y, S_out, idx, N, K, T, H, P,
         G, nunits);
