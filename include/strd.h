@@ -184,6 +184,33 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
                       int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * Block glue around the mixers (next row 3 of the scope table): what a hybrid layer does between
+ * its projections and the scan or attention, apart from matrix products.  The paper builds on
+ * the Mamba-2 block and does not restate these operations; they follow that block's published
+ * definition.  All: [dev] tensors of the io dtype (weights included) unless stated, fp32
+ * arithmetic, one rounding on output, asynchronous on `stream`, T = 0 allowed.
+ *
+ * rmsnorm:        out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + eps) * w            x, out [T, d], w [d]
+ * gated_rmsnorm:  v = y * silu(z); out = v / sqrt(mean_group(v^2) + eps) * w    y, out [T, D]; z rows of
+ *                 pitch ldz >= D elements; `groups` equal groups of D / groups channels each; w [D]
+ * conv1d_silu:    causal depthwise convolution over tokens with zero history, then SiLU,
+ *                   o[t,c] = silu(b[c] + sum_{k<W} w[c,k] * xbc[t-(W-1)+k, c]),
+ *                 on the first Cx + 2*Cb columns of xbc (rows of pitch ld elements); columns
+ *                 [0,Cx) go to x_out [T,Cx], the next Cb to B_out [T,Cb], the last Cb to C_out
+ *                 [T,Cb]; w [Cx+2*Cb, W], b [Cx+2*Cb] or NULL.  Cx, Cb, ld multiples of 8 and
+ *                 16-byte (bf16) / 32-byte (fp32) aligned bases, else STRD_EUNSUPPORTED.
+ * softplus_dt:    dt[t,h] = log(1 + exp(raw[t, col0+h] + bias[h])), raw rows of pitch ld in the io
+ *                 dtype, bias [H] fp32 or NULL, dt [T,H] fp32.
+ * ------------------------------------------------------------------------- */
+int strd_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, void *stream);
+int strd_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D,
+                       int groups, float eps, strd_dtype io, void *stream);
+int strd_conv1d_silu(const void *xbc, int ld, const void *w, const void *b, void *x_out, void *B_out,
+                     void *C_out, int T, int Cx, int Cb, int W, strd_dtype io, void *stream);
+int strd_softplus_dt(const void *raw, int ld, int col0, const float *bias, float *dt, int T, int H,
+                     strd_dtype io, void *stream);
+
+/* ---------------------------------------------------------------------------
  * schedule_budgets -- per-layer token budgets of a retention schedule (Sec. 3.2
  * and App. "Reduction Schedule Configurations").  alpha_l is relative to the
  * original count N0; budgets never grow with depth and never fall below

@@ -183,3 +183,37 @@ def attn(q, k, v, scale=None, rows=None):
     _check(_load().oracle_attn(_p(q), _p(k), _p(v), _p(o), T, Hq, Hkv, d, ctypes.c_double(scale),
                                _p(r), nrows), "attn")
     return o
+
+
+# ------------------------------------------------------------------ block glue -------------
+def rmsnorm(x, w, eps=1e-5):
+    x, w = _f64(x), _f64(w)
+    out = np.empty_like(x)
+    _check(_load().oracle_rmsnorm(_p(x), _p(w), _p(out), x.shape[0], x.shape[1], ctypes.c_double(eps)), "rmsnorm")
+    return out
+
+
+def gated_rmsnorm(y, z, w, groups=1, eps=1e-5):
+    y, z, w = _f64(y), _f64(z), _f64(w)
+    out = np.empty_like(y)
+    _check(_load().oracle_gated_rmsnorm(_p(y), _p(z), _p(w), _p(out), y.shape[0], y.shape[1], int(groups),
+                                        ctypes.c_double(eps)), "gated_rmsnorm")
+    return out
+
+
+def conv1d_silu(xbc, w, b=None):
+    """Causal depthwise conv + SiLU over all columns of xbc [T,C]; w [C,W], b [C] or None."""
+    xbc, w = _f64(xbc), _f64(w)
+    b = None if b is None else _f64(b)
+    out = np.empty_like(xbc)
+    _check(_load().oracle_conv1d_silu(_p(xbc), _p(w), _p(b), _p(out), xbc.shape[0], xbc.shape[1], w.shape[1]),
+           "conv1d_silu")
+    return out
+
+
+def softplus_dt(raw, bias=None):
+    raw = _f64(raw)
+    bias = None if bias is None else _f64(bias)
+    out = np.empty_like(raw)
+    _check(_load().oracle_softplus_dt(_p(raw), _p(bias), _p(out), raw.shape[0], raw.shape[1]), "softplus_dt")
+    return out

@@ -436,3 +436,71 @@ int oracle_attn(const double *q, const double *k, const double *v, double *o, in
         }
     return rc;
 }
+
+/* ------------------------------------------------------------------ */
+/* Block glue (the Mamba-2 block's operations around the scan; the      */
+/* paper builds on that block without restating them).                  */
+/* ------------------------------------------------------------------ */
+static double oracle_silu(double v) { return v / (1.0 + exp(-v)); }
+
+/* out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + eps) * w */
+int oracle_rmsnorm(const double *x, const double *w, double *out, int T, int d, double eps)
+{
+    if (T < 0 || d < 1) return -1;
+    for (int t = 0; t < T; ++t) {
+        double ss = 0.0;
+        for (int c = 0; c < d; ++c) ss += x[(size_t)t * d + c] * x[(size_t)t * d + c];
+        const double inv = 1.0 / sqrt(ss / d + eps);
+        for (int c = 0; c < d; ++c) out[(size_t)t * d + c] = x[(size_t)t * d + c] * inv * w[c];
+    }
+    return 0;
+}
+
+/* v = y * silu(z); per group of D/groups channels: out = v / sqrt(mean(v^2) + eps) * w */
+int oracle_gated_rmsnorm(const double *y, const double *z, const double *w, double *out, int T, int D,
+                         int groups, double eps)
+{
+    if (T < 0 || D < 1 || groups < 1 || D % groups) return -1;
+    const int gs = D / groups;
+    for (int t = 0; t < T; ++t)
+        for (int g = 0; g < groups; ++g) {
+            const size_t o = (size_t)t * D + (size_t)g * gs;
+            double ss = 0.0;
+            for (int c = 0; c < gs; ++c) {
+                const double v = y[o + c] * oracle_silu(z[o + c]);
+                ss += v * v;
+            }
+            const double inv = 1.0 / sqrt(ss / gs + eps);
+            for (int c = 0; c < gs; ++c) out[o + c] = y[o + c] * oracle_silu(z[o + c]) * inv * w[(size_t)g * gs + c];
+        }
+    return 0;
+}
+
+/* causal depthwise convolution with zero history, then SiLU:                     */
+/*   out[t,c] = silu(b[c] + sum_{k<W} w[c,k] * in[t-(W-1)+k, c]),  in, out [T,C]   */
+int oracle_conv1d_silu(const double *in, const double *w, const double *b, double *out, int T, int C, int W)
+{
+    if (T < 0 || C < 1 || W < 1) return -1;
+    for (int t = 0; t < T; ++t)
+        for (int c = 0; c < C; ++c) {
+            double acc = b ? b[c] : 0.0;
+            for (int k = 0; k < W; ++k) {
+                const int ts = t - (W - 1) + k;
+                if (ts >= 0) acc += w[(size_t)c * W + k] * in[(size_t)ts * C + c];
+            }
+            out[(size_t)t * C + c] = oracle_silu(acc);
+        }
+    return 0;
+}
+
+/* dt[t,h] = log(1 + exp(raw[t,h] + bias[h])) */
+int oracle_softplus_dt(const double *raw, const double *bias, double *dt, int T, int H)
+{
+    if (T < 0 || H < 1) return -1;
+    for (int t = 0; t < T; ++t)
+        for (int h = 0; h < H; ++h) {
+            const double v = raw[(size_t)t * H + h] + (bias ? bias[h] : 0.0);
+            dt[(size_t)t * H + h] = v > 0 ? v + log1p(exp(-v)) : log1p(exp(v));
+        }
+    return 0;
+}

@@ -36,6 +36,10 @@ _SIGNATURES = {
     "strd_ssd_prefill_gather": (_int, [_vp] * 10 + [_int] * 8 + [_int, _vp, _sz, _vp]),
     "strd_attn_prefill_workspace": (_sz, [_int] * 4 + [_int]),
     "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
+    "strd_rmsnorm": (_int, [_vp, _vp, _vp, _int, _int, _f32, _int, _vp]),
+    "strd_gated_rmsnorm": (_int, [_vp, _vp, _int, _vp, _vp, _int, _int, _int, _f32, _int, _vp]),
+    "strd_conv1d_silu": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp] + [_int] * 4 + [_int, _vp]),
+    "strd_softplus_dt": (_int, [_vp, _int, _int, _vp, _vp, _int, _int, _int, _vp]),
     "strd_schedule_budgets": (_int, [_vp, _int, _int, _int, _vp]),
     "strd_schedule_sigmoid": (_int, [_int, _c.c_double, _c.c_double, _c.c_double, _c.c_double, _vp]),
     "strd_schedule_step_decay": (_int, [_vp, _vp, _vp, _int, _int, _vp]),
@@ -324,6 +328,67 @@ def schedule_sigmoid(L: int, a_start: float = 1.0, a_end: float = 0.125, k: floa
     out = (ctypes.c_double * L)()
     _check(lib().strd_schedule_sigmoid(int(L), a_start, a_end, k, x0, ctypes.cast(out, _vp)), "schedule_sigmoid")
     return list(out)
+
+
+# ------------------------------------------------------------------ block glue -------------
+def _rows(t: torch.Tensor, what: str) -> int:
+    """Row pitch in elements of a 2-D GPU tensor whose rows are contiguous (a column slice is fine)."""
+    if not t.is_cuda:
+        raise StrdError("tensors must live on the GPU")
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise StrdError("%s: rows must be contiguous" % what)
+    return t.stride(0)
+
+
+def rmsnorm(x: torch.Tensor, w: torch.Tensor, eps: float = 1e-5, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(x, w, out)
+    T, d = x.shape
+    if not x.is_contiguous() or w.shape != (d,) or w.dtype != x.dtype:
+        raise StrdError("rmsnorm: x [T,d] contiguous, w [d] of the same dtype")
+    out = out if out is not None else torch.empty_like(x)
+    _check(lib().strd_rmsnorm(_ptr(x), _ptr(w), _ptr(out), T, d, eps, _io(x), _stream()), "rmsnorm")
+    return out
+
+
+def gated_rmsnorm(y: torch.Tensor, z: torch.Tensor, w: torch.Tensor, groups: int = 1, eps: float = 1e-5,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """rmsnorm(y * silu(z)) * w per group of channels; z may be a column slice of a wider matrix."""
+    _dev(y, w, out)
+    T, D = y.shape
+    if not y.is_contiguous() or z.shape != (T, D) or w.shape != (D,) or z.dtype != y.dtype or w.dtype != y.dtype:
+        raise StrdError("gated_rmsnorm: y, z [T,D], w [D], one dtype")
+    out = out if out is not None else torch.empty_like(y)
+    _check(lib().strd_gated_rmsnorm(_ptr(y), _ptr(z), _rows(z, "z"), _ptr(w), _ptr(out), T, D, groups, eps, _io(y),
+                                    _stream()), "gated_rmsnorm")
+    return out
+
+
+def conv1d_silu(xbc: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], Cx: int, Cb: int):
+    """Causal depthwise conv (w [Cx+2Cb, W]) + SiLU over the first Cx+2Cb columns of xbc (may be a
+    column slice); returns contiguous x [T,Cx], B [T,Cb], C [T,Cb]."""
+    _dev(w, b)
+    T = xbc.shape[0]
+    Ct = Cx + 2 * Cb
+    if xbc.shape[1] < Ct or w.dim() != 2 or w.shape[0] != Ct or w.dtype != xbc.dtype or not w.is_contiguous() \
+            or (b is not None and (b.shape != (Ct,) or b.dtype != xbc.dtype)):
+        raise StrdError("conv1d_silu: xbc [T, >=Cx+2Cb], w [Cx+2Cb, W], b [Cx+2Cb], one dtype")
+    e = lambda c: torch.empty((T, c), dtype=xbc.dtype, device=xbc.device)
+    xo, Bo, Co = e(Cx), e(Cb), e(Cb)
+    _check(lib().strd_conv1d_silu(_ptr(xbc), _rows(xbc, "xbc"), _ptr(w), _ptr(b), _ptr(xo), _ptr(Bo), _ptr(Co), T, Cx, Cb,
+                                  w.shape[1], _io(xbc), _stream()), "conv1d_silu")
+    return xo, Bo, Co
+
+
+def softplus_dt(raw: torch.Tensor, bias: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dt [T,H] fp32 = softplus(raw + bias); raw [T,H] may be a column slice, bias [H] fp32."""
+    _dev(bias)
+    T, H = raw.shape
+    if bias is not None and (bias.shape != (H,) or bias.dtype != torch.float32):
+        raise StrdError("softplus_dt: bias [H] fp32")
+    dt = torch.empty((T, H), dtype=torch.float32, device=raw.device)
+    _check(lib().strd_softplus_dt(_ptr(raw), _rows(raw, "raw"), 0, _ptr(bias), _ptr(dt), T, H, _io(raw), _stream()),
+           "softplus_dt")
+    return dt
 
 
 HYBRID_LAYERS = 62

@@ -170,6 +170,41 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
     return attn_general(q, k, v, o, T, Hq, Hkv, d, scale, io, as_stream(stream));
 }
 
+// ------------------------------------------------------------------ block glue -------------
+int strd_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, void *stream) {
+    if (T < 0 || d < 1 || !io_ok(io) || !(eps >= 0.f) || (T > 0 && (!x || !w || !out))) return STRD_EINVAL;
+    return glue_rmsnorm(x, w, out, T, d, eps, io, as_stream(stream));
+}
+
+int strd_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D, int groups,
+                       float eps, strd_dtype io, void *stream) {
+    if (T < 0 || D < 1 || groups < 1 || D % groups || ldz < D || !io_ok(io) || !(eps >= 0.f) ||
+        (T > 0 && (!y || !z || !w || !out)))
+        return STRD_EINVAL;
+    if ((long long)T * groups > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+    return glue_gated_rmsnorm(y, z, ldz, w, out, T, D, groups, eps, io, as_stream(stream));
+}
+
+int strd_conv1d_silu(const void *xbc, int ld, const void *w, const void *b, void *x_out, void *B_out, void *C_out, int T,
+                     int Cx, int Cb, int W, strd_dtype io, void *stream) {
+    if (T < 0 || Cx < 0 || Cb < 0 || Cx + 2 * Cb < 1 || W < 1 || ld < Cx + 2 * Cb || !io_ok(io) ||
+        (T > 0 && (!xbc || !w || (Cx && !x_out) || (Cb && (!B_out || !C_out)))))
+        return STRD_EINVAL;
+    // 8-channel vectors: column ranges, row pitch and base addresses must keep them whole and aligned
+    const size_t es = io == STRD_F32 ? 4 : 2;
+    if (Cx % 8 || Cb % 8 || ld % 8 || ((uintptr_t)xbc % (8 * es)) || ((uintptr_t)x_out % (8 * es)) ||
+        ((uintptr_t)B_out % (8 * es)) || ((uintptr_t)C_out % (8 * es)))
+        return STRD_EUNSUPPORTED;
+    if ((long long)T * ((Cx + 2 * Cb) / 8) > 0x7FFFFFFFLL * 256LL) return STRD_EUNSUPPORTED;
+    return glue_conv1d_silu(xbc, ld, w, b, x_out, B_out, C_out, T, Cx, Cb, W, io, as_stream(stream));
+}
+
+int strd_softplus_dt(const void *raw, int ld, int col0, const float *bias, float *dt, int T, int H, strd_dtype io,
+                     void *stream) {
+    if (T < 0 || H < 1 || col0 < 0 || ld < col0 + H || !io_ok(io) || (T > 0 && (!raw || !dt))) return STRD_EINVAL;
+    return glue_softplus_dt(raw, ld, col0, bias, dt, T, H, io, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ schedules (host) -------
 int strd_schedule_budgets(const double *alpha, int L, int N0, int K_min, int32_t *K_out) {
     if (!alpha || !K_out || L < 0 || N0 < 0 || K_min < 0) return STRD_EINVAL;

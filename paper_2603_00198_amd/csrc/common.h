@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "strd.h"
 
@@ -201,6 +202,13 @@ bool score_attn_mfma_supported(int M, int N, int Hq, int Hkv, int d, strd_dtype 
 size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv);
 int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
                     hipStream_t st);
+int glue_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, hipStream_t st);
+int glue_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D, int groups,
+                       float eps, strd_dtype io, hipStream_t st);
+int glue_conv1d_silu(const void *in, int ld, const void *w, const void *b, void *xo, void *Bo, void *Co, int T, int Cx,
+                     int Cb, int W, strd_dtype io, hipStream_t st);
+int glue_softplus_dt(const void *raw, int ld, int col0, const float *bias, float *dt, int T, int H, strd_dtype io,
+                     hipStream_t st);
 bool score_mamba_full_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
 int score_mamba_full_mfma(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H,
                           int G, int n, void *part_ws, hipStream_t st);

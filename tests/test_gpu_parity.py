@@ -273,6 +273,75 @@ def test_attn_prefill_parity(name, T):
     assert_close(synth.np64(o), want, TOL[synth.torch_dtype(w.dtype)], "attn o")
 
 
+# ------------------------------------------------------------------ block glue -------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,d", [(1, 64), (37, 4096), (300, 1000), (0, 128)])
+def test_rmsnorm_parity(T, d, dtype):
+    _say("rmsnorm T=%d d=%d %s" % (T, d, dtype))
+    g = torch.Generator(device=DEV).manual_seed(T + d)
+    x = (3 * torch.randn(T, d, generator=g, device=DEV)).to(dtype)
+    w = torch.randn(d, generator=g, device=DEV).to(dtype)
+    got = strd.rmsnorm(x, w, 1e-5)
+    if T:
+        assert_close(synth.np64(got), oracle.rmsnorm(synth.np64(x), synth.np64(w), 1e-5), TOL[dtype], "rmsnorm")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,D,groups", [(5, 64, 1), (33, 8192, 8), (130, 768, 3)])
+def test_gated_rmsnorm_parity(T, D, groups, dtype):
+    _say("gated_rmsnorm T=%d D=%d groups=%d %s" % (T, D, groups, dtype))
+    g = torch.Generator(device=DEV).manual_seed(T + D)
+    y = torch.randn(T, D, generator=g, device=DEV).to(dtype)
+    wide = (2 * torch.randn(T, D + 40, generator=g, device=DEV)).to(dtype)
+    z = wide[:, 24:24 + D]                                  # a column slice: rows of pitch D + 40
+    w = torch.randn(D, generator=g, device=DEV).to(dtype)
+    got = strd.gated_rmsnorm(y, z, w, groups, 1e-5)
+    want = oracle.gated_rmsnorm(synth.np64(y), synth.np64(z.contiguous()), synth.np64(w), groups, 1e-5)
+    assert_close(synth.np64(got), want, TOL[dtype], "gated_rmsnorm")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,Cx,Cb,W,extra", [(1, 8, 8, 4, 0), (50, 64, 16, 4, 8), (300, 256, 128, 4, 24), (17, 32, 8, 2, 0),
+                                             (9, 16, 8, 1, 0)])
+def test_conv1d_silu_parity(T, Cx, Cb, W, extra, dtype):
+    _say("conv1d_silu T=%d Cx=%d Cb=%d W=%d %s" % (T, Cx, Cb, W, dtype))
+    g = torch.Generator(device=DEV).manual_seed(T + Cx)
+    Ct = Cx + 2 * Cb
+    wide = torch.randn(T, Ct + extra, generator=g, device=DEV).to(dtype)   # trailing columns (dt) are not touched
+    w = (0.5 * torch.randn(Ct, W, generator=g, device=DEV)).to(dtype)
+    b = torch.randn(Ct, generator=g, device=DEV).to(dtype)
+    x, B, C = strd.conv1d_silu(wide, w, b, Cx, Cb)
+    want = oracle.conv1d_silu(synth.np64(wide[:, :Ct].contiguous()), synth.np64(w), synth.np64(b))
+    tol = TOL[dtype]
+    assert_close(synth.np64(x), want[:, :Cx], tol, "conv x")
+    assert_close(synth.np64(B), want[:, Cx:Cx + Cb], tol, "conv B")
+    assert_close(synth.np64(C), want[:, Cx + Cb:], tol, "conv C")
+    x2, _, _ = strd.conv1d_silu(wide, w, None, Cx, Cb)
+    assert_close(synth.np64(x2), oracle.conv1d_silu(synth.np64(wide[:, :Ct].contiguous()), synth.np64(w))[:, :Cx], tol,
+                 "conv without bias")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_softplus_dt_parity(dtype):
+    _say("softplus_dt %s" % dtype)
+    g = torch.Generator(device=DEV).manual_seed(3)
+    wide = (6 * torch.randn(77, 200, generator=g, device=DEV)).to(dtype)
+    raw = wide[:, 72:200]
+    bias = torch.randn(128, generator=g, device=DEV)
+    got = strd.softplus_dt(raw, bias)
+    want = oracle.softplus_dt(synth.np64(raw.contiguous()), synth.np64(bias))
+    assert_close(got.cpu().numpy().astype(np.float64), want, 1e-5, "softplus_dt")
+    assert (got > 0).all()
+
+
+def test_glue_refuses_misaligned_or_inconsistent_arguments():
+    x = torch.randn(8, 30, device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(strd.StrdError):
+        strd.conv1d_silu(x, torch.randn(20, 4, device=DEV, dtype=torch.bfloat16), None, 12, 4)   # not multiples of 8
+    with pytest.raises(strd.StrdError):
+        strd.gated_rmsnorm(x, x, torch.randn(30, device=DEV, dtype=torch.bfloat16), groups=4)     # 30 % 4 != 0
+
+
 # ------------------------------------------------------------------ whole reduced layer ----
 def _reduced_mamba_layer_dev(t, N, M, K, chunk):
     s = strd.score_mamba(t["B"][:N].contiguous(), t["C"][N:].contiguous(), t["dt"][:N].contiguous())

@@ -304,3 +304,58 @@ def test_reduced_scan_runs_over_retained_positions_only():
                               oracle.compact(B, idx, N, M)[0], oracle.compact(C, idx, N, M)[0])
     y_want = oracle.ssd_unrolled(x[keep], dt[keep], A, B[keep], C[keep])
     np.testing.assert_allclose(y_red, y_want, rtol=1e-12)
+
+
+# ----------------------------------------------------- block glue ----------
+# Pinned to library routines (torch CPU, fp64) and closed forms: the Mamba-2 block's operations
+# around the scan (the paper builds on that block and does not restate them).
+def test_conv1d_silu_is_a_causal_depthwise_convolution():
+    import torch
+    import torch.nn.functional as F
+    T, C, W = 11, 6, 4
+    x = RNG.standard_normal((T, C)); w = RNG.standard_normal((C, W)); b = RNG.standard_normal(C)
+    t = torch.from_numpy(x.T[None])                                    # [1, C, T]
+    ref = F.silu(F.conv1d(F.pad(t, (W - 1, 0)), torch.from_numpy(w[:, None, :]), torch.from_numpy(b), groups=C))
+    np.testing.assert_allclose(oracle.conv1d_silu(x, w, b), ref[0].T.numpy(), rtol=1e-12, atol=1e-14)
+    # causal: changing a later token leaves earlier outputs alone; token 0 sees only the last tap
+    x2 = x.copy(); x2[7] += 1.0
+    np.testing.assert_array_equal(oracle.conv1d_silu(x2, w, b)[:7], oracle.conv1d_silu(x, w, b)[:7])
+    a0 = b + w[:, W - 1] * x[0]
+    np.testing.assert_allclose(oracle.conv1d_silu(x, w, b)[0], a0 / (1 + np.exp(-a0)), rtol=1e-12)
+    # width 1, unit weight, no bias: plain SiLU
+    np.testing.assert_allclose(oracle.conv1d_silu(x, np.ones((C, 1))), x / (1 + np.exp(-x)), rtol=1e-12)
+
+
+def test_softplus_dt_matches_library_and_limits():
+    import torch
+    import torch.nn.functional as F
+    r = RNG.standard_normal((5, 3)) * 12; b = RNG.standard_normal(3)
+    np.testing.assert_allclose(oracle.softplus_dt(r, b), np.logaddexp(0.0, r + b), rtol=1e-12)
+    # torch switches to the identity above 20 (off by exp(-20) there)
+    np.testing.assert_allclose(oracle.softplus_dt(r, b), F.softplus(torch.from_numpy(r + b)).numpy(), rtol=1e-8)
+    big = oracle.softplus_dt(np.array([[800.0, -800.0, 0.0]]))
+    assert big[0, 0] == 800.0 and big[0, 1] == 0.0 and big[0, 2] == pytest.approx(np.log(2.0))
+    assert (oracle.softplus_dt(r, b) > 0).all()
+
+
+def test_rmsnorm_closed_forms():
+    x = RNG.standard_normal((7, 12)); w = RNG.standard_normal(12)
+    np.testing.assert_allclose(oracle.rmsnorm(x, w, 1e-5), x / np.sqrt((x ** 2).mean(1, keepdims=True) + 1e-5) * w,
+                               rtol=1e-12)
+    out = oracle.rmsnorm(3.0 * x, np.ones(12), 0.0)                    # scale invariant, unit mean square
+    np.testing.assert_allclose(out, oracle.rmsnorm(x, np.ones(12), 0.0), rtol=1e-12)
+    np.testing.assert_allclose((out ** 2).mean(1), 1.0, rtol=1e-12)
+
+
+def test_gated_rmsnorm_is_rmsnorm_of_the_gated_signal_per_group():
+    y = RNG.standard_normal((4, 8)); z = RNG.standard_normal((4, 8)); w = RNG.standard_normal(8)
+    v = y * (z / (1 + np.exp(-z)))
+    one = oracle.gated_rmsnorm(y, z, w, 1, 1e-6)
+    np.testing.assert_allclose(one, oracle.rmsnorm(v, w, 1e-6), rtol=1e-12)
+    two = oracle.gated_rmsnorm(y, z, w, 2, 1e-6)
+    for g in range(2):
+        np.testing.assert_allclose(two[:, 4 * g:4 * g + 4], oracle.rmsnorm(v[:, 4 * g:4 * g + 4], w[4 * g:4 * g + 4], 1e-6),
+                                   rtol=1e-12)
+    # a very positive gate passes y, a very negative one closes it
+    np.testing.assert_allclose(oracle.gated_rmsnorm(y, np.full_like(y, 50.0), w, 1, 1e-6), oracle.rmsnorm(y, w, 1e-6),
+                               rtol=1e-9)
