@@ -356,6 +356,6 @@ def test_gated_rmsnorm_is_rmsnorm_of_the_gated_signal_per_group():
     for g in range(2):
         np.testing.assert_allclose(two[:, 4 * g:4 * g + 4], oracle.rmsnorm(v[:, 4 * g:4 * g + 4], w[4 * g:4 * g + 4], 1e-6),
                                    rtol=1e-12)
-    # a very positive gate passes y, a very negative one closes it
-    np.testing.assert_allclose(oracle.gated_rmsnorm(y, np.full_like(y, 50.0), w, 1, 1e-6), oracle.rmsnorm(y, w, 1e-6),
+    # a large constant gate only scales y, which the norm (eps = 0) removes
+    np.testing.assert_allclose(oracle.gated_rmsnorm(y, np.full_like(y, 50.0), w, 1, 0.0), oracle.rmsnorm(y, w, 0.0),
                                rtol=1e-9)
