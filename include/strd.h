@@ -201,7 +201,11 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
  *                 16-byte (bf16) / 32-byte (fp32) aligned bases, else STRD_EUNSUPPORTED.
  * softplus_dt:    dt[t,h] = log(1 + exp(raw[t, col0+h] + bias[h])), raw rows of pitch ld in the io
  *                 dtype, bias [H] fp32 or NULL, dt [T,H] fp32.
+ * linear:         out[T,Nd] = x[T,Kd] . w[Kd,Nd] (+ residual[T,Nd], which may be `out` itself): the
+ *                 projections of a block, a plain dense product handed to rocBLAS (fp32 accumulation).
  * ------------------------------------------------------------------------- */
+int strd_linear(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
+                strd_dtype io, void *stream);
 int strd_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, void *stream);
 int strd_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D,
                        int groups, float eps, strd_dtype io, void *stream);

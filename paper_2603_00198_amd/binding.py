@@ -36,6 +36,7 @@ _SIGNATURES = {
     "strd_ssd_prefill_gather": (_int, [_vp] * 10 + [_int] * 8 + [_int, _vp, _sz, _vp]),
     "strd_attn_prefill_workspace": (_sz, [_int] * 4 + [_int]),
     "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
+    "strd_linear": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _vp]),
     "strd_rmsnorm": (_int, [_vp, _vp, _vp, _int, _int, _f32, _int, _vp]),
     "strd_gated_rmsnorm": (_int, [_vp, _vp, _int, _vp, _vp, _int, _int, _int, _f32, _int, _vp]),
     "strd_conv1d_silu": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp] + [_int] * 4 + [_int, _vp]),
@@ -338,6 +339,20 @@ def _rows(t: torch.Tensor, what: str) -> int:
     if t.dim() != 2 or t.stride(1) != 1:
         raise StrdError("%s: rows must be contiguous" % what)
     return t.stride(0)
+
+
+def linear(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = None,
+           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x [T,Kd] . w [Kd,Nd] (+ residual [T,Nd]); a plain library product."""
+    _dev(x, w, residual, out)
+    T, Kd = x.shape
+    Nd = w.shape[1]
+    if w.shape[0] != Kd or w.dtype != x.dtype or (residual is not None and (residual.shape != (T, Nd) or
+                                                                             residual.dtype != x.dtype)):
+        raise StrdError("linear: x [T,Kd], w [Kd,Nd], residual [T,Nd], one dtype")
+    out = out if out is not None else torch.empty((T, Nd), dtype=x.dtype, device=x.device)
+    _check(lib().strd_linear(_ptr(x), _ptr(w), _ptr(residual), _ptr(out), T, Kd, Nd, _io(x), _stream()), "linear")
+    return out
 
 
 def rmsnorm(x: torch.Tensor, w: torch.Tensor, eps: float = 1e-5, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -41,7 +41,8 @@ def build(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))
     tmp = LIB + ".tmp.%d" % os.getpid()
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs +
+                          ["-L/opt/rocm/lib", "-lrocblas"])   # rocBLAS: the plain projection products of the block glue
     os.replace(tmp, LIB)
     if verbose:
         print("built", LIB, "from", len(srcs), "sources")

@@ -205,6 +205,13 @@ int strd_softplus_dt(const void *raw, int ld, int col0, const float *bias, float
     return glue_softplus_dt(raw, ld, col0, bias, dt, T, H, io, as_stream(stream));
 }
 
+int strd_linear(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd, strd_dtype io,
+                void *stream) {
+    if (T < 0 || Kd < 1 || Nd < 1 || !io_ok(io) || !w || (T > 0 && (!x || !out))) return STRD_EINVAL;
+    if (T == 0) return STRD_OK;
+    return linear_rocblas(x, w, residual, out, T, Kd, Nd, io, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ schedules (host) -------
 int strd_schedule_budgets(const double *alpha, int L, int N0, int K_min, int32_t *K_out) {
     if (!alpha || !K_out || L < 0 || N0 < 0 || K_min < 0) return STRD_EINVAL;

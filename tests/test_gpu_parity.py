@@ -334,6 +334,22 @@ def test_softplus_dt_parity(dtype):
     assert (got > 0).all()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,Kd,Nd", [(1, 64, 8), (37, 300, 129), (256, 1024, 2048)])
+def test_linear_parity(T, Kd, Nd, dtype):
+    _say("linear T=%d Kd=%d Nd=%d %s" % (T, Kd, Nd, dtype))
+    g = torch.Generator(device=DEV).manual_seed(T + Kd)
+    x = torch.randn(T, Kd, generator=g, device=DEV).to(dtype)
+    w = (torch.randn(Kd, Nd, generator=g, device=DEV) / Kd ** 0.5).to(dtype)
+    r = torch.randn(T, Nd, generator=g, device=DEV).to(dtype)
+    tol = TOL[dtype]
+    assert_close(synth.np64(strd.linear(x, w)), synth.np64(x) @ synth.np64(w), tol, "linear")
+    assert_close(synth.np64(strd.linear(x, w, r)), synth.np64(x) @ synth.np64(w) + synth.np64(r), tol, "linear + residual")
+    acc = r.clone()
+    strd.linear(x, w, acc, out=acc)                       # residual stream updated in place
+    assert_close(synth.np64(acc), synth.np64(x) @ synth.np64(w) + synth.np64(r), tol, "linear in place")
+
+
 def test_glue_refuses_misaligned_or_inconsistent_arguments():
     x = torch.randn(8, 30, device=DEV, dtype=torch.bfloat16)
     with pytest.raises(strd.StrdError):
