@@ -146,6 +146,46 @@ def attn_inputs(w: Workload, hidden: torch.Tensor, seed: Optional[int] = None) -
     return {"q": q.contiguous(), "k": k.contiguous(), "v": v.contiguous()}
 
 
+CONV_WIDTH = 4   # taps of the short causal convolution of a Mamba-2 block
+
+
+def mamba_block_weights(w: Workload, device="cpu", seed: int = 0) -> Dict[str, torch.Tensor]:
+    """Random-init weights of one Mamba-2 block at the workload's shapes (set-up only).  Matrices
+    are [in, out] for y = x . W; scales keep activations O(1)."""
+    s = w.mamba
+    g = _gen(1000 + seed, device)
+    dt_ = torch_dtype(w.dtype)
+    d_inner, gn = s.H * s.P, s.G * s.n
+    rn = lambda *shape: torch.randn(*shape, generator=g, device=device)
+    return {
+        "norm_w": (1.0 + 0.1 * rn(w.d_model)).to(dt_),
+        "W_z": (rn(w.d_model, d_inner) / w.d_model ** 0.5).to(dt_),
+        "W_xbcdt": (rn(w.d_model, d_inner + 2 * gn + s.H) / w.d_model ** 0.5).to(dt_),
+        "conv_w": (rn(d_inner + 2 * gn, CONV_WIDTH) / CONV_WIDTH ** 0.5).to(dt_),
+        "conv_b": (0.1 * rn(d_inner + 2 * gn)).to(dt_),
+        "dt_bias": rn(s.H).float(),
+        "A": -torch.exp(2.0 * torch.rand(s.H, generator=g, device=device)).float(),
+        "D": rn(s.H).float(),
+        "gnorm_w": (1.0 + 0.1 * rn(d_inner)).to(dt_),
+        "W_out": (rn(d_inner, w.d_model) / d_inner ** 0.5).to(dt_),
+    }
+
+
+def attn_block_weights(w: Workload, device="cpu", seed: int = 0) -> Dict[str, torch.Tensor]:
+    """Random-init weights of one attention block (no positional encoding) at the workload's shapes."""
+    s = w.attn
+    g = _gen(2000 + seed, device)
+    dt_ = torch_dtype(w.dtype)
+    rn = lambda *shape: torch.randn(*shape, generator=g, device=device)
+    return {
+        "norm_w": (1.0 + 0.1 * rn(w.d_model)).to(dt_),
+        "W_q": (rn(w.d_model, s.Hq * s.d) / w.d_model ** 0.5).to(dt_),
+        "W_k": (rn(w.d_model, s.Hkv * s.d) / w.d_model ** 0.5).to(dt_),
+        "W_v": (rn(w.d_model, s.Hkv * s.d) / w.d_model ** 0.5).to(dt_),
+        "W_o": (rn(s.Hq * s.d, w.d_model) / (s.Hq * s.d) ** 0.5).to(dt_),
+    }
+
+
 def shrink(w: Workload, N: int, M: int, **kw) -> Workload:
     """Same layer shapes on a shorter sequence (parity cases the oracle finishes in seconds)."""
     from dataclasses import replace
