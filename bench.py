@@ -46,6 +46,10 @@ def parse_args():
                     help="instead of the layer benchmark: measure the Mamba-2 and attention layer at every token "
                          "count the paper's named schedules visit (c4 shapes) and print the modelled speed-up of "
                          "the mixers of the 62-layer hybrid under each schedule")
+    ap.add_argument("--block-stack", action="store_true",
+                    help="instead of the layer benchmark: the 8-block hidden-to-hidden stack of workload c4 "
+                         "(projections, glue, mixers, residual) with the progressive budgets against the same "
+                         "stack without reduction")
     ap.add_argument("--no-attention-extra", action="store_true",
                     help="skip the attention-layer figures appended to the default (c2) line")
     return ap.parse_args()
@@ -435,6 +439,56 @@ def stack_model(torch, strd, synth, dev):
         "context": PAPER_CONTEXT}))
 
 
+def block_stack(torch, strd, synth, dev, iters=5):
+    """Hidden-to-hidden 8-block stack (c4): full against progressively reduced, event-timed."""
+    from paper_2603_00198_amd import blocks
+    w = synth.WORKLOADS["c4"]
+    kinds = synth.C4_LAYERS
+    wts = [synth.mamba_block_weights(w, dev, l) if k == "mamba" else synth.attn_block_weights(w, dev, l)
+           for l, k in enumerate(kinds)]
+    hidden = synth.hidden_states(w, dev).to(torch.bfloat16)
+    budgets = strd.schedule_budgets(list(synth.C4_RETAIN), w.N)
+    full = [w.N] * len(kinds)
+    run = lambda b: blocks.run_blocks(kinds, wts, hidden, w.N, w.M, b, w.mamba, w.attn)
+    out = {}
+    for name, b in (("full", full), ("reduced", budgets)):
+        ms = time_events(torch, lambda: run(b), iters=iters, warmup=2)
+        out[name] = {"ms": ms, "input_tokens_per_s": w.T / (ms * 1e-3)}
+    # where the time of one full Mamba-2 block goes
+    h1 = hidden
+    parts = {}
+    s, wt = w.mamba, wts[0]
+    u = strd.rmsnorm(h1, wt["norm_w"])
+    parts["rmsnorm_us"] = 1e3 * time_events(torch, lambda: strd.rmsnorm(h1, wt["norm_w"]), iters=iters)
+    parts["in_proj_us"] = 1e3 * time_events(torch, lambda: (strd.linear(u, wt["W_z"]), strd.linear(u, wt["W_xbcdt"])), iters=iters)
+    xbcdt = strd.linear(u, wt["W_xbcdt"])
+    z = strd.linear(u, wt["W_z"])
+    d_inner, gn = s.H * s.P, s.G * s.n
+    parts["conv1d_silu_us"] = 1e3 * time_events(
+        torch, lambda: strd.conv1d_silu(xbcdt, wt["conv_w"], wt["conv_b"], d_inner, gn), iters=iters)
+    parts["softplus_dt_us"] = 1e3 * time_events(
+        torch, lambda: strd.softplus_dt(xbcdt[:, d_inner + 2 * gn:], wt["dt_bias"]), iters=iters)
+    x, B, C = strd.conv1d_silu(xbcdt, wt["conv_w"], wt["conv_b"], d_inner, gn)
+    dt = strd.softplus_dt(xbcdt[:, d_inner + 2 * gn:], wt["dt_bias"])
+    x3, B3, C3 = x.view(w.T, s.H, s.P), B.view(w.T, s.G, s.n), C.view(w.T, s.G, s.n)
+    parts["ssd_prefill_us"] = 1e3 * time_events(
+        torch, lambda: strd.ssd_prefill(x3, dt, wt["A"], B3, C3, wt["D"], chunk=s.chunk, want_state=False), iters=iters)
+    y, _ = strd.ssd_prefill(x3, dt, wt["A"], B3, C3, wt["D"], chunk=s.chunk, want_state=False)
+    y2 = y.view(w.T, d_inner)
+    parts["gated_rmsnorm_us"] = 1e3 * time_events(torch, lambda: strd.gated_rmsnorm(y2, z, wt["gnorm_w"], s.G), iters=iters)
+    g = strd.gated_rmsnorm(y2, z, wt["gnorm_w"], s.G)
+    parts["out_proj_us"] = 1e3 * time_events(torch, lambda: strd.linear(g, wt["W_out"], residual=h1), iters=iters)
+    eb = 2
+    glue_bytes = {"rmsnorm": 2 * w.T * w.d_model * eb, "conv1d_silu": 2 * w.T * (d_inner + 2 * gn) * eb,
+                  "gated_rmsnorm": 3 * w.T * d_inner * eb}
+    parts["glue_GBps"] = {k: v / (parts[k + "_us"] * 1e-6) / 1e9 for k, v in glue_bytes.items()}
+    print(json.dumps({
+        "block_stack": out, "speedup": out["full"]["ms"] / out["reduced"]["ms"], "workload": "c4: %s, N=%d M=%d, d_model=%d"
+        % ("+".join(kinds), w.N, w.M, w.d_model), "budgets": budgets, "full_mamba_block_parts": parts,
+        "note": "hidden-to-hidden: pre-norm, projections (rocBLAS), conv1d+SiLU, softplus, score/select/compact at the "
+                "reducing blocks, mixer, gated norm, out-projection + residual; no MLP blocks"}))
+
+
 def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     from dataclasses import replace
     wname, kind = WORKLOADS[name]
@@ -555,6 +609,9 @@ def main():
     name = args.workload
     if args.stack_model:
         stack_model(torch, strd, synth, dev)
+        return
+    if args.block_stack:
+        block_stack(torch, strd, synth, dev)
         return
     if args.profile:
         profile_run(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)

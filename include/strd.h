@@ -198,7 +198,7 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
  *                 on the first Cx + 2*Cb columns of xbc (rows of pitch ld elements); columns
  *                 [0,Cx) go to x_out [T,Cx], the next Cb to B_out [T,Cb], the last Cb to C_out
  *                 [T,Cb]; w [Cx+2*Cb, W], b [Cx+2*Cb] or NULL.  Cx, Cb, ld multiples of 8 and
- *                 16-byte (bf16) / 32-byte (fp32) aligned bases, else STRD_EUNSUPPORTED.
+ *                 16-byte (bf16) / 32-byte (fp32) aligned bases, W <= 4, else STRD_EUNSUPPORTED.
  * softplus_dt:    dt[t,h] = log(1 + exp(raw[t, col0+h] + bias[h])), raw rows of pitch ld in the io
  *                 dtype, bias [H] fp32 or NULL, dt [T,H] fp32.
  * linear:         out[T,Nd] = x[T,Kd] . w[Kd,Nd] (+ residual[T,Nd], which may be `out` itself): the

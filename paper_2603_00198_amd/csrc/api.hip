@@ -193,8 +193,10 @@ int strd_conv1d_silu(const void *xbc, int ld, const void *w, const void *b, void
     // 8-channel vectors: column ranges, row pitch and base addresses must keep them whole and aligned
     const size_t es = io == STRD_F32 ? 4 : 2;
     if (Cx % 8 || Cb % 8 || ld % 8 || ((uintptr_t)xbc % (8 * es)) || ((uintptr_t)x_out % (8 * es)) ||
-        ((uintptr_t)B_out % (8 * es)) || ((uintptr_t)C_out % (8 * es)))
+        ((uintptr_t)B_out % (8 * es)) || ((uintptr_t)C_out % (8 * es)) || ((uintptr_t)w % (8 * es)) ||
+        ((uintptr_t)b % (8 * es)))
         return STRD_EUNSUPPORTED;
+    if (W > glue_conv_max_width()) return STRD_EUNSUPPORTED;
     if ((long long)T * ((Cx + 2 * Cb) / 8) > 0x7FFFFFFFLL * 256LL) return STRD_EUNSUPPORTED;
     return glue_conv1d_silu(xbc, ld, w, b, x_out, B_out, C_out, T, Cx, Cb, W, io, as_stream(stream));
 }
