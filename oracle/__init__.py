@@ -217,3 +217,33 @@ def softplus_dt(raw, bias=None):
     out = np.empty_like(raw)
     _check(_load().oracle_softplus_dt(_p(raw), _p(bias), _p(out), raw.shape[0], raw.shape[1]), "softplus_dt")
     return out
+
+
+# ------------------------------------------------------------------ variants ---------------
+def avgpool(src, N, M, K, pos_in=None):
+    """Average-pool reduction of the N vision rows of src [N+M, D] to K rows; returns (dst, pos_out)."""
+    src = _f64(src)
+    assert src.ndim == 2 and src.shape[0] == N + M
+    dst = np.empty((K + M, src.shape[1]), np.float64)
+    pos_out = np.empty(K + M, np.int32)
+    pin = None if pos_in is None else np.ascontiguousarray(pos_in, dtype=np.int32)
+    _check(_load().oracle_avgpool(_p(src), _p(dst), N, M, K, src.shape[1], _p(pin), _p(pos_out)), "avgpool")
+    return dst, pos_out
+
+
+def ssd_decode_step(x1, dt1, A, B1, C1, D, S):
+    """One token of the recurrence from the carried state S [H,P,n] (paper Eqs. ssm_state_update,
+    ssm_output with T = 1); x1 [H,P], dt1 [H], B1, C1 [G,n].  Returns (y [H,P], S_new)."""
+    y, S_new = ssd_seq(np.asarray(x1)[None], np.asarray(dt1)[None], A, np.asarray(B1)[None], np.asarray(C1)[None],
+                       D=D, S_in=S)
+    return y[0], S_new
+
+
+def attn_decode_step(q1, k_cache, v_cache, scale=None):
+    """The newest token's attention output over all T cached rows (its own included): the last row
+    of causal attention.  q1 [Hq,d], k_cache, v_cache [T,Hkv,d]; returns [Hq,d]."""
+    k, v = _f64(k_cache), _f64(v_cache)
+    T = k.shape[0]
+    q = np.zeros((T,) + np.asarray(q1).shape, np.float64)
+    q[T - 1] = q1
+    return attn(q, k, v, scale=scale, rows=[T - 1])[0]

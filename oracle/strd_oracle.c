@@ -504,3 +504,33 @@ int oracle_softplus_dt(const double *raw, const double *bias, double *dt, int T,
         }
     return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* Average-pool reduction (the baseline the paper's "Reduction Types"  */
+/* ablation sets against query-based selection): the N vision rows are */
+/* cut into K consecutive windows, window j = rows [floor(j N / K),     */
+/* floor((j+1) N / K)), each replaced by its mean; the M text rows      */
+/* follow unchanged.  A pooled token takes the position of the first    */
+/* row of its window.  The paper does not state the window shape; this  */
+/* is the non-overlapping 1-D pooling along the token axis.             */
+/* src: [N+M,D]  dst: [K+M,D]  pos_in: [N+M] or NULL  pos_out: [K+M]    */
+/* ------------------------------------------------------------------ */
+int oracle_avgpool(const double *src, double *dst, int N, int M, int K, int D,
+                   const int32_t *pos_in, int32_t *pos_out)
+{
+    if (N < 0 || M < 0 || K < 0 || K > N || D < 0 || (N > 0 && K == 0)) return -1;
+    for (int j = 0; j < K; ++j) {
+        const int lo = (int)(((long long)j * N) / K), hi = (int)(((long long)(j + 1) * N) / K);
+        for (int c = 0; c < D; ++c) {
+            double acc = 0.0;
+            for (int r = lo; r < hi; ++r) acc += src[(size_t)r * D + c];
+            dst[(size_t)j * D + c] = acc / (double)(hi - lo);
+        }
+        if (pos_out) pos_out[j] = pos_in ? pos_in[lo] : lo;
+    }
+    for (int m = 0; m < M; ++m) {
+        for (int c = 0; c < D; ++c) dst[(size_t)(K + m) * D + c] = src[(size_t)(N + m) * D + c];
+        if (pos_out) pos_out[K + m] = pos_in ? pos_in[N + m] : N + m;
+    }
+    return 0;
+}

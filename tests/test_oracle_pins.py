@@ -359,3 +359,54 @@ def test_gated_rmsnorm_is_rmsnorm_of_the_gated_signal_per_group():
     # a large constant gate only scales y, which the norm (eps = 0) removes
     np.testing.assert_allclose(oracle.gated_rmsnorm(y, np.full_like(y, 50.0), w, 1, 0.0), oracle.rmsnorm(y, w, 0.0),
                                rtol=1e-9)
+
+
+# ---------------------------------------------------------------- variants ----
+def test_avgpool_matches_library_pooling_and_partitions_the_rows():
+    N, M, D = 24, 3, 5
+    src = RNG.standard_normal((N + M, D))
+    for K in (24, 12, 6, 1):                                   # N % K == 0: the library's 1-D average pooling
+        dst, pos = oracle.avgpool(src, N, M, K)
+        ref = torch.nn.functional.avg_pool1d(torch.from_numpy(src[:N].T.copy())[None], N // K)[0].T.numpy()
+        np.testing.assert_allclose(dst[:K], ref, rtol=1e-13, atol=1e-15)
+        np.testing.assert_array_equal(dst[K:], src[N:])        # text tail untouched
+        np.testing.assert_array_equal(pos, np.r_[np.arange(K) * (N // K), N + np.arange(M)])
+    np.testing.assert_array_equal(oracle.avgpool(src, N, M, N)[0], src)   # full budget: identity
+    # ragged windows (N % K != 0): sizes differ by at most one, cover every row once, keep the total
+    for K in (7, 5, 23):
+        dst, pos = oracle.avgpool(src, N, M, K)
+        edges = np.r_[pos[:K], N]
+        sizes = np.diff(edges)
+        assert sizes.min() >= N // K and sizes.max() <= N // K + 1 and sizes.sum() == N
+        np.testing.assert_allclose((dst[:K] * sizes[:, None]).sum(0), src[:N].sum(0), rtol=1e-12)
+        for j in range(K):
+            np.testing.assert_allclose(dst[j], src[edges[j]:edges[j + 1]].mean(0), rtol=1e-13, atol=1e-15)
+    const = np.tile(RNG.standard_normal(D), (N + M, 1))        # a constant sequence stays constant
+    np.testing.assert_allclose(oracle.avgpool(const, N, M, 7)[0], const[:7 + M], rtol=1e-14)
+    p_in = np.arange(N + M, dtype=np.int32) * 3 + 2             # positions compose through pos_in
+    np.testing.assert_array_equal(oracle.avgpool(src, N, M, 6, p_in)[1], np.r_[p_in[:N:4], p_in[N:]])
+
+
+def test_decode_steps_continue_the_prefill():
+    # scan: prefill over T tokens, then one decode step from the carried state == prefill over T + 1
+    x, dt, A, B, C, D, S = _ssd_case(9, 4, 3, 2, 5, seed=5)
+    y_all, S_all = oracle.ssd_seq(x, dt, A, B, C, D=D, S_in=S)
+    _, S_pre = oracle.ssd_seq(x[:8], dt[:8], A, B[:8], C[:8], D=D, S_in=S)
+    y1, S1 = oracle.ssd_decode_step(x[8], dt[8], A, B[8], C[8], D, S_pre)
+    np.testing.assert_allclose(y1, y_all[8], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(S1, S_all, rtol=1e-12, atol=1e-13)
+    # and the step itself, written out: S' = exp(dt A) S + dt x b^T, y = S' c + D x
+    Hh, G = 4, 2
+    for h in range(Hh):
+        g = h // (Hh // G)
+        Sn = np.exp(dt[8, h] * A[h]) * S_pre[h] + dt[8, h] * np.outer(x[8, h], B[8, g])
+        np.testing.assert_allclose(S1[h], Sn, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(y1[h], Sn @ C[8, g] + D[h] * x[8, h], rtol=1e-12, atol=1e-13)
+    # attention: the new token against the whole cache == library softmax attention of one query
+    T, Hq, Hkv, d = 11, 4, 2, 6
+    q1 = RNG.standard_normal((Hq, d)); k = RNG.standard_normal((T, Hkv, d)); v = RNG.standard_normal((T, Hkv, d))
+    o = oracle.attn_decode_step(q1, k, v)
+    kk = torch.from_numpy(k).repeat_interleave(Hq // Hkv, 1).permute(1, 0, 2)
+    vv = torch.from_numpy(v).repeat_interleave(Hq // Hkv, 1).permute(1, 0, 2)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q1)[:, None], kk, vv)[:, 0].numpy()
+    np.testing.assert_allclose(o, ref, rtol=1e-11, atol=1e-13)
