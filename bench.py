@@ -101,6 +101,28 @@ def time_events(torch, fn, iters=20, warmup=3):
     return ev.mean_ms()
 
 
+def time_graph(torch, fn, reps=20, replays=5):
+    """Mean ms per call of `fn` with `reps` calls captured into one HIP graph and replayed: the
+    device time of kernels that are shorter than the host's launch path."""
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(reps):
+                fn()
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (replays * reps)
+
+
 class MambaLayer:
     kind = "mamba"
 
@@ -439,6 +461,42 @@ def stack_model(torch, strd, synth, dev):
         "context": PAPER_CONTEXT}))
 
 
+def variants(torch, strd, synth, dev):
+    """Average-pool reduction and the decode hand-off at the shapes of c2 / c3 (random inputs: only
+    the shapes matter for these bandwidth kernels)."""
+    wm, wa = synth.WORKLOADS["c2"], synth.WORKLOADS["c3"]
+    out = {}
+    hid = torch.randn(wm.T, wm.d_model, device=dev).to(torch.bfloat16)
+    us = 1e3 * time_graph(torch, lambda: strd.avgpool(hid, wm.N, wm.M, wm.K))
+    nbytes = 2 * wm.d_model * (wm.T + wm.K + wm.M)
+    out["avgpool_c2_hidden"] = {"us": us, "GBps": nbytes / us * 1e-3, "frac_hbm": nbytes / us * 1e-3 / HBM_PEAK_GBS}
+    m = wm.mamba
+    x = torch.randn(m.H, m.P, device=dev).to(torch.bfloat16)
+    B = torch.randn(m.G, m.n, device=dev).to(torch.bfloat16)
+    C = torch.randn(m.G, m.n, device=dev).to(torch.bfloat16)
+    dt = torch.rand(m.H, device=dev) + 0.1
+    A = -torch.exp(2 * torch.rand(m.H, device=dev))
+    S = torch.randn(m.H, m.P, m.n, device=dev)
+    us = 1e3 * time_graph(torch, lambda: strd.ssd_decode_step(x, dt, A, B, C, None, S))
+    nbytes = 8 * m.H * m.P * m.n
+    out["ssd_decode_step_c2"] = {"us": us, "GBps": nbytes / us * 1e-3, "frac_hbm": nbytes / us * 1e-3 / HBM_PEAK_GBS}
+    a = wa.attn
+    q = torch.randn(a.Hq, a.d, device=dev).to(torch.bfloat16)
+    for tag, T in (("reduced_cache", wa.K + wa.M + 1), ("full_cache", wa.T + 1)):
+        kc = torch.randn(T, a.Hkv, a.d, device=dev).to(torch.bfloat16)
+        vc = torch.randn(T, a.Hkv, a.d, device=dev).to(torch.bfloat16)
+        ws = torch.empty(strd.lib().strd_attn_decode_step_workspace(T, a.Hq, a.Hkv, a.d, 1), dtype=torch.uint8,
+                         device=dev)
+        us = 1e3 * time_graph(torch, lambda: strd.attn_decode_step(q, kc, vc, ws=ws))
+        nbytes = 4 * T * a.Hkv * a.d
+        out["attn_decode_step_c3_" + tag] = {"T": T, "us": us, "GBps": nbytes / us * 1e-3,
+                                             "frac_hbm": nbytes / us * 1e-3 / HBM_PEAK_GBS}
+    out["note"] = ("average-pool baseline of the reduction-type ablation on the residual stream; one decode token from "
+                   "the state / the key-value rows a prefill leaves (25% budget vs none); device time per call from a "
+                   "graph of 20 calls; not part of the timed step")
+    return out
+
+
 def block_stack(torch, strd, synth, dev, iters=5):
     """Hidden-to-hidden 8-block stack (c4): full against progressively reduced, event-timed."""
     from paper_2603_00198_amd import blocks
@@ -640,6 +698,8 @@ def main():
         line["next_rows"] = {"score_mamba_full_us": line["gather_fused_variant"].pop("score_mamba_full_us"),
                              "note": "Full Mamba Dynamic score (decayed |w_tj|) on the same inputs; an ablation "
                                      "row, not part of the timed step"}
+    if name == "c2":
+        line.setdefault("next_rows", {})["variants"] = variants(torch, strd, synth, dev)
     if name == "c2" and not args.no_attention_extra:
         del layer
         torch.cuda.empty_cache()

@@ -215,6 +215,41 @@ int strd_softplus_dt(const void *raw, int ld, int col0, const float *bias, float
                      strd_dtype io, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * Variants (next row 4 of the scope table).
+ *
+ * avgpool -- the average-pooling reduction that the "Reduction Types" ablation (Sec. 4,
+ * ablation table, right half) sets against query-based selection.  The paper does not state
+ * the window shape; here the N vision rows are cut into K consecutive windows
+ * [floor(j N / K), floor((j+1) N / K)), j < K, each replaced by its mean (fp32 accumulation in
+ * row order, one rounding), and the M text rows follow unchanged.  src [dev] [N+M, D], dst [dev]
+ * [K+M, D], both of dtype io and contiguous (src == dst == NULL: positions only); pos_out [dev]
+ * [K+M] or NULL receives pos_in (NULL = identity) of the first row of each window, then of the
+ * text rows.  1 <= K <= N (K = 0 only with N = 0).
+ *
+ * ssd_decode_step -- one token of the Mamba-2 recurrence (Eqs. ssm_state_update, ssm_output with
+ * T = 1) from the state a prefill left in S_out:  S <- exp(dt_h A_h) S + dt_h x b^T (in place),
+ * y = S c + D x.  x, y [dev] [H, P] and B, C [dev] [G, n] of dtype io; dt, A, D (or NULL) [dev]
+ * fp32 [H]; S [dev] fp32 [H, P, n], read and written.
+ *
+ * attn_decode_step -- the newest token's causal attention over a cache of T key/value rows, its
+ * own row included (the last row of the appendix's softmax-attention equation): q, o [dev]
+ * [Hq, d]; k_cache, v_cache [dev] [T, Hkv, d] -- after a reduced prefill these are the K + M
+ * surviving rows followed by the generated ones.  d in {64, 128}, Hq / Hkv in {1, 2, 4, 8},
+ * 16-byte (bf16) / 32-byte (fp32) aligned bases, else STRD_EUNSUPPORTED; scale > 0.  Workspace
+ * [dev]: strd_attn_decode_step_workspace bytes, 16-byte aligned (STRD_EWORKSPACE otherwise).
+ *
+ * All asynchronous on `stream`; no call allocates.
+ * ------------------------------------------------------------------------- */
+int strd_avgpool(const void *src, void *dst, int N, int M, int K, int D, strd_dtype io, const int32_t *pos_in,
+                 int32_t *pos_out, void *stream);
+int strd_ssd_decode_step(const void *x, const float *dt, const float *A, const void *B, const void *C,
+                         const float *D, float *S, void *y, int H, int P, int G, int n, strd_dtype io,
+                         void *stream);
+size_t strd_attn_decode_step_workspace(int T, int Hq, int Hkv, int d, strd_dtype io);
+int strd_attn_decode_step(const void *q, const void *k_cache, const void *v_cache, void *o, int T, int Hq,
+                          int Hkv, int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * schedule_budgets -- per-layer token budgets of a retention schedule (Sec. 3.2
  * and App. "Reduction Schedule Configurations").  alpha_l is relative to the
  * original count N0; budgets never grow with depth and never fall below

@@ -41,6 +41,10 @@ _SIGNATURES = {
     "strd_gated_rmsnorm": (_int, [_vp, _vp, _int, _vp, _vp, _int, _int, _int, _f32, _int, _vp]),
     "strd_conv1d_silu": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp] + [_int] * 4 + [_int, _vp]),
     "strd_softplus_dt": (_int, [_vp, _int, _int, _vp, _vp, _int, _int, _int, _vp]),
+    "strd_avgpool": (_int, [_vp, _vp, _int, _int, _int, _int, _int, _vp, _vp, _vp]),
+    "strd_ssd_decode_step": (_int, [_vp] * 8 + [_int] * 4 + [_int, _vp]),
+    "strd_attn_decode_step_workspace": (_c.c_size_t, [_int, _int, _int, _int, _int]),
+    "strd_attn_decode_step": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _f32, _int, _vp, _c.c_size_t, _vp]),
     "strd_schedule_budgets": (_int, [_vp, _int, _int, _int, _vp]),
     "strd_schedule_sigmoid": (_int, [_int, _c.c_double, _c.c_double, _c.c_double, _c.c_double, _vp]),
     "strd_schedule_step_decay": (_int, [_vp, _vp, _vp, _int, _int, _vp]),
@@ -311,6 +315,58 @@ def attn_prefill(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: Optio
         ws, _ = _ws(need, q)
     _check(lib().strd_attn_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(o), T, Hq, Hkv, d, scale, io, _ptr(ws),
                                    0 if ws is None else ws.numel(), _stream()), "attn_prefill")
+    return o
+
+
+def avgpool(src: torch.Tensor, N: int, M: int, K: int, pos_in: Optional[torch.Tensor] = None,
+            want_pos: bool = False):
+    """Average-pool the N vision rows of src [N+M, D] into K consecutive windows, keep the M text
+    rows; returns dst [K+M, D] or (dst, pos_out)."""
+    _dev(src, pos_in)
+    if src.dim() != 2 or src.shape[0] != N + M:
+        raise StrdError("avgpool: src must be [N+M, D]")
+    dst = torch.empty((K + M, src.shape[1]), dtype=src.dtype, device=src.device)
+    pos = torch.empty(K + M, dtype=torch.int32, device=src.device) if (want_pos or pos_in is not None) else None
+    _check(lib().strd_avgpool(_ptr(src), _ptr(dst), N, M, K, src.shape[1], _io(src), _ptr(pos_in), _ptr(pos),
+                              _stream()), "avgpool")
+    return (dst, pos) if pos is not None else dst
+
+
+def ssd_decode_step(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,
+                    D: Optional[torch.Tensor], S: torch.Tensor) -> torch.Tensor:
+    """One token of the recurrence: x [H,P], dt [H] fp32, B, C [G,n], S [H,P,n] fp32 updated in
+    place; returns y [H,P]."""
+    _dev(x, dt, A, B, C, D, S)
+    H, P = x.shape
+    G, n = B.shape
+    if dt.shape != (H,) or A.shape != (H,) or C.shape != (G, n) or S.shape != (H, P, n) or S.dtype != torch.float32 \
+            or dt.dtype != torch.float32 or A.dtype != torch.float32 or B.dtype != x.dtype or C.dtype != x.dtype \
+            or (D is not None and (D.shape != (H,) or D.dtype != torch.float32)):
+        raise StrdError("ssd_decode_step: inconsistent shapes or dtypes")
+    y = torch.empty_like(x)
+    _check(lib().strd_ssd_decode_step(_ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(S), _ptr(y), H, P,
+                                      G, n, _io(x), _stream()), "ssd_decode_step")
+    return y
+
+
+def attn_decode_step(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, scale: Optional[float] = None,
+                     ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The newest token's attention over the T cached rows (its own included): q [Hq,d],
+    k_cache, v_cache [T,Hkv,d]; returns o [Hq,d]."""
+    _dev(q, k_cache, v_cache, ws)
+    Hq, d = q.shape
+    T, Hkv = k_cache.shape[:2]
+    if k_cache.shape != (T, Hkv, d) or v_cache.shape != (T, Hkv, d) or k_cache.dtype != q.dtype \
+            or v_cache.dtype != q.dtype:
+        raise StrdError("attn_decode_step: inconsistent shapes or dtypes")
+    io = _io(q)
+    if scale is None:
+        scale = d ** -0.5
+    o = torch.empty_like(q)
+    if ws is None:
+        ws, _ = _ws(lib().strd_attn_decode_step_workspace(T, Hq, Hkv, d, io), q)
+    _check(lib().strd_attn_decode_step(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), T, Hq, Hkv, d, scale, io,
+                                       _ptr(ws), 0 if ws is None else ws.numel(), _stream()), "attn_decode_step")
     return o
 
 

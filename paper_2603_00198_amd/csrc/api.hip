@@ -214,6 +214,42 @@ int strd_linear(const void *x, const void *w, const void *residual, void *out, i
     return linear_rocblas(x, w, residual, out, T, Kd, Nd, io, as_stream(stream));
 }
 
+// ------------------------------------------------------------------ variants ---------------
+int strd_avgpool(const void *src, void *dst, int N, int M, int K, int D, strd_dtype io, const int32_t *pos_in,
+                 int32_t *pos_out, void *stream) {
+    if (N < 0 || M < 0 || K < 0 || K > N || (N > 0 && K == 0) || D < 0 || !io_ok(io)) return STRD_EINVAL;
+    if ((src == nullptr) != (dst == nullptr)) return STRD_EINVAL;
+    if ((long long)N + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+    return avgpool_launch(src, dst, N, M, K, D, io, pos_in, pos_out, as_stream(stream));
+}
+
+int strd_ssd_decode_step(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
+                         float *S, void *y, int H, int P, int G, int n, strd_dtype io, void *stream) {
+    if (H < 1 || P < 1 || G < 1 || n < 1 || H % G || !io_ok(io) || !x || !dt || !A || !B || !C || !S || !y)
+        return STRD_EINVAL;
+    if ((long long)H * P > (1 << 24)) return STRD_EUNSUPPORTED;
+    return ssd_decode_launch(x, dt, A, B, C, D, S, y, H, P, G, n, io, as_stream(stream));
+}
+
+size_t strd_attn_decode_step_workspace(int T, int Hq, int Hkv, int d, strd_dtype io) {
+    (void)io;
+    if (T < 1 || Hq < 1 || Hkv < 1 || d < 1) return 0;
+    return attn_decode_workspace(T, Hq, Hkv, d);
+}
+
+int strd_attn_decode_step(const void *q, const void *k_cache, const void *v_cache, void *o, int T, int Hq, int Hkv,
+                          int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (T < 1 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io) || !(scale > 0.f) || !q || !k_cache || !v_cache ||
+        !o)
+        return STRD_EINVAL;
+    if (!attn_decode_supported(Hq, Hkv, d)) return STRD_EUNSUPPORTED;
+    const size_t al = 8 * (io == STRD_BF16 ? 2 : 4);
+    if ((uintptr_t)q % al || (uintptr_t)k_cache % al || (uintptr_t)v_cache % al) return STRD_EUNSUPPORTED;
+    const size_t need = attn_decode_workspace(T, Hq, Hkv, d);
+    if (!ws || ws_bytes < need || (uintptr_t)ws % 16) return STRD_EWORKSPACE;
+    return attn_decode_launch(q, k_cache, v_cache, o, T, Hq, Hkv, d, scale, io, (float *)ws, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ schedules (host) -------
 int strd_schedule_budgets(const double *alpha, int L, int N0, int K_min, int32_t *K_out) {
     if (!alpha || !K_out || L < 0 || N0 < 0 || K_min < 0) return STRD_EINVAL;

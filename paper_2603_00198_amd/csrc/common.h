@@ -212,6 +212,14 @@ int glue_conv1d_silu(const void *in, int ld, const void *w, const void *b, void 
                      int Cb, int W, strd_dtype io, hipStream_t st);
 int glue_softplus_dt(const void *raw, int ld, int col0, const float *bias, float *dt, int T, int H, strd_dtype io,
                      hipStream_t st);
+int avgpool_launch(const void *src, void *dst, int N, int M, int K, int D, strd_dtype io, const int32_t *pos_in,
+                   int32_t *pos_out, hipStream_t st);
+int ssd_decode_launch(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
+                      float *S, void *y, int H, int P, int G, int n, strd_dtype io, hipStream_t st);
+bool attn_decode_supported(int Hq, int Hkv, int d);
+size_t attn_decode_workspace(int T, int Hq, int Hkv, int d);
+int attn_decode_launch(const void *q, const void *kc, const void *vc, void *o, int T, int Hq, int Hkv, int d,
+                       float scale, strd_dtype io, float *ws, hipStream_t st);
 bool score_mamba_full_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io);
 int score_mamba_full_mfma(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H,
                           int G, int n, void *part_ws, hipStream_t st);
