@@ -177,7 +177,7 @@ int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, cons
  *     o_t^h = sum_{j<=t} softmax_j( scale * q_t^h . k_j^{kv(h)} ) v_j^{kv(h)}
  * in the order the tokens have in the (compacted) sequence.
  *   q [dev] [T, Hq, d]    k, v [dev] [T, Hkv, d]    o [dev] [T, Hq, d]
- * Requires T >= 0, Hq % Hkv == 0.
+ * Requires T >= 0, Hq % Hkv == 0, scale > 0 (else STRD_EINVAL).
  * ------------------------------------------------------------------------- */
 size_t strd_attn_prefill_workspace(int T, int Hq, int Hkv, int d, strd_dtype io);
 int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv,

@@ -161,7 +161,7 @@ size_t strd_attn_prefill_workspace(int T, int Hq, int Hkv, int d, strd_dtype io)
 
 int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d,
                       float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
-    if (T < 0 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io)) return STRD_EINVAL;
+    if (T < 0 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io) || !(scale > 0.f)) return STRD_EINVAL;
     if (T > 0 && (!q || !k || !v || !o)) return STRD_EINVAL;
     const size_t need = strd_attn_prefill_workspace(T, Hq, Hkv, d, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;

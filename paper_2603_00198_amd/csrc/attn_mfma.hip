@@ -27,16 +27,27 @@ constexpr int kThreads = 256;
 constexpr int kBM = 128;  // query positions per workgroup
 constexpr int kKC = 64;   // keys per LDS chunk
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazy = 8.f;  // log2 of how far a probability may exceed 1 before the reference moves
 
+// K rows are read 16 bytes per lane, 16 rows per quarter wave: conflict-free when the row pitch is
+// 4 words modulo 64 (one pad vector).  V is read with the transposing load, 4 rows x 64 bytes per
+// half wave: conflict-free when the pitch is 16 words modulo 64 (four pad vectors, never copied).
 template <int D>
 struct Tile {
     using A = AsyncTile<kKC, D / 8, kThreads / kWave>;
+    using AV = AsyncTile<kKC, D / 8, kThreads / kWave, 4, true>;
     static constexpr int kPitch = A::kPitch;
+    static constexpr int kPitchV = AV::kPitch;
     struct alignas(16) Half {
         bf16_t e[A::kBytes / 2];
         __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitch + c; }
     };
-    Half k[2], v[2];
+    struct alignas(16) HalfV {
+        bf16_t e[AV::kBytes / 2];
+        __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitchV + c; }
+    };
+    Half k[2];
+    HalfV v[2];
 };
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -52,6 +63,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const float lazy_raw = kLazy / scale2;  // the slack of the softmax reference, in raw score units
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int h = blockIdx.x % Hq, qb = nqb - 1 - blockIdx.x / Hq, kvh = h / (Hq / Hkv);
     const int t0 = qb * kBM;
@@ -70,28 +82,29 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
         for (int ks = 0; ks < KS; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks + 8 * half);
     }
 
-    // K / V chunks go global -> LDS directly; this lane's slots of a tile are fixed
+    // K / V chunks go global -> LDS directly; the slots of this lane are recomputed for every chunk
+    // (a few integer operations per 64 keys) rather than held in registers
     using AT = typename Tile<D>::A;
-    int st_row[AT::kIssues], st_col[AT::kIssues];
-#pragma unroll
-    for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
-    // 32-bit byte offsets (shared by K and V) of the next chunk to request; rows past T re-read row T - 1
+    using ATV = typename Tile<D>::AV;
     const uint32_t kv_row = (uint32_t)Hkv * D * 2;
-    uint32_t st_off[AT::kIssues], st_lim[AT::kIssues];
-#pragma unroll
-    for (int i = 0; i < AT::kIssues; ++i) {
-        const uint32_t col = ((uint32_t)kvh * D + st_col[i] * 8) * 2;
-        st_off[i] = (uint32_t)st_row[i] * kv_row + col;
-        st_lim[i] = (uint32_t)(T - 1) * kv_row + col;
-    }
-    auto stage = [&](int b) {  // requests the next chunk in sequence
+    const uint32_t kv_col = (uint32_t)kvh * D * 2;
+    int next_chunk = 0;
+    auto stage = [&](int b) {  // requests the next chunk in sequence; rows past T re-read row T - 1
 #pragma unroll
         for (int i = 0; i < AT::kIssues; ++i) {
-            const uint32_t off = min(st_off[i], st_lim[i]);
+            int row, cv;
+            AT::slot(w, lane, i, row, cv);
+            const uint32_t off = (uint32_t)min(next_chunk * kKC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
             AT::issue(reinterpret_cast<const char *>(k) + off, &lds.k[b], w, i);
-            AT::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], w, i);
-            st_off[i] += kKC * kv_row;
         }
+#pragma unroll
+        for (int i = 0; i < ATV::kIssues; ++i) {
+            int row, cv;
+            ATV::slot(w, lane, i, row, cv);
+            const uint32_t off = (uint32_t)min(next_chunk * kKC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
+            ATV::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], w, i);
+        }
+        ++next_chunk;
     };
 
     f32x16 oacc[DT];
@@ -127,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) sacc = mfma32(kf[ks], bq[ks], sacc);
                 // the transposed V fragments of the tile are requested now and arrive during the softmax
-                constexpr int kHi = 8 * Tile<D>::kPitch * 2;  // byte offset of the second 4 keys of a slot group
+                constexpr int kHi = 8 * Tile<D>::kPitchV * 2;  // byte offset of the second 4 keys of a slot group
                 strd_s16x4 vr8[2][(DT + 3) / 4][8];
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2) {
@@ -144,9 +157,12 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__res
                 float tm = -INFINITY;  // max of this lane half's 16 raw scores
 #pragma unroll
                 for (int i = 0; i < 16; ++i) tm = fmaxf(tm, sacc[i]);
-                // m_run (raw units) is common to both lane halves of a query; it only has to move, and
-                // the halves only have to talk, when some lane of the wave sees a larger score
-                if (__any(tm > m_run)) {
+                // m_run (raw units) is the reference the exponentials are taken against, common to both
+                // lane halves of a query.  Softmax does not care which reference is used, so it follows
+                // the running max lazily: it moves (and the accumulators are rescaled, and the halves
+                // talk) only when some lane sees a score more than 2^kLazy above it; until then the
+                // probabilities are merely allowed to reach 2^kLazy instead of 1.
+                if (__any(tm > m_run + lazy_raw)) {
                     tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
                     const float nm = fmaxf(m_run, tm);  // finite: key 0 is visible to every query
                     const float corr = ex2((m_run - nm) * scale2);
