@@ -184,3 +184,37 @@ def test_c5_long_video_attention_layer_sampled():
     rows = np.array([0, 127, 128, 5000, K - 1, K, Tr - 1], np.int32)
     o_ref = oracle.attn(f(qs), f(ks), f(vs), rows=rows)
     assert_close(f(o[torch.from_numpy(rows).long().to(DEV)]), o_ref, TOLB, "reduced attention rows")
+
+
+def test_variants_at_benchmark_shapes():
+    """Average-pool baseline on the c2 residual stream and one decode token at the c2 state / the c3
+    reduced cache: the shapes `bench.py` times under `next_rows.variants`, compared in full."""
+    _say("variants at c2 / c3 shapes")
+    wm, wa = synth.WORKLOADS["c2"], synth.WORKLOADS["c3"]
+    g = torch.Generator(device=DEV).manual_seed(11)
+    hid = torch.randn(wm.T, wm.d_model, generator=g, device=DEV).to(torch.bfloat16)
+    dst, pos = strd.avgpool(hid, wm.N, wm.M, wm.K, want_pos=True)
+    want, want_pos = oracle.avgpool(f(hid), wm.N, wm.M, wm.K)
+    np.testing.assert_array_equal(pos.cpu().numpy(), want_pos)
+    assert_close(f(dst), want, TOLB, "avgpool c2")
+
+    m = wm.mamba
+    x = torch.randn(m.H, m.P, generator=g, device=DEV).to(torch.bfloat16)
+    B = torch.randn(m.G, m.n, generator=g, device=DEV).to(torch.bfloat16)
+    C = torch.randn(m.G, m.n, generator=g, device=DEV).to(torch.bfloat16)
+    dt = torch.rand(m.H, generator=g, device=DEV) + 0.05
+    A = -torch.exp(2 * torch.rand(m.H, generator=g, device=DEV))
+    S = torch.randn(m.H, m.P, m.n, generator=g, device=DEV)
+    S0 = f(S)
+    y = strd.ssd_decode_step(x, dt, A, B, C, None, S)
+    y_ref, S_ref = oracle.ssd_decode_step(f(x), f(dt), f(A), f(B), f(C), None, S0)
+    assert_close(f(S), S_ref, 1e-5, "decode state c2")
+    assert_close(f(y), y_ref, TOLB, "decode y c2")
+
+    a = wa.attn
+    T = wa.K + wa.M + 1
+    q = torch.randn(a.Hq, a.d, generator=g, device=DEV).to(torch.bfloat16)
+    kc = torch.randn(T, a.Hkv, a.d, generator=g, device=DEV).to(torch.bfloat16)
+    vc = torch.randn(T, a.Hkv, a.d, generator=g, device=DEV).to(torch.bfloat16)
+    o = strd.attn_decode_step(q, kc, vc)
+    assert_close(f(o), oracle.attn_decode_step(f(q), f(kc), f(vc)), TOLB, "attn decode c3 reduced cache")
