@@ -56,7 +56,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                              const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
                                                              int Hq, int Hkv, float scale2, int nqb) {
     constexpr int KS = D / 16, DT = D / 32;
