@@ -116,11 +116,13 @@ def time_graph(torch, fn, reps=20, replays=5):
     torch.cuda.current_stream().wait_stream(side)
     graph.replay()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
     for _ in range(replays):
         graph.replay()
+    e1.record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / (replays * reps)
+    return e0.elapsed_time(e1) / (replays * reps)
 
 
 class MambaLayer:
@@ -592,11 +594,23 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         "compact_us": 1e3 * time_events(torch, layer.compact),
         "mixer_reduced_us": 1e3 * ms_mixer,
     }
+    # The event pair around a single short call also sees the host's launch path (the queue is
+    # empty when it starts); a graph of 20 back-to-back calls gives the device time per call.
+    dev_calls = {}
+    try:
+        dev_calls = {"score_us": 1e3 * time_graph(torch, layer.score),
+                     "select_topk_us": 1e3 * time_graph(torch, layer.select),
+                     "compact_us": 1e3 * time_graph(torch, layer.compact)}
+    except Exception as exc:
+        print("bench.py: per-call graph timing skipped: %s" % exc, file=sys.stderr)
     full_iters = max(3, min(20, int(200.0 / max(ms_mixer * (w.T / (w.K + w.M)), 1e-3))))
     ms_full = time_events(torch, layer.mixer_full, iters=full_iters, warmup=2)
     calls["mixer_full_us"] = 1e3 * ms_full
     Tr = w.K + w.M
     sel_compact_gbs = (layer.compact_bytes() + 4 * w.N) / ((calls["select_topk_us"] + calls["compact_us"]) * 1e-6) / 1e9
+    sel_compact_dev = None
+    if dev_calls:
+        sel_compact_dev = (layer.compact_bytes() + 4 * w.N) / ((dev_calls["select_topk_us"] + dev_calls["compact_us"]) * 1e-6) / 1e9
     if layer.mixer_bound == "hbm":
         ach = layer.mixer_bytes(Tr) / (ms_mixer * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": layer.mixer_name, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -641,7 +655,9 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         "layer": kind, "workload": name, "N": w.N, "M": w.M, "K": w.K, "budget": budget,
         "ms_per_step": ms_step, "graph_replay_ms_per_step": ms_graph, "tokens_per_s": w.T / (ms_step * 1e-3),
         "retained_tokens_per_s": Tr / (ms_step * 1e-3), "speedup_vs_full": ms_full / ms_step,
-        "calls": calls, "select_plus_compact_GBps": sel_compact_gbs,
+        "calls": calls, "calls_device_us": dev_calls, "select_plus_compact_GBps": sel_compact_gbs,
+        "select_plus_compact_device_GBps": sel_compact_dev,
+        "select_plus_compact_device_frac_of_hbm": None if sel_compact_dev is None else sel_compact_dev / HBM_PEAK_GBS,
         "select_plus_compact_frac_of_hbm": sel_compact_gbs / HBM_PEAK_GBS, "roofline": roof,
         "per_call_roofline": per_call,
     }
@@ -689,7 +705,10 @@ def main():
                    "parallelism": "1 GPU"},
         "speedup_vs_full": res["speedup_vs_full"], "retained_tokens_per_s": res["retained_tokens_per_s"],
         "graph_replay_ms_per_step": res["graph_replay_ms_per_step"],
-        "calls_us": res["calls"], "select_plus_compact_GBps": res["select_plus_compact_GBps"],
+        "calls_us": res["calls"], "calls_device_us": res["calls_device_us"],
+        "select_plus_compact_device_GBps": res["select_plus_compact_device_GBps"],
+        "select_plus_compact_device_frac_of_hbm": res["select_plus_compact_device_frac_of_hbm"],
+        "select_plus_compact_GBps": res["select_plus_compact_GBps"],
         "select_plus_compact_frac_of_hbm": res["select_plus_compact_frac_of_hbm"],
         "roofline": res["roofline"], "per_call_roofline": res["per_call_roofline"], "context": PAPER_CONTEXT,
     }
