@@ -4,16 +4,18 @@
 //
 // N is at most a few hundred thousand (<= 512 KB of scores), so the problem is latency-bound:
 // one 1024-lane workgroup does an MSB radix select on the order-preserving integer image of
-// the floats (11 + 11 + 10 bits, histogram in LDS), which yields the exact K-th value and how
-// many of its duplicates to keep, then one ordered pass (packed prefix sums) writes the
-// surviving indices.  Each lane owns 4 consecutive scores of every 4096-score tile; up to
-// 32768 scores the keys are read from memory once and stay in registers for all four passes,
-// beyond that they are re-read in batches of 8 tiles with all loads of a batch in flight
-// together.  Importance scores cluster (a near-uniform attention score puts every key into a
-// handful of exponent bins) and same-address LDS atomics serialise, so every bin has 16 copies,
-// one per lane modulo 16, in adjacent LDS words (different banks); the copies are summed when a
-// bin is picked.  The ordered pass scans 8 tiles per barrier.  No global atomics, no scratch
-// memory, bit-exact and deterministic.
+// the floats, which yields the exact K-th value and how many of its duplicates to keep, then one
+// ordered pass (packed prefix sums) writes the surviving indices.  The digits (11 bits each,
+// histogram in LDS) are taken from key - min(key): the scores of a layer lie close together, so
+// the leading bits of the raw keys carry no information, while the significant bits of the
+// offsets usually fit two passes and spread over the bins.  Each lane owns 4 consecutive scores
+// of every 4096-score tile; up to 32768 scores the keys are read from memory once and stay in
+// registers for all passes, beyond that they are re-read in batches of 8 tiles with all loads of
+// a batch in flight together.  Same-address LDS atomics serialise, so in the first pass every bin
+// has 16 copies, one per lane modulo 16, in adjacent LDS words (different banks), summed when a
+// bin is picked; later passes only count the keys of one bin of the pass before and use 2 copies
+// when those are few.  The ordered pass scans 8 tiles per barrier.  No global atomics, no
+// scratch memory, bit-exact and deterministic.
 #include "common.h"
 
 namespace strd {
@@ -25,6 +27,8 @@ constexpr int kBins = 2048;
 constexpr int kTile = kThreads * 4;  // scores per tile
 constexpr int kBatch = 8;            // tiles loaded together when streaming / scanned per barrier
 constexpr int kCopies = 16;          // copies of every histogram bin
+constexpr int kFewCopies = 2;        // copies in passes 1 and 2 when at most kFewKeys keys are still in play
+constexpr int kFewKeys = 4096;
 
 // Monotone map float -> uint32 (larger float = larger key); -0.0 is folded onto +0.0.
 // Every real float maps above 0, the key given to the slots past the end of the array.
@@ -46,9 +50,10 @@ __device__ __forceinline__ void load_tile(const float *__restrict__ scores, int 
     }
 }
 
-// hist[bin] += 1 in this lane's copy of the bin.
+// hist[bin] += 1 in this lane's copy of the bin (COPIES copies per bin, adjacent words).
+template <int COPIES>
 __device__ __forceinline__ void hist_add(uint32_t *hist, uint32_t bin, bool valid) {
-    if (valid) atomicAdd(&hist[bin * kCopies + (threadIdx.x & (kCopies - 1))], 1u);
+    if (valid) atomicAdd(&hist[bin * COPIES + (threadIdx.x & (COPIES - 1))], 1u);
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS round trips):
@@ -95,17 +100,26 @@ __device__ __forceinline__ void finish_scans(ScanScratch &sc) {
 // After a histogram pass: find the bin (scanning from the top) that holds the k-th largest key
 // and reduce k to its rank inside that bin.  All threads return the same (bin, k).  Thread t owns
 // bins 2047 - t and 1023 - t, so neighbouring threads read neighbouring 64-byte groups of copies.
+template <int COPIES>
 __device__ __forceinline__ void pick_bin(const uint32_t *hist, ScanScratch &sc, uint32_t *found, uint32_t &k,
                                          uint32_t &bin) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int d_hi = kBins - 1 - threadIdx.x, d_lo = d_hi - kThreads;
     uint32_t c_hi = 0, c_lo = 0;
+    if (COPIES >= 4) {
 #pragma unroll
-    for (int c = 0; c < kCopies; c += 4) {
-        const uint4 a = *reinterpret_cast<const uint4 *>(&hist[d_hi * kCopies + c]);
-        const uint4 b = *reinterpret_cast<const uint4 *>(&hist[d_lo * kCopies + c]);
-        c_hi += a.x + a.y + a.z + a.w;
-        c_lo += b.x + b.y + b.z + b.w;
+        for (int c = 0; c < COPIES; c += 4) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(&hist[d_hi * COPIES + c]);
+            const uint4 b = *reinterpret_cast<const uint4 *>(&hist[d_lo * COPIES + c]);
+            c_hi += a.x + a.y + a.z + a.w;
+            c_lo += b.x + b.y + b.z + b.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < COPIES; ++c) {
+            c_hi += hist[d_hi * COPIES + c];
+            c_lo += hist[d_lo * COPIES + c];
+        }
     }
     const uint32_t i_hi = wave_inclusive_scan(c_hi), i_lo = wave_inclusive_scan(c_lo);
     if (lane == kWave - 1) {
@@ -119,9 +133,11 @@ __device__ __forceinline__ void pick_bin(const uint32_t *hist, ScanScratch &sc, 
     if (above_hi < k && k <= above_hi + c_hi) {
         found[0] = (uint32_t)d_hi;
         found[1] = k - above_hi;
+        found[2] = c_hi;
     } else if (above_lo < k && k <= above_lo + c_lo) {
         found[0] = (uint32_t)d_lo;
         found[1] = k - above_lo;
+        found[2] = c_lo;
     }
     __syncthreads();
     bin = found[0];
@@ -134,14 +150,14 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
                                                                int32_t *__restrict__ idx) {
     extern __shared__ __attribute__((aligned(16))) uint32_t hist[];  // [kBins][kCopies]
     __shared__ ScanScratch scan;
-    __shared__ uint32_t found[3][2];         // (bin, rank inside the bin) of each pass
+    __shared__ uint32_t found[3][3];         // (bin, rank inside the bin, keys in the bin) of each pass
     const int tid = threadIdx.x;
     const int ntiles = (N + kTile - 1) / kTile;
-    auto zero_hist = [&]() {
-        for (int b = tid * 4; b < kBins * kCopies; b += kThreads * 4)
+    auto zero_hist = [&](int copies) {
+        for (int b = tid * 4; b < kBins * copies; b += kThreads * 4)
             *reinterpret_cast<uint4 *>(&hist[b]) = make_uint4(0, 0, 0, 0);
     };
-    zero_hist();
+    zero_hist(kCopies);
 
     constexpr int kHeld = TILES > 0 ? TILES : 1;
     uint32_t held[kHeld][4];
@@ -168,30 +184,72 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
             }
         }
     };
-    __syncthreads();
 
     // ---- radix select: exact key of the K-th largest score --------------------------------
-    uint32_t k = (uint32_t)K, prefix = 0, bin;
-    for_each_key([&](uint32_t key) { hist_add(hist, key >> 21, true); });  // pass 0: top 11 bits
-    __syncthreads();
-    pick_bin(hist, scan, found[0], k, bin);
-    prefix = bin << 21;
-    zero_hist();  // every lane has read its bins before the barrier inside pick_bin
-    __syncthreads();
-    for_each_key([&](uint32_t key) {  // pass 1: middle 11 bits of the keys that share the top 11
-        hist_add(hist, (key >> 10) & 0x7FFu, (key >> 21) == (prefix >> 21));
+    // Importance scores are close together (all scores of a layer within a factor of two is
+    // normal), so the leading bits of the keys say nothing: the digits are taken from
+    // rel = key - (smallest key) instead, whose nbits significant bits are cut into 11-bit digits
+    // from the top.  Scores within a factor of two need two passes instead of three, and the keys
+    // spread over the bins instead of crowding a few.
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+    for_each_key([&](uint32_t key) {
+        if (key) {  // 0 marks the slots past the end of the array
+            kmin = min(kmin, key);
+            kmax = max(kmax, key);
+        }
     });
-    __syncthreads();
-    pick_bin(hist, scan, found[1], k, bin);
-    prefix |= bin << 10;
-    zero_hist();
-    __syncthreads();
-    for_each_key([&](uint32_t key) {  // pass 2: low 10 bits
-        hist_add(hist, key & 0x3FFu, (key >> 10) == (prefix >> 10));
-    });
-    __syncthreads();
-    pick_bin(hist, scan, found[2], k, bin);
-    const uint32_t thresh = prefix | bin;  // key of the K-th largest score (a real score: > 0)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+    }
+    if ((tid & (kWave - 1)) == 0) {
+        scan.sums[0][tid / kWave] = kmin;
+        scan.sums[1][tid / kWave] = kmax;
+    }
+    __syncthreads();  // also publishes the cleared histogram
+#pragma unroll
+    for (int wv = 0; wv < kWaves; ++wv) {
+        kmin = min(kmin, scan.sums[0][wv]);
+        kmax = max(kmax, scan.sums[1][wv]);
+    }
+    const int nbits = 32 - __clz(kmax - kmin);     // 0 when all scores are equal
+    const int npass = (nbits + 10) / 11;           // uniform
+    // Pass 0 sees every key: 16 copies per bin, whatever the distribution.  A later pass only counts
+    // the keys of one bin of the pass before; when those are few, their digits rarely collide and a
+    // histogram with 2 copies per bin is 8 times cheaper to clear and to scan.
+    uint32_t k = (uint32_t)K, prefix = 0;          // prefix: the digits of rel fixed so far, in place
+    int shift_prev = 32;
+    bool few = false;
+    for (int pass = 0; pass < npass; ++pass) {
+        const int shift = max(nbits - 11 * (pass + 1), 0);
+        const uint32_t dmask = (1u << min(11, nbits - 11 * pass)) - 1u;
+        uint32_t bin;
+        if (pass > 0) {  // every lane has read its bins before the barrier inside pick_bin
+            zero_hist(few ? kFewCopies : kCopies);
+            __syncthreads();
+        }
+        const uint32_t pfx = shift_prev < 32 ? prefix >> shift_prev : 0u;
+        if (few) {
+            for_each_key([&](uint32_t key) {
+                const uint32_t rel = key - kmin;
+                hist_add<kFewCopies>(hist, (rel >> shift) & dmask, key != 0 && (shift_prev >= 32 || (rel >> shift_prev) == pfx));
+            });
+            __syncthreads();
+            pick_bin<kFewCopies>(hist, scan, found[pass], k, bin);
+        } else {
+            for_each_key([&](uint32_t key) {
+                const uint32_t rel = key - kmin;
+                hist_add<kCopies>(hist, (rel >> shift) & dmask, key != 0 && (shift_prev >= 32 || (rel >> shift_prev) == pfx));
+            });
+            __syncthreads();
+            pick_bin<kCopies>(hist, scan, found[pass], k, bin);
+        }
+        prefix |= bin << shift;
+        few = found[pass][2] <= kFewKeys;  // uniform
+        shift_prev = shift;
+    }
+    const uint32_t thresh = kmin + prefix;  // key of the K-th largest score (a real score: > 0)
     const uint32_t keep_eq = k;            // how many keys == thresh survive (the first ones)
 
     // ---- ordered write-out: kBatch tiles per barrier ----------------------------------------
