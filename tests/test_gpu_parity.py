@@ -96,6 +96,18 @@ def test_select_topk_tiny_and_denormal_scores():
     _topk_case(s, 8950)
 
 
+@pytest.mark.parametrize("N,K", [(8192, 2048), (32768, 8192), (40000, 39000)])
+def test_select_topk_narrow_range_and_signed_scores(N, K):
+    _say("topk narrow / signed N=%d K=%d" % (N, K))
+    r = np.random.default_rng(N + K)
+    _topk_case(((1.0 + r.random(N)) / N).astype(np.float32), K)       # within a factor of two: two 11-bit digits
+    _topk_case((1.0 + 1e-6 * r.random(N)).astype(np.float32), K)      # a few distinct values around 1: one digit
+    s = r.standard_normal(N).astype(np.float32)                       # both signs: three digits
+    s[::1001] = np.float32(np.inf)
+    s[5::1003] = np.float32(-np.inf)
+    _topk_case(s, K)
+
+
 # ------------------------------------------------------------------ scores -----------------
 def _mamba_case(w, seed=0):
     h = synth.hidden_states(w, DEV, seed)
