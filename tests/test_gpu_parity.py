@@ -285,6 +285,33 @@ def test_attn_prefill_parity(name, T):
     assert_close(synth.np64(o), want, TOL[synth.torch_dtype(w.dtype)], "attn o")
 
 
+@pytest.mark.parametrize("pattern", ["rising", "falling", "spiky", "flat"])
+def test_attn_prefill_lazy_reference_adversarial(pattern):
+    """Score patterns that stress the lazily-following softmax reference: a running max that grows at
+    every tile (rescale each time), one that never moves after the first key, isolated keys far
+    above the rest (jumps of hundreds of log2 units), and all scores equal."""
+    _say("attn_prefill adversarial scores: " + pattern)
+    T, Hq, Hkv, d = 700, 4, 2, 128
+    g = torch.Generator().manual_seed(5)
+    u = torch.nn.functional.normalize(torch.randn(d, generator=g), dim=0)
+    t = torch.arange(T, dtype=torch.float32)
+    if pattern == "rising":
+        kmag = 0.05 * t                      # score against q = 30 u grows by 1.5 per key
+    elif pattern == "falling":
+        kmag = -0.05 * t
+    elif pattern == "spiky":
+        kmag = torch.zeros(T)
+        kmag[37::97] = 12.0                  # 360 above the rest
+    else:
+        kmag = torch.zeros(T)
+    k = (kmag[:, None, None] * u + 0.01 * torch.randn(T, Hkv, d, generator=g)).to(torch.bfloat16)
+    q = (30.0 * u + 0.01 * torch.randn(T, Hq, d, generator=g)).to(torch.bfloat16)
+    v = torch.randn(T, Hkv, d, generator=g).to(torch.bfloat16)
+    o = strd.attn_prefill(q.to(DEV), k.to(DEV), v.to(DEV), scale=1.0)
+    want = oracle.attn(synth.np64(q), synth.np64(k), synth.np64(v), scale=1.0)
+    assert_close(synth.np64(o), want, TOL[torch.bfloat16], "attn o (%s)" % pattern)
+
+
 # ------------------------------------------------------------------ block glue -------------
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("T,d", [(1, 64), (37, 4096), (300, 1000), (0, 128)])
