@@ -46,6 +46,8 @@ def parse_args():
                     help="instead of the layer benchmark: measure the Mamba-2 and attention layer at every token "
                          "count the paper's named schedules visit (c4 shapes) and print the modelled speed-up of "
                          "the mixers of the 62-layer hybrid under each schedule")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="run this many independent sequences of the workload on one stream each and report the aggregate rate")
     ap.add_argument("--block-stack", action="store_true",
                     help="instead of the layer benchmark: the 8-block hidden-to-hidden stack of workload c4 "
                          "(projections, glue, mixers, residual) with the progressive budgets against the same "
@@ -499,6 +501,42 @@ def variants(torch, strd, synth, dev):
     return out
 
 
+def batch_mode(torch, strd, synth, name, budget, batch, steps, warmup, dev):
+    """`batch` independent sequences of the workload, one stream each (every entry point takes one
+    sequence; a batch is a set of streams): the steps of different sequences overlap on the GPU, which
+    is what the latency-bound parts of a step (top-k, launches, the scan's serial chain) leave room
+    for.  Reports the aggregate rate beside the single-sequence one."""
+    import dataclasses
+    w0 = dataclasses.replace(synth.WORKLOADS[name], budget=budget)
+    cls = MambaLayer if w0.mamba is not None and name != "c3" else AttnLayer
+    layers = [cls(torch, strd, synth, dataclasses.replace(w0, seed=w0.seed + 17 * i), dev) for i in range(batch)]
+    streams = [torch.cuda.Stream() for _ in range(batch)]
+
+    def round_all():
+        for layer, st in zip(layers, streams):
+            with torch.cuda.stream(st):
+                layer.step()
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    for _ in range(warmup):
+        round_all()
+        layers[0].step()
+    ms_one = timed(layers[0].step, steps)
+    ms_round = timed(round_all, steps)
+    print(json.dumps({
+        "batch": batch, "workload": name, "layer": layers[0].kind, "ms_per_step_single_sequence": ms_one,
+        "ms_per_round_of_batch": ms_round, "tokens_per_s_single": w0.T / (ms_one * 1e-3),
+        "tokens_per_s_batch": batch * w0.T / (ms_round * 1e-3), "gain": batch * ms_one / ms_round,
+        "note": "one stream per sequence, default priorities; inputs resident; same six calls per sequence"}))
+
+
 def block_stack(torch, strd, synth, dev, iters=5):
     """Hidden-to-hidden 8-block stack (c4): full against progressively reduced, event-timed."""
     from paper_2603_00198_amd import blocks
@@ -686,6 +724,9 @@ def main():
         return
     if args.block_stack:
         block_stack(torch, strd, synth, dev)
+        return
+    if args.batch > 0:
+        batch_mode(torch, strd, synth, name, args.budget, args.batch, args.steps, args.warmup, dev)
         return
     if args.profile:
         profile_run(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)
