@@ -191,13 +191,20 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
     // rel = key - (smallest key) instead, whose nbits significant bits are cut into 11-bit digits
     // from the top.  Scores within a factor of two need two passes instead of three, and the keys
     // spread over the bins instead of crowding a few.
+    // (When the keys do not fit the registers, finding the smallest key would cost one more pass
+    // over memory, as much as the digit it may save: the raw keys are used then.)
     uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-    for_each_key([&](uint32_t key) {
-        if (key) {  // 0 marks the slots past the end of the array
-            kmin = min(kmin, key);
-            kmax = max(kmax, key);
-        }
-    });
+    if (TILES > 0) {
+        for_each_key([&](uint32_t key) {
+            if (key) {  // 0 marks the slots past the end of the array
+                kmin = min(kmin, key);
+                kmax = max(kmax, key);
+            }
+        });
+    } else {
+        kmin = 0u;
+        kmax = 0xFFFFFFFFu;
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
