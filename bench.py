@@ -4,7 +4,7 @@
 A step is one pass of the whole hot path over one synthetic long-video-shaped sequence:
 score -> select_topk -> compact (every mixer input + the hidden states) -> mixer on the K + M
 survivors, all enqueued on one HIP stream without host synchronisation.  Inputs are resident
-in HBM before the timed region.  One JSON line is printed (see the design doc for the fields).
+in HBM before the timed region.  One JSON line is printed.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4m|c4a|c5m|c5a]
                   [--budget 0.25] [--no-cpu-baseline]

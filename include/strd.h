@@ -184,7 +184,7 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
                       int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
- * Block glue around the mixers (next row 3 of the scope table): what a hybrid layer does between
+ * Block glue around the mixers: what a hybrid layer does between
  * its projections and the scan or attention, apart from matrix products.  The paper builds on
  * the Mamba-2 block and does not restate these operations; they follow that block's published
  * definition.  All: [dev] tensors of the io dtype (weights included) unless stated, fp32
@@ -215,7 +215,7 @@ int strd_softplus_dt(const void *raw, int ld, int col0, const float *bias, float
                      strd_dtype io, void *stream);
 
 /* ---------------------------------------------------------------------------
- * Variants (next row 4 of the scope table).
+ * Variants around the reduced prefill.
  *
  * avgpool -- the average-pooling reduction that the "Reduction Types" ablation (Sec. 4,
  * ablation table, right half) sets against query-based selection.  The paper does not state

@@ -1,5 +1,4 @@
-"""Hidden-to-hidden blocks of a hybrid layer stack with token reduction inside (next row 3 of the
-scope table): pre-norm, projections, the Mamba-2 glue (short causal convolution + SiLU on x, B, C;
+"""Hidden-to-hidden blocks of a hybrid layer stack with token reduction inside: pre-norm, projections, the Mamba-2 glue (short causal convolution + SiLU on x, B, C;
 softplus on dt; gated RMS norm) or the attention glue, the mixer on the surviving tokens, the
 out-projection added to the residual stream.  A reducing block scores with its own projected
 b, c, dt (or q, k) -- after the convolution -- keeps the top K vision tokens and compacts what the
