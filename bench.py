@@ -46,6 +46,8 @@ def parse_args():
                     help="instead of the layer benchmark: measure the Mamba-2 and attention layer at every token "
                          "count the paper's named schedules visit (c4 shapes) and print the modelled speed-up of "
                          "the mixers of the 62-layer hybrid under each schedule")
+    ap.add_argument("--variants", action="store_true",
+                    help="time only the average-pool baseline and the decode steps (next_rows.variants of the default line)")
     ap.add_argument("--batch", type=int, default=0,
                     help="run this many independent sequences of the workload on one stream each and report the aggregate rate")
     ap.add_argument("--block-stack", action="store_true",
@@ -724,6 +726,9 @@ def main():
         return
     if args.block_stack:
         block_stack(torch, strd, synth, dev)
+        return
+    if args.variants:
+        print(json.dumps({"variants": variants(torch, strd, synth, dev)}))
         return
     if args.batch > 0:
         batch_mode(torch, strd, synth, name, args.budget, args.batch, args.steps, args.warmup, dev)
