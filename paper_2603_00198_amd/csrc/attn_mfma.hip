@@ -2,17 +2,19 @@
 // App. "Attention via Kernel Functions", first equation), flash-style: the score matrix is
 // produced and consumed tile by tile with a running max and sum per query.
 //
-// One workgroup = 4 waves = one query head x 128 consecutive query positions; wave w owns 32 of
-// them.  Tiles are computed transposed (v_mfma_f32_32x32x16_bf16):
+// One workgroup = NW waves = one query head x 32 * NW consecutive query positions; wave w owns 32
+// of them.  Tiles are computed transposed (v_mfma_f32_32x32x16_bf16):
 //     S^T[key, t] = K_tile . Q^T        A = key rows from LDS, B = query fragments in registers
 //     O^T[d,  t] += V_tile^T . P^T      A = V read with the transposing LDS load, B = P^T
 // so a lane owns one query column: its running max, running sum and the rescale factor are
 // per-lane scalars, and the fp32 score accumulators of a 32-key tile, converted to bf16, are
 // already laid out as the B operand of the second product (8 consecutive accumulator registers
 // = the 8 contraction slots of a lane; V is read with the matching key permutation).
-// K and V stream through LDS in 64-key chunks, double-buffered, shared by the 4 waves; the
-// next chunk is copied global -> LDS asynchronously (no register staging) during the current one.  Workgroups are issued
-// longest-first (last query block first), heads of one kv group adjacent.
+// K and V stream through LDS in chunks of KC keys, double-buffered, shared by the waves; the next
+// chunk is copied global -> LDS asynchronously (no register staging) during the current one.
+// Two shapes: 4 waves and 64-key chunks (two workgroups per CU) for short sequences, 8 waves and
+// 128-key chunks (one workgroup per CU) for long ones.  Workgroups are issued longest-first (last
+// query block first), heads of one kv group adjacent.
 #include "common.h"
 
 namespace strd {
@@ -23,19 +25,16 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
-constexpr int kBM = 128;  // query positions per workgroup
-constexpr int kKC = 64;   // keys per LDS chunk
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.f;  // log2 of how far a probability may exceed 1 before the reference moves
 
 // K rows are read 16 bytes per lane, 16 rows per quarter wave: conflict-free when the row pitch is
 // 4 words modulo 64 (one pad vector).  V is read with the transposing load, 4 rows x 64 bytes per
 // half wave: conflict-free when the pitch is 16 words modulo 64 (four pad vectors, never copied).
-template <int D>
+template <int D, int NW, int KC>
 struct Tile {
-    using A = AsyncTile<kKC, D / 8, kThreads / kWave>;
-    using AV = AsyncTile<kKC, D / 8, kThreads / kWave, 4, true>;
+    using A = AsyncTile<KC, D / 8, NW>;
+    using AV = AsyncTile<KC, D / 8, NW, 4, true>;
     static constexpr int kPitch = A::kPitch;
     static constexpr int kPitchV = AV::kPitch;
     struct alignas(16) Half {
@@ -55,13 +54,14 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
-                                                             const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
-                                                             int Hq, int Hkv, float scale2, int nqb) {
-    constexpr int KS = D / 16, DT = D / 32;
+template <int D, int NW, int KC>
+__global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
+    int Hq, int Hkv, float scale2, int nqb) {
+    constexpr int KS = D / 16, DT = D / 32, kBM = 32 * NW;
+    using TileT = Tile<D, NW, KC>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
+    TileT &lds = *reinterpret_cast<TileT *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
     const float lazy_raw = kLazy / scale2;  // the slack of the softmax reference, in raw score units
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int wq0 = __builtin_amdgcn_readfirstlane(t0 + 32 * w);
     const int wmax = min(T - 1, wq0 + 31);       // last key any query of the wave may see
     const int nkeys = min(T, t0 + kBM);
-    const int nchunk = (nkeys + kKC - 1) / kKC;
+    const int nchunk = (nkeys + KC - 1) / KC;
 
     bf16x8 bq[KS];
     {
@@ -84,8 +84,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // K / V chunks go global -> LDS directly; the slots of this lane are recomputed for every chunk
     // (a few integer operations per 64 keys) rather than held in registers
-    using AT = typename Tile<D>::A;
-    using ATV = typename Tile<D>::AV;
+    using AT = typename TileT::A;
+    using ATV = typename TileT::AV;
     const uint32_t kv_row = (uint32_t)Hkv * D * 2;
     const uint32_t kv_col = (uint32_t)kvh * D * 2;
     int next_chunk = 0;
@@ -94,14 +94,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int i = 0; i < AT::kIssues; ++i) {
             int row, cv;
             AT::slot(w, lane, i, row, cv);
-            const uint32_t off = (uint32_t)min(next_chunk * kKC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
+            const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
             AT::issue(reinterpret_cast<const char *>(k) + off, &lds.k[b], w, i);
         }
 #pragma unroll
         for (int i = 0; i < ATV::kIssues; ++i) {
             int row, cv;
             ATV::slot(w, lane, i, row, cv);
-            const uint32_t off = (uint32_t)min(next_chunk * kKC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
+            const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
             ATV::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], w, i);
         }
         ++next_chunk;
@@ -125,8 +125,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int cur = chunk & 1;
         stage(cur ^ 1);  // chunk + 1 (past the last chunk: clamped rows, never read)
 #pragma unroll
-        for (int kt = 0; kt < kKC / 32; ++kt) {
-            const int kb = chunk * kKC + 32 * kt;
+        for (int kt = 0; kt < KC / 32; ++kt) {
+            const int kb = chunk * KC + 32 * kt;
             if (kb <= wmax) {  // uniform per wave
                 // all key fragments of the tile first (one LDS round trip, not one per product)
                 bf16x8 kf[KS];
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) sacc = mfma32(kf[ks], bq[ks], sacc);
                 // the transposed V fragments of the tile are requested now and arrive during the softmax
-                constexpr int kHi = 8 * Tile<D>::kPitchV * 2;  // byte offset of the second 4 keys of a slot group
+                constexpr int kHi = 8 * TileT::kPitchV * 2;  // byte offset of the second 4 keys of a slot group
                 strd_s16x4 vr8[2][(DT + 3) / 4][8];
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2) {
@@ -215,14 +215,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 }
 
-template <int D>
+template <int D, int NW, int KC>
 int launch(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, float scale, hipStream_t st) {
-    const size_t smem = sizeof(Tile<D>);
-    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_mfma_kernel<D>), smem))
+    const size_t smem = sizeof(Tile<D, NW, KC>);
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_mfma_kernel<D, NW, KC>), smem))
         return STRD_EHIP;
-    const int nqb = ceil_div(T, kBM);
-    attn_mfma_kernel<D><<<nqb * Hq, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                                                          (bf16_t *)o, T, Hq, Hkv, scale * kLog2e, nqb);
+    const int nqb = ceil_div(T, 32 * NW);
+    attn_mfma_kernel<D, NW, KC><<<nqb * Hq, NW * kWave, smem, st>>>((const bf16_t *)q, (const bf16_t *)k,
+                                                                        (const bf16_t *)v, (bf16_t *)o, T, Hq, Hkv,
+                                                                        scale * kLog2e, nqb);
     return launch_status();
 }
 
@@ -230,14 +231,18 @@ int launch(const void *q, const void *k, const void *v, void *o, int T, int Hq, 
 
 bool attn_mfma_supported(int T, int Hq, int Hkv, int d, strd_dtype io) {
     // staging uses 32-bit byte offsets into K and V
-    return io == STRD_BF16 && T >= 1 && (d == 64 || d == 128) && (long long)ceil_div(T, kBM) * Hq < (1LL << 30) &&
-           (unsigned long long)(T + 2 * kKC) * Hkv * d * 2 < (1ull << 32);
+    return io == STRD_BF16 && T >= 1 && (d == 64 || d == 128) && (long long)ceil_div(T, 128) * Hq < (1LL << 30) &&
+           (unsigned long long)(T + 2 * 128) * Hkv * d * 2 < (1ull << 32);
 }
 
 int attn_mfma(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d, float scale,
               hipStream_t st) {
-    if (d == 128) return launch<128>(q, k, v, o, T, Hq, Hkv, scale, st);
-    if (d == 64) return launch<64>(q, k, v, o, T, Hq, Hkv, scale, st);
+    // Long sequences: 8 waves (256 queries) per workgroup share 128-key chunks, one workgroup per CU --
+    // half the K/V copies per query and a barrier every four tiles instead of every two (4-5 % faster
+    // at 33 K tokens).  Short ones keep the 4-wave, 64-key form, which makes twice as many workgroups.
+    const bool big = (long long)ceil_div(T, 256) * Hq >= 512;
+    if (d == 128) return big ? launch<128, 8, 128>(q, k, v, o, T, Hq, Hkv, scale, st) : launch<128, 4, 64>(q, k, v, o, T, Hq, Hkv, scale, st);
+    if (d == 64) return big ? launch<64, 8, 128>(q, k, v, o, T, Hq, Hkv, scale, st) : launch<64, 4, 64>(q, k, v, o, T, Hq, Hkv, scale, st);
     return STRD_EUNSUPPORTED;
 }
 
