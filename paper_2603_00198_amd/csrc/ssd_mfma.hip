@@ -2,7 +2,7 @@
 // "ssm_output") in its chunked form, i.e. the unrolled sum (Eq. "ssm_unrolled") split at
 // 64-token boundaries, with the recurrent state kept in registers for the whole sequence.
 //
-// Decomposition.  One workgroup (8 waves) owns one head h and a slab of 32 of its P channels
+// Decomposition.  One workgroup (11 waves) owns one head h and a slab of 32 of its P channels
 // and walks the sequence in 64-token steps; nothing but x, dt, B, C is read from HBM and
 // nothing but y (and the final state) is written.  Per step, with l_t the in-step cumulative
 // sum of dt*A (in log2 units) and all tiles staged in LDS:
@@ -18,18 +18,19 @@
 //
 // Roles.  Waves 0-3 ("output waves") compute (a)-(d), wave w for tokens 16w..16w+15 of the
 // step; causality makes wave 3 do four times the (a)-(c) work of wave 0.  Waves 4-7 ("state
-// waves") own the state rows for (e) in the opposite proportion (3, 2, 2, 1 sixteenths-of-n
-// tiles when n = 128), because wave 4+i shares a SIMD with wave i.
+// waves") own the state rows for (e) in roughly the opposite proportion (2, 3, 2, 1 tiles of 16
+// rows of n when n = 128), because wave 4+i shares a SIMD with wave i.
 //
-// Memory.  Every input reaches LDS by asynchronous global -> LDS copies (B and C: waves 4 and 5;
-// x and dt: wave 7), far enough ahead to cover HBM latency with only one workgroup per CU: x three steps ahead
-// (ring of 4), dt three steps ahead (ring of 4), the B and C tiles three steps ahead (ring of 3:
+// Memory.  Every input reaches LDS by asynchronous global -> LDS copies issued by two copy waves
+// (9 and 10: half of the B and C tiles each; wave 10 also x and dt), far enough ahead to cover HBM
+// latency with only one workgroup per CU: x three steps ahead (ring of 4), dt four steps ahead
+// (ring of 5), the B and C tiles three steps ahead (ring of 3:
 // a tile has landed two steps before its step, is read into registers during the step before
 // its step -- every wave fetches its B / C / x operands in the tail of the previous step and the
 // output waves compute (a) there -- and its slot is refilled during its own step; the tiles
-// are shared by the 32 workgroups of a group through the XCD's L2).  Wave 7 (the lightest)
-// turns dt into the scan l_t and the key factors of (b) two steps ahead, wave 6 (the next
-// lightest) makes the weighted copy w_j x_j one step ahead.  The bf16 state copy
+// are shared by the 32 workgroups of a group through the XCD's L2).  A helper wave (8) turns dt
+// into the scan l_t and the key factors of (b) two steps ahead and makes the weighted copy
+// w_j x_j one step ahead: chains of LDS round trips that no computing wave has to carry.  The bf16 state copy
 // is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the last row
 // with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.  Each wave runs a
 // straight-line specialisation (compile-time trip counts).
@@ -44,7 +45,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 64;         // tokens per step
 constexpr int kPB = 32;        // channels of the head per workgroup
-constexpr int kThreads = 640;  // 4 output waves + 4 state waves + 2 copy waves
+constexpr int kThreads = 704;  // 4 output waves + 4 state waves + 2 copy waves + 1 helper wave
 constexpr float kLog2e = 1.4426950408889634f;
 
 constexpr int kXRing = 4;   // x tiles in LDS (requested kXRing - 1 steps ahead)
@@ -126,19 +127,26 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     // step to step are c_t (for (d)), G^T and the x^T fragments of the coming step.
     bf16x8 cf[KS], xf[2][2];
     f32x4 acc[W + 1];
-    auto fetch = [&](int q) {
-        typename L::TileBC &tb = lds.bc[q % 3];
-        strd_s16x4 xr8[8];
+    strd_s16x4 xr8[8];
+    bf16x8 bfr[W + 1][KS];
+    // the LDS reads of the operands of step q: B and C fragments, then (separately, the registers
+    // are free later) the x fragments
+    auto fetch_issue_x = [&](int q) __attribute__((always_inline)) {
         issue_x_frags<L::kXP>(lds.xr[q % kXRing].x, lr, lb, xr8);
-        bf16x8 bfr[W + 1][KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
+    };
+    auto fetch_issue = [&](int q) __attribute__((always_inline)) {
+        typename L::TileBC &tb = lds.bc[q % 3];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int jt = 0; jt <= W; ++jt)
                 bfr[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
+        // last: the products of (d) that are still queued read the current c fragments
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) cf[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[tcol * L::kCP + 32 * ks + 8 * lb]);
         __builtin_amdgcn_sched_barrier(0);  // nothing moves across: loads above, arithmetic below
+    };
+    auto fetch_finish = [&]() __attribute__((always_inline)) {
         // (a): G^T tiles for key blocks jt <= W (independent accumulators)
 #pragma unroll
         for (int jt = 0; jt <= W; ++jt) acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -151,16 +159,18 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 
     if (GATHER) __syncthreads();  // the barriers of the prologue: (row tables written,)
     __syncthreads();              // first copies landed,
-    fetch(0);
+    fetch_issue(0);
+    fetch_issue_x(0);
+    fetch_finish();
     __syncthreads();              // scans of steps 0 and 1 published,
     __syncthreads();              // weighted x of step 0 published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
         typename L::Scan &bf = lds.scan[step % 3];
-        // What depends on the previous step (state copy, scan) is read here, all of it before any
-        // arithmetic: after the barrier all eight waves hit the LDS at once and a round trip is
-        // long, so the wave pays one, not one per phase.
+        // What depends on the previous step (scan, then state copy) is read here, all of it before
+        // any arithmetic: after the barrier all waves hit the LDS at once and a round trip is long,
+        // so the wave pays one, not one per phase.
         const float el_t = bf.ell[tcol];
         const float el_ref = bf.ell[W > 0 ? 16 * W - 1 : 0];
         f32x4 f_j[W > 0 ? W : 1];
@@ -174,8 +184,13 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
                 sf[pt][ks] = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
+        bf16x4 xv[2] = {};
+        if (D) {
+            const bf16_t *xt = lds.xr[step % kXRing].x;
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt) xv[pt] = *reinterpret_cast<const bf16x4 *>(&xt[tcol * L::kXP + 16 * pt + 4 * lb]);
+        }
         __builtin_amdgcn_sched_barrier(0);
-
         // (d): inter-step part from the state copy
         f32x4 yin[2];
 #pragma unroll
@@ -184,6 +199,12 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) yin[pt] = mfma16(sf[pt][ks], cf[ks], yin[pt]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // The operands of the next step (its tiles were published by the barrier that ended the
+        // previous step) are requested as soon as (d) has released the registers of the state
+        // copy; their LDS round trip runs under (b), (c) and the stores.
+        fetch_issue(step + 1);
+
         // (b): decay, dt and causal mask; pack pairs of key blocks as B operands of (c).
         // Blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan
         // at the last token before this wave's block (both exponents <= 0); diagonal block: direct.
@@ -215,16 +236,16 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
                                       __builtin_shufflevector(m4[2 * pr], m4[2 * pr + 1], 0, 1, 2, 3, 4, 5, 6, 7), yacc[pt]);
         }
         const float carry = fast_exp2(el_t);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_issue_x(step + 1);  // (c) has released the x fragments of this step
         if (step * kQ + tcol < T) {
-            const bf16_t *xt = lds.xr[step % kXRing].x;
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt) {
                 bf16x4 out;
                 if (D) {
-                    const bf16x4 xv = *reinterpret_cast<const bf16x4 *>(&xt[tcol * L::kXP + 16 * pt + 4 * lb]);
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i] + Dh * (float)xv[i]);
+                        out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i] + Dh * (float)xv[pt][i]);
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i]);
@@ -233,66 +254,22 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
             }
         }
         yp += y_step;
-        fetch(step + 1);  // its tiles were published by the barrier that ended the previous step
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_finish();
         lds_barrier();    // the y stores stay in flight
     }
 }
 
-// State wave SW: owns NT 16-row tiles of the state starting at tile T0 and does (e) for them;
-// SW == 3 also makes the scans, SW == 2 the weighted x and, in gather mode, the row tables.
+// State wave SW: owns NT 16-row tiles of the state starting at tile T0 and does (e) for them.
 template <int NS, int SW, bool GATHER>
-__device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict__ A, const float *__restrict__ S_in,
-                                           float *__restrict__ S_out, const int32_t *__restrict__ idx, int N, int K,
-                                           int T, int P, int h, int p0, int nsteps) {
+__device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict__ S_in, float *__restrict__ S_out,
+                                           int P, int h, int p0, int nsteps) {
     using L = Lds<NS>;
-    // state tiles per wave, in the opposite proportion to the causal work of the output wave
-    // on the same SIMD (n = 128: 3, 2, 2, 1 of 8 tiles; n = 64: one tile each)
-    constexpr int NT = NS == 128 ? (SW == 0 ? 3 : SW == 3 ? 1 : 2) : 1;
-    constexpr int T0 = NS == 128 ? (SW == 0 ? 0 : SW == 1 ? 3 : SW == 2 ? 5 : 7) : SW;
+    // state tiles per wave (n = 128: 2, 3, 2, 1 of 8 tiles; n = 64: one tile each): few where the
+    // output wave on the same SIMD has much causal work (3), or where the helper wave runs (0)
+    constexpr int NT = NS == 128 ? (SW == 1 ? 3 : SW == 3 ? 1 : 2) : 1;
+    constexpr int T0 = NS == 128 ? (SW == 0 ? 0 : SW == 1 ? 2 : SW == 2 ? 5 : 7) : SW;
     const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
-    const float Al2 = A[h] * kLog2e;
-
-    // gather mode, wave SW == 2 (it issues no copies, so its loads disturb nobody's count of
-    // outstanding copies): source rows of the tokens of `step`, tokens past T repeat the last one
-    // (an index outside [0, N) is clamped into the tensors instead of faulting).  The load runs one
-    // step ahead of the store so that its latency never sits inside a step.
-    const uint32_t last_row = (uint32_t)(N + (T - K) - 1);
-    auto load_row = [&](int step) -> uint32_t {
-        const int t = min(step * kQ + lane, T - 1);
-        return min((uint32_t)(t < K ? idx[t] : N + (t - K)), last_row);
-    };
-    uint32_t row_ahead = 0;
-    // wave SW == 3, lane = token: scan of dt*A of `step` from the dt ring and the key factors
-    auto make_scan = [&](int step) {
-        const float raw = lds.dt[step % kDtRing][lane];
-        const float dv = (step * kQ + lane < T) ? raw : 0.f;
-        const float inc = wave_inclusive_scan_f32(dv * Al2);
-        typename L::Scan &m = lds.scan[step % 3];
-        m.ell[lane] = inc;
-        m.dtv[lane] = dv;
-#pragma unroll
-        for (int wq = 1; wq < 4; ++wq) {  // only tokens j < 16 * wq are read; the exponent is <= 0 for them
-            const float lref = read_lane_f32(inc, 16 * wq - 1);
-            if (lane < 16 * wq) m.fw[L::fw_at(wq) + lane] = dv * fast_exp2(lref - inc);
-        }
-    };
-    // wave SW == 2, lane = token: weighted copy of the x row of the token (x tile and scan of
-    // `step` were published by the barrier of an earlier step)
-    auto make_xw = [&](int step) {
-        const bf16_t *xrow = lds.xr[step % kXRing].x + lane * L::kXP;
-        bf16x8 xv[kPB / 8];
-#pragma unroll
-        for (int c = 0; c < kPB / 8; ++c) xv[c] = *reinterpret_cast<const bf16x8 *>(xrow + 8 * c);
-        const typename L::Scan &m = lds.scan[step % 3];
-        const float wv = m.dtv[lane] * fast_exp2(m.ell[kQ - 1] - m.ell[lane]);
-#pragma unroll
-        for (int c = 0; c < kPB / 8; ++c) {
-            bf16x8 xs;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[c][e] * wv);
-            *reinterpret_cast<bf16x8 *>(&lds.xw[step & 1].v[lane][8 * c]) = xs;
-        }
-    };
 
     // state: fp32 master in registers ([n rows][p cols] tiles), bf16 copy in LDS
     f32x4 sacc[NT][2];
@@ -308,17 +285,20 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
             *reinterpret_cast<bf16x4 *>(&lds.s[0][pp][n0]) = sv;
         }
     // b^T fragments of the owned state tiles ([tile][token half]) are read from the B tile one
-    // step early, in the tail of the previous step, like the output waves' tile operands
+    // step early (its tile was published by the barrier that ended the step before), in the same
+    // batch of LDS reads as the operands of the current step
     bf16x8 bt[NT][2];
-    auto fetch_b = [&](int q) {
+    strd_s16x4 br8[(NT + 1) / 2][8];
+    auto fetch_b_issue = [&](int q) __attribute__((always_inline)) {
         typename L::TileBC &tb = lds.bc[q % 3];
-        strd_s16x4 br8[(NT + 1) / 2][8];
 #pragma unroll
         for (int n2 = 0; n2 < NT; n2 += 2) {  // two tiles per group of reads, the second only used if owned
             constexpr int R = L::kCP * 2;
             lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
                 &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], br8[n2 / 2]);
         }
+    };
+    auto fetch_b_finish = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int n2 = 0; n2 < NT; n2 += 2) {
             lds_settle8(br8[n2 / 2]);
@@ -332,27 +312,13 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
         }
     };
 
-    // prologue, in step with the copy waves: (row tables 0..3 |) first copies landed | scans 0
-    // and 1 (, row table 4) | weighted x 0
-    if (GATHER) {
-        if (SW == 2) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
-        }
-        __syncthreads();
-    }
+    // prologue, in step with the other waves: (row tables 0..3 |) first copies landed | scans 0
+    // and 1 | weighted x 0
+    if (GATHER) __syncthreads();
     __syncthreads();
-    if (GATHER && SW == 2) {  // the prologue's requests have read table 0
-        lds.rowtab[0][lane] = load_row(4);
-        row_ahead = load_row(5);
-    }
-    fetch_b(0);
-    if (SW == 3) {
-        make_scan(0);
-        make_scan(1);
-    }
+    fetch_b_issue(0);
+    fetch_b_finish();
     __syncthreads();
-    if (SW == 2) make_xw(0);
     __syncthreads();
 
     for (int step = 0; step < nsteps; ++step) {
@@ -361,9 +327,11 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
         // (e) for the rows this wave owns: S^T = 2^(l_Q) S^T + b^T (w x)
         strd_s16x4 xr8[8];
         issue_x_frags<kPB + 8>(&lds.xw[cur].v[0][0], lr, lb, xr8);
-        const float decay_q = fast_exp2(bf.ell[kQ - 1]);
+        const float ell_q = bf.ell[kQ - 1];
+        fetch_b_issue(step + 1);
         bf16x8 xf[2][2];
-        take_x_frags(xr8, xf);
+        take_x_frags(xr8, xf);  // waits for the whole batch
+        const float decay_q = fast_exp2(ell_q);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
@@ -382,16 +350,7 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
                 bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                 *reinterpret_cast<bf16x4 *>(&lds.s[cur ^ 1][pt * 16 + lr][(T0 + nt) * 16 + lb * 4]) = sv;
             }
-        fetch_b(step + 1);  // its tile was published by the barrier that ended the previous step
-        // dt up to step + 2 and x up to step + 1 landed before the barrier that ended the previous step
-        if (SW == 3) make_scan(step + 2);
-        if (SW == 2) make_xw(step + 1);
-        if (GATHER && SW == 2) {
-            // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
-            // rows of step + 1, last used two steps ago
-            lds.rowtab[(step + 1) & 3][lane] = row_ahead;
-            row_ahead = load_row(step + 6);
-        }
+        fetch_b_finish();  // after the products that read the current fragments
         lds_barrier();
     }
 
@@ -405,12 +364,106 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
     }
 }
 
+// Helper wave: everything that is derived from dt and x alone, ahead of the steps that use it,
+// so that no computing wave carries these LDS round trips: lane = token; the scan of dt*A and the
+// key factors of (b) two steps ahead, the weighted copy w_j x_j one step ahead and, in gather
+// mode, the source rows of the tokens five steps ahead.
+template <int NS, bool GATHER>
+__device__ __forceinline__ void helper_wave(Lds<NS> &lds, const float *__restrict__ A, const int32_t *__restrict__ idx,
+                                            int N, int K, int T, int h, int nsteps) {
+    using L = Lds<NS>;
+    const int lane = threadIdx.x & 63;
+    const float Al2 = A[h] * kLog2e;
+    // the youngest wave of its SIMD would lose every issue arbitration against the two computing
+    // waves there; its chain is the longest of the step, so it goes first
+    __builtin_amdgcn_s_setprio(3);
+
+    // gather mode (this wave issues no copies, so its loads disturb nobody's count of outstanding
+    // copies): source rows of the tokens of `step`, tokens past T repeat the last one (an index
+    // outside [0, N) is clamped into the tensors instead of faulting).  The load runs one step
+    // ahead of the store so that its latency never sits inside a step.
+    const uint32_t last_row = (uint32_t)(N + (T - K) - 1);
+    auto load_row = [&](int step) -> uint32_t {
+        const int t = min(step * kQ + lane, T - 1);
+        return min((uint32_t)(t < K ? idx[t] : N + (t - K)), last_row);
+    };
+    uint32_t row_ahead = 0;
+    // scan of dt*A of `step` and the key factors, from the raw dt of the lane's token
+    auto make_scan = [&](int step, float raw) __attribute__((always_inline)) {
+        const float dv = (step * kQ + lane < T) ? raw : 0.f;
+        const float inc = wave_inclusive_scan_f32(dv * Al2);
+        typename L::Scan &m = lds.scan[step % 3];
+        m.ell[lane] = inc;
+        m.dtv[lane] = dv;
+#pragma unroll
+        for (int wq = 1; wq < 4; ++wq) {  // only tokens j < 16 * wq are read; the exponent is <= 0 for them
+            const float lref = read_lane_f32(inc, 16 * wq - 1);
+            if (lane < 16 * wq) m.fw[L::fw_at(wq) + lane] = dv * fast_exp2(lref - inc);
+        }
+    };
+    // One call makes the weighted copy of the x rows of step `sx` (x tile and scan of `sx` were
+    // published by the barrier of an earlier step) and the scan of step `ss` (its dt row landed
+    // before that barrier too).  All LDS reads are issued before any arithmetic: one round trip.
+    auto make = [&](int sx, int ss, bool with_xw, bool with_scan) __attribute__((always_inline)) {
+        const bf16_t *xrow = lds.xr[sx % kXRing].x + lane * L::kXP;
+        const typename L::Scan &m = lds.scan[sx % 3];
+        const float raw = lds.dt[ss % kDtRing][lane];
+        if (with_xw) {
+            bf16x8 xv[kPB / 8];
+            const float dj = m.dtv[lane], lj = m.ell[lane], lq = m.ell[kQ - 1];
+#pragma unroll
+            for (int c = 0; c < kPB / 8; ++c) xv[c] = *reinterpret_cast<const bf16x8 *>(xrow + 8 * c);
+            __builtin_amdgcn_sched_barrier(0);
+            const float wv = dj * fast_exp2(lq - lj);
+#pragma unroll
+            for (int c = 0; c < kPB / 8; ++c) {
+                bf16x8 xs;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[c][e] * wv);
+                *reinterpret_cast<bf16x8 *>(&lds.xw[sx & 1].v[lane][8 * c]) = xs;
+            }
+        }
+        if (with_scan) make_scan(ss, raw);
+    };
+
+    // prologue, in step with the other waves: (row tables 0..3 |) first copies landed | scans 0
+    // and 1 (, row table 4) | weighted x 0
+    if (GATHER) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
+        __syncthreads();
+    }
+    __syncthreads();
+    if (GATHER) {  // the prologue's requests have read table 0
+        lds.rowtab[0][lane] = load_row(4);
+        row_ahead = load_row(5);
+    }
+    make(0, 0, false, true);
+    make(0, 1, false, true);
+    __syncthreads();
+    make(0, 0, true, false);
+    __syncthreads();
+
+    for (int step = 0; step < nsteps; ++step) {
+        // dt up to step + 2 and x up to step + 1 landed before the barrier that ended the previous
+        // step; the scan of step + 1 was published by it
+        make(step + 1, step + 2, true, true);
+        if (GATHER) {
+            // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
+            // rows of step + 1, last used two steps ago
+            lds.rowtab[(step + 1) & 3][lane] = row_ahead;
+            row_ahead = load_row(step + 6);
+        }
+        lds_barrier();
+    }
+}
+
 // Copy waves: every input reaches LDS through their asynchronous global -> LDS copies (B and C:
 // half a tile each; x and dt: copy wave 0).  They run ahead of the consumers by a fixed number
 // of steps and block on the copy path instead of them.
 // GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
 // kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy;
-// the rows of a step come from a table that state wave 2 keeps five steps ahead.
+// the rows of a step come from a table that the helper wave keeps five steps ahead.
 template <int NS, int CW, bool GATHER>
 __device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
                                           const bf16_t *__restrict__ B, const bf16_t *__restrict__ C,
@@ -530,12 +583,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 3))
         case 1: output_wave<NS, 1, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
         case 2: output_wave<NS, 2, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
         case 3: output_wave<NS, 3, GATHER>(lds, D, y, T, H, P, h, p0, nsteps); break;
-        case 4: state_wave<NS, 0, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
-        case 5: state_wave<NS, 1, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
-        case 6: state_wave<NS, 2, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
-        case 7: state_wave<NS, 3, GATHER>(lds, A, S_in, S_out, idx, N, K, T, P, h, p0, nsteps); break;
-        case 8: copy_wave<NS, 0, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
-        default: copy_wave<NS, 1, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
+        case 4: state_wave<NS, 0, GATHER>(lds, S_in, S_out, P, h, p0, nsteps); break;
+        case 5: state_wave<NS, 1, GATHER>(lds, S_in, S_out, P, h, p0, nsteps); break;
+        case 6: state_wave<NS, 2, GATHER>(lds, S_in, S_out, P, h, p0, nsteps); break;
+        case 7: state_wave<NS, 3, GATHER>(lds, S_in, S_out, P, h, p0, nsteps); break;
+        // wave i runs on SIMD i % 4: the helper shares a SIMD with the lightest output wave, the
+        // heaviest output wave (3) shares its SIMD with the lightest state wave only
+        case 8: helper_wave<NS, GATHER>(lds, A, idx, N, K, T, h, nsteps); break;
+        case 9: copy_wave<NS, 1, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
+        default: copy_wave<NS, 0, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
     }
 }
 
