@@ -69,9 +69,7 @@ struct Lds {
         float ell[kQ];  // inclusive cumulative sum of dt*A*log2(e) inside the step
         float dtv[kQ];  // dt (0 past the end of the sequence)
         float fw[96];   // key factors of query block W = 1..3 at fw_at(W): dt_j * 2^(l_{16W-1} - l_j), j < 16W
-    };
-    struct alignas(16) Xw {
-        bf16_t v[kQ][kPB + 8];  // w_j * x_j, w_j = dt_j * 2^(l_Q - l_j): B operand of the state update
+        float w[kQ];    // weights of the state update: w_j = dt_j * 2^(l_Q - l_j)
     };
     static constexpr int fw_at(int W) { return W <= 1 ? 0 : W == 2 ? 16 : 48; }
     TileBC bc[3];
@@ -79,7 +77,6 @@ struct Lds {
     float dt[kDtRing][kQ];
     uint32_t rowtab[4][kQ];  // gather mode: source row of every token of steps q, q % 4 = slot
     Scan scan[3];  // made two steps ahead
-    Xw xw[2];      // made one step ahead
     bf16_t s[2][kPB][kSP];  // state before the step, [p][n]
 };
 
@@ -162,8 +159,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     fetch_issue(0);
     fetch_issue_x(0);
     fetch_finish();
-    __syncthreads();              // scans of steps 0 and 1 published,
-    __syncthreads();              // weighted x of step 0 published
+    __syncthreads();              // scans of steps 0 and 1 published
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
@@ -284,21 +280,33 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
             bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
             *reinterpret_cast<bf16x4 *>(&lds.s[0][pp][n0]) = sv;
         }
-    // b^T fragments of the owned state tiles ([tile][token half]) are read from the B tile one
-    // step early (its tile was published by the barrier that ended the step before), in the same
-    // batch of LDS reads as the operands of the current step
-    bf16x8 bt[NT][2];
-    strd_s16x4 br8[(NT + 1) / 2][8];
-    auto fetch_b_issue = [&](int q) __attribute__((always_inline)) {
+    // Operands of (e) for step q, all of them from tiles that were published a step or more before
+    // q: b^T fragments of the owned state tiles ([tile][token half]) and the weighted x fragments
+    // w_j x_j (token-contracted fragments of the x tile times the weights of the scan, rounded to
+    // bf16).  They are prepared in the tail of step q - 1, so that a step starts with its products:
+    // the new state is published early and no LDS round trip sits on the state's chain.
+    bf16x8 bt[NT][2], xwf[2][2];
+    float decay_q = 1.f;
+    auto prepare = [&](int q) __attribute__((always_inline)) {
         typename L::TileBC &tb = lds.bc[q % 3];
+        const typename L::Scan &m = lds.scan[q % 3];
+        strd_s16x4 xr8[8], br8[(NT + 1) / 2][8];
+        issue_x_frags<L::kXP>(lds.xr[q % kXRing].x, lr, lb, xr8);
 #pragma unroll
         for (int n2 = 0; n2 < NT; n2 += 2) {  // two tiles per group of reads, the second only used if owned
             constexpr int R = L::kCP * 2;
             lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(
                 &tb.b[(4 * lb + (lr >> 2)) * L::kCP + (T0 + n2) * 16 + 4 * (lr & 3)], br8[n2 / 2]);
         }
-    };
-    auto fetch_b_finish = [&]() __attribute__((always_inline)) {
+        // weights of the fragment's token slots: slot e is token 32 pr + 16 (e / 4) + 4 lb + e % 4
+        f32x4 wv[2][2];
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) wv[pr][hi] = *reinterpret_cast<const f32x4 *>(&m.w[32 * pr + 16 * hi + 4 * lb]);
+        const float ell_q = m.ell[kQ - 1];
+        bf16x8 xf[2][2];
+        take_x_frags(xr8, xf);  // waits for the whole batch
 #pragma unroll
         for (int n2 = 0; n2 < NT; n2 += 2) {
             lds_settle8(br8[n2 / 2]);
@@ -310,28 +318,25 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
                         bt[n2 + d][pr] = tr_pair(br8[n2 / 2][4 * d + 2 * pr], br8[n2 / 2][4 * d + 2 * pr + 1]);
                 }
         }
+        decay_q = fast_exp2(ell_q);
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xwf[pr][pt][e] = (bf16_t)((float)xf[pr][pt][e] * wv[pr][e >> 2][e & 3]);
     };
 
     // prologue, in step with the other waves: (row tables 0..3 |) first copies landed | scans 0
-    // and 1 | weighted x 0
+    // and 1
     if (GATHER) __syncthreads();
     __syncthreads();
-    fetch_b_issue(0);
-    fetch_b_finish();
     __syncthreads();
-    __syncthreads();
+    prepare(0);
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
-        typename L::Scan &bf = lds.scan[step % 3];
         // (e) for the rows this wave owns: S^T = 2^(l_Q) S^T + b^T (w x)
-        strd_s16x4 xr8[8];
-        issue_x_frags<kPB + 8>(&lds.xw[cur].v[0][0], lr, lb, xr8);
-        const float ell_q = bf.ell[kQ - 1];
-        fetch_b_issue(step + 1);
-        bf16x8 xf[2][2];
-        take_x_frags(xr8, xf);  // waits for the whole batch
-        const float decay_q = fast_exp2(ell_q);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
@@ -339,7 +344,7 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] = mfma16(bt[nt][pr], xf[pr][pt], sacc[nt][pt]);
+                for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] = mfma16(bt[nt][pr], xwf[pr][pt], sacc[nt][pt]);
         }
         // publish the new state copy
 #pragma unroll
@@ -350,7 +355,8 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
                 bf16x4 sv = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                 *reinterpret_cast<bf16x4 *>(&lds.s[cur ^ 1][pt * 16 + lr][(T0 + nt) * 16 + lb * 4]) = sv;
             }
-        fetch_b_finish();  // after the products that read the current fragments
+        __builtin_amdgcn_sched_barrier(0);
+        prepare(step + 1);  // x, B and scan of step + 1 were published by the barrier that ended step - 1
         lds_barrier();
     }
 
@@ -388,46 +394,24 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const float *__restric
         return min((uint32_t)(t < K ? idx[t] : N + (t - K)), last_row);
     };
     uint32_t row_ahead = 0;
-    // scan of dt*A of `step` and the key factors, from the raw dt of the lane's token
-    auto make_scan = [&](int step, float raw) __attribute__((always_inline)) {
+    // scan of dt*A of `step` from the dt ring, the key factors of (b) and the weights of (e)
+    auto make_scan = [&](int step) __attribute__((always_inline)) {
+        const float raw = lds.dt[step % kDtRing][lane];
         const float dv = (step * kQ + lane < T) ? raw : 0.f;
         const float inc = wave_inclusive_scan_f32(dv * Al2);
         typename L::Scan &m = lds.scan[step % 3];
         m.ell[lane] = inc;
         m.dtv[lane] = dv;
+        m.w[lane] = dv * fast_exp2(read_lane_f32(inc, kQ - 1) - inc);
 #pragma unroll
         for (int wq = 1; wq < 4; ++wq) {  // only tokens j < 16 * wq are read; the exponent is <= 0 for them
             const float lref = read_lane_f32(inc, 16 * wq - 1);
             if (lane < 16 * wq) m.fw[L::fw_at(wq) + lane] = dv * fast_exp2(lref - inc);
         }
     };
-    // One call makes the weighted copy of the x rows of step `sx` (x tile and scan of `sx` were
-    // published by the barrier of an earlier step) and the scan of step `ss` (its dt row landed
-    // before that barrier too).  All LDS reads are issued before any arithmetic: one round trip.
-    auto make = [&](int sx, int ss, bool with_xw, bool with_scan) __attribute__((always_inline)) {
-        const bf16_t *xrow = lds.xr[sx % kXRing].x + lane * L::kXP;
-        const typename L::Scan &m = lds.scan[sx % 3];
-        const float raw = lds.dt[ss % kDtRing][lane];
-        if (with_xw) {
-            bf16x8 xv[kPB / 8];
-            const float dj = m.dtv[lane], lj = m.ell[lane], lq = m.ell[kQ - 1];
-#pragma unroll
-            for (int c = 0; c < kPB / 8; ++c) xv[c] = *reinterpret_cast<const bf16x8 *>(xrow + 8 * c);
-            __builtin_amdgcn_sched_barrier(0);
-            const float wv = dj * fast_exp2(lq - lj);
-#pragma unroll
-            for (int c = 0; c < kPB / 8; ++c) {
-                bf16x8 xs;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xs[e] = (bf16_t)((float)xv[c][e] * wv);
-                *reinterpret_cast<bf16x8 *>(&lds.xw[sx & 1].v[lane][8 * c]) = xs;
-            }
-        }
-        if (with_scan) make_scan(ss, raw);
-    };
 
     // prologue, in step with the other waves: (row tables 0..3 |) first copies landed | scans 0
-    // and 1 (, row table 4) | weighted x 0
+    // and 1 (, row table 4)
     if (GATHER) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
@@ -438,16 +422,12 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const float *__restric
         lds.rowtab[0][lane] = load_row(4);
         row_ahead = load_row(5);
     }
-    make(0, 0, false, true);
-    make(0, 1, false, true);
-    __syncthreads();
-    make(0, 0, true, false);
+    make_scan(0);
+    make_scan(1);
     __syncthreads();
 
     for (int step = 0; step < nsteps; ++step) {
-        // dt up to step + 2 and x up to step + 1 landed before the barrier that ended the previous
-        // step; the scan of step + 1 was published by it
-        make(step + 1, step + 2, true, true);
+        make_scan(step + 2);  // dt up to step + 2 landed before the barrier that ended the previous step
         if (GATHER) {
             // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
             // rows of step + 1, last used two steps ago
@@ -546,7 +526,6 @@ __device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict
     async_tile_wait();
     __syncthreads();  // first copies landed
     __syncthreads();  // (scans of steps 0 and 1)
-    __syncthreads();  // (weighted x of step 0)
 
     for (int step = 0; step < nsteps; ++step) {
         if (step + 3 < nsteps) {  // uniform; nothing past the last step is requested
