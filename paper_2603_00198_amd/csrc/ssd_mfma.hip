@@ -375,28 +375,30 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
 // key factors of (b) two steps ahead, the weighted copy w_j x_j one step ahead and, in gather
 // mode, the source rows of the tokens five steps ahead.
 template <int NS, bool GATHER>
-__device__ __forceinline__ void helper_wave(Lds<NS> &lds, const float *__restrict__ A, const int32_t *__restrict__ idx,
-                                            int N, int K, int T, int h, int nsteps) {
+__device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
+                                            const float *__restrict__ A, const int32_t *__restrict__ idx, int N, int K,
+                                            int T, int H, int P, int h, int p0, int nsteps) {
     using L = Lds<NS>;
+    using XT = typename L::XT;
     const int lane = threadIdx.x & 63;
     const float Al2 = A[h] * kLog2e;
     // the youngest wave of its SIMD would lose every issue arbitration against the two computing
     // waves there; its chain is the longest of the step, so it goes first
     __builtin_amdgcn_s_setprio(3);
 
-    // gather mode (this wave issues no copies, so its loads disturb nobody's count of outstanding
-    // copies): source rows of the tokens of `step`, tokens past T repeat the last one (an index
+    // gather mode: source rows of the tokens of `step`, tokens past T repeat the last one (an index
     // outside [0, N) is clamped into the tensors instead of faulting).  The load runs one step
-    // ahead of the store so that its latency never sits inside a step.
+    // ahead of the store so that its latency never sits inside a step; every call issues exactly
+    // one global load (K >= 1 here), which the count of outstanding copies below relies on.
     const uint32_t last_row = (uint32_t)(N + (T - K) - 1);
     auto load_row = [&](int step) -> uint32_t {
         const int t = min(step * kQ + lane, T - 1);
-        return min((uint32_t)(t < K ? idx[t] : N + (t - K)), last_row);
+        const int32_t kept = idx[min(t, K - 1)];
+        return min((uint32_t)(t < K ? kept : N + (t - K)), last_row);
     };
     uint32_t row_ahead = 0;
     // scan of dt*A of `step` from the dt ring, the key factors of (b) and the weights of (e)
-    auto make_scan = [&](int step) __attribute__((always_inline)) {
-        const float raw = lds.dt[step % kDtRing][lane];
+    auto make_scan = [&](int step, float raw) __attribute__((always_inline)) {
         const float dv = (step * kQ + lane < T) ? raw : 0.f;
         const float inc = wave_inclusive_scan_f32(dv * Al2);
         typename L::Scan &m = lds.scan[step % 3];
@@ -410,66 +412,17 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const float *__restric
         }
     };
 
-    // prologue, in step with the other waves: (row tables 0..3 |) first copies landed | scans 0
-    // and 1 (, row table 4)
-    if (GATHER) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
-        __syncthreads();
-    }
-    __syncthreads();
-    if (GATHER) {  // the prologue's requests have read table 0
-        lds.rowtab[0][lane] = load_row(4);
-        row_ahead = load_row(5);
-    }
-    make_scan(0);
-    make_scan(1);
-    __syncthreads();
-
-    for (int step = 0; step < nsteps; ++step) {
-        make_scan(step + 2);  // dt up to step + 2 landed before the barrier that ended the previous step
-        if (GATHER) {
-            // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
-            // rows of step + 1, last used two steps ago
-            lds.rowtab[(step + 1) & 3][lane] = row_ahead;
-            row_ahead = load_row(step + 6);
-        }
-        lds_barrier();
-    }
-}
-
-// Copy waves: every input reaches LDS through their asynchronous global -> LDS copies (B and C:
-// half a tile each; x and dt: copy wave 0).  They run ahead of the consumers by a fixed number
-// of steps and block on the copy path instead of them.
-// GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
-// kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy;
-// the rows of a step come from a table that the helper wave keeps five steps ahead.
-template <int NS, int CW, bool GATHER>
-__device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
-                                          const bf16_t *__restrict__ B, const bf16_t *__restrict__ C,
-                                          int T, int H, int P, int G, int h, int p0, int g, int nsteps) {
-    using L = Lds<NS>;
-    using BC = typename L::BC;
-    using XT = typename L::XT;
-    const int lane = threadIdx.x & 63;
-    // Byte offsets (32 bits) of this lane's copies at the next step to request, per-step strides and
-    // end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes them inert).
-    const uint32_t bc_row = (uint32_t)G * NS * 2, x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
-    // dense mode: running offsets; gather mode: (row in the step, column offset) per copy and the
-    // number of the next step to request, the row itself comes from the row table
-    uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues], off_x[XT::kIssues], lim_x[XT::kIssues];
-    int row_bc[BC::kIssues], row_x[XT::kIssues];
+    // The asynchronous global -> LDS copies of x (three steps ahead, ring of 4) and dt (four steps
+    // ahead, ring of 5).  Byte offsets (32 bits) of this lane's copies at the next step to request,
+    // per-step strides and end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes
+    // them inert); gather mode: (row in the step, column offset) per copy, the row itself comes
+    // from the row table.
+    const uint32_t x_row = (uint32_t)H * P * 2, dt_row = (uint32_t)H * 4;
+    uint32_t off_x[XT::kIssues], lim_x[XT::kIssues];
+    int row_x[XT::kIssues];
     uint32_t off_dt = (uint32_t)lane * dt_row + (uint32_t)h * 4;
     const uint32_t lim_dt = (uint32_t)(T - 1) * dt_row + (uint32_t)h * 4;
-    int next_bc = 0, next_x = 0, next_dt = 0;
-#pragma unroll
-    for (int i = 0; i < BC::kIssues; ++i) {
-        int cv;
-        BC::slot(CW, lane, i, row_bc[i], cv);
-        const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
-        off_bc[i] = GATHER ? col : (uint32_t)row_bc[i] * bc_row + col;
-        lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
-    }
+    int next_x = 0, next_dt = 0;
 #pragma unroll
     for (int i = 0; i < XT::kIssues; ++i) {
         int cv;
@@ -477,6 +430,106 @@ __device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict
         const uint32_t col = ((uint32_t)h * P + p0 + cv * 8) * 2;
         off_x[i] = GATHER ? col : (uint32_t)row_x[i] * x_row + col;
         lim_x[i] = (uint32_t)(T - 1) * x_row + col;
+    }
+    // each call requests the next not yet requested step of its stream into ring slot b
+    auto request_x = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < XT::kIssues; ++i) {
+            const uint32_t o = GATHER ? lds.rowtab[next_x & 3][row_x[i]] * x_row + off_x[i] : min(off_x[i], lim_x[i]);
+            XT::issue(reinterpret_cast<const char *>(x) + o, lds.xr[b].x, 0, i);
+            if (!GATHER) off_x[i] += kQ * x_row;
+        }
+        ++next_x;
+    };
+    auto request_dt = [&](int b) __attribute__((always_inline)) {  // 64 lanes x 4 bytes
+        const uint32_t o = GATHER ? lds.rowtab[next_dt & 3][lane] * dt_row + (uint32_t)h * 4 : min(off_dt, lim_dt);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + o),
+            (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
+        off_dt += kQ * dt_row;
+        ++next_dt;
+    };
+    // Vector-memory operations issued per step (the copies and, in gather mode, the one load of
+    // row indices after them); everything older has landed once at most that many are
+    // outstanding (they complete in order).  s_waitcnt immediate, gfx9 layout:
+    // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+    constexpr int kNewest = XT::kIssues + 1 + (GATHER ? 1 : 0);
+    constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
+
+    // prologue, in step with the other waves: (row tables 0..3 |) first copies landed | scans 0
+    // and 1 (, row table 4)
+    if (GATHER) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {  // fill the rings up to their look-ahead (x: steps 0..2, dt: steps 0..3)
+        if (q < 3) request_x(q);
+        request_dt(q);
+    }
+    async_tile_wait();
+    __syncthreads();
+    if (GATHER) {  // the prologue's requests have read table 0
+        lds.rowtab[0][lane] = load_row(4);
+        row_ahead = load_row(5);
+    }
+    make_scan(0, lds.dt[0][lane]);
+    make_scan(1, lds.dt[1][lane]);
+    __syncthreads();
+
+    for (int step = 0; step < nsteps; ++step) {
+        const bool more = step + 3 < nsteps;  // uniform; nothing past the last step is requested
+        // dt up to step + 2 landed before the barrier that ended the previous step; read before this
+        // step's copies are requested, so that no wait for them can sit in front of the read
+        const float raw = lds.dt[(step + 2) % kDtRing][lane];
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+            request_x((step + kXRing - 1) % kXRing);     // x of step + 3; slot last read in step - 1
+            request_dt((step + kDtRing - 1) % kDtRing);  // dt of step + 4; slot last read in step - 2
+        }
+        make_scan(step + 2, raw);
+        if (GATHER) {
+            // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
+            // rows of step + 1, last used two steps ago
+            lds.rowtab[(step + 1) & 3][lane] = row_ahead;
+            row_ahead = load_row(step + 6);
+        }
+        if (more)
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);  // everything requested in earlier steps has landed
+        else
+            async_tile_wait();
+        lds_barrier();  // publishes it; this step's copies stay in flight
+    }
+}
+
+// Copy waves: the B and C tiles reach LDS through their asynchronous global -> LDS copies, half a
+// tile each.  They run ahead of the consumers by a fixed number of steps and block on the copy
+// path instead of them.
+// GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
+// kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy;
+// the rows of a step come from a table that the helper wave keeps five steps ahead.
+template <int NS, int CW, bool GATHER>
+__device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict__ B, const bf16_t *__restrict__ C,
+                                          int T, int G, int g, int nsteps) {
+    using L = Lds<NS>;
+    using BC = typename L::BC;
+    const int lane = threadIdx.x & 63;
+    // Byte offsets (32 bits) of this lane's copies at the next step to request, per-step strides and
+    // end-of-sequence clamps (rows past T re-read the last row; dt = 0 makes them inert).
+    const uint32_t bc_row = (uint32_t)G * NS * 2;
+    // dense mode: running offsets; gather mode: (row in the step, column offset) per copy and the
+    // number of the next step to request, the row itself comes from the row table
+    uint32_t off_bc[BC::kIssues], lim_bc[BC::kIssues];
+    int row_bc[BC::kIssues];
+    int next_bc = 0;
+#pragma unroll
+    for (int i = 0; i < BC::kIssues; ++i) {
+        int cv;
+        BC::slot(CW, lane, i, row_bc[i], cv);
+        const uint32_t col = ((uint32_t)g * NS + cv * 8) * 2;
+        off_bc[i] = GATHER ? col : (uint32_t)row_bc[i] * bc_row + col;
+        lim_bc[i] = (uint32_t)(T - 1) * bc_row + col;
     }
     // each call requests the next not yet requested step of its stream into ring slot b
     auto request_bc = [&](int b) {
@@ -489,52 +542,25 @@ __device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict
         }
         ++next_bc;
     };
-    auto request_x = [&](int b) {
-#pragma unroll
-        for (int i = 0; i < XT::kIssues; ++i) {
-            const uint32_t o = GATHER ? lds.rowtab[next_x & 3][row_x[i]] * x_row + off_x[i] : min(off_x[i], lim_x[i]);
-            XT::issue(reinterpret_cast<const char *>(x) + o, lds.xr[b].x, 0, i);
-            if (!GATHER) off_x[i] += kQ * x_row;
-        }
-        ++next_x;
-    };
-    auto request_dt = [&](int b) {  // 64 lanes x 4 bytes
-        const uint32_t o = GATHER ? lds.rowtab[next_dt & 3][lane] * dt_row + (uint32_t)h * 4 : min(off_dt, lim_dt);
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(dt) + o),
-            (__attribute__((address_space(3))) void *)lds.dt[b], 4, 0, 0);
-        off_dt += kQ * dt_row;
-        ++next_dt;
-    };
     // Copies issued per step; everything older has landed once at most that many are outstanding
     // (vector-memory operations complete in order).  s_waitcnt immediate, gfx9 layout:
     // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-    constexpr int kNewest = 2 * BC::kIssues + (CW == 0 ? XT::kIssues + 1 : 0);
+    constexpr int kNewest = 2 * BC::kIssues;
     static_assert(kNewest < 64, "vmcnt has 6 bits");
     constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
 
-    // prologue: fill the rings up to their look-ahead (B / C and x: steps 0..2, dt: steps 0..3)
+    // prologue: fill the ring up to its look-ahead (steps 0..2)
     if (GATHER) __syncthreads();  // row tables of steps 0..3 written
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (q < 3) {
-            request_bc(q);
-            if (CW == 0) request_x(q);
-        }
-        if (CW == 0) request_dt(q);
-    }
+    for (int q = 0; q < 3; ++q) request_bc(q);
     async_tile_wait();
     __syncthreads();  // first copies landed
     __syncthreads();  // (scans of steps 0 and 1)
 
     for (int step = 0; step < nsteps; ++step) {
         if (step + 3 < nsteps) {  // uniform; nothing past the last step is requested
-            request_bc(step % 3);                        // tile step + 3; the slot's tile (step) was read in step - 1
-            if (CW == 0) {
-                request_x((step + kXRing - 1) % kXRing);     // x of step + 3; slot last read in step - 1
-                request_dt((step + kDtRing - 1) % kDtRing);  // dt of step + 4; slot last read in step - 3
-            }
-            __builtin_amdgcn_s_waitcnt(kWaitOlder);      // everything requested in earlier steps has landed
+            request_bc(step % 3);                    // tile step + 3; the slot's tile (step) was read in step - 1
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);  // everything requested in earlier steps has landed
         } else {
             async_tile_wait();
         }
@@ -568,9 +594,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 3))
         case 7: state_wave<NS, 3, GATHER>(lds, S_in, S_out, P, h, p0, nsteps); break;
         // wave i runs on SIMD i % 4: the helper shares a SIMD with the lightest output wave, the
         // heaviest output wave (3) shares its SIMD with the lightest state wave only
-        case 8: helper_wave<NS, GATHER>(lds, A, idx, N, K, T, h, nsteps); break;
-        case 9: copy_wave<NS, 1, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
-        default: copy_wave<NS, 0, GATHER>(lds, x, dt, B, C, T, H, P, G, h, p0, g, nsteps); break;
+        case 8: helper_wave<NS, GATHER>(lds, x, dt, A, idx, N, K, T, H, P, h, p0, nsteps); break;
+        case 9: copy_wave<NS, 1, GATHER>(lds, B, C, T, G, g, nsteps); break;
+        default: copy_wave<NS, 0, GATHER>(lds, B, C, T, G, g, nsteps); break;
     }
 }
 
