@@ -2,7 +2,7 @@
 // "ssm_output") in its chunked form, i.e. the unrolled sum (Eq. "ssm_unrolled") split at
 // 64-token boundaries, with the recurrent state kept in registers for the whole sequence.
 //
-// Decomposition.  One workgroup (11 waves) owns one head h and a slab of 32 of its P channels
+// Decomposition.  One workgroup (12 waves) owns one head h and a slab of 32 of its P channels
 // and walks the sequence in 64-token steps; nothing but x, dt, B, C is read from HBM and
 // nothing but y (and the final state) is written.  Per step, with l_t the in-step cumulative
 // sum of dt*A (in log2 units) and all tiles staged in LDS:
@@ -21,19 +21,22 @@
 // waves") own the state rows for (e) in roughly the opposite proportion (2, 3, 2, 1 tiles of 16
 // rows of n when n = 128), because wave 4+i shares a SIMD with wave i.
 //
-// Memory.  Every input reaches LDS by asynchronous global -> LDS copies issued by two copy waves
-// (9 and 10: half of the B and C tiles each; wave 10 also x and dt), far enough ahead to cover HBM
-// latency with only one workgroup per CU: x three steps ahead (ring of 4), dt four steps ahead
-// (ring of 5), the B and C tiles three steps ahead (ring of 3:
-// a tile has landed two steps before its step, is read into registers during the step before
-// its step -- every wave fetches its B / C / x operands in the tail of the previous step and the
-// output waves compute (a) there -- and its slot is refilled during its own step; the tiles
-// are shared by the 32 workgroups of a group through the XCD's L2).  A helper wave (8) turns dt
-// into the scan l_t and the key factors of (b) two steps ahead and makes the weighted copy
-// w_j x_j one step ahead: chains of LDS round trips that no computing wave has to carry.  The bf16 state copy
-// is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the last row
-// with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.  Each wave runs a
-// straight-line specialisation (compile-time trip counts).
+// Memory.  Every input reaches LDS by asynchronous global -> LDS copies, far enough ahead to cover
+// HBM latency with only one workgroup per CU: three copy waves (9-11) request a third of the B and
+// C tiles each, three steps ahead (ring of 3: a tile has landed two steps before its step, is read
+// into registers during the step before its step and its slot is refilled during its own step; the
+// tiles are shared by the 32 workgroups of a group through the XCD's L2); a helper wave (8)
+// requests x three steps ahead (ring of 4) and dt four steps ahead (ring of 5), turns dt into the
+// scan l_t, the key factors of (b) and the weights w_j two steps ahead and, in gather mode, keeps
+// the row tables.  Issuing a copy costs a wave 50-100 ns, which is why the copies are spread over
+// four waves that do nothing else.  Every computing wave fetches the operands that come from the
+// tiles alone one step early: the output waves request the B / C / x fragments of the next step
+// right after (d) and compute its (a) in the tail of the step; the state waves read their b^T and
+// x fragments of the next step in the tail, weight the x fragments with w_j in registers and start
+// the next step with the products of (e), so the new state copy is published early.  The bf16
+// state copy is double-buffered.  One workgroup barrier per step.  Rows past T are copies of the
+// last row with dt = 0, which makes them inert in (b)-(e); their y rows are not stored.  Each wave
+// runs a straight-line specialisation (compile-time trip counts).
 #include "common.h"
 
 namespace strd {
@@ -45,7 +48,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 64;         // tokens per step
 constexpr int kPB = 32;        // channels of the head per workgroup
-constexpr int kThreads = 704;  // 4 output waves + 4 state waves + 2 copy waves + 1 helper wave
+constexpr int kCopyWaves = 3;
+constexpr int kThreads = 64 * (9 + kCopyWaves);  // 4 output waves + 4 state waves + 1 helper wave + the copy waves
 constexpr float kLog2e = 1.4426950408889634f;
 
 constexpr int kXRing = 4;   // x tiles in LDS (requested kXRing - 1 steps ahead)
@@ -53,7 +57,7 @@ constexpr int kDtRing = 5;  // dt rows in LDS (requested kDtRing - 1 steps ahead
 
 template <int NS>
 struct Lds {
-    using BC = AsyncTile<kQ, NS / 8, 2, 2, true>;   // B / C tile, filled by two waves, 2 pad vectors per row
+    using BC = AsyncTile<kQ, NS / 8, kCopyWaves, 2, true>;  // B / C tile, filled by the copy waves, 2 pad vectors per row
     using XT = AsyncTile<kQ, kPB / 8, 1, 1, true>;  // x tile of the slab, filled by one wave, 1 pad vector per row
     static constexpr int kCP = BC::kPitch;    // bf16 elements per row of the B / C tiles
     static constexpr int kXP = XT::kPitch;    // bf16 elements per row of the x tiles
@@ -370,10 +374,10 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
     }
 }
 
-// Helper wave: everything that is derived from dt and x alone, ahead of the steps that use it,
-// so that no computing wave carries these LDS round trips: lane = token; the scan of dt*A and the
-// key factors of (b) two steps ahead, the weighted copy w_j x_j one step ahead and, in gather
-// mode, the source rows of the tokens five steps ahead.
+// Helper wave: the copies of x and dt, and everything that is derived from dt alone, ahead of the
+// steps that use it, so that no computing wave carries these LDS round trips: lane = token; the
+// scan of dt*A, the key factors of (b) and the weights of (e) two steps ahead and, in gather mode,
+// the source rows of the tokens five steps ahead.
 template <int NS, bool GATHER>
 __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restrict__ x, const float *__restrict__ dt,
                                             const float *__restrict__ A, const int32_t *__restrict__ idx, int N, int K,
@@ -382,8 +386,8 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
     using XT = typename L::XT;
     const int lane = threadIdx.x & 63;
     const float Al2 = A[h] * kLog2e;
-    // the youngest wave of its SIMD would lose every issue arbitration against the two computing
-    // waves there; its chain is the longest of the step, so it goes first
+    // a young wave of its SIMD, it would lose every issue arbitration against the two computing
+    // waves there, and the copies it requests are the ones that come from furthest away
     __builtin_amdgcn_s_setprio(3);
 
     // gather mode: source rows of the tokens of `step`, tokens past T repeat the last one (an index
@@ -595,8 +599,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 3))
         // wave i runs on SIMD i % 4: the helper shares a SIMD with the lightest output wave, the
         // heaviest output wave (3) shares its SIMD with the lightest state wave only
         case 8: helper_wave<NS, GATHER>(lds, x, dt, A, idx, N, K, T, H, P, h, p0, nsteps); break;
-        case 9: copy_wave<NS, 1, GATHER>(lds, B, C, T, G, g, nsteps); break;
-        default: copy_wave<NS, 0, GATHER>(lds, B, C, T, G, g, nsteps); break;
+        case 9: copy_wave<NS, 0, GATHER>(lds, B, C, T, G, g, nsteps); break;
+        case 10: copy_wave<NS, 1, GATHER>(lds, B, C, T, G, g, nsteps); break;
+        default: copy_wave<NS, 2, GATHER>(lds, B, C, T, G, g, nsteps); break;
     }
 }
 
