@@ -80,6 +80,7 @@ struct Lds {
     TileX xr[kXRing];
     float dt[kDtRing][kQ];
     uint32_t rowtab[4][kQ];  // gather mode: source row of every token of steps q, q % 4 = slot
+    int32_t rawidx[4][kQ];   // gather mode: entries of the kept-index list for steps q, q % 4 = slot
     Scan scan[3];  // made two steps ahead
     bf16_t s[2][kPB][kSP];  // state before the step, [p][n]
 };
@@ -390,17 +391,23 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
     // waves there, and the copies it requests are the ones that come from furthest away
     __builtin_amdgcn_s_setprio(3);
 
-    // gather mode: source rows of the tokens of `step`, tokens past T repeat the last one (an index
-    // outside [0, N) is clamped into the tensors instead of faulting).  The load runs one step
-    // ahead of the store so that its latency never sits inside a step; every call issues exactly
-    // one global load (K >= 1 here), which the count of outstanding copies below relies on.
+    // gather mode: source rows of the tokens of `step`; tokens past T repeat the last one, and an
+    // index outside [0, N) is clamped into the tensors instead of faulting.  Inside the loop the
+    // entries of the kept-index list travel like every other input: an asynchronous copy into LDS
+    // seven steps ahead, read two steps later and turned into the row table of five steps ahead --
+    // a load into a register would make the wave wait for all its outstanding copies, too.
     const uint32_t last_row = (uint32_t)(N + (T - K) - 1);
-    auto load_row = [&](int step) -> uint32_t {
-        const int t = min(step * kQ + lane, T - 1);
-        const int32_t kept = idx[min(t, K - 1)];
+    auto token_of = [&](int step) { return min(step * kQ + lane, T - 1); };
+    auto row_of = [&](int step, int32_t kept) -> uint32_t {
+        const int t = token_of(step);
         return min((uint32_t)(t < K ? kept : N + (t - K)), last_row);
     };
-    uint32_t row_ahead = 0;
+    auto kept_of = [&](int step) -> int32_t { return idx[min(token_of(step), K - 1)]; };  // K >= 1 here
+    auto request_kept = [&](int step) __attribute__((always_inline)) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(idx + min(token_of(step), K - 1)),
+            (__attribute__((address_space(3))) void *)lds.rawidx[step & 3], 4, 0, 0);
+    };
     // scan of dt*A of `step` from the dt ring, the key factors of (b) and the weights of (e)
     auto make_scan = [&](int step, float raw) __attribute__((always_inline)) {
         const float dv = (step * kQ + lane < T) ? raw : 0.f;
@@ -453,9 +460,8 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
         off_dt += kQ * dt_row;
         ++next_dt;
     };
-    // Vector-memory operations issued per step (the copies and, in gather mode, the one load of
-    // row indices after them); everything older has landed once at most that many are
-    // outstanding (they complete in order).  s_waitcnt immediate, gfx9 layout:
+    // Copies issued per step (x, dt and, in gather mode, the entries of the kept-index list);
+    // everything older has landed once at most that many are outstanding (they complete in order).  s_waitcnt immediate, gfx9 layout:
     // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
     constexpr int kNewest = XT::kIssues + 1 + (GATHER ? 1 : 0);
     constexpr int kWaitOlder = (kNewest & 15) | (7 << 4) | (15 << 8) | ((kNewest >> 4) << 14);
@@ -464,7 +470,9 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
     // and 1 (, row table 4)
     if (GATHER) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = load_row(q);
+        for (int q = 0; q < 4; ++q) lds.rowtab[q][lane] = row_of(q, kept_of(q));
+        lds.rawidx[5 & 3][lane] = kept_of(5);  // read in steps 0 and 1, before the first copied entries
+        lds.rawidx[6 & 3][lane] = kept_of(6);
         __syncthreads();
     }
 #pragma unroll
@@ -474,10 +482,7 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
     }
     async_tile_wait();
     __syncthreads();
-    if (GATHER) {  // the prologue's requests have read table 0
-        lds.rowtab[0][lane] = load_row(4);
-        row_ahead = load_row(5);
-    }
+    if (GATHER) lds.rowtab[0][lane] = row_of(4, kept_of(4));  // the prologue's requests have read table 0
     make_scan(0, lds.dt[0][lane]);
     make_scan(1, lds.dt[1][lane]);
     __syncthreads();
@@ -487,18 +492,18 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
         // dt up to step + 2 landed before the barrier that ended the previous step; read before this
         // step's copies are requested, so that no wait for them can sit in front of the read
         const float raw = lds.dt[(step + 2) % kDtRing][lane];
+        int32_t kept = 0;
+        if (GATHER) kept = lds.rawidx[(step + 5) & 3][lane];  // requested in step - 2 (or by the prologue)
         __builtin_amdgcn_sched_barrier(0);
         if (more) {
             request_x((step + kXRing - 1) % kXRing);     // x of step + 3; slot last read in step - 1
             request_dt((step + kDtRing - 1) % kDtRing);  // dt of step + 4; slot last read in step - 2
+            if (GATHER) request_kept(step + 7);          // slot last read in step - 2
         }
         make_scan(step + 2, raw);
-        if (GATHER) {
-            // rows of step + 5, first used in the next step (dt of step + 5); the slot held the
-            // rows of step + 1, last used two steps ago
-            lds.rowtab[(step + 1) & 3][lane] = row_ahead;
-            row_ahead = load_row(step + 6);
-        }
+        // gather mode: rows of step + 5, first used in the next step (dt of step + 5); the slot held
+        // the rows of step + 1, last used two steps ago
+        if (GATHER) lds.rowtab[(step + 1) & 3][lane] = row_of(step + 5, kept);
         if (more)
             __builtin_amdgcn_s_waitcnt(kWaitOlder);  // everything requested in earlier steps has landed
         else
