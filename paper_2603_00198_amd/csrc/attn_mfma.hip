@@ -12,9 +12,10 @@
 // = the 8 contraction slots of a lane; V is read with the matching key permutation).
 // K and V stream through LDS in chunks of KC keys, double-buffered, shared by the waves; the next
 // chunk is copied global -> LDS asynchronously (no register staging) during the current one.
-// Two shapes: 4 waves and 64-key chunks (two workgroups per CU) for short sequences, 8 waves and
-// 128-key chunks (one workgroup per CU) for long ones.  Workgroups are issued longest-first (last
-// query block first), heads of one kv group adjacent.
+// Two shapes: 4 waves that request their own copies and 64-key chunks (two workgroups per CU) for
+// short sequences; 8 computing waves, 4 copy waves and 128-key chunks (one workgroup per CU) for
+// long ones.  Workgroups are issued longest-first (last query block first), heads of one kv group
+// adjacent.
 #include "common.h"
 
 namespace strd {
@@ -31,10 +32,11 @@ constexpr float kLazy = 8.f;  // log2 of how far a probability may exceed 1 befo
 // K rows are read 16 bytes per lane, 16 rows per quarter wave: conflict-free when the row pitch is
 // 4 words modulo 64 (one pad vector).  V is read with the transposing load, 4 rows x 64 bytes per
 // half wave: conflict-free when the pitch is 16 words modulo 64 (four pad vectors, never copied).
-template <int D, int NW, int KC>
+// NC = number of waves that fill the tiles.
+template <int D, int NC, int KC>
 struct Tile {
-    using A = AsyncTile<KC, D / 8, NW>;
-    using AV = AsyncTile<KC, D / 8, NW, 4, true>;
+    using A = AsyncTile<KC, D / 8, NC>;
+    using AV = AsyncTile<KC, D / 8, NC, 4, true>;
     static constexpr int kPitch = A::kPitch;
     static constexpr int kPitchV = AV::kPitch;
     struct alignas(16) Half {
@@ -54,12 +56,13 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int D, int NW, int KC>
-__global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
+// NW computing waves and NC copy waves; NC = 0: the computing waves request the copies themselves.
+template <int D, int NW, int NC, int KC>
+__global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_eu(2, NC ? 3 : 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
     int Hq, int Hkv, float scale2, int nqb) {
     constexpr int KS = D / 16, DT = D / 32, kBM = 32 * NW;
-    using TileT = Tile<D, NW, KC>;
+    using TileT = Tile<D, NC ? NC : NW, KC>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     TileT &lds = *reinterpret_cast<TileT *>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
@@ -75,37 +78,53 @@ __global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)
     const int nkeys = min(T, t0 + kBM);
     const int nchunk = (nkeys + KC - 1) / KC;
 
+    // K / V chunks go global -> LDS directly, one chunk ahead of the products.  Requesting a copy
+    // blocks a wave for as long as the CU's copy path is busy with earlier ones (about half of the
+    // time at long sequences), so there the requests are kept out of the waves that feed the matrix
+    // cores: the last NC waves of the workgroup do nothing else.  With NC = 0 every computing wave
+    // requests its share.  The slots of a lane are recomputed for every chunk (a few integer
+    // operations) rather than held in registers.
+    using AT = typename TileT::A;
+    using ATV = typename TileT::AV;
+    const int cw = NC ? w - NW : w;
+    const uint32_t kv_row = (uint32_t)Hkv * D * 2;
+    const uint32_t kv_col = (uint32_t)kvh * D * 2;
+    int next_chunk = 0;
+    auto stage = [&](int b) __attribute__((always_inline)) {  // requests the next chunk in sequence; rows past T re-read row T - 1
+#pragma unroll
+        for (int i = 0; i < AT::kIssues; ++i) {
+            int row, cv;
+            AT::slot(cw, lane, i, row, cv);
+            const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
+            AT::issue(reinterpret_cast<const char *>(k) + off, &lds.k[b], cw, i);
+        }
+#pragma unroll
+        for (int i = 0; i < ATV::kIssues; ++i) {
+            int row, cv;
+            ATV::slot(cw, lane, i, row, cv);
+            const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
+            ATV::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], cw, i);
+        }
+        ++next_chunk;
+    };
+    if (NC > 0 && w >= NW) {  // copy wave
+        stage(0);
+        async_tile_wait();
+        lds_barrier();
+        for (int chunk = 0; chunk < nchunk; ++chunk) {
+            stage((chunk & 1) ^ 1);  // chunk + 1 (past the last chunk: clamped rows, never read)
+            async_tile_wait();
+            lds_barrier();
+        }
+        return;
+    }
+
     bf16x8 bq[KS];
     {
         const bf16_t *qp = q + ((size_t)min(tq, T - 1) * Hq + h) * D;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks + 8 * half);
     }
-
-    // K / V chunks go global -> LDS directly; the slots of this lane are recomputed for every chunk
-    // (a few integer operations per 64 keys) rather than held in registers
-    using AT = typename TileT::A;
-    using ATV = typename TileT::AV;
-    const uint32_t kv_row = (uint32_t)Hkv * D * 2;
-    const uint32_t kv_col = (uint32_t)kvh * D * 2;
-    int next_chunk = 0;
-    auto stage = [&](int b) {  // requests the next chunk in sequence; rows past T re-read row T - 1
-#pragma unroll
-        for (int i = 0; i < AT::kIssues; ++i) {
-            int row, cv;
-            AT::slot(w, lane, i, row, cv);
-            const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
-            AT::issue(reinterpret_cast<const char *>(k) + off, &lds.k[b], w, i);
-        }
-#pragma unroll
-        for (int i = 0; i < ATV::kIssues; ++i) {
-            int row, cv;
-            ATV::slot(w, lane, i, row, cv);
-            const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
-            ATV::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], w, i);
-        }
-        ++next_chunk;
-    };
 
     f32x16 oacc[DT];
 #pragma unroll
@@ -118,12 +137,14 @@ __global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)
     const int vb = lane >> 4, vr = lane & 15;
     const int v_krow = 4 * (vb >> 1) + (vr >> 2), v_col = 16 * (vb & 1) + 4 * (vr & 3);
 
-    stage(0);
-    async_tile_wait();
-    __syncthreads();
+    if (NC == 0) {
+        stage(0);
+        async_tile_wait();
+    }
+    lds_barrier();  // chunk 0 has landed
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int cur = chunk & 1;
-        stage(cur ^ 1);  // chunk + 1 (past the last chunk: clamped rows, never read)
+        if (NC == 0) stage(cur ^ 1);  // chunk + 1 (past the last chunk: clamped rows, never read)
 #pragma unroll
         for (int kt = 0; kt < KC / 32; ++kt) {
             const int kb = chunk * KC + 32 * kt;
@@ -195,8 +216,8 @@ __global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)
                     }
             }
         }
-        async_tile_wait();
-        __syncthreads();
+        if (NC == 0) async_tile_wait();
+        lds_barrier();  // chunk + 1 has landed, every wave is done with this one
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
@@ -215,13 +236,13 @@ __global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)
     }
 }
 
-template <int D, int NW, int KC>
+template <int D, int NW, int NC, int KC>
 int launch(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, float scale, hipStream_t st) {
-    const size_t smem = sizeof(Tile<D, NW, KC>);
-    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_mfma_kernel<D, NW, KC>), smem))
+    const size_t smem = sizeof(Tile<D, NC ? NC : NW, KC>);
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_mfma_kernel<D, NW, NC, KC>), smem))
         return STRD_EHIP;
     const int nqb = ceil_div(T, 32 * NW);
-    attn_mfma_kernel<D, NW, KC><<<nqb * Hq, NW * kWave, smem, st>>>((const bf16_t *)q, (const bf16_t *)k,
+    attn_mfma_kernel<D, NW, NC, KC><<<nqb * Hq, (NW + NC) * kWave, smem, st>>>((const bf16_t *)q, (const bf16_t *)k,
                                                                         (const bf16_t *)v, (bf16_t *)o, T, Hq, Hkv,
                                                                         scale * kLog2e, nqb);
     return launch_status();
@@ -237,12 +258,15 @@ bool attn_mfma_supported(int T, int Hq, int Hkv, int d, strd_dtype io) {
 
 int attn_mfma(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d, float scale,
               hipStream_t st) {
-    // Long sequences: 8 waves (256 queries) per workgroup share 128-key chunks, one workgroup per CU --
-    // half the K/V copies per query and a barrier every four tiles instead of every two (4-5 % faster
-    // at 33 K tokens).  Short ones keep the 4-wave, 64-key form, which makes twice as many workgroups.
-    const bool big = (long long)ceil_div(T, 256) * Hq >= 512;
-    if (d == 128) return big ? launch<128, 8, 128>(q, k, v, o, T, Hq, Hkv, scale, st) : launch<128, 4, 64>(q, k, v, o, T, Hq, Hkv, scale, st);
-    if (d == 64) return big ? launch<64, 8, 128>(q, k, v, o, T, Hq, Hkv, scale, st) : launch<64, 4, 64>(q, k, v, o, T, Hq, Hkv, scale, st);
+    // Long sequences: 8 computing waves (256 queries) per workgroup share 128-key chunks that 4 copy
+    // waves bring in, one workgroup per CU -- half the K/V copies per query, a barrier every four
+    // tiles instead of every two, and no computing wave ever blocks on the copy path (12 % faster
+    // at 33 K tokens than the other form).  Short ones keep 4 waves that copy for themselves and
+    // 64-key chunks, which makes twice as many workgroups; the crossover lies near 1.5 workgroups of
+    // the long form per CU.
+    const bool big = (long long)ceil_div(T, 256) * Hq >= 384;
+    if (d == 128) return big ? launch<128, 8, 4, 128>(q, k, v, o, T, Hq, Hkv, scale, st) : launch<128, 4, 0, 64>(q, k, v, o, T, Hq, Hkv, scale, st);
+    if (d == 64) return big ? launch<64, 8, 4, 128>(q, k, v, o, T, Hq, Hkv, scale, st) : launch<64, 4, 0, 64>(q, k, v, o, T, Hq, Hkv, scale, st);
     return STRD_EUNSUPPORTED;
 }
 
