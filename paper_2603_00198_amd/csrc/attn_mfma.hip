@@ -158,8 +158,12 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
                 f32x16 sacc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+                // products first: the other wave of the SIMD is most likely in its softmax, and a
+                // matrix instruction that waits behind its vector instructions leaves the matrix pipe idle
+                __builtin_amdgcn_s_setprio(2);
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) sacc = mfma32(kf[ks], bq[ks], sacc);
+                __builtin_amdgcn_s_setprio(0);
                 // the transposed V fragments of the tile are requested now and arrive during the softmax
                 constexpr int kHi = 8 * TileT::kPitchV * 2;  // byte offset of the second 4 keys of a slot group
                 strd_s16x4 vr8[2][(DT + 3) / 4][8];
@@ -204,6 +208,7 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
                     pf[i >> 3][i & 7] = (bf16_t)p;
                 }
                 l_run += ps;
+                __builtin_amdgcn_s_setprio(2);
 #pragma unroll
                 for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
@@ -214,6 +219,7 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
                         for (int dd = 0; dd < 4; ++dd)
                             if (dp + dd < DT) oacc[dp + dd] = mfma32(tr_pair(r[2 * dd], r[2 * dd + 1]), pf[ks2], oacc[dp + dd]);
                     }
+                __builtin_amdgcn_s_setprio(0);
             }
         }
         if (NC == 0) async_tile_wait();
