@@ -285,6 +285,25 @@ def test_attn_prefill_parity(name, T):
     assert_close(synth.np64(o), want, TOL[synth.torch_dtype(w.dtype)], "attn o")
 
 
+# Many heads on a short sequence: enough 256-query blocks for the form with 8 computing and 4 copy
+# waves, at sizes the oracle still finishes in seconds; 188, 1 and 255 queries in the last block.
+WIDE_ATTN = {
+    "wide128": synth.shrink(synth.WORKLOADS["c3"], N=800, M=0, d_model=256, attn=synth.AttnShape(Hq=128, Hkv=32, d=128)),
+    "wide64": synth.shrink(synth.WORKLOADS["c3"], N=800, M=0, d_model=256, attn=synth.AttnShape(Hq=192, Hkv=48, d=64)),
+}
+
+
+@pytest.mark.parametrize("name,T", [("wide128", 700), ("wide128", 513), ("wide64", 767)])
+def test_attn_prefill_parity_many_heads(name, T):
+    w = WIDE_ATTN[name]
+    _say("attn_prefill %s T=%d Hq=%d" % (name, T, w.attn.Hq))
+    t = _attn_case(w, seed=T)
+    q, k, v = (t[n][:T].contiguous() for n in ("q", "k", "v"))
+    o = strd.attn_prefill(q, k, v)
+    want = oracle.attn(synth.np64(q), synth.np64(k), synth.np64(v))
+    assert_close(synth.np64(o), want, TOL[torch.bfloat16], "attn o")
+
+
 @pytest.mark.parametrize("pattern", ["rising", "falling", "spiky", "flat"])
 def test_attn_prefill_lazy_reference_adversarial(pattern):
     """Score patterns that stress the lazily-following softmax reference: a running max that grows at
