@@ -224,6 +224,37 @@ def test_ssd_prefill_parity(name, T, extras):
     assert_close(synth.np64(S_out), Sw, tol, "ssd S_out")
 
 
+@pytest.mark.parametrize("T", [2, 63, 64, 65, 128, 129, 191, 192, 193, 256, 257, 320, 449, 512, 513])
+def test_ssd_prefill_step_boundaries(T):
+    """Sequence lengths around the 64-token steps and around the look-ahead of the copies (one to
+    nine steps): dense with D and a carried-in state, and through an index list."""
+    _say("ssd_prefill step boundaries T=%d" % T)
+    H, P, G, n = 4, 64, 2, 128
+    g = torch.Generator().manual_seed(1000 + T)
+    M = min(7, T - 1)
+    K = T - M
+    N = 2 * K + 3
+    rows = N + M
+    x = torch.randn(rows, H, P, generator=g).to(torch.bfloat16)
+    B = (torch.randn(rows, G, n, generator=g) / n ** 0.5).to(torch.bfloat16)
+    C = torch.randn(rows, G, n, generator=g).to(torch.bfloat16)
+    dt = torch.nn.functional.softplus(torch.randn(rows, H, generator=g))
+    A = -torch.exp(2 * torch.rand(H, generator=g))
+    D = torch.randn(H, generator=g)
+    S_in = torch.randn(H, P, n, generator=g)
+    idx = torch.sort(torch.randperm(N, generator=g)[:K]).values.to(torch.int32)
+    keep = torch.cat([idx.long(), torch.arange(N, rows)])
+    f = synth.np64
+    y_ref, S_ref = oracle.ssd_seq(f(x[keep]), f(dt[keep]), f(A), f(B[keep]), f(C[keep]), f(D), f(S_in))
+    dev = lambda t: t.to(DEV)
+    y, S = strd.ssd_prefill(dev(x[keep].contiguous()), dev(dt[keep].contiguous()), dev(A), dev(B[keep].contiguous()),
+                            dev(C[keep].contiguous()), D=dev(D), S_in=dev(S_in))
+    assert_close(f(y), y_ref, TOL[torch.bfloat16], "y")
+    assert_close(f(S), S_ref, TOL[torch.bfloat16], "S_out")
+    y_g, S_g = strd.ssd_prefill_gather(dev(x), dev(dt), dev(A), dev(B), dev(C), dev(idx), N, M, D=dev(D), S_in=dev(S_in))
+    assert torch.equal(y_g, y) and torch.equal(S_g, S), "the gathering scan must give the bits of compact + scan"
+
+
 def test_ssd_prefill_split_call_continues_the_scan():
     w = MAMBA_CASES["c2-short"]
     _say("ssd_prefill split call")
