@@ -320,11 +320,11 @@ def test_attn_prefill_parity(name, T):
 # waves, at sizes the oracle still finishes in seconds; 188, 1 and 255 queries in the last block.
 WIDE_ATTN = {
     "wide128": synth.shrink(synth.WORKLOADS["c3"], N=800, M=0, d_model=256, attn=synth.AttnShape(Hq=128, Hkv=32, d=128)),
-    "wide64": synth.shrink(synth.WORKLOADS["c3"], N=800, M=0, d_model=256, attn=synth.AttnShape(Hq=192, Hkv=48, d=64)),
+    "wide64": synth.shrink(synth.WORKLOADS["c3"], N=1100, M=0, d_model=256, attn=synth.AttnShape(Hq=192, Hkv=48, d=64)),
 }
 
 
-@pytest.mark.parametrize("name,T", [("wide128", 700), ("wide128", 513), ("wide64", 767)])
+@pytest.mark.parametrize("name,T", [("wide128", 700), ("wide128", 513), ("wide64", 767), ("wide64", 640), ("wide64", 1025)])
 def test_attn_prefill_parity_many_heads(name, T):
     w = WIDE_ATTN[name]
     _say("attn_prefill %s T=%d Hq=%d" % (name, T, w.attn.Hq))
