@@ -105,7 +105,9 @@ __device__ __forceinline__ void lds_read_tr8(const void *p, strd_s16x4 (&r)[8]) 
 }
 // The same eight reads without the wait: the results may be used only after lds_settle8() on
 // the same registers.  Splitting issue and wait lets a wave put all the LDS reads of a step in
-// flight at once instead of paying one LDS round trip per group of reads.
+// flight at once instead of paying one LDS round trip per group of reads.  Between the two the
+// compiler takes the registers for loaded, so it must never have a reason to move them: a kernel
+// that uses this has to fit its register budget without spilling (the build is checked for it).
 template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
 __device__ __forceinline__ void lds_issue_tr8(const void *p, strd_s16x4 (&r)[8]) {
     const uint32_t a = lds_offset(p);

@@ -141,3 +141,21 @@ def test_synthetic_inputs_are_seeded_and_shaped():
     norms = h1[:1024].norm(dim=1)
     assert (norms > 4 * norms.median()).float().mean() > 0.02
     assert synth.WORKLOADS["c2"].K == 2048 and synth.WORKLOADS["c3"].K == 8192
+
+
+def test_kernels_with_split_lds_reads_do_not_spill():
+    """ssd_mfma.hip and attn_mfma.hip issue LDS reads from inline assembly and wait for them later;
+    between the two the compiler believes the destination registers hold their values.  A spill of
+    such a register before the wait would save garbage, so these kernels must fit their register
+    budget without scratch memory.  The compiler's own resource report is the check."""
+    import subprocess
+    from paper_2603_00198_amd import build as strd_build
+    for name in ("ssd_mfma.hip", "attn_mfma.hip"):
+        src = os.path.join(strd_build.CSRC, name)
+        cmd = [strd_build.HIPCC] + strd_build.FLAGS + ["--cuda-device-only", "-c", src, "-o", os.devnull,
+                                                       "-Rpass-analysis=kernel-resource-usage"]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
+        scratch = [int(v) for v in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
+        assert scratch, "no resource report for " + name
+        assert all(v == 0 for v in scratch), "%s: a kernel uses scratch memory: %s" % (name, scratch)
