@@ -251,20 +251,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 
     // query tiles go global -> LDS directly; the lse of the tile's rows goes through a register
+    // (the slots of this lane are recomputed for every tile, a few integer operations, rather than
+    // held in registers: the kernel needs all 256 of them for operands and accumulators)
     using AT = typename Tile<D>::A;
-    int st_row[AT::kIssues], st_col[AT::kIssues];
-#pragma unroll
-    for (int i = 0; i < AT::kIssues; ++i) AT::slot(w, lane, i, st_row[i], st_col[i]);
     float stage_lse = 0.f;
     // rows per kv head are usually a power of two: shift and mask instead of a division per copy
     const int rep_shift = (rep & (rep - 1)) == 0 ? __builtin_ctz(rep) : -1;  // uniform
     auto stage = [&](int chunk, int b) {
+        int lane_now = lane;
+        asm volatile("" : "+v"(lane_now));  // keeps the slot arithmetic here instead of in registers across the loop
 #pragma unroll
         for (int i = 0; i < AT::kIssues; ++i) {
-            const int rr = min(chunk * kRows + st_row[i], R - 1);
+            int st_row, st_col;
+            AT::slot(w, lane_now, i, st_row, st_col);
+            const int rr = min(chunk * kRows + st_row, R - 1);
             const size_t qi = rep_shift >= 0 ? (size_t)(rr >> rep_shift) * Hq + kvh * rep + (rr & (rep - 1))
                                              : qrow_index(rr, rep, Hq, kvh);
-            AT::issue(q + qi * D + st_col[i] * 8, &lds.t[b], w, i);
+            AT::issue(q + qi * D + st_col * 8, &lds.t[b], w, i);
         }
         if (tid < kRows) {
             const int rr = chunk * kRows + tid;
