@@ -154,7 +154,8 @@ class MambaLayer:
         lib = strd.lib()
         io = 1 if w.dtype == "bf16" else 0
         nb = max(lib.strd_score_mamba_workspace(M, N, s.H, s.G, s.n, io),
-                 lib.strd_ssd_prefill_workspace(w.T, s.H, s.P, s.G, s.n, s.chunk, io), 16)
+                 lib.strd_ssd_prefill_workspace(w.T, s.H, s.P, s.G, s.n, s.chunk, io),
+                 lib.strd_select_topk_workspace(N, w.K), 16)
         self.ws = e(nb, dtype=torch.uint8)
         self.ws_full = e(max(lib.strd_score_mamba_full_workspace(M, N, s.H, s.G, s.n, io), 16), dtype=torch.uint8)
         self.scores_full = e(N, dtype=torch.float32)
@@ -167,7 +168,7 @@ class MambaLayer:
         self.strd.score_mamba_full(self.Bv, self.Ct, self.t["dt"], self.t["A"], out=self.scores_full, ws=self.ws_full)
 
     def select(self):
-        self.strd.select_topk(self.scores, self.w.K, out=self.idx)
+        self.strd.select_topk(self.scores, self.w.K, out=self.idx, ws=self.ws)
 
     def compact(self):
         N, M = self.w.N, self.w.M
@@ -243,7 +244,8 @@ class AttnLayer:
         lib = strd.lib()
         io = 1 if w.dtype == "bf16" else 0
         nb = max(lib.strd_score_attn_workspace(M, N, s.Hq, s.Hkv, s.d, io),
-                 lib.strd_attn_prefill_workspace(w.T, s.Hq, s.Hkv, s.d, io), 16)
+                 lib.strd_attn_prefill_workspace(w.T, s.Hq, s.Hkv, s.d, io),
+                 lib.strd_select_topk_workspace(N, w.K), 16)
         self.ws = e(nb, dtype=torch.uint8)
         self.mixer_ev = None
 
@@ -251,7 +253,7 @@ class AttnLayer:
         self.strd.score_attn(self.qt, self.kv, out=self.scores, ws=self.ws)
 
     def select(self):
-        self.strd.select_topk(self.scores, self.w.K, out=self.idx)
+        self.strd.select_topk(self.scores, self.w.K, out=self.idx, ws=self.ws)
 
     def compact(self):
         N, M = self.w.N, self.w.M

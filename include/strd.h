@@ -106,6 +106,9 @@ int strd_score_mamba_full(const void *B_vis, const void *C_txt, const float *dt_
  *   scores [dev] [N] fp32, finite and >= 0 (both score kinds are); -0.0 counts as 0
  *   idx    [dev] [K] int32 output, strictly ascending
  * Requires 1 <= K <= N.  Bit-exact and deterministic.
+ *   ws     [dev] strd_select_topk_workspace(N, K) bytes (0 up to 32768 scores and above 2^20;
+ *          about 26 KB of histograms and counters between); contents need not be initialised and
+ *          are not preserved; STRD_EWORKSPACE if it is missing or too small
  * ------------------------------------------------------------------------- */
 size_t strd_select_topk_workspace(int N, int K);
 int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes,

@@ -84,15 +84,16 @@ int strd_score_mamba_full(const void *B_vis, const void *C_txt, const float *dt_
 
 // ------------------------------------------------------------------ select_topk ------------
 size_t strd_select_topk_workspace(int N, int K) {
-    (void)N; (void)K;
-    return 0;
+    (void)K;
+    return N >= 1 ? select_topk_ws(N) : 0;
 }
 
 int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes, void *stream) {
-    (void)ws; (void)ws_bytes;
     if (!scores || !idx || N < 1 || K < 1 || K > N) return STRD_EINVAL;
     if (N > (1 << 30)) return STRD_EUNSUPPORTED;
-    return select_topk_launch(scores, N, K, idx, as_stream(stream));
+    const size_t need = select_topk_ws(N);
+    if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    return select_topk_launch(scores, N, K, idx, ws, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ compact ----------------

@@ -184,7 +184,8 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? STRD_OK : 
 // ---- entry points of the individual kernel files (all enqueue on `s`, return strd_status) ----
 int compact_launch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
                    const int32_t *pos_in, int32_t *pos_out, hipStream_t s);
-int select_topk_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s);
+size_t select_topk_ws(int N);
+int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws, hipStream_t s);
 
 // general SIMT kernels: any shape, fp32 or bf16 I/O, fp32 arithmetic
 size_t score_attn_general_ws(int M, int Hq);

@@ -2,8 +2,11 @@
 // keep the top K while preserving temporal order).  Ties at the K-th value go to the lowest
 // index, which is what a stable sort by (score desc, index asc) gives.
 //
-// N is at most a few hundred thousand (<= 512 KB of scores), so the problem is latency-bound:
-// one 1024-lane workgroup does an MSB radix select on the order-preserving integer image of
+// N is at most a few hundred thousand (<= 512 KB of scores), so the problem is latency-bound.
+// Up to 32768 scores (and beyond 2^20, streaming) one 1024-lane workgroup does everything in one
+// launch; between the two a chain of six short launches with one workgroup per 4096 scores is
+// three to four times faster than streaming (see "Wide form" below).
+// The one-launch form: an MSB radix select on the order-preserving integer image of
 // the floats, which yields the exact K-th value and how many of its duplicates to keep, then one
 // ordered pass (packed prefix sums) writes the surviving indices.  The digits (11 bits each,
 // histogram in LDS) are taken from key - min(key): the scores of a layer lie close together, so
@@ -317,9 +320,164 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Wide form, 32768 < N <= kWideMax * 4096: one workgroup per 4096-score tile and a chain of short
+// launches instead of one workgroup that streams the scores four times.  The same MSB radix
+// select on the raw keys (three digits of 11, 11 and 10 bits), with one histogram per digit in
+// global memory that the workgroups add their local counts to; the launch that counts digit p
+// first picks the bin of digit p - 1 (every workgroup for itself, from the finished histogram;
+// workgroup 0 leaves the result in memory for the launches after it).  The last two launches count
+// the survivors of every tile and write them out in order.  Integer atomics only: the result is
+// bit-exact and deterministic.
+constexpr int kWideMax = 256;   // tiles (workgroups) at most
+constexpr int kWideCopies = 4;  // copies of a bin in the local histogram of one tile
+
+struct WideWs {
+    uint32_t ghist[3][kBins];       // global histograms of the three digits
+    uint32_t state[3][4];           // after picking digit p: (prefix so far, rank inside the bin)
+    uint32_t counts[kWideMax][2];   // per tile: keys above the threshold, keys equal to it
+};
+
+__device__ __forceinline__ int wide_shift(int pass) { return pass == 0 ? 21 : pass == 1 ? 10 : 0; }
+__device__ __forceinline__ uint32_t wide_mask(int pass) { return pass == 2 ? 0x3FFu : 0x7FFu; }
+
+__global__ __launch_bounds__(kThreads) void topk_wide_zero_kernel(WideWs *ws) {
+    uint32_t *h = &ws->ghist[0][0];
+    for (int i = threadIdx.x; i < 3 * kBins; i += kThreads) h[i] = 0u;
+}
+
+// Picks the bin of digit PASS - 1 from its finished global histogram; returns the prefix and rank
+// after it (the same in every thread of every workgroup).
+template <int PASS>
+__device__ __forceinline__ void wide_pick(WideWs *ws, int K, uint32_t *pickbuf, ScanScratch &scan, uint32_t *found,
+                                          uint32_t &prefix, uint32_t &k) {
+    prefix = 0;
+    k = (uint32_t)K;
+    if (PASS > 1) {
+        prefix = ws->state[PASS - 2][0];
+        k = ws->state[PASS - 2][1];
+    }
+    for (int b = threadIdx.x; b < kBins; b += kThreads) pickbuf[b] = ws->ghist[PASS - 1][b];
+    __syncthreads();
+    uint32_t bin;
+    pick_bin<1>(pickbuf, scan, found, k, bin);
+    prefix |= bin << wide_shift(PASS - 1);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ws->state[PASS - 1][0] = prefix;
+        ws->state[PASS - 1][1] = k;
+    }
+}
+
+// Launch PASS = 0, 1, 2: local histogram of digit PASS over the tile's keys that carry the digits
+// picked so far, added to the global histogram.
+template <int PASS>
+__global__ __launch_bounds__(kThreads) void topk_wide_hist_kernel(const float *__restrict__ scores, int N, int K,
+                                                                    WideWs *ws) {
+    __shared__ __attribute__((aligned(16))) uint32_t hist[kBins * kWideCopies];
+    __shared__ uint32_t pickbuf[kBins];
+    __shared__ ScanScratch scan;
+    __shared__ uint32_t found[3];
+    const int tid = threadIdx.x;
+    for (int b = tid * 4; b < kBins * kWideCopies; b += kThreads * 4)
+        *reinterpret_cast<uint4 *>(&hist[b]) = make_uint4(0, 0, 0, 0);
+    uint32_t key[4];
+    load_tile(scores, N, blockIdx.x, key);
+    uint32_t prefix = 0, k = (uint32_t)K;
+    if constexpr (PASS > 0) wide_pick<PASS>(ws, K, pickbuf, scan, found, prefix, k);
+    __syncthreads();  // the cleared histogram
+    const int shift = wide_shift(PASS), shift_prev = PASS > 0 ? wide_shift(PASS - 1) : 32;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        hist_add<kWideCopies>(hist, (key[u] >> shift) & wide_mask(PASS),
+                              key[u] != 0 && (PASS == 0 || (key[u] >> shift_prev) == (prefix >> shift_prev)));
+    __syncthreads();
+    for (int b = tid; b < kBins; b += kThreads) {
+        const uint4 c = *reinterpret_cast<const uint4 *>(&hist[b * kWideCopies]);
+        const uint32_t n = c.x + c.y + c.z + c.w;
+        if (n) atomicAdd(&ws->ghist[PASS][b], n);
+    }
+}
+
+// Picks the last digit: the threshold key and how many keys equal to it survive; counts the tile's
+// keys above and equal to the threshold.
+__global__ __launch_bounds__(kThreads) void topk_wide_count_kernel(const float *__restrict__ scores, int N, int K,
+                                                                     WideWs *ws) {
+    __shared__ uint32_t pickbuf[kBins];
+    __shared__ ScanScratch scan;
+    __shared__ uint32_t found[3];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    uint32_t key[4];
+    load_tile(scores, N, blockIdx.x, key);
+    uint32_t thresh, keep_eq;
+    wide_pick<3>(ws, K, pickbuf, scan, found, thresh, keep_eq);
+    uint32_t cnt = 0;  // low 16 bits: keys > thresh, high 16 bits: keys == thresh
+#pragma unroll
+    for (int u = 0; u < 4; ++u) cnt += (key[u] > thresh ? 1u : 0u) + (key[u] == thresh ? 0x10000u : 0u);
+    const uint32_t inc = wave_inclusive_scan(cnt);
+    if (lane == kWave - 1) scan.sums[0][wave] = inc;
+    finish_scans(scan);
+    if (tid == 0) {
+        const uint32_t total = scan.base[0][kWaves];
+        ws->counts[blockIdx.x][0] = total & 0xFFFFu;
+        ws->counts[blockIdx.x][1] = total >> 16;
+    }
+}
+
+// Ordered write-out of one tile; the tiles before it are accounted for by their counts.
+__global__ __launch_bounds__(kThreads) void topk_wide_emit_kernel(const float *__restrict__ scores, int N,
+                                                                    const WideWs *__restrict__ ws,
+                                                                    int32_t *__restrict__ idx) {
+    __shared__ ScanScratch scan;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    uint32_t key[4];
+    load_tile(scores, N, blockIdx.x, key);
+    const uint32_t thresh = ws->state[2][0], keep_eq = ws->state[2][1];
+    uint32_t out_base = 0, eq_base = 0;  // survivors / duplicates of thresh in the tiles before this one
+    for (int g = 0; g < (int)blockIdx.x; ++g) {  // uniform, at most kWideMax - 1 trips of two cached loads
+        const uint32_t gt = ws->counts[g][0], eq = ws->counts[g][1];
+        out_base += gt + (min(eq_base + eq, keep_eq) - min(eq_base, keep_eq));
+        eq_base += eq;
+    }
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) cnt += (key[u] > thresh ? 1u : 0u) + (key[u] == thresh ? 0x10000u : 0u);
+    const uint32_t inc = wave_inclusive_scan(cnt);
+    if (lane == kWave - 1) scan.sums[0][wave] = inc;
+    finish_scans(scan);
+    const uint32_t ex = scan.base[0][wave] + inc - cnt;
+    const int i0 = blockIdx.x * kTile + tid * 4;
+    uint32_t gt_before = ex & 0xFFFFu, eq_before = eq_base + (ex >> 16);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const bool gt = key[u] > thresh, eq = key[u] == thresh;
+        if (gt || (eq && eq_before < keep_eq)) {
+            const uint32_t eq_kept = min(eq_before, keep_eq) - min(eq_base, keep_eq);
+            idx[out_base + gt_before + eq_kept] = i0 + u;
+        }
+        gt_before += gt ? 1u : 0u;
+        eq_before += eq ? 1u : 0u;
+    }
+}
+
 }  // namespace
 
-int select_topk_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s) {
+size_t select_topk_ws(int N) {
+    return (N > 8 * kTile && N <= kWideMax * kTile) ? align_up(sizeof(WideWs), 256) : 0;
+}
+
+int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws, hipStream_t s) {
+    if (select_topk_ws(N)) {
+        WideWs *w = reinterpret_cast<WideWs *>(ws);
+        const int G = ceil_div(N, kTile);
+        topk_wide_zero_kernel<<<1, kThreads, 0, s>>>(w);
+        topk_wide_hist_kernel<0><<<G, kThreads, 0, s>>>(scores, N, K, w);
+        topk_wide_hist_kernel<1><<<G, kThreads, 0, s>>>(scores, N, K, w);
+        topk_wide_hist_kernel<2><<<G, kThreads, 0, s>>>(scores, N, K, w);
+        topk_wide_count_kernel<<<G, kThreads, 0, s>>>(scores, N, K, w);
+        topk_wide_emit_kernel<<<G, kThreads, 0, s>>>(scores, N, w, idx);
+        return launch_status();
+    }
     const size_t smem = (size_t)kBins * kCopies * sizeof(uint32_t);
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<2>), smem) ||
         !allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<8>), smem) ||

@@ -108,6 +108,22 @@ def test_select_topk_narrow_range_and_signed_scores(N, K):
     _topk_case(s, K)
 
 
+@pytest.mark.parametrize("N", [32769, 70000, 1 << 20, (1 << 20) + 1])
+def test_select_topk_many_workgroup_form(N):
+    """Above 32768 scores the selection runs as a chain of launches with one workgroup per 4096
+    scores (up to 2^20 scores; beyond that one streaming workgroup again): a single score in the
+    last tile, ties that span tiles, all scores equal, K = 1 and K = N."""
+    _say("topk wide form N=%d" % N)
+    r = np.random.default_rng(N)
+    s = (r.random(N, dtype=np.float32) ** 3).astype(np.float32)
+    for K in (1, N // 4, N - 1, N):
+        _topk_case(s, K)
+    t = (r.integers(0, 5, N) / np.float32(5)).astype(np.float32)      # five levels: every tile full of ties
+    for K in (N // 10, N // 2 + 1):
+        _topk_case(t, K)
+    _topk_case(np.full(N, 0.25, dtype=np.float32), N // 3)            # all equal: the first N // 3 indices
+
+
 # ------------------------------------------------------------------ scores -----------------
 def _mamba_case(w, seed=0):
     h = synth.hidden_states(w, DEV, seed)
