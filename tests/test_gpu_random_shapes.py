@@ -105,3 +105,112 @@ def test_scores_and_selection_random_shape(seed):
     kv = torch.randn(N, Hkv, d, generator=g).to(torch.bfloat16)
     sa = strd.score_attn(_dev(qt), _dev(kv))
     assert_close(sa.cpu().numpy(), oracle.score_attn(f(qt), f(kv)), TOL[torch.bfloat16], "score_attn")
+
+
+def _bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_compact_random_shape(seed):
+    """Compaction (Sec. 3.1: the retained tokens keep their order and positions), bit for bit, for
+    row sizes that are and are not multiples of 16 bytes, one tensor and several in one launch."""
+    rng = np.random.default_rng(4000 + seed)
+    g = torch.Generator().manual_seed(4000 + seed)
+    N = int(rng.integers(1, 4000))
+    M = int(rng.integers(0, 100))
+    K = int(rng.integers(0, N + 1))
+    count = int(rng.integers(1, 6))
+    shapes = []
+    for _ in range(count):        # rows are whole 4-byte words: an even element count for bf16
+        dtype = torch.bfloat16 if rng.integers(2) else torch.float32
+        elems = [2, 6, 8, 24, 130, 256, 1000, 4096] if dtype == torch.bfloat16 else [1, 2, 7, 8, 24, 65, 256, 1000, 4096]
+        shapes.append((int(rng.choice(elems)), dtype))
+    _say("compact random N=%d M=%d K=%d rows=%s" % (N, M, K, [(e, str(d)) for e, d in shapes]))
+    srcs = [torch.randn(N + M, e, generator=g).to(d) for e, d in shapes]
+    idx = torch.sort(torch.randperm(N, generator=g)[:K]).values.to(torch.int32)
+    pos_in = torch.randperm(3 * (N + M), generator=g)[: N + M].to(torch.int32)
+    outs, pos = strd.compact_batch([_dev(t) for t in srcs], _dev(idx), N, M, pos_in=_dev(pos_in))
+    for t, o in zip(srcs, outs):
+        want, want_pos = oracle.compact(_bits(t).numpy(), idx.numpy(), N, M, pos_in=pos_in.numpy())
+        np.testing.assert_array_equal(_bits(o.cpu()).numpy(), want)
+        np.testing.assert_array_equal(pos.cpu().numpy(), want_pos)
+    one, pos1 = strd.compact(_dev(srcs[0]), _dev(idx), N, M, pos_in=_dev(pos_in))
+    assert torch.equal(one, outs[0]) and torch.equal(pos1, pos)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_avgpool_random_shape(seed):
+    """The average-pool baseline (Sec. 4.1) for window sizes from 1 row to the whole sequence."""
+    rng = np.random.default_rng(5000 + seed)
+    g = torch.Generator().manual_seed(5000 + seed)
+    N = int(rng.integers(1, 3000))
+    M = int(rng.integers(0, 60))
+    K = int(rng.integers(1, N + 1)) if rng.integers(3) else int(rng.integers(1, min(N, 8) + 1))
+    D = int(rng.choice([7, 8, 24, 136, 256, 1024]))
+    dtype = torch.bfloat16 if rng.integers(2) else torch.float32
+    _say("avgpool random N=%d M=%d K=%d D=%d %s" % (N, M, K, D, dtype))
+    src = torch.randn(N + M, D, generator=g).to(dtype)
+    pos_in = torch.randperm(3 * (N + M), generator=g)[: N + M].to(torch.int32)
+    dst, pos = strd.avgpool(_dev(src), N, M, K, pos_in=_dev(pos_in))
+    want, want_pos = oracle.avgpool(f(src), N, M, K, pos_in.numpy())
+    np.testing.assert_array_equal(pos.cpu().numpy(), want_pos)
+    assert_close(f(dst), want, TOL[dtype], "avgpool")
+    assert torch.equal(dst[K:].cpu(), src[N:])
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_decode_steps_random_shape(seed):
+    """One token of the recurrence (Eq. 1) and of causal attention over a cache (Sec. 3.1)."""
+    rng = np.random.default_rng(6000 + seed)
+    g = torch.Generator().manual_seed(6000 + seed)
+    dtype = torch.bfloat16 if rng.integers(2) else torch.float32
+    G = int(rng.choice([1, 2, 3]))
+    H = G * int(rng.choice([1, 2, 4]))
+    P = int(rng.choice([3, 5, 32, 64]))
+    n = int(rng.choice([10, 16, 64, 128, 200]))
+    _say("ssd_decode_step random H=%d P=%d G=%d n=%d %s" % (H, P, G, n, dtype))
+    x = torch.randn(H, P, generator=g).to(dtype)
+    dt = torch.nn.functional.softplus(torch.randn(H, generator=g))
+    A = -torch.exp(2 * torch.rand(H, generator=g))
+    B = torch.randn(G, n, generator=g).to(dtype)
+    C = torch.randn(G, n, generator=g).to(dtype)
+    D = torch.randn(H, generator=g) if rng.integers(2) else None
+    S = torch.randn(H, P, n, generator=g)
+    S_dev = _dev(S)
+    y = strd.ssd_decode_step(_dev(x), _dev(dt), _dev(A), _dev(B), _dev(C), None if D is None else _dev(D), S_dev)
+    y_ref, S_ref = oracle.ssd_decode_step(f(x), f(dt), f(A), f(B), f(C), None if D is None else f(D), f(S))
+    assert_close(f(S_dev), S_ref, 1e-5, "state")
+    assert_close(f(y), y_ref, TOL[dtype], "y")
+
+    T = int(rng.integers(1, 20000))
+    Hkv = int(rng.choice([1, 2, 8]))
+    Hq = Hkv * int(rng.choice([1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    _say("attn_decode_step random T=%d Hq=%d Hkv=%d d=%d %s" % (T, Hq, Hkv, d, dtype))
+    q = torch.randn(Hq, d, generator=g).to(dtype)
+    k = torch.randn(T, Hkv, d, generator=g).to(dtype)
+    v = torch.randn(T, Hkv, d, generator=g).to(dtype)
+    o = strd.attn_decode_step(_dev(q), _dev(k), _dev(v))
+    assert_close(f(o), oracle.attn_decode_step(f(q), f(k), f(v)), TOL[dtype], "attn_decode_step")
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_score_mamba_full_random_shape(seed):
+    """The decayed Mamba score (Eq. 3 with the decay of Eq. 2 kept) for mild and strong decay."""
+    rng = np.random.default_rng(7000 + seed)
+    g = torch.Generator().manual_seed(7000 + seed)
+    N = int(rng.integers(1, 3000))
+    M = int(rng.integers(1, 100))
+    G = int(rng.choice([1, 2, 8]))
+    H = G * int(rng.choice([1, 4, 16]))
+    n = int(rng.choice([64, 128]))
+    a_scale = float(rng.choice([1.0, 0.05, 0.003]))
+    _say("score_mamba_full random N=%d M=%d G=%d H=%d n=%d A x %g" % (N, M, G, H, n, a_scale))
+    Ball = (torch.randn(N + M, G, n, generator=g) / n ** 0.5).to(torch.bfloat16)
+    Call = torch.randn(N + M, G, n, generator=g).to(torch.bfloat16)
+    dt = torch.nn.functional.softplus(torch.randn(N + M, H, generator=g) - 2)
+    A = -torch.exp(2 * torch.rand(H, generator=g)) * a_scale
+    got = strd.score_mamba_full(_dev(Ball[:N].contiguous()), _dev(Call[N:].contiguous()), _dev(dt), _dev(A))
+    want = oracle.score_mamba_full(f(Ball), f(Call), f(dt), f(A), N)
+    assert_close(got.cpu().numpy(), want, TOL[torch.bfloat16], "score_mamba_full")
