@@ -1,6 +1,6 @@
 """Are the oracle's pins sharp?  One plausible mistake at a time (a dropped factor, a wrong index, a
-swapped operand, an off-by-one) is planted in a copy of the oracle's C source, the copy is rebuilt
-and the pins are run against it: every mutant has to fail at least one pin.  CPU only; the mistakes
+swapped operand, an off-by-one) is planted in a copy of the oracle's source (the C routines, then the
+reference blocks that chain them), the copy is rebuilt and the pins are run against it: every mutant has to fail at least one pin.  CPU only; the mistakes
 live in temporary copies, never in the tree."""
 import os
 import shutil
@@ -81,15 +81,36 @@ MUTANTS = [
      "pos_out[j] = pos_in ? pos_in[lo] : lo;", "pos_out[j] = pos_in ? pos_in[hi - 1] : hi - 1;", 1),
 ]
 
+# the same for the reference blocks (oracle/blocks.py), which chain the oracle's routines
+BLOCK_MUTANTS = [
+    ("block with B and C taken from each other's columns",
+     "xbc[:, d_inner:d_inner + gn].reshape(T, G, n), \\\n        xbc[:, d_inner + gn:].reshape(T, G, n)",
+     "xbc[:, d_inner + gn:].reshape(T, G, n), \\\n        xbc[:, d_inner:d_inner + gn].reshape(T, G, n)", 1),
+    ("block without the residual connection",
+     "return r(g @ wt[\"W_out\"] + hidden), pre", "return r(g @ wt[\"W_out\"]), pre", 1),
+    ("block whose gated norm runs over all channels at once",
+     "wt[\"gnorm_w\"], G, eps)", "wt[\"gnorm_w\"], 1, eps)", 1),
+    ("block without the dt bias",
+     "softplus_dt(xbcdt[:, d_inner + 2 * gn:], wt[\"dt_bias\"])", "softplus_dt(xbcdt[:, d_inner + 2 * gn:], None)", 1),
+    ("reduced block that forgets to compact the gate",
+     "x, B, C, dt, z, hidden = (compact(a, idx, N, M)[0] for a in (x, B, C, dt, z, hidden))",
+     "x, B, C, dt, hidden = (compact(a, idx, N, M)[0] for a in (x, B, C, dt, hidden)); z = z[:idx.shape[0] + M]", 1),
+    ("attention block that compacts the wrong residual rows",
+     "q, k, v, hidden = (compact(a, idx, N, M)[0] for a in (q, k, v, hidden))",
+     "q, k, v = (compact(a, idx, N, M)[0] for a in (q, k, v)); hidden = hidden[:idx.shape[0] + M]", 1),
+    ("attention block with keys from the value projection",
+     "k = r(u @ wt[\"W_k\"]).reshape(T, Hkv, d)", "k = r(u @ wt[\"W_v\"]).reshape(T, Hkv, d)", 1),
+]
+
 
 def _run_mutant(args):
-    slot, (what, old, new, count), source, base = args
+    slot, (what, old, new, count), (fname, source), base = args
     d = os.path.join(base, "m%d" % slot)
     shutil.rmtree(d, ignore_errors=True)
     os.makedirs(os.path.join(d, "oracle"))
-    for name in ("__init__.py", "blocks.py"):
+    for name in ("__init__.py", "blocks.py", "strd_oracle.c"):
         shutil.copy(os.path.join(ROOT, "oracle", name), os.path.join(d, "oracle", name))
-    with open(os.path.join(d, "oracle", "strd_oracle.c"), "w") as fh:
+    with open(os.path.join(d, "oracle", fname), "w") as fh:
         fh.write(source.replace(old, new) if count == 0 else source.replace(old, new, count))
     shutil.copytree(os.path.join(ROOT, "tests"), os.path.join(d, "tests"), ignore=shutil.ignore_patterns("__pycache__"))
     os.symlink(os.path.join(ROOT, "paper_2603_00198_amd"), os.path.join(d, "paper_2603_00198_amd"))
@@ -99,15 +120,19 @@ def _run_mutant(args):
     return what, r.returncode, r.stdout[-600:]
 
 
+def _source(fname):
+    with open(os.path.join(ROOT, "oracle", fname)) as fh:
+        return fname, fh.read()
+
+
 def test_every_planted_mistake_fails_a_pin(tmp_path):
-    with open(os.path.join(ROOT, "oracle", "strd_oracle.c")) as fh:
-        source = fh.read()
-    for what, old, new, count in MUTANTS:
-        assert old in source, "the oracle no longer contains the text this mutant replaces: " + what
+    jobs = [(m, _source("strd_oracle.c")) for m in MUTANTS] + [(m, _source("blocks.py")) for m in BLOCK_MUTANTS]
+    for (what, old, new, count), (fname, source) in jobs:
+        assert old in source, "%s no longer contains the text this mutant replaces: %s" % (fname, what)
     workers = 4
     survivors, broken = [], []
-    for start in range(0, len(MUTANTS), workers):
-        batch = [(slot, m, source, str(tmp_path)) for slot, m in enumerate(MUTANTS[start:start + workers])]
+    for start in range(0, len(jobs), workers):
+        batch = [(slot, m, src, str(tmp_path)) for slot, (m, src) in enumerate(jobs[start:start + workers])]
         with ThreadPoolExecutor(workers) as pool:
             for what, rc, tail in pool.map(_run_mutant, batch):
                 if rc == 0:
@@ -120,7 +145,5 @@ def test_every_planted_mistake_fails_a_pin(tmp_path):
 
 def test_the_unchanged_oracle_passes_in_the_same_harness(tmp_path):
     """The harness itself: the same copy-build-run with nothing planted passes."""
-    with open(os.path.join(ROOT, "oracle", "strd_oracle.c")) as fh:
-        source = fh.read()
-    what, rc, tail = _run_mutant((0, ("nothing", "", "", 1), source, str(tmp_path)))
+    what, rc, tail = _run_mutant((0, ("nothing", "", "", 1), _source("strd_oracle.c"), str(tmp_path)))
     assert rc == 0, tail

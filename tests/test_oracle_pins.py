@@ -410,3 +410,86 @@ def test_decode_steps_continue_the_prefill():
     vv = torch.from_numpy(v).repeat_interleave(Hq // Hkv, 1).permute(1, 0, 2)
     ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q1)[:, None], kk, vv)[:, 0].numpy()
     np.testing.assert_allclose(o, ref, rtol=1e-11, atol=1e-13)
+
+
+# ------------------------------------------------------------------ reference blocks -------
+def _library_mamba_block(hidden, N, M, wt, H, P, G, n, idx, eps):
+    """The published Mamba-2 block put together from torch's own routines (fp64), the scan as the
+    plain token-by-token recurrence; idx (kept vision tokens) is applied after the convolution."""
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    h = t(hidden)
+    d_inner, gn = H * P, G * n
+    u = F.rms_norm(h, (h.shape[1],), t(wt["norm_w"]), eps)
+    z = u @ t(wt["W_z"])
+    xbcdt = u @ t(wt["W_xbcdt"])
+    C_all = d_inner + 2 * gn
+    W = wt["conv_w"].shape[1]
+    conv = F.conv1d(xbcdt[:, :C_all].T[None], t(wt["conv_w"])[:, None, :], t(wt["conv_b"]), padding=W - 1,
+                    groups=C_all)[0, :, : h.shape[0]].T
+    xbc = F.silu(conv)
+    dt = F.softplus(xbcdt[:, C_all:] + t(wt["dt_bias"]))
+    if idx is not None:
+        keep = torch.cat([torch.from_numpy(np.asarray(idx)).long(), torch.arange(N, N + M)])
+        xbc, dt, z, h = xbc[keep], dt[keep], z[keep], h[keep]
+    T = xbc.shape[0]
+    x = xbc[:, :d_inner].reshape(T, H, P)
+    B = xbc[:, d_inner:d_inner + gn].reshape(T, G, n).repeat_interleave(H // G, 1)
+    C = xbc[:, d_inner + gn:].reshape(T, G, n).repeat_interleave(H // G, 1)
+    A, D = t(wt["A"]), t(wt["D"])
+    S = torch.zeros(H, P, n, dtype=torch.float64)
+    y = torch.empty(T, H, P, dtype=torch.float64)
+    for i in range(T):
+        S = torch.exp(dt[i] * A)[:, None, None] * S + dt[i][:, None, None] * x[i][:, :, None] * B[i][:, None, :]
+        y[i] = torch.einsum("hpn,hn->hp", S, C[i]) + D[:, None] * x[i]
+    v = (y.reshape(T, d_inner) * F.silu(z)).reshape(T, G, d_inner // G)
+    g = (F.rms_norm(v, (d_inner // G,), None, eps).reshape(T, d_inner)) * t(wt["gnorm_w"])
+    return (g @ t(wt["W_out"]) + h).numpy()
+
+
+def _library_attn_block(hidden, N, M, wt, Hq, Hkv, d, idx, eps):
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    h = t(hidden)
+    u = F.rms_norm(h, (h.shape[1],), t(wt["norm_w"]), eps)
+    q, k, v = u @ t(wt["W_q"]), u @ t(wt["W_k"]), u @ t(wt["W_v"])
+    if idx is not None:
+        keep = torch.cat([torch.from_numpy(np.asarray(idx)).long(), torch.arange(N, N + M)])
+        q, k, v, h = q[keep], k[keep], v[keep], h[keep]
+    T = q.shape[0]
+    q = q.reshape(T, Hq, d).permute(1, 0, 2)
+    k = k.reshape(T, Hkv, d).repeat_interleave(Hq // Hkv, 1).permute(1, 0, 2)
+    v = v.reshape(T, Hkv, d).repeat_interleave(Hq // Hkv, 1).permute(1, 0, 2)
+    o = F.scaled_dot_product_attention(q, k, v, is_causal=True).permute(1, 0, 2).reshape(T, Hq * d)
+    return (o @ t(wt["W_o"]) + h).numpy()
+
+
+@pytest.mark.parametrize("reduced", [False, True])
+def test_reference_blocks_match_a_composition_of_library_routines(reduced):
+    """The reference blocks (which chain the oracle's routines) against the same blocks assembled from
+    torch's rms_norm, grouped conv1d, silu, softplus and scaled_dot_product_attention.  The reference
+    rounds every stored tensor to the device's type; with "f32" that rounding is far below the
+    tolerance, so this pins the order of the stages, the x | B | C | dt split, the gate, the grouped
+    norm, the residual and what is compacted."""
+    import oracle.blocks as ref
+    rng = np.random.default_rng(11)
+    N, M, dm, H, P, G, n, W = 40, 6, 24, 4, 8, 2, 6, 4
+    d_inner, gn = H * P, G * n
+    wt = {"norm_w": 1 + 0.1 * rng.standard_normal(dm), "W_z": rng.standard_normal((dm, d_inner)) / dm ** 0.5,
+          "W_xbcdt": rng.standard_normal((dm, d_inner + 2 * gn + H)) / dm ** 0.5,
+          "conv_w": rng.standard_normal((d_inner + 2 * gn, W)) / 2, "conv_b": 0.1 * rng.standard_normal(d_inner + 2 * gn),
+          "dt_bias": rng.standard_normal(H) - 1, "A": -np.exp(rng.standard_normal(H)), "D": rng.standard_normal(H),
+          "gnorm_w": 1 + 0.1 * rng.standard_normal(d_inner), "W_out": rng.standard_normal((d_inner, dm)) / d_inner ** 0.5}
+    hidden = rng.standard_normal((N + M, dm))
+    idx = np.sort(rng.choice(N, 13, replace=False)).astype(np.int32) if reduced else None
+    got, _ = ref.mamba_block(hidden, N, M, wt, H, P, G, n, "f32", idx=idx, eps=1e-5)
+    want = _library_mamba_block(hidden, N, M, wt, H, P, G, n, idx, 1e-5)
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=2e-5)
+
+    Hq, Hkv, d = 4, 2, 8
+    wa = {"norm_w": 1 + 0.1 * rng.standard_normal(dm), "W_q": rng.standard_normal((dm, Hq * d)) / dm ** 0.5,
+          "W_k": rng.standard_normal((dm, Hkv * d)) / dm ** 0.5, "W_v": rng.standard_normal((dm, Hkv * d)) / dm ** 0.5,
+          "W_o": rng.standard_normal((Hq * d, dm)) / (Hq * d) ** 0.5}
+    got, _ = ref.attn_block(hidden, N, M, wa, Hq, Hkv, d, "f32", idx=idx, eps=1e-5)
+    want = _library_attn_block(hidden, N, M, wa, Hq, Hkv, d, idx, 1e-5)
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=2e-5)
