@@ -389,6 +389,10 @@ def test_rmsnorm_parity(T, d, dtype):
     got = strd.rmsnorm(x, w, 1e-5)
     if T:
         assert_close(synth.np64(got), oracle.rmsnorm(synth.np64(x), synth.np64(w), 1e-5), TOL[dtype], "rmsnorm")
+        # rows whose mean square is at or below eps: eps decides the result, so its place in the formula shows
+        small = (x.float() * 1e-3).to(dtype)
+        assert_close(synth.np64(strd.rmsnorm(small, w, 1e-5)), oracle.rmsnorm(synth.np64(small), synth.np64(w), 1e-5),
+                     TOL[dtype], "rmsnorm, small rows")
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -403,6 +407,10 @@ def test_gated_rmsnorm_parity(T, D, groups, dtype):
     got = strd.gated_rmsnorm(y, z, w, groups, 1e-5)
     want = oracle.gated_rmsnorm(synth.np64(y), synth.np64(z.contiguous()), synth.np64(w), groups, 1e-5)
     assert_close(synth.np64(got), want, TOL[dtype], "gated_rmsnorm")
+    y_small = (y.float() * 2e-3).to(dtype)                  # groups whose mean square is near eps
+    got = strd.gated_rmsnorm(y_small, z, w, groups, 1e-5)
+    want = oracle.gated_rmsnorm(synth.np64(y_small), synth.np64(z.contiguous()), synth.np64(w), groups, 1e-5)
+    assert_close(synth.np64(got), want, TOL[dtype], "gated_rmsnorm, small rows")
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
