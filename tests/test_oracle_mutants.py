@@ -79,6 +79,34 @@ MUTANTS = [
      "hi = (int)(((long long)(j + 1) * N) / K);", "hi = (int)(((long long)(j + 1) * N + K - 1) / K);", 1),
     ("pooled token placed at the end of its window",
      "pos_out[j] = pos_in ? pos_in[lo] : lo;", "pos_out[j] = pos_in ? pos_in[hi - 1] : hi - 1;", 1),
+    ("equal scores resolved towards the higher index",
+     "return (x->i > y->i) - (x->i < y->i);", "return (x->i < y->i) - (x->i > y->i);", 1),
+    ("recurrence without the skip term",
+     "yt[p] = out + (D ? D[h] * xt[p] : 0.0);", "yt[p] = out;", 1),
+    ("recurrence that ignores the incoming state",
+     "if (S_in) memcpy(S, S_in + (size_t)h * P * n, sizeof(double) * (size_t)P * n);\n        for (int t = 0; t < T; ++t) {\n"
+     "            const double dtt",
+     "for (int t = 0; t < T; ++t) {\n            const double dtt", 1),
+    ("recurrence that hands the state back in another head's slot",
+     "if (S_out) memcpy(S_out + (size_t)h * P * n, S, sizeof(double) * (size_t)P * n);\n        free(S);\n    }",
+     "if (S_out) memcpy(S_out + (size_t)(H - 1 - h) * P * n, S, sizeof(double) * (size_t)P * n);\n        free(S);\n    }", 1),
+    ("decayed score with growth instead of decay",
+     "decay *= exp(dt[(size_t)u * H + h] * A[h]);\n                const double *b = Ball",
+     "decay *= exp(-dt[(size_t)u * H + h] * A[h]);\n                const double *b = Ball", 1),
+    ("convolution without the bias",
+     "double acc = b ? b[c] : 0.0;", "double acc = 0.0;", 1),
+    ("pooling that averages the text rows in",
+     "dst[(size_t)(K + m) * D + c] = src[(size_t)(N + m) * D + c];", "dst[(size_t)(K + m) * D + c] = src[(size_t)(N - 1) * D + c];", 1),
+    ("softmax attention normalised by the largest weight",
+     "const double w = z[j] / denom;", "const double w = z[j];", 1),
+]
+
+# and for the thin Python layer over the C routines (oracle/__init__.py)
+WRAPPER_MUTANTS = [
+    ("default scale 1/d instead of 1/sqrt(d)",
+     "scale = 1.0 / np.sqrt(d)", "scale = 1.0 / d", 0),
+    ("decode step that queries with the oldest row",
+     "q[T - 1] = q1\n    return attn(q, k, v, scale=scale, rows=[T - 1])[0]", "q[0] = q1\n    return attn(q, k, v, scale=scale, rows=[0])[0]", 1),
 ]
 
 # the same for the reference blocks (oracle/blocks.py), which chain the oracle's routines
@@ -126,7 +154,8 @@ def _source(fname):
 
 
 def test_every_planted_mistake_fails_a_pin(tmp_path):
-    jobs = [(m, _source("strd_oracle.c")) for m in MUTANTS] + [(m, _source("blocks.py")) for m in BLOCK_MUTANTS]
+    jobs = [(m, _source("strd_oracle.c")) for m in MUTANTS] + [(m, _source("blocks.py")) for m in BLOCK_MUTANTS] + \
+        [(m, _source("__init__.py")) for m in WRAPPER_MUTANTS]
     for (what, old, new, count), (fname, source) in jobs:
         assert old in source, "%s no longer contains the text this mutant replaces: %s" % (fname, what)
     workers = 4
