@@ -159,3 +159,48 @@ def test_kernels_with_split_lds_reads_do_not_spill():
         scratch = [int(v) for v in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
         assert scratch, "no resource report for " + name
         assert all(v == 0 for v in scratch), "%s: a kernel uses scratch memory: %s" % (name, scratch)
+
+
+def test_entry_points_refuse_inconsistent_arguments_on_the_host():
+    """Every compute entry point validates its arguments on the host and returns STRD_EINVAL before
+    anything is launched: one field at a time is made inconsistent in an otherwise consistent call.
+    The pointers are placeholders that are never dereferenced on the host, which is why this runs only
+    where no GPU is visible (a call that slipped through validation then ends in a HIP error code,
+    not in a launch)."""
+    if torch.cuda.is_available():
+        pytest.skip("placeholder pointers: only run without a GPU")
+    L = binding.lib()
+    P, BIG, F32, BF16 = 0x1000, 1 << 40, 0, 1
+    EINVAL, EHIP = -1, -4
+    # name -> (consistent argument list, {position: inconsistent value, ...})
+    cases = {
+        "strd_score_attn": ([P, P, P, 8, 100, 4, 2, 64, 0.125, BF16, P, BIG, None],
+                            {0: None, 1: None, 2: None, 3: 0, 4: 0, 5: 3, 6: 0, 7: 0, 8: 0.0, 9: 7}),
+        "strd_score_mamba": ([P, P, P, P, 8, 100, 8, 2, 64, BF16, P, BIG, None],
+                             {0: None, 1: None, 2: None, 3: None, 4: 0, 5: 0, 6: 7, 7: 0, 8: 0, 9: 7}),
+        "strd_score_mamba_full": ([P, P, P, P, P, 8, 100, 8, 2, 64, BF16, P, BIG, None],
+                                  {0: None, 2: None, 3: None, 4: None, 5: 0, 6: 0, 7: 7, 8: 0, 9: 0, 10: 7}),
+        "strd_select_topk": ([P, 100, 10, P, None, 0, None], {0: None, 1: 0, 2: 0, 3: None}),
+        "strd_compact": ([P, P, P, 100, 4, 10, 64, None, None, None], {1: None, 2: None, 3: -1, 4: -1, 5: 101, 6: 6}),
+        "strd_ssd_prefill": ([P, P, P, P, P, None, None, P, None, 64, 8, 64, 2, 128, 64, BF16, P, BIG, None],
+                             {0: None, 1: None, 2: None, 3: None, 4: None, 7: None, 9: -1, 10: 7, 11: 0, 12: 0, 13: 0,
+                              14: 0, 15: 7}),
+        "strd_ssd_prefill_gather": ([P, P, P, P, P, None, None, P, P, None, 100, 4, 10, 8, 64, 2, 128, 64, BF16, None, 0, None],
+                                    {0: None, 2: None, 7: None, 8: None, 10: -1, 11: -1, 12: 101, 13: 7, 14: 0, 16: 0,
+                                     17: 0, 18: 7}),
+        "strd_attn_prefill": ([P, P, P, P, 64, 4, 2, 128, 0.09, BF16, P, BIG, None],
+                              {0: None, 1: None, 2: None, 3: None, 4: -1, 5: 3, 6: 0, 7: 0, 8: -1.0, 9: 7}),
+        "strd_rmsnorm": ([P, P, P, 8, 64, 1e-5, BF16, None], {0: None, 1: None, 2: None, 3: -1, 4: 0, 5: -1.0, 6: 7}),
+        "strd_avgpool": ([P, P, 100, 4, 10, 64, BF16, None, None, None], {1: None, 2: -1, 3: -1, 4: 101, 6: 7}),
+        "strd_attn_decode_step": ([P, P, P, P, 100, 4, 2, 64, 0.125, BF16, P, BIG, None], {0: None, 3: None, 4: 0, 5: 3, 9: 7}),
+    }
+    for name, (good, bad) in cases.items():
+        fn = getattr(L, name)
+        assert len(good) == len(fn.argtypes), name
+        # the consistent call gets past validation and, with no GPU, fails loudly: a HIP error code, no fallback
+        assert fn(*good) == EHIP, name
+        for pos, value in bad.items():
+            args = list(good)
+            args[pos] = value
+            rc = fn(*args)
+            assert rc == EINVAL, "%s accepted argument %d = %r (returned %d)" % (name, pos, value, rc)
