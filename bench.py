@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the mixer kernel at the default budget (0.25), from the rocprofv3
 # FETCH_SIZE + WRITE_SIZE counter runs whose summaries are under profiles/ (scaled there by a
 # plain copy of known size); counters cannot be read from inside this process.
-MEASURED_TRAFFIC_BYTES = {("c2", 0.25): 47.2e6 + 35.7e6, ("c3", 0.25): 539.1e6 + 69.2e6}
+MEASURED_TRAFFIC_BYTES = {("c2", 0.25): 47.2e6 + 35.7e6, ("c3", 0.25): 530.9e6 + 69.2e6}
 PAPER_CONTEXT = "paper: 3.8-4.2x LLM-stage prefill speed-up at ~25% budget, whole 12B hybrid, 1x A100, 36864 vision tokens"
 
 

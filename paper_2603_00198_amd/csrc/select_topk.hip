@@ -17,7 +17,8 @@
 // a batch in flight together.  Same-address LDS atomics serialise, so in the first pass every bin
 // has 16 copies, one per lane modulo 16, in adjacent LDS words (different banks), summed when a
 // bin is picked; later passes only count the keys of one bin of the pass before and use 2 copies
-// when those are few.  The ordered pass scans 8 tiles per barrier.  No global atomics, no
+// when those are few; once a bin holds no more than one wave's worth of keys the remaining digits
+// are skipped and one wave ranks those keys directly.  The ordered pass scans 8 tiles per barrier.  No global atomics, no
 // scratch memory, bit-exact and deterministic.
 #include "common.h"
 
@@ -32,6 +33,7 @@ constexpr int kBatch = 8;            // tiles loaded together when streaming / s
 constexpr int kCopies = 16;          // copies of every histogram bin
 constexpr int kFewCopies = 2;        // copies in passes 1 and 2 when at most kFewKeys keys are still in play
 constexpr int kFewKeys = 4096;
+constexpr int kRankKeys = 64;        // at most this many keys still in play: one wave ranks them directly
 
 // Monotone map float -> uint32 (larger float = larger key); -0.0 is folded onto +0.0.
 // Every real float maps above 0, the key given to the slots past the end of the array.
@@ -154,7 +156,10 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
     extern __shared__ __attribute__((aligned(16))) uint32_t hist[];  // [kBins][kCopies]
     __shared__ ScanScratch scan;
     __shared__ uint32_t found[3][3];         // (bin, rank inside the bin, keys in the bin) of each pass
+    __shared__ uint32_t cand[kRankKeys];     // direct ranking: the keys (less kmin) still in play
+    __shared__ uint32_t ncand, ranked_key[2];
     const int tid = threadIdx.x;
+    if (tid == 0) ncand = 0u;                // published by the first barrier below
     const int ntiles = (N + kTile - 1) / kTile;
     auto zero_hist = [&](int copies) {
         for (int b = tid * 4; b < kBins * copies; b += kThreads * 4)
@@ -230,8 +235,36 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
     // histogram with 2 copies per bin is 8 times cheaper to clear and to scan.
     uint32_t k = (uint32_t)K, prefix = 0;          // prefix: the digits of rel fixed so far, in place
     int shift_prev = 32;
-    bool few = false;
+    bool few = false, ranked = false;
     for (int pass = 0; pass < npass; ++pass) {
+        if (pass > 0 && found[pass - 1][2] <= (uint32_t)kRankKeys) {  // uniform
+            // The bin of the pass before holds a wave's worth of keys at most: collect them and let every
+            // lane of wave 0 count the keys above and equal to its own -- two barriers instead of one or
+            // two more histogram passes of five each.
+            const uint32_t pfx = prefix >> shift_prev;
+            for_each_key([&](uint32_t key) {
+                const uint32_t rel = key - kmin;
+                if (key != 0 && (rel >> shift_prev) == pfx) cand[atomicAdd(&ncand, 1u)] = rel;
+            });
+            __syncthreads();
+            if (tid < kWave) {
+                const uint32_t c = (uint32_t)__builtin_amdgcn_readfirstlane((int)ncand);
+                const uint32_t mine = (uint32_t)tid < c ? cand[tid] : 0u;
+                uint32_t above = 0, equal = 0;
+                for (uint32_t j = 0; j < c; ++j) {
+                    const uint32_t other = (uint32_t)__builtin_amdgcn_readlane((int)mine, (int)j);
+                    above += other > mine ? 1u : 0u;
+                    equal += other == mine ? 1u : 0u;
+                }
+                if ((uint32_t)tid < c && above < k && k <= above + equal) {  // lanes with equal keys agree
+                    ranked_key[0] = mine;
+                    ranked_key[1] = k - above;
+                }
+            }
+            __syncthreads();
+            ranked = true;
+            break;
+        }
         const int shift = max(nbits - 11 * (pass + 1), 0);
         const uint32_t dmask = (1u << min(11, nbits - 11 * pass)) - 1u;
         uint32_t bin;
@@ -259,8 +292,9 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__re
         few = found[pass][2] <= kFewKeys;  // uniform
         shift_prev = shift;
     }
-    const uint32_t thresh = kmin + prefix;  // key of the K-th largest score (a real score: > 0)
-    const uint32_t keep_eq = k;            // how many keys == thresh survive (the first ones)
+    // key of the K-th largest score (a real score: > 0) and how many keys equal to it survive (the first ones)
+    const uint32_t thresh = kmin + (ranked ? ranked_key[0] : prefix);
+    const uint32_t keep_eq = ranked ? ranked_key[1] : k;
 
     // ---- ordered write-out: kBatch tiles per barrier ----------------------------------------
     uint32_t out_base = 0, eq_base = 0;  // survivors / duplicates of thresh seen in earlier tiles
