@@ -87,6 +87,28 @@ def test_select_topk_ties_go_to_lowest_index(levels):
         _topk_case(s, K)
 
 
+@pytest.mark.parametrize("in_bin", [1, 2, 63, 64, 65, 200])
+@pytest.mark.parametrize("N", [6000, 30000])
+def test_select_topk_small_last_bin(N, in_bin):
+    """Scores built from their bit patterns so that the first 11-bit digit of key - min(key) leaves
+    exactly `in_bin` candidates, some of them equal: at most 64 are ranked directly by one wave, more
+    go through another digit.  The K-th score is placed on every rank inside that bin."""
+    _say("topk small last bin N=%d in_bin=%d" % (N, in_bin))
+    r = np.random.default_rng(N + in_bin)
+    top = r.integers(0, 2048, N)                      # first digit of the 22-bit offset
+    top[top == 1000] = 999
+    off = (top.astype(np.int64) << 11) + r.integers(0, 2048, N)
+    off[0], off[1] = 0, (1 << 22) - 1                 # the offsets span exactly 22 bits
+    where = r.choice(np.arange(2, N), in_bin, replace=False)
+    low = r.integers(0, 2048, in_bin)
+    low[: in_bin // 3] = low[-1]                      # duplicates of one candidate
+    off[where] = (1000 << 11) + low
+    s = (np.uint32(0x3F800000) + off.astype(np.uint32)).view(np.float32)   # positive floats, order = offset order
+    above = int((off >= (1001 << 11)).sum())
+    for rank in sorted({1, 2, in_bin // 3, in_bin // 2, in_bin - 1, in_bin} - {0}):
+        _topk_case(s, above + rank)
+
+
 def test_select_topk_tiny_and_denormal_scores():
     _say("topk denormals")
     r = np.random.default_rng(3)
