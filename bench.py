@@ -6,8 +6,13 @@ score -> select_topk -> compact (every mixer input + the hidden states) -> mixer
 survivors, all enqueued on one HIP stream without host synchronisation.  Inputs are resident
 in HBM before the timed region.  One JSON line is printed.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4m|c4a|c5m|c5a]
-                  [--budget 0.25] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5m|c5a|c2|c3|c4m|c4a]
+                  [--budget 0.25] [--no-cpu-baseline] [--no-extras]
+
+The default line is the long-video configuration (131072 vision + 512 text tokens, 25 %): the
+Mamba-2 layer is `value`, the attention layer of the same configuration rides along under
+`attention_layer` with the same steps and warm-up, the two smaller single-layer workloads under
+`other_workloads`.
 """
 from __future__ import annotations
 
@@ -23,10 +28,37 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
-# HBM bytes per launch of the mixer kernel at the default budget (0.25), from the rocprofv3
-# FETCH_SIZE + WRITE_SIZE counter runs whose summaries are under profiles/ (scaled there by a
-# plain copy of known size); counters cannot be read from inside this process.
-MEASURED_TRAFFIC_BYTES = {("c2", 0.25): 47.2e6 + 35.7e6, ("c3", 0.25): 530.9e6 + 69.2e6}
+KERNEL_STEP = 64               # tokens per step of the scan kernel, whatever `chunk` the caller names
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+KERNEL_SOURCES = {"ssd_prefill": "ssd_mfma.hip", "attn_prefill": "attn_mfma.hip"}
+
+
+def kernel_source_hash(kernel):
+    import hashlib
+    path = os.path.join(ROOT, "paper_2603_00198_amd", "csrc", KERNEL_SOURCES[kernel])
+    return hashlib.sha1(open(path, "rb").read()).hexdigest()[:12]
+
+
+def measured_traffic(workload, budget, kernel):
+    """HBM bytes per launch of the mixer kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs
+    summarised in profiles/hbm_traffic.md (counters cannot be read from inside this process).  A row
+    counts only while the kernel's source is the one that was profiled; otherwise None."""
+    try:
+        rows = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None
+    for line in rows:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 6 and cells[0] == workload and cells[2] == kernel:
+            try:
+                if abs(float(cells[1]) - budget) > 1e-9 or cells[5] != kernel_source_hash(kernel):
+                    continue
+                return float(cells[3]) + float(cells[4])
+            except ValueError:
+                continue
+    return None
+
+
 PAPER_CONTEXT = "paper: 3.8-4.2x LLM-stage prefill speed-up at ~25% budget, whole 12B hybrid, 1x A100, 36864 vision tokens"
 
 
@@ -35,7 +67,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c5m",
+                    help="headline workload (default c5m: the Mamba-2 layer of the long-video configuration, the "
+                         "largest one; the line then also carries c5a, c2 and c3)")
     ap.add_argument("--budget", type=float, default=0.25)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile", action="store_true",
@@ -54,8 +88,8 @@ def parse_args():
                     help="instead of the layer benchmark: the 8-block hidden-to-hidden stack of workload c4 "
                          "(projections, glue, mixers, residual) with the progressive budgets against the same "
                          "stack without reduction")
-    ap.add_argument("--no-attention-extra", action="store_true",
-                    help="skip the attention-layer figures appended to the default (c2) line")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline workload: skip the other layers appended to the default line")
     return ap.parse_args()
 
 
@@ -205,10 +239,11 @@ class MambaLayer:
         s, eb = self.s, self.hidden.element_size()
         return T * (2 * s.H * s.P * eb + 2 * s.G * s.n * eb + 4 * s.H)
 
-    def mixer_flops(self, T):
+    def mixer_flops(self, T, Q=KERNEL_STEP):
+        """Causal flop count of the chunked scan with intra-chunk length Q: Q = 64 is what the kernel's
+        formulation needs (its step length), Q = the workload's chunk the count of that formulation."""
         s = self.s
-        Q = s.chunk
-        return T * (s.H * (Q * s.P + 4 * s.n * s.P) + s.G * Q * s.n)   # causal count
+        return T * (s.H * (Q * s.P + 4 * s.n * s.P) + s.G * Q * s.n)
 
     def compact_bytes(self):
         w, s, eb = self.w, self.s, self.hidden.element_size()
@@ -280,7 +315,7 @@ class AttnLayer:
         s, eb = self.s, self.hidden.element_size()
         return T * (2 * s.Hq * s.d + 2 * s.Hkv * s.d) * eb
 
-    def mixer_flops(self, T):
+    def mixer_flops(self, T, Q=None):
         s = self.s
         return 2.0 * T * T * s.d * s.Hq          # causal: half of 4 T^2 d Hq
 
@@ -296,30 +331,49 @@ class AttnLayer:
     mixer_name, mixer_bound = "attn_prefill", "mfma"
 
 
-def cpu_baseline_mamba(layer, synth):
-    """The fp64 oracle, as it stands, on the same reduced Mamba-2 layer (all of it)."""
+def cpu_baseline_mamba(layer, synth, budget_s=12.0):
+    """The fp64 oracle, as it stands, on the same reduced Mamba-2 layer.  Short sequences: all of it,
+    repeated for about `budget_s` seconds.  Long ones: score, selection and compaction in full, the scan
+    on two heads of every group (heads are independent; the time is scaled to all heads)."""
     import numpy as np
     import oracle
-    w, t = layer.w, layer.t
+    w, t, s = layer.w, layer.t, layer.s
     N, M, K = w.N, w.M, w.K
     f = synth.np64
+    small = N <= 20000
+    heads = list(range(s.H)) if small else sorted({g * (s.H // s.G) + j for g in range(s.G) for j in (0, 1)} & set(range(s.H)))
+    hsel = layer.torch.tensor(heads, device=t["x"].device)
     Bv, Ct, dtv = f(t["B"][:N]), f(t["C"][N:]), f(t["dt"][:N])
-    full = {k: f(t[k]) for k in ("x", "B", "C", "dt")}
+    full = {"x": f(t["x"][:, hsel]), "dt": f(t["dt"][:, hsel]), "B": f(t["B"]), "C": f(t["C"])}
+    A = f(t["A"][hsel])
+    grp = np.array([h // (s.H // s.G) for h in heads])
     hid = layer.hidden.cpu().view(layer.torch.int16).numpy() if w.dtype == "bf16" else layer.hidden.cpu().numpy()
-    A = f(t["A"])
     oracle.select_topk(np.zeros(4), 2)          # load the library outside the timed region
-    reps, t0 = 0, time.perf_counter()
-    while reps < 40 and time.perf_counter() - t0 < 10.0:   # about 10 s of CPU work
-        s = oracle.score_mamba(Bv, Ct, dtv)
-        idx = oracle.select_topk(s, K)
+    reps, t_rest, t_scan, t0 = 0, 0.0, 0.0, time.perf_counter()
+    while reps < 40 and time.perf_counter() - t0 < budget_s:
+        ta = time.perf_counter()
+        sc = oracle.score_mamba(Bv, Ct, dtv)
+        idx = oracle.select_topk(sc, K)
         red = {k: oracle.compact(v, idx, N, M)[0] for k, v in full.items()}
         oracle.compact(hid, idx, N, M)
-        oracle.ssd_seq(red["x"], red["dt"], A, red["B"], red["C"])
+        tb = time.perf_counter()
+        if small:
+            oracle.ssd_seq(red["x"], red["dt"], A, red["B"], red["C"])
+        else:   # one call per group: its two sampled heads against the group's B, C
+            for g in range(s.G):
+                sel = np.nonzero(grp == g)[0]
+                oracle.ssd_seq(red["x"][:, sel], red["dt"][:, sel], A[sel], red["B"][:, g:g + 1], red["C"][:, g:g + 1])
+        tc = time.perf_counter()
+        t_rest += tb - ta
+        t_scan += tc - tb
         reps += 1
-    dt = (time.perf_counter() - t0) / reps
-    return {"value": (N + M) / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "the whole reduced layer of this workload (all %d vision + %d text tokens, all heads), "
-                      "fp64, mean of %d passes of %.2f s" % (N, M, reps, dt)}
+    dt = (t_rest + t_scan * (s.H / len(heads))) / reps
+    what = ("the whole reduced layer of this workload (all %d vision + %d text tokens, all heads), fp64, mean of %d "
+            "passes of %.2f s" % (N, M, reps, dt)) if small else (
+            "score, selection and compaction of all %d + %d tokens in full (%.1f s), the scan over the %d survivors on "
+            "%d of %d heads (%.1f s), scaled to all heads: est. %.1f s for the whole layer; x was compacted for the "
+            "sampled heads only" % (N, M, t_rest / reps, K + M, len(heads), s.H, t_scan / reps, dt))
+    return {"value": (N + M) / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle", "sample": what}
 
 
 def cpu_single_thread_c1(torch, synth):
@@ -591,6 +645,12 @@ def block_stack(torch, strd, synth, dev, iters=5):
                 "reducing blocks, mixer, gated norm, out-projection + residual; no MLP blocks"}))
 
 
+def median(vals):
+    v = sorted(vals)
+    n = len(v)
+    return 0.0 if n == 0 else (v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2]))
+
+
 def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     from dataclasses import replace
     wname, kind = WORKLOADS[name]
@@ -607,7 +667,14 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / steps
     ms_mixer = layer.mixer_ev.mean_ms()
+    ms_mixer_median = median([a.elapsed_time(b) for a, b in layer.mixer_ev.pairs])
     layer.mixer_ev = None
+    # the same K steps again, each bracketed by its own event pair: the median step
+    step_ev = EventPairs(torch)
+    for _ in range(steps):
+        step_ev.wrap(layer.step)
+    torch.cuda.synchronize()
+    ms_step_median = median([a.elapsed_time(b) for a, b in step_ev.pairs])
     # the same step captured once into a HIP graph and replayed (no per-launch host work)
     ms_graph = None
     try:
@@ -635,6 +702,7 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
         "select_topk_us": 1e3 * time_events(torch, layer.select),
         "compact_us": 1e3 * time_events(torch, layer.compact),
         "mixer_reduced_us": 1e3 * ms_mixer,
+        "mixer_reduced_median_us": 1e3 * ms_mixer_median,
     }
     # The event pair around a single short call also sees the host's launch path (the queue is
     # empty when it starts); a graph of 20 back-to-back calls gives the device time per call.
@@ -653,28 +721,36 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
     sel_compact_dev = None
     if dev_calls:
         sel_compact_dev = (layer.compact_bytes() + 4 * w.N) / ((dev_calls["select_topk_us"] + dev_calls["compact_us"]) * 1e-6) / 1e9
+    traffic = measured_traffic(name, budget, layer.mixer_name)
     if layer.mixer_bound == "hbm":
         ach = layer.mixer_bytes(Tr) / (ms_mixer * 1e-3) / 1e9
+        tf_step = layer.mixer_flops(Tr, KERNEL_STEP) / (ms_mixer * 1e-3) / 1e12
+        tf_chunk = layer.mixer_flops(Tr, layer.s.chunk) / (ms_mixer * 1e-3) / 1e12
         roof = {"bound": "hbm", "kernel": layer.mixer_name, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((name, budget)),
-                "mfma_tflops": layer.mixer_flops(Tr) / (ms_mixer * 1e-3) / 1e12,
-                "mfma_frac": layer.mixer_flops(Tr) / (ms_mixer * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+                "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
+                "mfma_tflops": tf_step, "mfma_frac": tf_step / MFMA_BF16_PEAK_TFLOPS,
+                "mfma_tflops_at_chunk_%d" % layer.s.chunk: tf_chunk,
+                "mfma_frac_at_chunk_%d" % layer.s.chunk: tf_chunk / MFMA_BF16_PEAK_TFLOPS,
+                "mfma_note": "causal flop count of the chunked scan at the kernel's own step of %d tokens (what it has to "
+                             "execute); beside it the count of the same scan at the workload's chunk of %d, which this "
+                             "kernel never executes" % (KERNEL_STEP, layer.s.chunk)}
     else:
         ach = layer.mixer_flops(Tr) / (ms_mixer * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": layer.mixer_name, "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((name, budget))}
+                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic}
     # every call against both published peaks (algorithmic work / event-timed duration)
     def fr(nbytes, flops, us):
         return {"us": us, "GBps": nbytes / (us * 1e-6) / 1e9, "frac_hbm": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                 "TFLOPs": flops / (us * 1e-6) / 1e12, "frac_mfma": flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     sb, sf = layer.score_work()
     per_call = {
-        "score": fr(sb, sf, calls["score_us"]),
-        "select_topk": fr(4 * w.N + 4 * w.K, 0.0, calls["select_topk_us"]),
-        "compact": fr(layer.compact_bytes(), 0.0, calls["compact_us"]),
+        "score": fr(sb, sf, dev_calls.get("score_us", calls["score_us"])),
+        "select_topk": fr(4 * w.N + 4 * w.K, 0.0, dev_calls.get("select_topk_us", calls["select_topk_us"])),
+        "compact": fr(layer.compact_bytes(), 0.0, dev_calls.get("compact_us", calls["compact_us"])),
         "mixer_reduced": fr(layer.mixer_bytes(Tr), layer.mixer_flops(Tr), calls["mixer_reduced_us"]),
         "mixer_full": fr(layer.mixer_bytes(w.T), layer.mixer_flops(w.T), calls["mixer_full_us"]),
+        "note": "algorithmic bytes and flops of each call over its duration (score, select_topk, compact: device time "
+                "per call from a graph of 20 calls; mixers: HIP events on the stream)",
     }
     fused = None
     if kind == "mamba":   # variant: the scan gathers its inputs itself (same y, bit for bit; see tests)
@@ -693,9 +769,14 @@ def measure(torch, strd, synth, name, budget, steps, warmup, dev):
                  "note": "ssd_prefill_gather reads x, dt, B, C through idx; only the residual stream is compacted"}
         layer.fused = False
         fused["score_mamba_full_us"] = 1e3 * time_events(torch, layer.score_full)
+    s = w.mamba if kind == "mamba" else w.attn
     res = {
-        "layer": kind, "workload": name, "N": w.N, "M": w.M, "K": w.K, "budget": budget,
-        "ms_per_step": ms_step, "graph_replay_ms_per_step": ms_graph, "tokens_per_s": w.T / (ms_step * 1e-3),
+        "layer": kind, "workload": name,
+        "config": "%s: single %s layer, %d vision + %d text tokens, budget %.0f%% (K=%d), batch 1, %s"
+                  % (name, "Mamba-2" if kind == "mamba" else "attention", w.N, w.M, 100 * budget, w.K, repr(s)),
+        "N": w.N, "M": w.M, "K": w.K, "budget": budget, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_step, "ms_per_step_median": ms_step_median, "graph_replay_ms_per_step": ms_graph,
+        "tokens_per_s": w.T / (ms_step * 1e-3),
         "retained_tokens_per_s": Tr / (ms_step * 1e-3), "speedup_vs_full": ms_full / ms_step,
         "calls": calls, "calls_device_us": dev_calls, "select_plus_compact_GBps": sel_compact_gbs,
         "select_plus_compact_device_GBps": sel_compact_dev,
@@ -740,16 +821,16 @@ def main():
         return
     res, layer = measure(torch, strd, synth, name, args.budget, args.steps, args.warmup, dev)
     w = layer.w
-    s = w.mamba if layer.kind == "mamba" else w.attn
     line = {
         "metric": "retained-token prefill tokens/s per layer at 25% budget; speedup vs full prefill",
         "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": res["ms_per_step"], "ms_per_step_median": res["ms_per_step_median"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s: single %s layer, %d vision + %d text tokens, budget %.0f%% (K=%d), batch 1, %s"
-                               % (name, "Mamba-2" if layer.kind == "mamba" else "attention", w.N, w.M,
-                                  100 * args.budget, w.K, repr(s)),
+        "config": {"workload": res["config"],
                    "tokens_counted": "input tokens N+M per reduced-layer step (score+select+compact+mixer)",
+                   "timing": "value = (N+M) / wall-clock mean of the K timed steps; ms_per_step_median = median of the "
+                             "same K steps timed one by one with HIP events",
                    "parallelism": "1 GPU"},
         "speedup_vs_full": res["speedup_vs_full"], "retained_tokens_per_s": res["retained_tokens_per_s"],
         "graph_replay_ms_per_step": res["graph_replay_ms_per_step"],
@@ -765,23 +846,32 @@ def main():
         line["next_rows"] = {"score_mamba_full_us": line["gather_fused_variant"].pop("score_mamba_full_us"),
                              "note": "Full Mamba Dynamic score (decayed |w_tj|) on the same inputs; an ablation "
                                      "row, not part of the timed step"}
-    if name == "c2":
-        line.setdefault("next_rows", {})["variants"] = variants(torch, strd, synth, dev)
-    if name == "c2" and not args.no_attention_extra:
-        del layer
-        torch.cuda.empty_cache()
-        extra, alayer = measure(torch, strd, synth, "c3", args.budget, max(3, args.steps // 10),
-                                max(1, args.warmup // 5), dev)
-        line["attention_layer"] = extra
-        del alayer
-        torch.cuda.empty_cache()
-        layer = None
     if not args.no_cpu_baseline:
-        if layer is None:
-            from dataclasses import replace
-            layer = MambaLayer(torch, strd, synth, replace(synth.WORKLOADS["c2"], budget=args.budget), dev)
         line["cpu_baseline"] = cpu_baseline_mamba(layer, synth) if layer.kind == "mamba" \
             else cpu_baseline_attn(layer, synth)
+    del layer
+    torch.cuda.empty_cache()
+    extras = not args.no_extras and name == "c5m"
+    if extras:
+        # the attention layer of the same long-video configuration, with the same steps and warm-up,
+        # then the two smaller single-layer workloads
+        ares, alayer = measure(torch, strd, synth, "c5a", args.budget, args.steps, args.warmup, dev)
+        if not args.no_cpu_baseline:
+            ares["cpu_baseline"] = cpu_baseline_attn(alayer, synth)
+        line["attention_layer"] = ares
+        del alayer
+        torch.cuda.empty_cache()
+        line["other_workloads"] = {}
+        for other in ("c2", "c3"):
+            ores, olayer = measure(torch, strd, synth, other, args.budget, args.steps, args.warmup, dev)
+            ores.pop("per_call_roofline", None)
+            if "gather_fused_variant" in ores:
+                ores["gather_fused_variant"].pop("score_mamba_full_us", None)
+            line["other_workloads"][other] = ores
+            del olayer
+            torch.cuda.empty_cache()
+        line.setdefault("next_rows", {})["variants"] = variants(torch, strd, synth, dev)
+    if not args.no_cpu_baseline:
         line["cpu_baseline"]["single_thread_c1"] = cpu_single_thread_c1(torch, synth)
     print(json.dumps(line))
 

@@ -10,7 +10,10 @@
  *   - A sequence is N vision tokens followed by M text tokens (Sec. 3.1).  All
  *     tensors are token-major, contiguous, batch 1.
  *   - Pointers marked [dev] are device pointers owned by the caller; [host] are
- *     host pointers.  The library allocates, frees and retains nothing.
+ *     host pointers.  The library allocates, frees and retains no device memory, with
+ *     one exception that is stated where it applies: strd_linear hands its product to
+ *     rocBLAS and keeps that library's handle (and whatever it allocates) for the life
+ *     of the process.
  *   - `io` is the element type of the tensors declared `const void*` / `void*`
  *     (STRD_F32 or STRD_BF16); accumulation, exponentials, decay, state and scores
  *     are always fp32.
@@ -18,12 +21,21 @@
  *     stream) and the call returns without synchronising.
  *   - `ws` is caller-provided scratch [dev] of at least the size the matching
  *     *_workspace() query returns (may be NULL when that size is 0); its contents
- *     are undefined before and after the call.  Buffers must be 16-byte aligned.
+ *     are undefined before and after the call.  Tensor buffers and `ws` must be 16-byte
+ *     aligned (the matrix-core kernels move 16-byte vectors straight from the caller's
+ *     pointers; a misaligned buffer on such a shape is STRD_EINVAL), fp32 vectors of
+ *     per-head or per-token scalars (A, D, dt) need only their natural alignment.
  *   - Return value: STRD_OK or a negative strd_status.  On STRD_EINVAL,
  *     STRD_EUNSUPPORTED and STRD_EWORKSPACE nothing was launched and no output was
  *     written.  STRD_EHIP reports a failed launch (hipGetLastError).
  *   - Shapes the kernels are not built for give STRD_EUNSUPPORTED; there is no CPU
  *     or library fallback.
+ *   - The two scores and the two mixers each have two device kernels: a matrix-core
+ *     (MFMA) kernel for bf16 tensors in the tile shapes listed at strd_*_kernel_path
+ *     below, and a plain SIMT kernel in fp32 arithmetic that serves fp32 tensors (whose
+ *     1e-4 tolerance bf16 matrix cores cannot meet) and every other bf16 shape.  The SIMT
+ *     kernels are one to two orders of magnitude slower; which one a call will run is
+ *     never implicit: strd_*_kernel_path answers it from the shape alone.
  */
 #ifndef STRD_H
 #define STRD_H
@@ -50,6 +62,18 @@ const char *strd_status_string(int status);
 
 /* ABI version: major * 1000 + minor. */
 int strd_version(void);
+
+/* Which device kernel a call with these sizes runs: STRD_PATH_MFMA (bf16 matrix cores),
+ * STRD_PATH_SIMT (fp32 arithmetic on the vector units: fp32 tensors, and bf16 shapes outside
+ * the matrix-core tiles) or STRD_PATH_NONE (the call would return STRD_EINVAL or
+ * STRD_EUNSUPPORTED).  Matrix-core shapes, all bf16: score_attn and attn_prefill d in {64, 128};
+ * score_mamba n in {64, 128}; ssd_prefill n in {64, 128} and P a multiple of 32 (and every
+ * tensor below 4 GiB).  Host-only, touches no device. */
+typedef enum { STRD_PATH_NONE = 0, STRD_PATH_MFMA = 1, STRD_PATH_SIMT = 2 } strd_kernel_path;
+int strd_score_attn_kernel_path(int M, int N, int Hq, int Hkv, int d, strd_dtype io);
+int strd_score_mamba_kernel_path(int M, int N, int H, int G, int n, strd_dtype io);
+int strd_ssd_prefill_kernel_path(int T, int H, int P, int G, int n, strd_dtype io);
+int strd_attn_prefill_kernel_path(int T, int Hq, int Hkv, int d, strd_dtype io);
 
 /* ---------------------------------------------------------------------------
  * score_attn -- attention-layer importance (Sec. 3.1 "Attention Layers"):
@@ -103,7 +127,10 @@ int strd_score_mamba_full(const void *B_vis, const void *C_txt, const float *dt_
 /* ---------------------------------------------------------------------------
  * select_topk -- keep the K highest-scoring vision tokens, in temporal order
  * (Sec. 3.1 "Token Selection").  Ties at the K-th score go to the lowest index.
- *   scores [dev] [N] fp32, finite and >= 0 (both score kinds are); -0.0 counts as 0
+ *   scores [dev] [N] fp32, finite and >= 0 (both score kinds are); -0.0 counts as 0.  Other
+ *          values do not break the call: negative scores and infinities order as numbers, NaNs
+ *          by their bit patterns (positive-signed above +inf, negative-signed below -inf), and
+ *          exactly K indices are written in every case
  *   idx    [dev] [K] int32 output, strictly ascending
  * Requires 1 <= K <= N.  Bit-exact and deterministic.
  *   ws     [dev] strd_select_topk_workspace(N, K) bytes (0 up to 32768 scores and above 2^20;
@@ -152,9 +179,11 @@ int strd_compact_batch(const strd_compact_item *items, int n_items, const int32_
  *   B,C [dev] [T, G, n]          D  [dev] [H] fp32 or NULL
  *   S_in  [dev] [H, P, n] fp32 or NULL (zero state)
  *   y     [dev] [T, H, P]        S_out [dev] [H, P, n] fp32 or NULL
- * `chunk` is the caller's chunk length (> 0); results do not depend on it beyond
- * rounding and the kernels tile time themselves.  S_out of one call fed as S_in of
- * the next continues the same scan.  Requires T >= 0, H % G == 0.
+ * `chunk` is the chunk length of the caller's formulation (> 0).  It is validated and
+ * otherwise unused: it does NOT select the tiling.  The kernels always cut time into
+ * 64-token steps and carry the state across them on chip, so results do not depend on
+ * `chunk` at all.  S_out of one call fed as S_in of the next continues the same scan.
+ * Requires T >= 0, H % G == 0.
  * ------------------------------------------------------------------------- */
 size_t strd_ssd_prefill_workspace(int T, int H, int P, int G, int n, int chunk, strd_dtype io);
 int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void *B, const void *C,
@@ -206,6 +235,9 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
  *                 dtype, bias [H] fp32 or NULL, dt [T,H] fp32.
  * linear:         out[T,Nd] = x[T,Kd] . w[Kd,Nd] (+ residual[T,Nd], which may be `out` itself): the
  *                 projections of a block, a plain dense product handed to rocBLAS (fp32 accumulation).
+ *                 The one entry point that retains something: the first call on a process creates a
+ *                 rocBLAS handle (which allocates device workspace of its own) and keeps it until the
+ *                 process ends; calls are serialised on it.  Not for callers that must not allocate.
  * ------------------------------------------------------------------------- */
 int strd_linear(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
                 strd_dtype io, void *stream);

@@ -21,6 +21,10 @@ _vp, _int, _i64, _f32, _sz = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_float, _c.c
 _SIGNATURES = {
     "strd_status_string": (_c.c_char_p, [_int]),
     "strd_version": (_int, []),
+    "strd_score_attn_kernel_path": (_int, [_int] * 6),
+    "strd_score_mamba_kernel_path": (_int, [_int] * 6),
+    "strd_ssd_prefill_kernel_path": (_int, [_int] * 6),
+    "strd_attn_prefill_kernel_path": (_int, [_int] * 5),
     "strd_score_attn_workspace": (_sz, [_int] * 5 + [_int]),
     "strd_score_attn": (_int, [_vp, _vp, _vp] + [_int] * 5 + [_f32, _int, _vp, _sz, _vp]),
     "strd_score_mamba_workspace": (_sz, [_int] * 5 + [_int]),
@@ -76,6 +80,16 @@ def lib():
 
 def exported_symbols() -> Sequence[str]:
     return tuple(_SIGNATURES)
+
+
+PATH_NONE, PATH_MFMA, PATH_SIMT = 0, 1, 2
+
+
+def kernel_path(op: str, *sizes: int, dtype: torch.dtype = torch.bfloat16) -> int:
+    """PATH_MFMA / PATH_SIMT / PATH_NONE for op in {"score_attn", "score_mamba", "ssd_prefill",
+    "attn_prefill"} with the size arguments of that entry point (host only)."""
+    io = STRD_BF16 if dtype == torch.bfloat16 else STRD_F32
+    return getattr(lib(), "strd_%s_kernel_path" % op)(*[int(v) for v in sizes], io)
 
 
 def _check(rc: int, what: str):

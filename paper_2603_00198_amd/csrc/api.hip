@@ -12,6 +12,9 @@ namespace {
 
 inline bool io_ok(strd_dtype io) { return io == STRD_F32 || io == STRD_BF16; }
 inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
+// The kernels read and write 16-byte vectors straight from the caller's pointers.
+template <typename... P>
+inline bool aligned16(const P *...p) { return ((... | (uintptr_t)p) & 15u) == 0; }
 
 }  // namespace
 
@@ -43,6 +46,7 @@ int strd_score_attn(const void *q_txt, const void *k_vis, float *scores, int M, 
         !(scale > 0.f))
         return STRD_EINVAL;
     if ((long long)M * Hq > (1 << 30)) return STRD_EUNSUPPORTED;
+    if (score_attn_mfma_supported(M, N, Hq, Hkv, d, io) && !aligned16(q_txt, k_vis, scores, ws)) return STRD_EINVAL;
     const size_t need = strd_score_attn_workspace(M, N, Hq, Hkv, d, io);
     if (!ws || ws_bytes < need) return STRD_EWORKSPACE;
     if (score_attn_mfma_supported(M, N, Hq, Hkv, d, io))
@@ -60,6 +64,7 @@ int strd_score_mamba(const void *B_vis, const void *C_txt, const float *dt_vis, 
                      int H, int G, int n, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
     if (!B_vis || !C_txt || !dt_vis || !scores || M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G || !io_ok(io))
         return STRD_EINVAL;
+    if (score_mamba_mfma_supported(M, N, H, G, n, io) && !aligned16(B_vis, C_txt, dt_vis, scores, ws)) return STRD_EINVAL;
     const size_t need = strd_score_mamba_workspace(M, N, H, G, n, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
     if (score_mamba_mfma_supported(M, N, H, G, n, io))
@@ -76,6 +81,7 @@ int strd_score_mamba_full(const void *B_vis, const void *C_txt, const float *dt_
                           int M, int N, int H, int G, int n, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
     if (!B_vis || !C_txt || !dt_all || !A || !scores || M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G || !io_ok(io))
         return STRD_EINVAL;
+    if (score_mamba_full_mfma_supported(M, N, H, G, n, io) && !aligned16(B_vis, C_txt, dt_all, scores, ws)) return STRD_EINVAL;
     if ((long long)N + M > 0x7FFFFFFFLL || H > 65535 * 256) return STRD_EUNSUPPORTED;
     const size_t need = strd_score_mamba_full_workspace(M, N, H, G, n, io);
     if (!ws || ws_bytes < need) return STRD_EWORKSPACE;
@@ -89,7 +95,7 @@ size_t strd_select_topk_workspace(int N, int K) {
 }
 
 int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes, void *stream) {
-    if (!scores || !idx || N < 1 || K < 1 || K > N) return STRD_EINVAL;
+    if (!scores || !idx || N < 1 || K < 1 || K > N || !aligned16(scores, ws)) return STRD_EINVAL;
     if (N > (1 << 30)) return STRD_EUNSUPPORTED;
     const size_t need = select_topk_ws(N);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
@@ -126,6 +132,7 @@ int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void 
                      strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
     if (T < 0 || H < 1 || P < 1 || G < 1 || n < 1 || H % G || chunk < 1 || !io_ok(io) || !A) return STRD_EINVAL;
     if (T > 0 && (!x || !dt || !B || !C || !y)) return STRD_EINVAL;
+    if (ssd_mfma_supported(T, T, H, P, G, n, io) && !aligned16(x, B, C, S_in, y, S_out, ws)) return STRD_EINVAL;
     const size_t need = strd_ssd_prefill_workspace(T, H, P, G, n, chunk, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
     if (ssd_mfma_supported(T, T, H, P, G, n, io))
@@ -143,6 +150,7 @@ int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, cons
         return STRD_EINVAL;
     const long long T = (long long)K + M;
     if (T > 0 && (!x || !dt || !B || !C || !y || (K > 0 && !idx))) return STRD_EINVAL;
+    if (!aligned16(x, B, C, S_in, y, S_out)) return STRD_EINVAL;
     if (T == 0 || (long long)N + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
     if (!ssd_mfma_supported((int)T, N + M, H, P, G, n, io)) return STRD_EUNSUPPORTED;
     if (K == 0) {  // only the text rows survive: a dense scan over the tail of the tensors
@@ -164,11 +172,36 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
                       float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
     if (T < 0 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io) || !(scale > 0.f)) return STRD_EINVAL;
     if (T > 0 && (!q || !k || !v || !o)) return STRD_EINVAL;
+    if (attn_mfma_supported(T, Hq, Hkv, d, io) && !aligned16(q, k, v, o, ws)) return STRD_EINVAL;
     const size_t need = strd_attn_prefill_workspace(T, Hq, Hkv, d, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
     if (attn_mfma_supported(T, Hq, Hkv, d, io)) return attn_mfma(q, k, v, o, T, Hq, Hkv, d, scale, as_stream(stream));
     if (!attn_general_supported(d)) return STRD_EUNSUPPORTED;
     return attn_general(q, k, v, o, T, Hq, Hkv, d, scale, io, as_stream(stream));
+}
+
+// ------------------------------------------------------------------ kernel paths -----------
+int strd_score_attn_kernel_path(int M, int N, int Hq, int Hkv, int d, strd_dtype io) {
+    if (M < 1 || N < 1 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io) || (long long)M * Hq > (1 << 30))
+        return STRD_PATH_NONE;
+    return score_attn_mfma_supported(M, N, Hq, Hkv, d, io) ? STRD_PATH_MFMA : STRD_PATH_SIMT;
+}
+
+int strd_score_mamba_kernel_path(int M, int N, int H, int G, int n, strd_dtype io) {
+    if (M < 1 || N < 1 || H < 1 || G < 1 || n < 1 || H % G || !io_ok(io)) return STRD_PATH_NONE;
+    return score_mamba_mfma_supported(M, N, H, G, n, io) ? STRD_PATH_MFMA : STRD_PATH_SIMT;
+}
+
+int strd_ssd_prefill_kernel_path(int T, int H, int P, int G, int n, strd_dtype io) {
+    if (T < 0 || H < 1 || P < 1 || G < 1 || n < 1 || H % G || !io_ok(io)) return STRD_PATH_NONE;
+    if (ssd_mfma_supported(T, T, H, P, G, n, io)) return STRD_PATH_MFMA;
+    return ssd_general_supported(n) ? STRD_PATH_SIMT : STRD_PATH_NONE;
+}
+
+int strd_attn_prefill_kernel_path(int T, int Hq, int Hkv, int d, strd_dtype io) {
+    if (T < 0 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io)) return STRD_PATH_NONE;
+    if (attn_mfma_supported(T, Hq, Hkv, d, io)) return STRD_PATH_MFMA;
+    return attn_general_supported(d) ? STRD_PATH_SIMT : STRD_PATH_NONE;
 }
 
 // ------------------------------------------------------------------ block glue -------------

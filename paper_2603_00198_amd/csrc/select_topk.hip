@@ -36,11 +36,14 @@ constexpr int kFewKeys = 4096;
 constexpr int kRankKeys = 64;        // at most this many keys still in play: one wave ranks them directly
 
 // Monotone map float -> uint32 (larger float = larger key); -0.0 is folded onto +0.0.
-// Every real float maps above 0, the key given to the slots past the end of the array.
+// Every score maps above 0, the key given to the slots past the end of the array: the one bit
+// pattern whose image would be 0 (a negative NaN, all bits set) shares key 1 with its neighbour,
+// so that exactly K indices are written whatever the input holds.  NaNs are ordered by their
+// bits: positive ones above +inf, negative ones below -inf.
 __device__ __forceinline__ uint32_t order_key(float f) {
     uint32_t b = __float_as_uint(f);
     if (b == 0x80000000u) b = 0u;
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return max((b & 0x80000000u) ? ~b : (b | 0x80000000u), 1u);
 }
 
 // Keys of the 4 scores this lane owns in tile `t` (0 past the end).

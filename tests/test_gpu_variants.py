@@ -80,7 +80,7 @@ def test_ssd_decode_step_parity(H, P, G, n, with_D, dtype):
     y_ref, S_ref = oracle.ssd_decode_step(synth.np64(x), synth.np64(dt), synth.np64(A), synth.np64(B), synth.np64(C),
                                           None if D is None else synth.np64(D), synth.np64(S))
     assert_close(synth.np64(S_dev), S_ref, 1e-5, "state")          # the state stays fp32 for either io dtype
-    assert_close(synth.np64(y), y_ref, TOL[dtype], "y")
+    assert_close(synth.np64(y), y_ref, TOL[dtype], "y", units=(0,))
 
 
 def test_decode_continues_a_reduced_mamba_prefill():
@@ -102,8 +102,8 @@ def test_decode_continues_a_reduced_mamba_prefill():
     keep = np.r_[idx.cpu().numpy(), np.arange(N, T0 + 2)]
     n64 = {k: synth.np64(v) for k, v in t.items()}
     y_ref, S_ref = oracle.ssd_seq(n64["x"][keep], n64["dt"][keep], n64["A"], n64["B"][keep], n64["C"][keep])
-    assert_close(synth.np64(torch.stack(ys)), y_ref[-2:], TOL[torch.bfloat16], "decoded y")
-    assert_close(synth.np64(S), S_ref, TOL[torch.bfloat16], "state after decode")
+    assert_close(synth.np64(torch.stack(ys)), y_ref[-2:], TOL[torch.bfloat16], "decoded y", units=(0, 1))
+    assert_close(synth.np64(S), S_ref, TOL[torch.bfloat16], "state after decode", units=(0,))
 
 
 # ------------------------------------------------------------------ attn_decode_step -------
@@ -126,7 +126,7 @@ def test_attn_decode_step_parity(T, Hq, Hkv, d, dtype):
         k[T // 3] = (3 * q.float().view(Hkv, Hq // Hkv, d).mean(1)).to(dtype)
     o = strd.attn_decode_step(q.to(DEV), k.to(DEV), v.to(DEV))
     ref = oracle.attn_decode_step(synth.np64(q), synth.np64(k), synth.np64(v))
-    assert_close(synth.np64(o), ref, TOL[dtype], "attn_decode_step")
+    assert_close(synth.np64(o), ref, TOL[dtype], "attn_decode_step", units=(0,))
 
 
 def test_decode_continues_a_reduced_attention_prefill():
@@ -148,7 +148,7 @@ def test_decode_continues_a_reduced_attention_prefill():
     keep = np.r_[idx.cpu().numpy(), np.arange(N, T0 + 1)]
     n64 = {k: synth.np64(v) for k, v in t.items()}
     ref = oracle.attn(n64["q"][keep], n64["k"][keep], n64["v"][keep], rows=[K + M])[0]
-    assert_close(synth.np64(o), ref, TOL[torch.bfloat16], "decode over the compacted cache")
+    assert_close(synth.np64(o), ref, TOL[torch.bfloat16], "decode over the compacted cache", units=(0,))
     # and it agrees with the prefill kernel run over the same K + M + 1 rows
     o_pre = strd.attn_prefill(dev["q"][torch.from_numpy(keep).to(DEV)].contiguous(), k_cache, v_cache)[-1]
     assert_close(synth.np64(o), synth.np64(o_pre), TOL[torch.bfloat16], "decode vs prefill last row")

@@ -159,6 +159,10 @@ def test_kernels_with_split_lds_reads_do_not_spill():
         scratch = [int(v) for v in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
         assert scratch, "no resource report for " + name
         assert all(v == 0 for v in scratch), "%s: a kernel uses scratch memory: %s" % (name, scratch)
+        # a register saved to another register file (no scratch needed) would carry stale data just the same
+        for what in ("VGPRs Spill", "SGPRs Spill", "AGPRs"):
+            vals = [int(v) for v in re.findall(what + r": (\d+)", r.stderr)]
+            assert len(vals) == len(scratch) and all(v == 0 for v in vals), "%s: %s = %s" % (name, what, vals)
 
 
 def test_entry_points_refuse_inconsistent_arguments_on_the_host():
@@ -204,3 +208,30 @@ def test_entry_points_refuse_inconsistent_arguments_on_the_host():
             args[pos] = value
             rc = fn(*args)
             assert rc == EINVAL, "%s accepted argument %d = %r (returned %d)" % (name, pos, value, rc)
+
+
+def test_matrix_core_shapes_refuse_misaligned_tensors_and_report_their_kernel_path():
+    """16-byte vectors are moved straight from the caller's pointers on the matrix-core shapes: a
+    misaligned tensor is refused on the host.  Which kernel a shape runs is answered without a GPU."""
+    L = binding.lib()
+    P, BIG, F32, BF16 = 0x1000, 1 << 40, 0, 1
+    EINVAL = -1
+    assert L.strd_score_attn(P + 8, P, P, 8, 100, 4, 2, 64, 0.125, BF16, P, BIG, None) == EINVAL
+    assert L.strd_score_mamba(P, P + 2, P, P, 8, 100, 8, 2, 64, BF16, P, BIG, None) == EINVAL
+    assert L.strd_ssd_prefill(P + 4, P, P, P, P, None, None, P, None, 64, 8, 64, 2, 128, 64, BF16, P, BIG, None) == EINVAL
+    assert L.strd_attn_prefill(P, P, P + 8, P, 64, 4, 2, 128, 0.09, BF16, P, BIG, None) == EINVAL
+    assert L.strd_select_topk(P + 4, 100, 10, P, None, 0, None) == EINVAL
+    kp = strd.kernel_path
+    bf, f32 = torch.bfloat16, torch.float32
+    assert kp("score_attn", 256, 32768, 32, 8, 128) == strd.PATH_MFMA
+    assert kp("score_attn", 256, 32768, 32, 8, 96) == strd.PATH_SIMT
+    assert kp("score_attn", 32, 1024, 4, 2, 64, dtype=f32) == strd.PATH_SIMT
+    assert kp("score_attn", 32, 1024, 4, 3, 64) == strd.PATH_NONE
+    assert kp("score_mamba", 128, 8192, 128, 8, 128) == strd.PATH_MFMA
+    assert kp("score_mamba", 128, 8192, 128, 8, 40) == strd.PATH_SIMT
+    assert kp("ssd_prefill", 2176, 128, 64, 8, 128) == strd.PATH_MFMA
+    assert kp("ssd_prefill", 2176, 128, 24, 8, 128) == strd.PATH_SIMT
+    assert kp("ssd_prefill", 1056, 8, 32, 1, 16, dtype=f32) == strd.PATH_SIMT
+    assert kp("attn_prefill", 8448, 32, 8, 128) == strd.PATH_MFMA
+    assert kp("attn_prefill", 100, 6, 3, 40) == strd.PATH_SIMT
+    assert kp("attn_prefill", 100, 6, 4, 64) == strd.PATH_NONE
