@@ -141,6 +141,21 @@ size_t strd_select_topk_workspace(int N, int K);
 int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, size_t ws_bytes,
                      void *stream);
 
+/* select_topk_noalloc -- strd_select_topk for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result,
+ * bit for bit; no workspace argument: the histograms and counters of the selection live in a
+ * 26 KB array inside the library's image, one copy per GPU, held until the process ends.  The
+ * call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine).
+ *   N at most strd_select_topk_noalloc_max_n() = 1 048 576 scores; more gives STRD_EUNSUPPORTED
+ *   and nothing is launched.  Other arguments and errors as strd_select_topk.
+ * All calls on one GPU share that GPU's array (every call clears what it needs on `stream`
+ * before using it, so nothing is carried from one call to the next): calls that overlap on one
+ * GPU -- different streams, or different threads -- race; serialise them.  The first call on each
+ * GPU looks the array's device address up (hipGetSymbolAddress); make that first call outside
+ * any stream capture. */
+int strd_select_topk_noalloc_max_n(void);
+int strd_select_topk_noalloc(const float *scores, int N, int K, int32_t *idx, void *stream);
+
 /* ---------------------------------------------------------------------------
  * compact -- drop the unselected vision tokens of one per-token tensor
  * (Sec. 3.1: retained tokens continue; text tokens are never dropped):

@@ -8,12 +8,12 @@ from .binding import (  # noqa: F401
     linear, rmsnorm, gated_rmsnorm, conv1d_silu, softplus_dt, avgpool, ssd_decode_step, attn_decode_step,
     schedule_step_decay, schedule_named, hybrid_layout, HYBRID_LAYERS, LAYER_MAMBA, LAYER_MLP, LAYER_ATTN, NAMED_SCHEDULES,
     score_attn, score_mamba, score_mamba_full, select_topk, ssd_prefill, ssd_prefill_gather,
-    kernel_path, PATH_NONE, PATH_MFMA, PATH_SIMT,
+    select_topk_noalloc, kernel_path, PATH_NONE, PATH_MFMA, PATH_SIMT,
 )
 
 __all__ = [
     "LIB_PATH", "StrdError", "lib", "score_attn", "score_mamba", "score_mamba_full", "select_topk", "compact", "compact_batch",
     "ssd_prefill", "ssd_prefill_gather", "attn_prefill", "schedule_budgets", "schedule_sigmoid", "schedule_step_decay",
     "linear", "rmsnorm", "gated_rmsnorm", "conv1d_silu", "softplus_dt", "avgpool", "ssd_decode_step", "attn_decode_step",
-    "kernel_path", "PATH_NONE", "PATH_MFMA", "PATH_SIMT", "schedule_named", "hybrid_layout", "HYBRID_LAYERS", "LAYER_MAMBA", "LAYER_MLP", "LAYER_ATTN", "NAMED_SCHEDULES",
+    "select_topk_noalloc", "kernel_path", "PATH_NONE", "PATH_MFMA", "PATH_SIMT", "schedule_named", "hybrid_layout", "HYBRID_LAYERS", "LAYER_MAMBA", "LAYER_MLP", "LAYER_ATTN", "NAMED_SCHEDULES",
 ]

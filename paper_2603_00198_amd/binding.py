@@ -33,6 +33,8 @@ _SIGNATURES = {
     "strd_score_mamba_full": (_int, [_vp] * 5 + [_int] * 5 + [_int, _vp, _sz, _vp]),
     "strd_select_topk_workspace": (_sz, [_int, _int]),
     "strd_select_topk": (_int, [_vp, _int, _int, _vp, _vp, _sz, _vp]),
+    "strd_select_topk_noalloc_max_n": (_int, []),
+    "strd_select_topk_noalloc": (_int, [_vp, _int, _int, _vp, _vp]),
     "strd_compact": (_int, [_vp, _vp, _vp, _int, _int, _int, _i64, _vp, _vp, _vp]),
     "strd_compact_batch": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp]),
     "strd_ssd_prefill_workspace": (_sz, [_int] * 6 + [_int]),
@@ -207,6 +209,15 @@ def select_topk(scores: torch.Tensor, K: int, out: Optional[torch.Tensor] = None
         ws, _ = _ws(need, scores)
     _check(lib().strd_select_topk(_ptr(scores), N, K, _ptr(out), _ptr(ws), 0 if ws is None else ws.numel(),
                                   _stream()), "select_topk")
+    return out
+
+
+def select_topk_noalloc(scores: torch.Tensor, K: int, out: torch.Tensor) -> torch.Tensor:
+    """select_topk through the entry point that allocates nothing: `out` [K] int32 is the caller's."""
+    _dev(scores, out)
+    if scores.dtype != torch.float32 or scores.dim() != 1 or out.dtype != torch.int32 or out.shape != (K,):
+        raise StrdError("scores must be a 1-D fp32 tensor, out a [K] int32 tensor")
+    _check(lib().strd_select_topk_noalloc(_ptr(scores), scores.shape[0], K, _ptr(out), _stream()), "select_topk_noalloc")
     return out
 
 

@@ -102,6 +102,14 @@ int strd_select_topk(const float *scores, int N, int K, int32_t *idx, void *ws, 
     return select_topk_launch(scores, N, K, idx, ws, as_stream(stream));
 }
 
+int strd_select_topk_noalloc_max_n(void) { return select_topk_static_max_n(); }
+
+int strd_select_topk_noalloc(const float *scores, int N, int K, int32_t *idx, void *stream) {
+    if (!scores || !idx || N < 1 || K < 1 || K > N || !aligned16(scores)) return STRD_EINVAL;
+    if (N > select_topk_static_max_n()) return STRD_EUNSUPPORTED;
+    return select_topk_static_launch(scores, N, K, idx, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ compact ----------------
 int strd_compact_batch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
                        const int32_t *pos_in, int32_t *pos_out, void *stream) {

@@ -186,6 +186,8 @@ int compact_launch(const strd_compact_item *items, int n_items, const int32_t *i
                    const int32_t *pos_in, int32_t *pos_out, hipStream_t s);
 size_t select_topk_ws(int N);
 int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws, hipStream_t s);
+int select_topk_static_max_n();
+int select_topk_static_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s);
 
 // general SIMT kernels: any shape, fp32 or bf16 I/O, fp32 arithmetic
 size_t score_attn_general_ws(int M, int Hq);

@@ -529,4 +529,41 @@ int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws
     return launch_status();
 }
 
+// ---- the same selection for callers that cannot allocate --------------------------------------
+// The histograms and per-tile counts of the many-workgroup form live in an array that is part of
+// the library's image instead of a caller-provided workspace: every GPU the library runs on
+// holds its own copy at its own address for the life of the process.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns
+// for the current device.
+constexpr int kStaticMaxN = kWideMax * kTile;   // 2^20 scores
+constexpr size_t kStaticBytes = (sizeof(WideWs) + 255) / 256 * 256;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticBytes];
+
+int select_topk_static_max_n() { return kStaticMaxN; }
+
+int select_topk_static_launch(const float *scores, int N, int K, int32_t *idx, hipStream_t s) {
+    constexpr int kMaxDev = 64;
+    static std::mutex mu;
+    static void *ptr[kMaxDev];   // device address of `scratch` on each GPU, looked up once
+    if (N > kStaticMaxN || select_topk_ws(N) > kStaticBytes) return STRD_EUNSUPPORTED;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return STRD_EHIP;
+    void *p = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!ptr[dev]) {
+            void *q = nullptr;
+            if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) {
+                (void)hipGetLastError();
+                return STRD_EHIP;
+            }
+            ptr[dev] = q;
+        }
+        p = ptr[dev];
+    }
+    // every launch of the chain starts from a kernel that clears the histograms; the counts and
+    // picked digits are written before they are read
+    return select_topk_launch(scores, N, K, idx, p, s);
+}
+
 }  // namespace strd

@@ -185,6 +185,7 @@ def test_entry_points_refuse_inconsistent_arguments_on_the_host():
         "strd_score_mamba_full": ([P, P, P, P, P, 8, 100, 8, 2, 64, BF16, P, BIG, None],
                                   {0: None, 2: None, 3: None, 4: None, 5: 0, 6: 0, 7: 7, 8: 0, 9: 0, 10: 7}),
         "strd_select_topk": ([P, 100, 10, P, None, 0, None], {0: None, 1: 0, 2: 0, 3: None}),
+        "strd_select_topk_noalloc": ([P, 100, 10, P, None], {0: None, 1: 0, 2: 0, 3: None}),
         "strd_compact": ([P, P, P, 100, 4, 10, 64, None, None, None], {1: None, 2: None, 3: -1, 4: -1, 5: 101, 6: 6}),
         "strd_ssd_prefill": ([P, P, P, P, P, None, None, P, None, 64, 8, 64, 2, 128, 64, BF16, P, BIG, None],
                              {0: None, 1: None, 2: None, 3: None, 4: None, 7: None, 9: -1, 10: 7, 11: 0, 12: 0, 13: 0,
@@ -221,6 +222,7 @@ def test_matrix_core_shapes_refuse_misaligned_tensors_and_report_their_kernel_pa
     assert L.strd_ssd_prefill(P + 4, P, P, P, P, None, None, P, None, 64, 8, 64, 2, 128, 64, BF16, P, BIG, None) == EINVAL
     assert L.strd_attn_prefill(P, P, P + 8, P, 64, 4, 2, 128, 0.09, BF16, P, BIG, None) == EINVAL
     assert L.strd_select_topk(P + 4, 100, 10, P, None, 0, None) == EINVAL
+    assert L.strd_select_topk_noalloc(P + 4, 100, 10, P, None) == EINVAL
     kp = strd.kernel_path
     bf, f32 = torch.bfloat16, torch.float32
     assert kp("score_attn", 256, 32768, 32, 8, 128) == strd.PATH_MFMA
