@@ -217,7 +217,7 @@ class MambaLayer:
         t, o = self.t, self.o
         if self.fused:
             self.strd.ssd_prefill_gather(t["x"], t["dt"], t["A"], t["B"], t["C"], self.idx, self.w.N, self.w.M,
-                                         chunk=self.s.chunk, want_state=False, out=self.y_red)
+                                         chunk=self.s.chunk, want_state=False, out=self.y_red, ws=self.ws)
         else:
             self.strd.ssd_prefill(o["x"], o["dt"], t["A"], o["B"], o["C"], chunk=self.s.chunk, want_state=False,
                                   out=self.y_red, ws=self.ws)

@@ -304,9 +304,9 @@ def ssd_prefill(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Ten
 def ssd_prefill_gather(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,
                        idx: torch.Tensor, N: int, M: int, D: Optional[torch.Tensor] = None,
                        S_in: Optional[torch.Tensor] = None, chunk: int = 256, want_state: bool = True,
-                       out: Optional[torch.Tensor] = None):
+                       out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
     """Mamba-2 scan over rows idx (vision) + the M text rows of the uncompacted inputs [N+M, ...]."""
-    _dev(x, dt, A, B, C, D, S_in, idx, out)
+    _dev(x, dt, A, B, C, D, S_in, idx, out, ws)
     Ttot, H, P = x.shape
     G, n = B.shape[1:]
     K = idx.shape[0]
@@ -317,8 +317,11 @@ def ssd_prefill_gather(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: to
     io = _io(x)
     y = out if out is not None else torch.empty((K + M, H, P), dtype=x.dtype, device=x.device)
     S_out = torch.empty(H, P, n, dtype=torch.float32, device=x.device) if want_state else None
+    if ws is None:
+        ws, _ = _ws(lib().strd_ssd_prefill_workspace(K + M, H, P, G, n, chunk, io), x)
     _check(lib().strd_ssd_prefill_gather(_ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(S_in), _ptr(idx),
-                                         _ptr(y), _ptr(S_out), N, M, K, H, P, G, n, chunk, io, None, 0, _stream()),
+                                         _ptr(y), _ptr(S_out), N, M, K, H, P, G, n, chunk, io, _ptr(ws),
+                                         0 if ws is None else ws.numel(), _stream()),
            "ssd_prefill_gather")
     return y, S_out
 

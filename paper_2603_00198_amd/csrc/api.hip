@@ -12,6 +12,12 @@ namespace {
 
 inline bool io_ok(strd_dtype io) { return io == STRD_F32 || io == STRD_BF16; }
 inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
+// The two matrix-core kernels of the scan: segments of the sequence side by side (ssd_seg) where that
+// pays, one workgroup per (head, 32 channels) over the whole sequence (ssd_mfma) otherwise.
+inline bool use_seg(int T, int rows, int H, int P, int G, int n, strd_dtype io) {
+    return ssd_seg_supported(T, rows, H, P, G, n, io) &&
+           (ssd_seg_preferred(T, H, P) || !ssd_mfma_supported(T, rows, H, P, G, n, io));
+}
 // The kernels read and write 16-byte vectors straight from the caller's pointers.
 template <typename... P>
 inline bool aligned16(const P *...p) { return ((... | (uintptr_t)p) & 15u) == 0; }
@@ -131,8 +137,9 @@ int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, i
 
 // ------------------------------------------------------------------ ssd_prefill ------------
 size_t strd_ssd_prefill_workspace(int T, int H, int P, int G, int n, int chunk, strd_dtype io) {
-    (void)T; (void)H; (void)P; (void)G; (void)n; (void)chunk; (void)io;
-    return 0;
+    (void)chunk;
+    if (T < 1 || H < 1 || P < 1 || G < 1 || n < 1 || H % G) return 0;
+    return use_seg(T, T, H, P, G, n, io) ? ssd_seg_ws(T, H, P, n) : 0;
 }
 
 int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
@@ -140,11 +147,13 @@ int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void 
                      strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
     if (T < 0 || H < 1 || P < 1 || G < 1 || n < 1 || H % G || chunk < 1 || !io_ok(io) || !A) return STRD_EINVAL;
     if (T > 0 && (!x || !dt || !B || !C || !y)) return STRD_EINVAL;
-    if (ssd_mfma_supported(T, T, H, P, G, n, io) && !aligned16(x, B, C, S_in, y, S_out, ws)) return STRD_EINVAL;
+    const bool mfma = ssd_mfma_supported(T, T, H, P, G, n, io) || ssd_seg_supported(T, T, H, P, G, n, io);
+    if (mfma && !aligned16(x, B, C, S_in, y, S_out, ws)) return STRD_EINVAL;
     const size_t need = strd_ssd_prefill_workspace(T, H, P, G, n, chunk, io);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
-    if (ssd_mfma_supported(T, T, H, P, G, n, io))
-        return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, nullptr, 0, 0, T, H, P, G, n, as_stream(stream));
+    if (use_seg(T, T, H, P, G, n, io))
+        return ssd_seg(x, dt, A, B, C, D, S_in, y, S_out, nullptr, 0, 0, T, H, P, G, n, ws, as_stream(stream));
+    if (mfma) return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, nullptr, 0, 0, T, H, P, G, n, as_stream(stream));
     if (!ssd_general_supported(n)) return STRD_EUNSUPPORTED;
     return ssd_general(x, dt, A, B, C, D, S_in, y, S_out, T, H, P, G, n, io, as_stream(stream));
 }
@@ -153,21 +162,31 @@ int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, cons
                             const float *D, const float *S_in, const int32_t *idx, void *y, float *S_out, int N, int M,
                             int K, int H, int P, int G, int n, int chunk, strd_dtype io, void *ws, size_t ws_bytes,
                             void *stream) {
-    (void)ws; (void)ws_bytes;
     if (N < 0 || M < 0 || K < 0 || K > N || H < 1 || P < 1 || G < 1 || n < 1 || H % G || chunk < 1 || !io_ok(io) || !A)
         return STRD_EINVAL;
     const long long T = (long long)K + M;
     if (T > 0 && (!x || !dt || !B || !C || !y || (K > 0 && !idx))) return STRD_EINVAL;
-    if (!aligned16(x, B, C, S_in, y, S_out)) return STRD_EINVAL;
+    if (!aligned16(x, B, C, S_in, y, S_out, ws)) return STRD_EINVAL;
     if (T == 0 || (long long)N + M > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
-    if (!ssd_mfma_supported((int)T, N + M, H, P, G, n, io)) return STRD_EUNSUPPORTED;
+    if (!ssd_seg_supported((int)T, N + M, H, P, G, n, io) && !ssd_mfma_supported((int)T, N + M, H, P, G, n, io))
+        return STRD_EUNSUPPORTED;
+    // the same choice of kernel as strd_ssd_prefill makes for K + M tokens: the results must be the same bits
+    const bool old = !use_seg((int)T, (int)T, H, P, G, n, io) || !ssd_seg_supported((int)T, N + M, H, P, G, n, io);
+    if (old && !ssd_mfma_supported((int)T, N + M, H, P, G, n, io)) return STRD_EUNSUPPORTED;
+    const size_t need = old ? 0 : ssd_seg_ws((int)T, H, P, n);
+    if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
     if (K == 0) {  // only the text rows survive: a dense scan over the tail of the tensors
         const size_t es = 2;
-        return ssd_mfma((const char *)x + (size_t)N * H * P * es, dt + (size_t)N * H, A,
-                        (const char *)B + (size_t)N * G * n * es, (const char *)C + (size_t)N * G * n * es, D, S_in, y,
-                        S_out, nullptr, 0, 0, (int)T, H, P, G, n, as_stream(stream));
+        if (old)
+            return ssd_mfma((const char *)x + (size_t)N * H * P * es, dt + (size_t)N * H, A,
+                            (const char *)B + (size_t)N * G * n * es, (const char *)C + (size_t)N * G * n * es, D, S_in, y,
+                            S_out, nullptr, 0, 0, (int)T, H, P, G, n, as_stream(stream));
+        return ssd_seg((const char *)x + (size_t)N * H * P * es, dt + (size_t)N * H, A,
+                       (const char *)B + (size_t)N * G * n * es, (const char *)C + (size_t)N * G * n * es, D, S_in, y,
+                       S_out, nullptr, 0, 0, (int)T, H, P, G, n, ws, as_stream(stream));
     }
-    return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, idx, N, K, (int)T, H, P, G, n, as_stream(stream));
+    if (old) return ssd_mfma(x, dt, A, B, C, D, S_in, y, S_out, idx, N, K, (int)T, H, P, G, n, as_stream(stream));
+    return ssd_seg(x, dt, A, B, C, D, S_in, y, S_out, idx, N, K, (int)T, H, P, G, n, ws, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ attn_prefill -----------
@@ -202,7 +221,7 @@ int strd_score_mamba_kernel_path(int M, int N, int H, int G, int n, strd_dtype i
 
 int strd_ssd_prefill_kernel_path(int T, int H, int P, int G, int n, strd_dtype io) {
     if (T < 0 || H < 1 || P < 1 || G < 1 || n < 1 || H % G || !io_ok(io)) return STRD_PATH_NONE;
-    if (ssd_mfma_supported(T, T, H, P, G, n, io)) return STRD_PATH_MFMA;
+    if (ssd_seg_supported(T, T, H, P, G, n, io) || ssd_mfma_supported(T, T, H, P, G, n, io)) return STRD_PATH_MFMA;
     return ssd_general_supported(n) ? STRD_PATH_SIMT : STRD_PATH_NONE;
 }
 

@@ -124,6 +124,22 @@ __device__ __forceinline__ void lds_issue_tr8(const void *p, strd_s16x4 (&r)[8])
         : "v"(a), "i"(O0), "i"(O1), "i"(O2), "i"(O3), "i"(O4), "i"(O5), "i"(O6), "i"(O7)
         : "memory");
 }
+// Four reads, same contract as lds_issue_tr8 / lds_settle8.
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_issue_tr4(const void *p, strd_s16x4 (&r)[4]) {
+    const uint32_t a = lds_offset(p);
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %4 offset:%5\n\t"
+        "ds_read_b64_tr_b16 %1, %4 offset:%6\n\t"
+        "ds_read_b64_tr_b16 %2, %4 offset:%7\n\t"
+        "ds_read_b64_tr_b16 %3, %4 offset:%8"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(a), "i"(O0), "i"(O1), "i"(O2), "i"(O3)
+        : "memory");
+}
+__device__ __forceinline__ void lds_settle4(strd_s16x4 (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : : "memory");
+}
 // Wait for every LDS operation of the wave; the registers pass through the statement so that no
 // use of them can be scheduled before it.
 __device__ __forceinline__ void lds_settle8(strd_s16x4 (&r)[8]) {
@@ -235,6 +251,12 @@ bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io
 size_t score_mamba_mfma_ws(int N, int G);
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
                      void *ws, hipStream_t st);
+bool ssd_seg_supported(int T, int rows, int H, int P, int G, int n, strd_dtype io);
+size_t ssd_seg_ws(int T, int H, int P, int n);
+bool ssd_seg_preferred(int T, int H, int P);
+int ssd_seg(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
+            const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G, int n,
+            void *ws, hipStream_t st);
 bool ssd_mfma_supported(int T, int rows, int H, int P, int G, int n, strd_dtype io);
 int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
              const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G,

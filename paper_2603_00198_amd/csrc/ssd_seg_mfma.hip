@@ -1,0 +1,825 @@
+// ssd_prefill on bf16 matrix cores: the Mamba-2 recurrence (paper Eqs. "ssm_state_update",
+// "ssm_output") in its chunked form, i.e. the unrolled sum (Eq. "ssm_unrolled") split at
+// 64-token boundaries, with the recurrent state of a head kept in the registers of the waves
+// that own it for a whole segment of the sequence.
+//
+// Decomposition.  One workgroup owns 32*NC consecutive channels of one head (NC = 2: the whole
+// head when P = 64) and one segment of the sequence, which it walks in 64-token steps.  Per
+// step, with l_t the in-step cumulative sum of dt*A (log2 units):
+//   (a) G^T[j,t] = b_j . c_t                                      contraction over the state dim n
+//   (b) M[t,j]   = G^T[j,t] * 2^(l_t-l_j) * dt_j  for j <= t, else 0            (fp32, then bf16)
+//   (c) Y^T[p,t] = sum_j x_j[p] M[t,j]                            contraction over tokens
+//   (d) Y^T[p,t] += 2^(l_t) * sum_n S[p,n] c_t[n]                 S = state before the step
+//   (e) S^T[n,p] = 2^(l_Q) S^T[n,p] + sum_j b_j[n] (w_j x_j[p]),  w_j = dt_j 2^(l_Q-l_j)
+// every product a v_mfma_f32_16x16x32_bf16.  (a) and (b) depend on the head only, not on the
+// channel: two "G waves" do them once per workgroup, two query blocks of 16 tokens each, keep the
+// weights M in registers -- the accumulators of (a), rounded to bf16, are the B operand of (c) as
+// they stand -- and go on to (c) for all the workgroup's channels and to the outputs.  (d) and (e)
+// belong to NC "compute waves", one per slab of 32 channels, which hold their slab's state
+// S^T[n, 32] in fp32 accumulator registers from the first step to the last.  The accumulator
+// layout of (e) is at the same time the A-operand layout of (d) (the contraction index n runs
+// over the accumulator rows a lane holds), so the state is converted to bf16 in registers and
+// never passes through LDS; the carried part (d) of a step's outputs goes to the G waves through
+// LDS in accumulator layout, rounded to bf16 (8 bytes per lane, no bank conflicts).
+//
+// Waves (NC + 6): NC compute waves; 2 G waves; one wave each that only requests the asynchronous
+// global -> LDS copies of the B tiles, the C tiles and the x tiles, two steps ahead (rings of 3);
+// a helper wave that requests dt three steps ahead and turns it into the scan l_t, the key
+// factors of (b), the weights of (e) and the carries of (d) one step ahead (and keeps the row
+// tables of the gather form).  One LDS-only barrier per step.  The outputs of a step leave one
+// step late: the G waves keep (c) of step i in registers, the compute waves leave the carried
+// part (d) of step i in LDS (bf16, double-buffered), the barrier that ends the step publishes it,
+// and the G waves add the two and store them while the arithmetic of step i + 1 runs.
+//
+// Segments.  A head is a serial chain over time; to fill the chip the sequence is cut into a few
+// long segments that run side by side, each from a zero state (the first from S_in).  A segment
+// leaves its final local state and its total decay in the workspace; a second, small kernel adds
+// what the true incoming state contributes to the first tokens of each later segment,
+//   y_t += 2^(l_t) * E c_t,   E = state at the segment's start, l_t = decay since then,
+// for as many 64-token tiles as 2^(l_t) is not yet zero in fp32 (a handful at the decay rates of
+// a trained layer, the whole segment if A = 0: always exact), and completes S_out.
+//
+// GATHER: token t of the sequence is row idx[t] (t < K) or N + t - K of the tensors, i.e. the
+// kernel reads the uncompacted x, dt, B, C through the kept-index list instead of a compacted copy.
+#include "common.h"
+
+namespace strd {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kQ = 64;       // tokens per step
+constexpr int kRB = 3;       // B / C tiles in LDS (requested kRB - 1 steps ahead)
+constexpr int kRX = 3;       // x tiles in LDS
+constexpr int kRD = 4;       // dt rows in LDS (requested kRD - 1 steps ahead)
+constexpr int threads_for(int NC) { return 64 * (NC + 6); }  // compute waves + 2 G waves + 3 copy waves + helper
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct SegArgs {
+    const bf16_t *x;
+    const float *dt, *A;
+    const bf16_t *B, *C;
+    const float *D, *S_in;
+    bf16_t *y;
+    float *S_out;  // final state [H, P, n] or null
+    float *lend;   // [nseg - 1, H, P, n]: final local state of every segment but the last
+    float *ltot;   // [nseg, H]: total log2 decay of every segment
+    const int32_t *idx;
+    int N, K, T, H, P, G;
+    int nseg, seg_steps;  // segments and 64-token steps per segment (the last may be shorter)
+    int wg_per_seg;       // H * P / (32 * NC)
+};
+
+template <int NS, int NC>
+struct LdsS {
+    using BT = AsyncTile<kQ, NS / 8, 1, 2, true>;  // one B or C tile, filled by one wave, 2 pad vectors per row
+    using XT = AsyncTile<kQ, NC * 4, 1, 1, true>;  // x tile of the workgroup's channels, 1 pad vector per row
+    static constexpr int kCP = BT::kPitch;         // bf16 elements per row of the B / C tiles
+    static constexpr int kXP = XT::kPitch;         // ... of the x tiles
+    struct alignas(16) TileBC {
+        bf16_t c[BT::kBytes / 2];
+        bf16_t b[BT::kBytes / 2];
+    };
+    struct alignas(16) TileX {
+        bf16_t x[XT::kBytes / 2];
+    };
+    struct alignas(16) Scan {
+        float ell[kQ];    // inclusive cumulative sum of dt*A*log2(e) inside the step
+        float dtv[kQ];    // dt (0 past the end of the sequence)
+        float fw[96];     // key factors of query block W = 1..3 at fw_at(W): dt_j * 2^(l_{16W-1} - l_j), j < 16W
+        float w[kQ];      // weights of the state update: w_j = dt_j * 2^(l_Q - l_j)
+        float carry[kQ];  // 2^(l_t); carry[kQ - 1] is the decay of the state over the step
+    };
+    static constexpr int fw_at(int W) { return W <= 1 ? 0 : W == 2 ? 16 : 48; }
+    TileBC bc[kRB];
+    TileX xr[kRX];
+    float dt[kRD][kQ];
+    Scan scan[2];
+    bf16x4 yin[2][8 * NC][64];  // carried part of the outputs of step i, [i % 2][query block * 2 NC + channel tile][lane]
+    uint32_t rowtab[4][kQ];  // gather mode: source row of every token of local step i, i % 4 = slot
+    int32_t rawidx[4][kQ];   // gather mode: entries of the kept-index list for local step i, i % 4 = slot
+};
+
+static_assert(sizeof(LdsS<128, 2>) <= 160 * 1024, "one workgroup must fit the 160 KB of LDS of a CU");
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+__device__ __forceinline__ float read_lane_f32(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ __forceinline__ bf16x8 cat8(bf16x4 lo, bf16x4 hi) {
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+__device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
+    return bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+}
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
+// (gfx9 layout: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14); n < 64.
+constexpr int vm_wait_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+// The k slots of a token-contracted fragment: slot s of lane group lb in token half kr is token
+// 32 kr + 4 lb + (s & 3) + 16 (s >> 2).  Every operand that is contracted over tokens (x in (c)
+// and (e), b in (e), M in (c), the weights w) uses this one order.
+
+// The four token-contracted fragments of the x tile for a slab of 32 channels at column c0
+// ([kr = token half][pt = channel half]).  Issued early (issue_x_frags), usable after take_x_frags.
+template <int PITCH>
+__device__ __forceinline__ void issue_x_frags(const bf16_t *xt, int c0, int lr, int lb, strd_s16x4 (&r)[8]) {
+    constexpr int R = PITCH * 2;  // row pitch in bytes
+    lds_issue_tr8<0, 16 * R, 32, 16 * R + 32, 32 * R, 48 * R, 32 * R + 32, 48 * R + 32>(
+        xt + (4 * lb + (lr >> 2)) * PITCH + c0 + 4 * (lr & 3), r);
+}
+__device__ __forceinline__ void take_x_frags(strd_s16x4 (&r)[8], bf16x8 (&xf)[2][2]) {
+    lds_settle8(r);
+    xf[0][0] = tr_pair(r[0], r[1]);
+    xf[0][1] = tr_pair(r[2], r[3]);
+    xf[1][0] = tr_pair(r[4], r[5]);
+    xf[1][1] = tr_pair(r[6], r[7]);
+}
+
+// ---- compute wave: the slab of 32 channels at column 32 * cw of the workgroup's x tile: (d), (e) ----
+template <int NS, int NC, bool GATHER>
+__device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a, int cw, int h, int pin, int nloc,
+                                             const float *s_src, float *s_dst) {
+    using L = LdsS<NS, NC>;
+    constexpr int KS = NS / 32;  // k-steps of the products contracted over n
+    constexpr int NT = NS / 16;  // 16-row tiles of the state
+    const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
+    const int xcol = 32 * cw;  // first column of the slab in the x tile
+
+    // state: S^T[n][p] tiles, rows n = 16 nt + 4 lb + i, columns p = pin + 32 cw + 16 pt + lr
+    f32x4 sacc[NT][2];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt) {
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (s_src) v = *reinterpret_cast<const f32x4 *>(s_src + ((size_t)h * a.P + pin + xcol + 16 * pt + lr) * NS + 16 * nt + 4 * lb);
+            sacc[nt][pt] = v;
+        }
+
+    if (GATHER) __syncthreads();  // prologue barriers: (row tables written |)
+    __syncthreads();              // first copies landed |
+    __syncthreads();              // scan of the first step
+
+    for (int i = 0; i < nloc; ++i) {
+        const typename L::Scan &sc = lds.scan[i & 1];
+        const typename L::TileBC &tb = lds.bc[i % kRB];
+        const bf16_t *xt = lds.xr[i % kRX].x;
+        // ---- LDS reads that do not depend on the arithmetic of the step are requested first ----
+        // x fragments and the first b^T fragments (transposing reads, for (e)); weights; c rows
+        constexpr int R = L::kCP * 2;
+        strd_s16x4 xr8[8], ba[8], bb[8];
+        issue_x_frags<L::kXP>(xt, xcol, lr, lb, xr8);
+        const bf16_t *bbase = &tb.b[(4 * lb + (lr >> 2)) * L::kCP + 4 * (lr & 3)];
+        // state tile d of a group of four: columns + 16 d of the b tile; rows + 0, 16 (token half 0: slots
+        // 0-3, 4-7), + 32, 48 (token half 1); ba: tiles 0, 1; bb: tiles 2, 3
+        lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(bbase, ba);
+        lds_issue_tr8<64, 16 * R + 64, 32 * R + 64, 48 * R + 64, 96, 16 * R + 96, 32 * R + 96, 48 * R + 96>(bbase, bb);
+        f32x4 wv[2][2];
+#pragma unroll
+        for (int kr = 0; kr < 2; ++kr)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) wv[kr][hi] = *reinterpret_cast<const f32x4 *>(&sc.w[32 * kr + 16 * hi + 4 * lb]);
+        const float dq = sc.carry[kQ - 1];
+        // (d): Y^T[p, t] = sum_n S[p, n] c_t[n] (the factor 2^(l_t) is applied where the outputs are summed).
+        // A operand straight from the accumulators: the lane holds rows 4 lb .. 4 lb + 3 of state tiles
+        // 2 ks and 2 ks + 1 for column p = lr, i.e. the k slots n = 32 ks + 4 lb + s (s < 4),
+        // 32 ks + 16 + 4 lb + s - 4 (s >= 4) of row p; the c fragments are read in the same slot order
+        // (two 8-byte reads).  Once the bf16 copy exists the accumulators are free: their decay, which
+        // (e) needs, is interleaved with the products of (d), so that vector and matrix pipe overlap.
+        bf16x8 sb[2][KS];
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) sb[pt][ks] = cat8(to_bf16x4(sacc[2 * ks][pt]), to_bf16x4(sacc[2 * ks + 1][pt]));
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            bf16x8 cf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16_t *row = &tb.c[(16 * tt + lr) * L::kCP + 32 * ks + 4 * lb];
+                cf[ks] = cat8(*reinterpret_cast<const bf16x4 *>(row), *reinterpret_cast<const bf16x4 *>(row + 16));
+            }
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt) {
+                f32x4 yin = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) yin = mfma16(sb[pt][ks], cf[ks], yin);
+                lds.yin[i & 1][tt * (2 * NC) + 2 * cw + pt][lane] = to_bf16x4(yin);  // to the G wave of query block tt
+            }
+            // a quarter of the state's decay per query block
+#pragma unroll
+            for (int nt = tt * (NT / 4); nt < (tt + 1) * (NT / 4); ++nt)
+#pragma unroll
+                for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] *= dq;
+        }
+        // (e): S^T = 2^(l_Q) S^T + b^T (w x).  The x fragments, weighted in registers, are the B operand.
+        bf16x8 xf[2][2], xwf[2][2];
+        take_x_frags(xr8, xf);  // waits for every read requested above
+#pragma unroll
+        for (int kr = 0; kr < 2; ++kr)
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xwf[kr][pt][e] = (bf16_t)((float)xf[kr][pt][e] * wv[kr][e >> 2][e & 3]);
+#pragma unroll
+        for (int n4 = 0; n4 < NT; n4 += 4) {
+            lds_settle8(ba);
+            lds_settle8(bb);
+            bf16x8 bt[4][2];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const strd_s16x4 *r = d < 2 ? &ba[4 * d] : &bb[4 * (d - 2)];
+                bt[d][0] = tr_pair(r[0], r[1]);
+                bt[d][1] = tr_pair(r[2], r[3]);
+            }
+            if (n4 + 4 < NT) {  // next group of four tiles: columns + 64
+                lds_issue_tr8<128, 16 * R + 128, 32 * R + 128, 48 * R + 128, 160, 16 * R + 160, 32 * R + 160, 48 * R + 160>(bbase, ba);
+                lds_issue_tr8<192, 16 * R + 192, 32 * R + 192, 48 * R + 192, 224, 16 * R + 224, 32 * R + 224, 48 * R + 224>(bbase, bb);
+            }
+            // independent products back to back: first token half of all eight tiles, then the second
+#pragma unroll
+            for (int kr = 0; kr < 2; ++kr)
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt) sacc[n4 + d][pt] = mfma16(bt[d][kr], xwf[kr][pt], sacc[n4 + d][pt]);
+        }
+        lds_barrier();  // the step is over
+    }
+
+    if (s_dst) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+                *reinterpret_cast<f32x4 *>(s_dst + ((size_t)h * a.P + pin + xcol + 16 * pt + lr) * NS + 16 * nt + 4 * lb) =
+                    sacc[nt][pt];
+    }
+}
+
+// ---- G wave GW: (a), (b), (c) and the outputs of the query blocks {0, 3} (GW = 0) or {1, 2} (GW = 1) ----
+// The outputs of a step leave one step late: (a)-(c) of step i are summed up in registers during step i,
+// the carried part arrives from the compute waves with the barrier that ends the step.
+template <int NS, int NC, int GW, bool GATHER>
+__device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int h, int chan0, int tok0, int nloc) {
+    using L = LdsS<NS, NC>;
+    constexpr int KS = NS / 32;
+    constexpr int PT = 2 * NC;                                  // 16-channel tiles of the workgroup
+    constexpr int TA = GW == 0 ? 0 : 1, TB = GW == 0 ? 3 : 2;  // the two query blocks of this wave
+    const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
+    const int HP = a.H * a.P;
+    const float Dh = a.D ? a.D[h] : 0.f;
+    f32x4 ya[PT], yb[PT];  // (c) (+ D x) of the step before, until its carried part arrives
+    // Outputs of a step: what is in ya / yb plus the carried part the compute waves left in LDS.
+    // A lane holds 4 channels of one token, i.e. 8 bytes of a 32 PT-byte row of y; stored like that,
+    // every store instruction would touch 16 rows with 32 bytes each.  The rows are turned in LDS first
+    // -- in the slots of the carried parts this wave has just read, which nobody needs before the step
+    // after next -- so that a lane stores 16 bytes and a store instruction writes whole rows.  The three
+    // stages (read the carried part; add and write the rows; read them back and store) are spread over
+    // the arithmetic of the next step, so that their LDS round trips are not waited for.
+    constexpr int NCH = 2 * PT;    // 16-byte pieces per row of the workgroup's channels
+    constexpr int RPI = 64 / NCH;  // rows per store instruction
+    const int srow = lane / NCH, spc = lane % NCH;
+    bf16x4 ia[PT], ib[PT];
+    bf16x8 va[16 / RPI], vb[16 / RPI];
+    float cra = 0.f, crb = 0.f;  // 2^(l_t) of this lane's tokens in the step whose outputs are waiting
+    auto emit_read = [&](int j) __attribute__((always_inline)) {
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            ia[pt] = lds.yin[j & 1][TA * PT + pt][lane];
+            ib[pt] = lds.yin[j & 1][TB * PT + pt][lane];
+        }
+    };
+    auto emit_turn = [&](int j) __attribute__((always_inline)) {
+        char *sta = reinterpret_cast<char *>(&lds.yin[j & 1][TA * PT][0]), *stb = reinterpret_cast<char *>(&lds.yin[j & 1][TB * PT][0]);
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            bf16x4 oa, ob;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                oa[e] = (bf16_t)(ya[pt][e] + cra * (float)ia[pt][e]);
+                ob[e] = (bf16_t)(yb[pt][e] + crb * (float)ib[pt][e]);
+            }
+            // row lr, piece 2 pt + lb / 2 (pieces swizzled by the row so that rows do not share banks), half lb % 2
+            const int off = lr * (16 * NCH) + (((2 * pt + (lb >> 1)) ^ (lr & (NCH - 1))) << 4) + ((lb & 1) << 3);
+            *reinterpret_cast<bf16x4 *>(sta + off) = oa;
+            *reinterpret_cast<bf16x4 *>(stb + off) = ob;
+        }
+    };
+    auto emit_back = [&](int j) __attribute__((always_inline)) {
+        const char *sta = reinterpret_cast<const char *>(&lds.yin[j & 1][TA * PT][0]), *stb = reinterpret_cast<const char *>(&lds.yin[j & 1][TB * PT][0]);
+#pragma unroll
+        for (int k = 0; k < 16 / RPI; ++k) {
+            const int r = srow + RPI * k;
+            const int off = r * (16 * NCH) + ((spc ^ (r & (NCH - 1))) << 4);
+            va[k] = *reinterpret_cast<const bf16x8 *>(sta + off);
+            vb[k] = *reinterpret_cast<const bf16x8 *>(stb + off);
+        }
+    };
+    auto emit_store = [&](int j) __attribute__((always_inline)) {
+        const int tbase = tok0 + j * kQ;
+#pragma unroll
+        for (int k = 0; k < 16 / RPI; ++k) {
+            const int r = srow + RPI * k;
+            if (tbase + 16 * TA + r < a.T)
+                *reinterpret_cast<bf16x8 *>(a.y + (size_t)(tbase + 16 * TA + r) * HP + chan0 + 8 * spc) = va[k];
+            if (tbase + 16 * TB + r < a.T)
+                *reinterpret_cast<bf16x8 *>(a.y + (size_t)(tbase + 16 * TB + r) * HP + chan0 + 8 * spc) = vb[k];
+        }
+    };
+    if (GATHER) __syncthreads();
+    __syncthreads();
+    __syncthreads();
+
+    for (int i = 0; i < nloc; ++i) {
+        const typename L::Scan &sc = lds.scan[i & 1];
+        const typename L::TileBC &tb = lds.bc[i % kRB];
+        const bf16_t *xt = lds.xr[i % kRX].x;
+        const bool prev = i > 0;  // uniform: the step before has outputs waiting
+        // fragments: b rows of key blocks 0..TB, c rows of the two query blocks
+        strd_s16x4 xr8[NC][8];
+        bf16x8 bf[TB + 1][KS], cfa[KS], cfb[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int jt = 0; jt <= TB; ++jt)
+                bf[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
+            cfa[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * TA + lr) * L::kCP + 32 * ks + 8 * lb]);
+            cfb[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * TB + lr) * L::kCP + 32 * ks + 8 * lb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // (a)
+        f32x4 ga[TA + 1], gb[TB + 1];
+#pragma unroll
+        for (int jt = 0; jt <= TA; ++jt) ga[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jt = 0; jt <= TB; ++jt) gb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int jt = 0; jt <= TA; ++jt) ga[jt] = mfma16(bf[jt][ks], cfa[ks], ga[jt]);
+#pragma unroll
+            for (int jt = 0; jt <= TB; ++jt) gb[jt] = mfma16(bf[jt][ks], cfb[ks], gb[jt]);
+        }
+        // while (a) runs: the x fragments of every channel tile (for (c)) and the carried part of the step
+        // before (published by the barrier that ended it) are requested
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) issue_x_frags<L::kXP>(xt, 32 * c, lr, lb, xr8[c]);
+        if (prev) emit_read(i - 1);
+        // what (b) needs from the scan of the head
+        const float el_a = sc.ell[16 * TA + lr], el_b = sc.ell[16 * TB + lr];
+        const float ref_a = TA > 0 ? sc.ell[16 * TA - 1] : 0.f, ref_b = sc.ell[16 * TB - 1];
+        const f32x4 elj_a = *reinterpret_cast<const f32x4 *>(&sc.ell[16 * TA + 4 * lb]);
+        const f32x4 elj_b = *reinterpret_cast<const f32x4 *>(&sc.ell[16 * TB + 4 * lb]);
+        const f32x4 dtj_a = *reinterpret_cast<const f32x4 *>(&sc.dtv[16 * TA + 4 * lb]);
+        const f32x4 dtj_b = *reinterpret_cast<const f32x4 *>(&sc.dtv[16 * TB + 4 * lb]);
+        f32x4 fja[TA > 0 ? TA : 1] = {}, fjb[TB];
+#pragma unroll
+        for (int jt = 0; jt < TA; ++jt) fja[jt] = *reinterpret_cast<const f32x4 *>(&sc.fw[L::fw_at(TA) + 16 * jt + 4 * lb]);
+#pragma unroll
+        for (int jt = 0; jt < TB; ++jt) fjb[jt] = *reinterpret_cast<const f32x4 *>(&sc.fw[L::fw_at(TB) + 16 * jt + 4 * lb]);
+        bf16x4 xva[PT] = {}, xvb[PT] = {};
+        if (a.D) {
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                xva[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TA + lr) * L::kXP + 16 * pt + 4 * lb]);
+                xvb[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TB + lr) * L::kXP + 16 * pt + 4 * lb]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // (b): blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan at
+        // the last token before the query block (both exponents <= 0); diagonal block: direct, masked.
+        // The weights, rounded to bf16, are the B operand of (c) as they stand in the registers.
+        auto weigh = [&](int tt, int jt, f32x4 g, float el_t, float e_ref, f32x4 fj, f32x4 elj, f32x4 dtj)
+                         __attribute__((always_inline)) -> bf16x4 {
+            bf16x4 mv;
+            if (jt < tt) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) mv[e] = (bf16_t)(g[e] * e_ref * fj[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float val = g[e] * fast_exp2(el_t - elj[e]) * dtj[e];
+                    mv[e] = (bf16_t)((4 * lb + e <= lr) ? val : 0.f);  // causal mask
+                }
+            }
+            return mv;
+        };
+        const float era = TA > 0 ? fast_exp2(el_a - ref_a) : 0.f, erb = fast_exp2(el_b - ref_b);
+        bf16x4 ma[4], mb[4];
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            ma[jt] = mb[jt] = bf16x4{(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+            if (jt <= TA) ma[jt] = weigh(TA, jt, ga[jt <= TA ? jt : 0], el_a, era, fja[jt < TA ? jt : 0], elj_a, dtj_a);
+            if (jt <= TB) mb[jt] = weigh(TB, jt, gb[jt <= TB ? jt : 0], el_b, erb, fjb[jt < TB ? jt : 0], elj_b, dtj_b);
+        }
+        // the rows of the step before are summed, written for turning and read back; they travel under (c)
+        if (prev) {
+            emit_turn(i - 1);
+            emit_back(i - 1);
+        }
+        // (c): Y^T[p, t] = sum_j x_j[p] M[t, j]; query block tt needs the key halves kr <= tt / 2
+        bf16x8 xf[NC][2][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) take_x_frags(xr8[c], xf[c]);
+        // the stores of the step before go out now, not at the end of the step: the copies of the step
+        // share the CU's path to memory with them and were requested at its start
+        if (prev) emit_store(i - 1);
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            ya[pt] = yb[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (a.D) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    ya[pt][e] = Dh * (float)xva[pt][e];
+                    yb[pt][e] = Dh * (float)xvb[pt][e];
+                }
+            }
+#pragma unroll
+            for (int kr = 0; kr < 2; ++kr) {
+                if (2 * kr <= TA) ya[pt] = mfma16(xf[pt >> 1][kr][pt & 1], cat8(ma[2 * kr], ma[2 * kr + 1]), ya[pt]);
+                if (2 * kr <= TB) yb[pt] = mfma16(xf[pt >> 1][kr][pt & 1], cat8(mb[2 * kr], mb[2 * kr + 1]), yb[pt]);
+            }
+        }
+        cra = sc.carry[16 * TA + lr];
+        crb = sc.carry[16 * TB + lr];
+        lds_barrier();  // the step is over
+    }
+    emit_read(nloc - 1);
+    emit_turn(nloc - 1);
+    emit_back(nloc - 1);
+    emit_store(nloc - 1);
+}
+
+// Source row of token t of the sequence (gather form); an index outside [0, N) is clamped into
+// the tensors instead of faulting.
+__device__ __forceinline__ uint32_t gather_row(const SegArgs &a, int t, int32_t kept) {
+    const uint32_t last_row = (uint32_t)(a.N + (a.T - a.K) - 1);
+    return min((uint32_t)(t < a.K ? kept : a.N + (t - a.K)), last_row);
+}
+
+// ---- helper wave: dt copies, the scans of the head, the row tables of the gather form ---------
+template <int NS, int NC, bool GATHER>
+__device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a, int h, int tok0, int nloc, int seg) {
+    using L = LdsS<NS, NC>;
+    const int lane = threadIdx.x & 63;
+    const float Al2 = a.A[h] * kLog2e;
+    __builtin_amdgcn_s_setprio(3);
+    auto token_of = [&](int i) { return min(tok0 + i * kQ + lane, a.T - 1); };
+    auto kept_of = [&](int i) -> int32_t { return a.idx[min(token_of(i), a.K - 1)]; };  // K >= 1 in gather mode
+    auto request_kept = [&](int i) __attribute__((always_inline)) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(a.idx + min(token_of(i), a.K - 1)),
+                                         (__attribute__((address_space(3))) void *)lds.rawidx[i & 3], 4, 0, 0);
+    };
+    const uint32_t dt_row = (uint32_t)a.H * 4;
+    auto request_dt = [&](int i) __attribute__((always_inline)) {  // 64 lanes x 4 bytes; rows past T re-read the last row
+        const uint32_t row = GATHER ? lds.rowtab[i & 3][lane] : (uint32_t)token_of(i);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(a.dt) + row * dt_row + (uint32_t)h * 4),
+            (__attribute__((address_space(3))) void *)lds.dt[i % kRD], 4, 0, 0);
+    };
+    // scan of dt*A of local step i, the key factors of (b), the weights of (e), the carries of (d);
+    // returns the total log2 decay of the step
+    auto make_scan = [&](int i, float raw) __attribute__((always_inline)) -> float {
+        const float dv = (tok0 + i * kQ + lane < a.T) ? raw : 0.f;
+        const float inc = wave_inclusive_scan_f32(dv * Al2);
+        typename L::Scan &m = lds.scan[i & 1];
+        const float tot = read_lane_f32(inc, kQ - 1);
+        m.ell[lane] = inc;
+        m.dtv[lane] = dv;
+        m.w[lane] = dv * fast_exp2(tot - inc);
+        m.carry[lane] = fast_exp2(inc);
+#pragma unroll
+        for (int wq = 1; wq < 4; ++wq) {  // only tokens j < 16 * wq are read; the exponent is <= 0 for them
+            const float lref = read_lane_f32(inc, 16 * wq - 1);
+            if (lane < 16 * wq) m.fw[L::fw_at(wq) + lane] = dv * fast_exp2(lref - inc);
+        }
+        return tot;
+    };
+    constexpr int kNewest = 1 + (GATHER ? 1 : 0);  // copies requested per step
+
+    if (GATHER) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds.rowtab[i][lane] = gather_row(a, token_of(i), kept_of(i));
+        lds.rawidx[4 & 3][lane] = kept_of(4);  // read in steps 0 and 1, before the first copied entries
+        lds.rawidx[5 & 3][lane] = kept_of(5);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        if (i < nloc) request_dt(i);
+    async_tile_wait();
+    __syncthreads();  // first copies landed
+    float ltot = make_scan(0, lds.dt[0][lane]);
+    __syncthreads();  // scan of the first step
+
+    for (int i = 0; i < nloc; ++i) {
+        // dt of step i + 1 landed before the barrier that ended the previous step (or in the prologue)
+        const float raw = lds.dt[(i + 1) % kRD][lane];
+        int32_t kept = 0;
+        if (GATHER) kept = lds.rawidx[(i + 4) & 3][lane];
+        __builtin_amdgcn_sched_barrier(0);
+        const bool more = i + 3 < nloc;  // uniform; nothing past the segment is requested
+        if (more) {
+            request_dt(i + 3);                     // slot last read in step i - 2
+            if (GATHER) request_kept(i + 6);       // slot last read in step i - 2
+        }
+        if (i + 1 < nloc) ltot += make_scan(i + 1, raw);  // buffer last read in step i - 1
+        if (GATHER) lds.rowtab[(i + 4) & 3][lane] = gather_row(a, token_of(i + 4), kept);  // slot last used in step i - 2
+        if (more)
+            __builtin_amdgcn_s_waitcnt(vm_wait_imm(kNewest));  // everything requested in earlier steps has landed
+        else
+            async_tile_wait();
+        lds_barrier();
+    }
+    if (lane == 0 && a.ltot) a.ltot[(size_t)seg * a.H + h] = ltot;
+}
+
+// ---- copy waves: one tile stream each (WHAT = 0: x, 1: B, 2: C), two steps ahead.  A wave that
+// requests a copy stands still until the CU's copy path takes it, so these waves do nothing else.
+template <int NS, int NC, int WHAT, bool GATHER>
+__device__ __forceinline__ void copy_wave(LdsS<NS, NC> &lds, const SegArgs &a, int col_bytes, int tok0, int nloc) {
+    using L = LdsS<NS, NC>;
+    using TT = typename std::conditional<WHAT == 0, typename L::XT, typename L::BT>::type;
+    const int lane = threadIdx.x & 63;
+    __builtin_amdgcn_s_setprio(3);
+    const char *src = reinterpret_cast<const char *>(WHAT == 0 ? a.x : WHAT == 1 ? a.B : a.C);
+    const uint32_t row_bytes = WHAT == 0 ? (uint32_t)a.H * a.P * 2 : (uint32_t)a.G * NS * 2;
+    int row_of[TT::kIssues];
+    uint32_t col_of[TT::kIssues];
+#pragma unroll
+    for (int k = 0; k < TT::kIssues; ++k) {
+        int cv;
+        TT::slot(0, lane, k, row_of[k], cv);
+        col_of[k] = (uint32_t)col_bytes + (uint32_t)cv * 16;
+    }
+    auto request = [&](int i) __attribute__((always_inline)) {
+        bf16_t *dst = WHAT == 0 ? lds.xr[i % kRX].x : WHAT == 1 ? lds.bc[i % kRB].b : lds.bc[i % kRB].c;
+#pragma unroll
+        for (int k = 0; k < TT::kIssues; ++k) {
+            const uint32_t row = GATHER ? lds.rowtab[i & 3][row_of[k]] : (uint32_t)min(tok0 + i * kQ + row_of[k], a.T - 1);
+            TT::issue(src + (size_t)row * row_bytes + col_of[k], dst, 0, k);
+        }
+    };
+    static_assert(TT::kIssues < 64, "vmcnt has 6 bits");
+
+    if (GATHER) __syncthreads();  // row tables of steps 0..3 written
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        if (i < nloc) request(i);
+    async_tile_wait();
+    __syncthreads();  // first copies landed
+    __syncthreads();
+
+    for (int i = 0; i < nloc; ++i) {
+        const bool more = i + 2 < nloc;  // uniform
+        if (more) request(i + 2);        // slot last read in step i - 1
+        if (more)
+            __builtin_amdgcn_s_waitcnt(vm_wait_imm(TT::kIssues));  // the tile of step i + 1 has landed
+        else
+            async_tile_wait();
+        lds_barrier();  // publishes it; this step's copies stay in flight
+    }
+}
+
+template <int NS, int NC, bool GATHER>
+__global__ __launch_bounds__(threads_for(NC)) void ssd_seg_kernel(SegArgs a, int nunits) {
+    using L = LdsS<NS, NC>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    L &lds = *reinterpret_cast<L *>(smem_raw);
+
+    const int unit = xcd_swizzle(blockIdx.x, nunits);
+    if (unit >= nunits) return;
+    const int seg = unit / a.wg_per_seg, u = unit % a.wg_per_seg;
+    const int chan0 = u * (32 * NC);
+    const int h = chan0 / a.P, pin = chan0 % a.P, g = h / (a.H / a.G);
+    const int nsteps = (a.T + kQ - 1) / kQ;
+    const int s0 = seg * a.seg_steps;
+    const int nloc = min(a.seg_steps, nsteps - s0);
+    const int tok0 = s0 * kQ;
+    // where the segment's state comes from and goes to
+    const float *s_src = seg == 0 ? a.S_in : nullptr;
+    float *s_dst = seg == a.nseg - 1 ? a.S_out : a.lend + (size_t)seg * a.H * a.P * NS;
+    const int wave = threadIdx.x >> 6;
+    if (wave < NC) {
+        compute_wave<NS, NC, GATHER>(lds, a, wave, h, pin, nloc, s_src, s_dst);
+        return;
+    }
+    // wave i runs on SIMD i % 4 (NC = 2): the compute waves have SIMDs 0 and 1 to themselves but for one copy wave each
+    switch (wave - NC) {
+        case 0: g_wave<NS, NC, 0, GATHER>(lds, a, h, chan0, tok0, nloc); break;
+        case 1: g_wave<NS, NC, 1, GATHER>(lds, a, h, chan0, tok0, nloc); break;
+        case 2: copy_wave<NS, NC, 1, GATHER>(lds, a, g * NS * 2, tok0, nloc); break;
+        case 3: copy_wave<NS, NC, 2, GATHER>(lds, a, g * NS * 2, tok0, nloc); break;
+        case 4: helper_wave<NS, NC, GATHER>(lds, a, h, tok0, nloc, seg); break;
+        default: copy_wave<NS, NC, 0, GATHER>(lds, a, chan0 * 2, tok0, nloc); break;
+    }
+}
+
+// ---- the contribution of the incoming state to the first tokens of segments 1.. and S_out -----
+// grid = (boundary b = 1..nseg, head, z); b < nseg: y of segment b; b == nseg: S_out.
+constexpr int kFixThreads = 256;
+constexpr int kFixZ = 4;  // workgroups that share the tiles of one (segment, head)
+
+template <int NS, bool GATHER>
+__global__ __launch_bounds__(kFixThreads) void ssd_fix_kernel(SegArgs a) {
+    constexpr int KS = NS / 32;
+    const int b = 1 + blockIdx.x, h = blockIdx.y, z = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lb = lane >> 4;
+    const size_t seg_elems = (size_t)a.H * a.P * NS;
+    // weight of segment s' < b in the state at the start of segment b: prod_{s' < u < b} 2^(ltot[u])
+    // (uniform; the loops below stop at the first segment whose weight is zero)
+    if (b == a.nseg) {
+        if (!a.S_out) return;
+        float f = fast_exp2(a.ltot[(size_t)(b - 1) * a.H + h]);
+        const int per = a.P * NS / 4;  // float4s of the head's state
+        for (int s = b - 2; s >= 0 && f != 0.f; --s) {
+            const float *src = a.lend + (size_t)s * seg_elems + (size_t)h * a.P * NS;
+            float *dst = a.S_out + (size_t)h * a.P * NS;
+            for (int e = z * kFixThreads + threadIdx.x; e < per; e += kFixZ * kFixThreads) {
+                f32x4 v = reinterpret_cast<const f32x4 *>(src)[e], o = reinterpret_cast<f32x4 *>(dst)[e];
+                reinterpret_cast<f32x4 *>(dst)[e] = o + f * v;
+            }
+            f *= fast_exp2(a.ltot[(size_t)s * a.H + h]);
+        }
+        return;
+    }
+    const int HP = a.H * a.P, g = h / (a.H / a.G);
+    const int tok0 = b * a.seg_steps * kQ;
+    const int tend = min(a.T, (b + 1) * a.seg_steps * kQ);
+    const float Al2 = a.A[h] * kLog2e;
+    auto row_of = [&](int t) -> size_t {
+        t = min(t, a.T - 1);
+        return GATHER ? (size_t)gather_row(a, t, a.idx[min(t, a.K - 1)]) : (size_t)t;
+    };
+    // E = state at the start of segment b, as A-operand fragments (rows p = 16 pt + lr, k slots
+    // n = 32 ks + 8 lb + s) of this wave's channel tiles pt = wave, wave + 4, ...; requested before it is
+    // known whether any token needs it, so that its latency runs under that of the dt loads
+    constexpr int kMaxPT = 1;  // channel tiles per wave held in registers (P <= 64); more are loaded when their turn comes
+    const int npt = (a.P / 16 - wave + 3) / 4;
+    bf16x8 ef[kMaxPT][KS];
+    auto load_e = [&](int pt, bf16x8 (&out)[KS]) __attribute__((always_inline)) {
+        f32x4 acc[KS][2];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc[ks][0] = acc[ks][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float f = 1.f;
+        for (int s = b - 1; s >= 0 && f != 0.f; --s) {
+            const float *src = a.lend + (size_t)s * seg_elems + ((size_t)h * a.P + 16 * pt + lr) * NS + 8 * lb;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                acc[ks][0] += f * *reinterpret_cast<const f32x4 *>(src + 32 * ks);
+                acc[ks][1] += f * *reinterpret_cast<const f32x4 *>(src + 32 * ks + 4);
+            }
+            f *= fast_exp2(a.ltot[(size_t)s * a.H + h]);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) out[ks] = cat8(to_bf16x4(acc[ks][0]), to_bf16x4(acc[ks][1]));
+    };
+    // dt of kFixZ tiles at once (lane = token); the first batch travels together with the E fragments
+    float dv[kFixZ];
+    auto load_dt = [&](int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < kFixZ; ++q) {
+            const int t = tok0 + (k0 + q) * kQ + lane;
+            dv[q] = t < tend ? a.dt[row_of(t) * a.H + h] : 0.f;
+        }
+    };
+    load_dt(0);
+#pragma unroll
+    for (int q = 0; q < kMaxPT; ++q)
+        if (q < npt) load_e(wave + 4 * q, ef[q]);
+    float prefix = 0.f;  // log2 decay from the segment's start to the tile's start
+    for (int k0 = 0; tok0 + k0 * kQ < tend; k0 += kFixZ) {
+        if (k0 > 0) load_dt(k0);
+        float cr = 0.f;
+        bool dead = false;
+#pragma unroll
+        for (int q = 0; q < kFixZ; ++q) {
+            const float inc = prefix + wave_inclusive_scan_f32(dv[q] * Al2);
+            if (read_lane_f32(fast_exp2(inc), 0) == 0.f) dead = true;  // nothing reaches this tile, nor any later one
+            if (q == z && !dead) cr = (tok0 + (k0 + q) * kQ + lane) < tend ? fast_exp2(inc) : 0.f;
+            prefix = read_lane_f32(inc, kQ - 1);
+        }
+        // this workgroup's tile of the batch: k0 + z
+        const int k = k0 + z;
+        auto repair = [&](int pt, const bf16x8 (&et)[KS]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const int tq = tok0 + k * kQ + 16 * tt + lr;  // this lane's token of the query block
+                const float crt = __shfl(cr, 16 * tt + lr, 64);
+                if (__ballot(crt != 0.f) == 0ull) continue;   // uniform per wave
+                const bf16_t *crow = a.C + (row_of(tq) * a.G + g) * NS + 8 * lb;
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = mfma16(et[ks], *reinterpret_cast<const bf16x8 *>(crow + 32 * ks), acc);
+                if (tq < tend && crt != 0.f) {
+                    bf16x4 *yq = reinterpret_cast<bf16x4 *>(a.y + (size_t)tq * HP + (size_t)h * a.P + 16 * pt + 4 * lb);
+                    const bf16x4 old = *yq;
+                    bf16x4 out;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) out[e] = (bf16_t)((float)old[e] + crt * acc[e]);
+                    *yq = out;
+                }
+            }
+        };
+        if (__ballot(cr != 0.f) != 0ull) {
+#pragma unroll
+            for (int q = 0; q < kMaxPT; ++q)
+                if (q < npt) repair(wave + 4 * q, ef[q]);
+            for (int q = kMaxPT; q < npt; ++q) {
+                bf16x8 et[KS];
+                load_e(wave + 4 * q, et);
+                repair(wave + 4 * q, et);
+            }
+        }
+        if (dead) break;
+    }
+}
+
+template <int NS, int NC, bool GATHER>
+int launch(const SegArgs &a, hipStream_t st) {
+    const int nunits = a.nseg * a.wg_per_seg;
+    const size_t smem = sizeof(LdsS<NS, NC>);
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&ssd_seg_kernel<NS, NC, GATHER>), smem)) return STRD_EHIP;
+    ssd_seg_kernel<NS, NC, GATHER><<<xcd_grid(nunits), threads_for(NC), smem, st>>>(a, nunits);
+    if (a.nseg > 1) ssd_fix_kernel<NS, GATHER><<<dim3(a.nseg, a.H, kFixZ), kFixThreads, 0, st>>>(a);
+    return launch_status();
+}
+
+// channels per workgroup / 32: the whole head when that divides, else one slab
+int slabs_per_wg(int P) { return P % 64 == 0 ? 2 : 1; }
+
+}  // namespace
+
+// How the sequence is cut: as many segments as it takes to give every CU a workgroup, each at least
+// kMinSegSteps steps long (a shorter segment costs more in its prologue and at its seam than it gains).
+void ssd_seg_plan(int T, int H, int P, int *nseg, int *seg_steps) {
+    constexpr int kMinSegSteps = 8, kCUs = 256;
+    const int nsteps = (T + kQ - 1) / kQ;
+    const int wg = H * (P / 32) / slabs_per_wg(P);
+    int s = wg >= kCUs ? 1 : (kCUs + wg - 1) / wg;
+    s = max(1, min(s, nsteps / kMinSegSteps));
+    const int per = (nsteps + s - 1) / s;
+    *seg_steps = max(per, 1);
+    *nseg = max(1, (nsteps + *seg_steps - 1) / *seg_steps);
+}
+
+size_t ssd_seg_ws(int T, int H, int P, int n) {
+    int nseg, seg_steps;
+    ssd_seg_plan(T, H, P, &nseg, &seg_steps);
+    if (nseg <= 1) return 0;
+    return align_up((size_t)(nseg - 1) * H * P * n * sizeof(float), 256) + align_up((size_t)nseg * H * sizeof(float), 256);
+}
+
+// `rows` = number of rows of the source tensors (T for the dense call, N + M for the gather call)
+bool ssd_seg_supported(int T, int rows, int H, int P, int G, int n, strd_dtype io) {
+    const unsigned long long lim = 1ull << 32, r = (unsigned long long)(rows > T ? rows : T) + 2 * kQ;
+    return io == STRD_BF16 && T >= 1 && (n == 64 || n == 128) && P % 32 == 0 && (long long)H * (P / 32) < (1 << 22) &&
+           r * H * 4 < lim && H <= 65535;
+}
+
+// Whether this kernel or the one that walks the whole sequence in one workgroup per (head, 32
+// channels) (ssd_mfma) is the faster one.  This kernel moves about half the bytes per token through
+// a CU's copy path (B and C tiles serve the whole head) and fills the chip with few heads, but pays
+// for its segments with a longer prologue and a second launch: it wins once a segment is long
+// (measured: from about 32 steps at 128 heads), or when the other kernel would leave CUs idle.
+bool ssd_seg_preferred(int T, int H, int P) {
+    int nseg, seg_steps;
+    ssd_seg_plan(T, H, P, &nseg, &seg_steps);
+    return nseg >= 2 && (seg_steps >= 32 || H * (P / 32) < 128);
+}
+
+int ssd_seg(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
+            const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G, int n,
+            void *ws, hipStream_t st) {
+    SegArgs a;
+    a.x = (const bf16_t *)x; a.dt = dt; a.A = A; a.B = (const bf16_t *)B; a.C = (const bf16_t *)C; a.D = D; a.S_in = S_in;
+    a.y = (bf16_t *)y; a.S_out = S_out; a.idx = idx; a.N = N; a.K = K; a.T = T; a.H = H; a.P = P; a.G = G;
+    ssd_seg_plan(T, H, P, &a.nseg, &a.seg_steps);
+    const int nc = slabs_per_wg(P);
+    a.wg_per_seg = H * (P / 32) / nc;
+    a.lend = a.ltot = nullptr;
+    if (a.nseg > 1) {
+        if (!ws) return STRD_EWORKSPACE;
+        a.lend = (float *)ws;
+        a.ltot = (float *)((char *)ws + align_up((size_t)(a.nseg - 1) * H * P * n * sizeof(float), 256));
+    }
+#define STRD_SEG_LAUNCH(NS_, NC_)                                                      \
+    return idx ? launch<NS_, NC_, true>(a, st) : launch<NS_, NC_, false>(a, st)
+    if (n == 128 && nc == 2) { STRD_SEG_LAUNCH(128, 2); }
+    if (n == 128 && nc == 1) { STRD_SEG_LAUNCH(128, 1); }
+    if (n == 64 && nc == 2) { STRD_SEG_LAUNCH(64, 2); }
+    if (n == 64 && nc == 1) { STRD_SEG_LAUNCH(64, 1); }
+#undef STRD_SEG_LAUNCH
+    return STRD_EUNSUPPORTED;
+}
+
+}  // namespace strd

@@ -293,6 +293,43 @@ def test_ssd_prefill_step_boundaries(T):
     assert torch.equal(y_g, y) and torch.equal(S_g, S), "the gathering scan must give the bits of compact + scan"
 
 
+@pytest.mark.parametrize("a_scale", [1.0, 1e-3, 0.0])
+@pytest.mark.parametrize("T,H,P,G,n", [(1600, 4, 64, 2, 128), (2085, 4, 64, 1, 128), (1100, 6, 96, 2, 64), (1300, 2, 128, 1, 64)])
+def test_ssd_prefill_segments_of_the_sequence(T, H, P, G, n, a_scale):
+    """Few heads and a long sequence: the kernel cuts the sequence into segments that run side by
+    side and repairs the seams afterwards.  With the workload's A the state at a seam dies within a
+    few tokens; with A scaled down, or A = 0 (no decay at all), it reaches across whole segments and
+    through several seams.  Dense with D and a carried-in state, and through an index list."""
+    _say("ssd_prefill segments T=%d H=%d P=%d G=%d n=%d A x %g" % (T, H, P, G, n, a_scale))
+    g = torch.Generator().manual_seed(T + H)
+    M = 19
+    K = T - M
+    N = K + K // 3 + 5
+    rows = N + M
+    x = torch.randn(rows, H, P, generator=g).to(torch.bfloat16)
+    B = (torch.randn(rows, G, n, generator=g) / n ** 0.5).to(torch.bfloat16)
+    C = torch.randn(rows, G, n, generator=g).to(torch.bfloat16)
+    dt = torch.nn.functional.softplus(torch.randn(rows, H, generator=g))
+    A = -torch.exp(2 * torch.rand(H, generator=g)) * a_scale
+    D = torch.randn(H, generator=g)
+    S_in = torch.randn(H, P, n, generator=g)
+    idx = torch.sort(torch.randperm(N, generator=g)[:K]).values.to(torch.int32)
+    keep = torch.cat([idx.long(), torch.arange(N, rows)])
+    f = synth.np64
+    y_ref, S_ref = oracle.ssd_seq(f(x[keep]), f(dt[keep]), f(A), f(B[keep]), f(C[keep]), f(D), f(S_in))
+    dev = lambda t: t.to(DEV)
+    y, S = strd.ssd_prefill(dev(x[keep].contiguous()), dev(dt[keep].contiguous()), dev(A), dev(B[keep].contiguous()),
+                            dev(C[keep].contiguous()), D=dev(D), S_in=dev(S_in))
+    assert_close(f(y), y_ref, TOL[torch.bfloat16], "y", units=(1,))
+    assert_close(f(S), S_ref, TOL[torch.bfloat16], "S_out", units=(0,))
+    y_g, S_g = strd.ssd_prefill_gather(dev(x), dev(dt), dev(A), dev(B), dev(C), dev(idx), N, M, D=dev(D), S_in=dev(S_in))
+    assert torch.equal(y_g, y) and torch.equal(S_g, S), "the gathering scan must give the bits of compact + scan"
+    # without a state output the seams are repaired all the same
+    y2, none = strd.ssd_prefill(dev(x[keep].contiguous()), dev(dt[keep].contiguous()), dev(A), dev(B[keep].contiguous()),
+                                dev(C[keep].contiguous()), D=dev(D), S_in=dev(S_in), want_state=False)
+    assert none is None and torch.equal(y2, y)
+
+
 def test_ssd_prefill_split_call_continues_the_scan():
     w = MAMBA_CASES["c2-short"]
     _say("ssd_prefill split call")
