@@ -14,8 +14,8 @@
 // chunk is copied global -> LDS asynchronously (no register staging) during the current one.
 // Two shapes: 4 waves that request their own copies and 64-key chunks (two workgroups per CU) for
 // short sequences; 8 computing waves, 4 copy waves and 128-key chunks (one workgroup per CU) for
-// long ones.  Workgroups are issued longest-first (last query block first), heads of one kv group
-// adjacent.
+// long ones.  Workgroups are issued longest-first (last query block first), the query heads of one
+// kv group back to back on one XCD.
 #include "common.h"
 
 namespace strd {
@@ -68,7 +68,21 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
     const float lazy_raw = kLazy / scale2;  // the slack of the softmax reference, in raw score units
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
-    const int h = blockIdx.x % Hq, qb = nqb - 1 - blockIdx.x / Hq, kvh = h / (Hq / Hkv);
+    // Workgroup b runs on XCD b % 8, each with an L2 of its own.  When the kv heads divide evenly over
+    // the XCDs, all query heads and query blocks of one kv head go to one XCD, so its K and V stream
+    // through one L2 (and the query heads of the group, issued back to back, share each chunk there)
+    // instead of through all eight; otherwise heads are simply dealt round.  Longest blocks first.
+    int h, qb;
+    if (Hkv % kXcd == 0) {
+        const int xcd = blockIdx.x % kXcd, j = blockIdx.x / kXcd, per = Hkv / kXcd, gq = Hq / Hkv;
+        const int r = j / per;
+        h = (xcd + kXcd * (j % per)) * gq + r % gq;
+        qb = nqb - 1 - r / gq;
+    } else {
+        h = blockIdx.x % Hq;
+        qb = nqb - 1 - blockIdx.x / Hq;
+    }
+    const int kvh = h / (Hq / Hkv);
     const int t0 = qb * kBM;
     const int tq = t0 + 32 * w + lc;             // this lane's query position
     // first query of the wave, in a scalar register so that tests on it are real branches (the wave

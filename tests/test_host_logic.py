@@ -144,13 +144,13 @@ def test_synthetic_inputs_are_seeded_and_shaped():
 
 
 def test_kernels_with_split_lds_reads_do_not_spill():
-    """ssd_mfma.hip and attn_mfma.hip issue LDS reads from inline assembly and wait for them later;
+    """ssd_mfma.hip, ssd_seg_mfma.hip and attn_mfma.hip issue LDS reads from inline assembly and wait for them later;
     between the two the compiler believes the destination registers hold their values.  A spill of
     such a register before the wait would save garbage, so these kernels must fit their register
     budget without scratch memory.  The compiler's own resource report is the check."""
     import subprocess
     from paper_2603_00198_amd import build as strd_build
-    for name in ("ssd_mfma.hip", "attn_mfma.hip"):
+    for name in ("ssd_mfma.hip", "ssd_seg_mfma.hip", "attn_mfma.hip"):
         src = os.path.join(strd_build.CSRC, name)
         cmd = [strd_build.HIPCC] + strd_build.FLAGS + ["--cuda-device-only", "-c", src, "-o", os.devnull,
                                                        "-Rpass-analysis=kernel-resource-usage"]
