@@ -6,13 +6,23 @@
 // A operand, and folds |acc| into one running sum per lane, so the reduction over text rows
 // costs no cross-lane traffic until a single lane-half exchange at the end.
 //
-// Kernel 1: one workgroup = 4 waves = 128*CT consecutive tokens of ONE group (grid = token
+// Two kernels make the group partials a[g][i].
+// Short sequences: one workgroup = 4 waves = 128*CT consecutive tokens of ONE group (grid = token
 // tiles x groups, so even 8192 tokens give 512 workgroups); the text tile (128 rows) is
 // double-buffered in LDS, filled by asynchronous global -> LDS copies, shared by the 4 waves.
-// It writes a[g][i] = sum_m |b_i^g . c_m^g|.  Kernel 2: 16 lanes per token sum dt_i^h * a[g(h)][i]
+// It writes a[g][i] = sum_m |b_i^g . c_m^g|, and 16 lanes per token then sum dt_i^h * a[g(h)][i]
 // over the heads and scale.
+// Long sequences: one workgroup per CU keeps all text rows of its group in LDS and its 8 waves
+// walk a slice of the tokens with no barriers (score_mamba_res_kernel below); the dt sum of the
+// group is folded in there, and a small kernel adds the groups and scales.
 // No atomics, fixed summation order: bit-reproducible.  HBM traffic is one pass over B_vis and
 // dt_vis; C_txt (M*n*2 bytes per group) is re-read per workgroup from L2.
+// With Gaussian operands the products run at about half the nominal matrix-core rate on this
+// part whatever feeds them (the same loop on register-resident random operands, with no loads
+// at all, takes as long; on low-entropy operands it takes half as long): the clock under
+// full-rate products of random data is what bounds the long-sequence kernel, not its loads.
+#include <algorithm>
+
 #include "common.h"
 
 namespace strd {
@@ -202,6 +212,206 @@ __global__ __launch_bounds__(kThreads) void score_mamba_full_reduce_kernel(const
     s[i] = tot * norm;
 }
 
+// ---- long sequences: the text rows of a group stay resident in LDS ------------------------------
+// One workgroup = 8 waves = one group x one slice of the vision tokens (grid = slices x groups,
+// at most one workgroup per CU).  The group's text rows are copied into LDS once (up to
+// kResBytes of them at a time), after which the waves share nothing: each takes token tiles of
+// 32*CT tokens in turn, loads their b fragments and the group's dt values straight from global
+// memory, and runs through all text rows with no barrier.  Products for the next 32 text rows
+// are issued before the previous accumulators are folded, so the |acc| additions run under the
+// matrix-core work.  It writes a[g][i] = (sum_{h in g} dt_i^h) * sum_m |b_i^g . c_m^g|; the sum over
+// groups and the scale are a second, small kernel.  The workgroups of one slice are dealt to one
+// XCD, so that the dt rows (each group reads its own 4*H/G bytes of every row) meet in one L2.
+typedef int strd_i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kResThreads = 512;
+constexpr int kResBytes = 156 * 1024;  // LDS for text rows (160 KB per CU less a little for the runtime)
+
+template <int NS>
+constexpr int res_max_rows() { return kResBytes / ((NS / 8 + 1) * 16) / 32 * 32; }
+
+template <int NS, int CT>
+__global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16_t *__restrict__ Bv,
+                                                                      const bf16_t *__restrict__ Ct,
+                                                                      const float *__restrict__ dtv,
+                                                                      float *__restrict__ part, int M, int N, int G,
+                                                                      int H, int slices, int slice_len) {
+    constexpr int KS = NS / 16, VR = NS / 8, VP = VR + 1, kPitch = VP * 8, kRows = res_max_rows<NS>();
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const bf16_t *text = reinterpret_cast<const bf16_t *>(smem_raw);
+
+    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int slice, g;
+    if (slices % kXcd == 0) {  // workgroup b runs on XCD b % 8: keep the groups of a slice together
+        const int j = blockIdx.x / kXcd;
+        g = j % G;
+        slice = (blockIdx.x % kXcd) * (slices / kXcd) + j / G;
+    } else {
+        g = blockIdx.x % G;
+        slice = blockIdx.x / G;
+    }
+    const int t_begin = slice * slice_len, t_end = min(N, t_begin + slice_len);
+    const int ntile = (t_end - t_begin + 32 * CT - 1) / (32 * CT);
+    const int hpg = H / G;
+
+    for (int m0 = 0; m0 < M; m0 += kRows) {
+        const int rows = min(kRows, M - m0);  // valid text rows of this pass
+        const int nmt = (rows + 31) / 32;  // 32-row products
+        if (m0 > 0) __syncthreads();  // every wave is done with the previous rows
+        // rows past the last one are zeros, so their products add nothing
+        const int slots = nmt * 32 * VP;
+        for (int s0 = w * 64; s0 < slots; s0 += (kResThreads / kWave) * 64) {
+            const int s = s0 + lane, r = s / VP, cv = s % VP;
+            if (s < slots && cv < VR) {
+                if (r < rows)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(Ct + ((size_t)(m0 + r) * G + g) * NS + cv * 8),
+                        (__attribute__((address_space(3))) void *)(smem_raw + (size_t)s0 * 16), 16, 0, 0);
+                else
+                    *reinterpret_cast<strd_i32x4 *>(smem_raw + (size_t)s * 16) = strd_i32x4{0, 0, 0, 0};
+            }
+        }
+        async_tile_wait();
+        __syncthreads();
+
+        // b fragments of a tile: lane = token column, 8 consecutive k (lanes past the end repeat the last token)
+        auto load_b = [&](int tt, bf16x8(&bf)[CT][KS]) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const int t = min(t_begin + tt * (32 * CT) + 32 * ct + lc, N - 1);
+                const bf16_t *bp = Bv + ((size_t)t * G + g) * NS + 8 * half;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) bf[ct][ks] = *reinterpret_cast<const bf16x8 *>(bp + 16 * ks);
+            }
+        };
+        bf16x8 bfr[CT][KS];
+        load_b(w, bfr);
+        for (int tt = w; tt < ntile; tt += kResThreads / kWave) {
+            const int tok0 = t_begin + tt * (32 * CT);
+            // the fragments of this wave's next tile are requested now and used after this tile's
+            // products (past the last tile they re-read the sequence's last token and are dropped)
+            bf16x8 bnx[CT][KS];
+            load_b(tt + kResThreads / kWave, bnx);
+            // last pass: the dt values of the group; each half of the wave sums one half of them.
+            // With 16 heads per group the loads are issued here and used after the products.
+            const bool last = m0 + kRows >= M;
+            const bool dt16 = hpg == 16;  // rows of 16*G floats from a 16-byte aligned base: float4 loads
+            float4 dq[CT][2];
+            if (last && dt16) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const float4 *d4 = reinterpret_cast<const float4 *>(
+                        dtv + (size_t)min(tok0 + 32 * ct + lc, N - 1) * H + g * 16 + half * 8);
+                    dq[ct][0] = d4[0];
+                    dq[ct][1] = d4[1];
+                }
+            }
+            // Per 32 text rows: the products of token block 0 while the accumulator of the last
+            // block (previous rows) is folded, then block 1 while block 0 is folded, ...  Each of
+            // the KS pieces of a text row is replaced by the piece of the row 32 further on right
+            // after its last product, a whole block of products before it is needed.
+            float part_sum[CT];
+            f32x16 acc[CT];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                part_sum[ct] = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[ct][i] = 0.f;
+            }
+            const bf16_t *ap = text + lc * kPitch + 8 * half;
+            bf16x8 a[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) a[ks] = *reinterpret_cast<const bf16x8 *>(ap + 16 * ks);
+            auto fold = [&](int ct) {
+                float t = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t += fabsf(acc[ct][i]);
+                part_sum[ct] += t;
+            };
+            for (int mt = 0; mt < nmt; ++mt) {
+                const bf16_t *np = ap + (size_t)min(mt + 1, nmt - 1) * 32 * kPitch;
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    f32x16 c;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) c[i] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bfr[ct][ks], c, 0, 0, 0);
+                        if (ct == CT - 1) a[ks] = *reinterpret_cast<const bf16x8 *>(np + 16 * ks);
+                    }
+                    fold(ct == 0 ? CT - 1 : ct - 1);  // a block whose products are complete (zeros the first time)
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (ct == CT - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 16 / KS, 0);
+                    }
+                    acc[ct] = c;
+                }
+            }
+            fold(CT - 1);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) bfr[ct][ks] = bnx[ct][ks];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                float col = part_sum[ct] + __shfl_xor(part_sum[ct], 32, kWave);
+                const int t = tok0 + 32 * ct + lc;
+                float *dst = part + (size_t)g * N + t;
+                const bool mine = half == 0 && t < t_end;
+                if (m0 > 0 && mine) col += *dst;
+                if (last) {
+                    float a = 0.f;
+                    if (dt16) {
+                        a = ((dq[ct][0].x + dq[ct][0].y) + (dq[ct][0].z + dq[ct][0].w)) +
+                            ((dq[ct][1].x + dq[ct][1].y) + (dq[ct][1].z + dq[ct][1].w));
+                    } else {
+                        const float *dp = dtv + (size_t)min(t, N - 1) * H + g * hpg;
+                        for (int j = half; j < hpg; j += 2) a += dp[j];
+                    }
+                    col *= a + __shfl_xor(a, 32, kWave);
+                }
+                if (mine) *dst = col;
+            }
+        }
+    }
+}
+
+// Token slices of the resident-text kernel: as many as fill the CUs, a multiple of 8 when
+// possible (XCD placement), each a whole number of 32*CT-token tiles.
+inline void res_plan(int N, int G, int ct, int *slices, int *slice_len) {
+    int want = std::max(1, 256 / G);
+    if (want >= kXcd) want = want / kXcd * kXcd;
+    const int tile = 32 * ct;
+    int len = (ceil_div(N, want) + tile - 1) / tile * tile;
+    int ns = ceil_div(N, len);
+    if (ns >= kXcd && ns % kXcd) {  // a little shorter slices so that their number is a multiple of 8 again
+        const int up = (ns + kXcd - 1) / kXcd * kXcd;
+        const int len2 = (ceil_div(N, up) + tile - 1) / tile * tile;
+        if (ceil_div(N, len2) % kXcd == 0) { len = len2; ns = ceil_div(N, len2); }
+    }
+    *slices = ns;
+    *slice_len = len;
+}
+
+template <int NS, int CT>
+int launch_res(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, void *ws,
+               hipStream_t st) {
+    const int rows = std::min(res_max_rows<NS>(), (M + 31) / 32 * 32);
+    const size_t smem = (size_t)rows * (NS / 8 + 1) * 16;
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&score_mamba_res_kernel<NS, CT>), smem)) return STRD_EHIP;
+    int slices, slice_len;
+    res_plan(N, G, CT, &slices, &slice_len);
+    float *part = (float *)ws;
+    score_mamba_res_kernel<NS, CT><<<slices * G, kResThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, dt, part,
+                                                                         M, N, G, H, slices, slice_len);
+    score_mamba_full_reduce_kernel<<<ceil_div(N, kThreads), kThreads, 0, st>>>(part, s, N, G,
+                                                                             1.f / ((float)M * (float)H));
+    return launch_status();
+}
+
 template <int NS, int CT>
 int launch_full(const void *B, const void *C, const float *U, const float *V, float *s, int M, int N, int H, int G,
                 void *ws, hipStream_t st) {
@@ -243,6 +453,13 @@ size_t score_mamba_mfma_ws(int N, int G) { return align_up((size_t)G * N * sizeo
 
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
                      void *ws, hipStream_t st) {
+    // Long sequences: text rows resident in LDS, one workgroup per CU.  It pays once every wave
+    // has a few token tiles of its own (one slice = N / (256 / G) tokens, shared by 8 waves).
+    const long long per_slice = (long long)N / std::max(1, 256 / G);
+    if (per_slice >= 4096)
+        return n == 128 ? launch_res<128, 2>(B, C, dt, s, M, N, H, G, ws, st) : launch_res<64, 2>(B, C, dt, s, M, N, H, G, ws, st);
+    if (per_slice >= 512)
+        return n == 128 ? launch_res<128, 1>(B, C, dt, s, M, N, H, G, ws, st) : launch_res<64, 1>(B, C, dt, s, M, N, H, G, ws, st);
     // wide token tiles once there are enough of them to fill 256 CUs several times over
     const bool wide = (long long)N * G >= 256LL * 256 * 8;
     if (n == 128)

@@ -5,7 +5,9 @@ so that the tests can hand identical tensors to the HIP library and to the CPU
 oracle.  A sequence is N vision tokens (frames x tokens-per-frame) followed by
 M text tokens (paper Sec. 3.1).  Hidden states are Gaussian; the mixer inputs
 are seeded Gaussian projections of them (set-up glue, outside the library);
-dt = softplus(N(0,1)) > 0 and A = -exp(U(0,2)) < 0 per head.
+dt = softplus(N(0,1)) > 0 and A = -exp(U(0,2)) < 0 per head.  All random numbers come from
+torch's CPU generator, once, in fp32, whatever device the tensors then live on; the projections
+(fp32 matrix products, set-up only) run where the tensors are.
 
 The real workloads (long-video benchmarks at 256-512 frames) are not
 available offline; these tensors stand in for them.
@@ -88,30 +90,40 @@ def torch_dtype(name: str) -> torch.dtype:
     return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
 
 
-def _gen(seed: int, device) -> torch.Generator:
-    g = torch.Generator(device=device)
+def _gen(seed: int, device=None) -> torch.Generator:
+    """Every random number is drawn on the host (torch's CPU generator), whatever device the tensor
+    is for: a workload is the same tensor on every box.  `device` is accepted for the callers' sake."""
+    g = torch.Generator(device="cpu")
     g.manual_seed(int(seed))
     return g
+
+
+def _randn(g: torch.Generator, device, *shape) -> torch.Tensor:
+    return torch.randn(*shape, generator=g, dtype=torch.float32).to(device)
+
+
+def _rand(g: torch.Generator, device, *shape) -> torch.Tensor:
+    return torch.rand(*shape, generator=g, dtype=torch.float32).to(device)
 
 
 def hidden_states(w: Workload, device="cpu", seed: Optional[int] = None) -> torch.Tensor:
     """[N+M, d_model] fp32 hidden states (vision rows first)."""
     g = _gen(w.seed if seed is None else seed, device)
-    h = torch.randn(w.T, w.d_model, generator=g, device=device, dtype=torch.float32)
+    h = _randn(g, device, w.T, w.d_model)
     if w.frame_corr > 0.0:
         nf = (w.N + w.tokens_per_frame - 1) // w.tokens_per_frame
-        f = torch.randn(nf, w.d_model, generator=g, device=device, dtype=torch.float32)
+        f = _randn(g, device, nf, w.d_model)
         rho = w.frame_corr
         shared = f.repeat_interleave(w.tokens_per_frame, dim=0)[: w.N]
         h[: w.N] = rho * shared + (1.0 - rho * rho) ** 0.5 * h[: w.N]
     if w.outlier_frac > 0.0:
-        pick = torch.rand(w.N, generator=g, device=device) < w.outlier_frac
+        pick = _rand(g, device, w.N) < w.outlier_frac
         h[: w.N][pick] *= w.outlier_scale
     return h
 
 
 def _project(h: torch.Tensor, out_features: int, g: torch.Generator, rows: int = 16384) -> torch.Tensor:
-    wgt = torch.randn(h.shape[1], out_features, generator=g, device=h.device, dtype=torch.float32)
+    wgt = _randn(g, h.device, h.shape[1], out_features)
     wgt /= h.shape[1] ** 0.5
     out = torch.empty(h.shape[0], out_features, device=h.device, dtype=torch.float32)
     for r0 in range(0, h.shape[0], rows):
@@ -129,8 +141,8 @@ def mamba_inputs(w: Workload, hidden: torch.Tensor, seed: Optional[int] = None) 
     x = _project(hidden, s.H * s.P, g).to(dt_io).view(T, s.H, s.P)
     B = _project(hidden, s.G * s.n, g).to(dt_io).view(T, s.G, s.n)
     C = _project(hidden, s.G * s.n, g).to(dt_io).view(T, s.G, s.n)
-    dt = torch.nn.functional.softplus(torch.randn(T, s.H, generator=g, device=dev, dtype=torch.float32))
-    A = -torch.exp(2.0 * torch.rand(s.H, generator=g, device=dev, dtype=torch.float32))
+    dt = torch.nn.functional.softplus(_randn(g, dev, T, s.H))
+    A = -torch.exp(2.0 * _rand(g, dev, s.H))
     return {"x": x.contiguous(), "B": B.contiguous(), "C": C.contiguous(), "dt": dt.contiguous(), "A": A}
 
 
@@ -157,7 +169,7 @@ def mamba_block_weights(w: Workload, device="cpu", seed: int = 0) -> Dict[str, t
     g = _gen(1000 + seed, device)
     dt_ = torch_dtype(w.dtype)
     d_inner, gn = s.H * s.P, s.G * s.n
-    rn = lambda *shape: torch.randn(*shape, generator=g, device=device)
+    rn = lambda *shape: _randn(g, device, *shape)
     return {
         "norm_w": (1.0 + 0.1 * rn(w.d_model)).to(dt_),
         "W_z": (rn(w.d_model, d_inner) / w.d_model ** 0.5).to(dt_),
@@ -165,7 +177,7 @@ def mamba_block_weights(w: Workload, device="cpu", seed: int = 0) -> Dict[str, t
         "conv_w": (rn(d_inner + 2 * gn, CONV_WIDTH) / CONV_WIDTH ** 0.5).to(dt_),
         "conv_b": (0.1 * rn(d_inner + 2 * gn)).to(dt_),
         "dt_bias": rn(s.H).float(),
-        "A": -torch.exp(2.0 * torch.rand(s.H, generator=g, device=device)).float(),
+        "A": -torch.exp(2.0 * _rand(g, device, s.H)).float(),
         "D": rn(s.H).float(),
         "gnorm_w": (1.0 + 0.1 * rn(d_inner)).to(dt_),
         "W_out": (rn(d_inner, w.d_model) / d_inner ** 0.5).to(dt_),
@@ -177,7 +189,7 @@ def attn_block_weights(w: Workload, device="cpu", seed: int = 0) -> Dict[str, to
     s = w.attn
     g = _gen(2000 + seed, device)
     dt_ = torch_dtype(w.dtype)
-    rn = lambda *shape: torch.randn(*shape, generator=g, device=device)
+    rn = lambda *shape: _randn(g, device, *shape)
     return {
         "norm_w": (1.0 + 0.1 * rn(w.d_model)).to(dt_),
         "W_q": (rn(w.d_model, s.Hq * s.d) / w.d_model ** 0.5).to(dt_),

@@ -76,6 +76,32 @@ def test_attn_prefill_random_shape(seed):
     assert_close(f(o[rows]), oracle.attn(f(q), f(k), f(v), rows=rows), TOL[torch.bfloat16], "o", units=(0, 1))
 
 
+# N, M, G, H, n: sequences long enough for the kernel that keeps a group's text rows in LDS -- one
+# and two token blocks per wave, ragged token and text counts, more text rows than fit LDS at once
+# (two passes), head counts per group other than 16, a single group
+LONG_SCORE_CASES = [
+    (16411, 37, 8, 128, 128),
+    (40000, 200, 8, 128, 128),
+    (17000, 600, 8, 128, 128),
+    (33001, 1150, 8, 24, 64),
+    (66000, 129, 2, 32, 128),
+    (131075, 64, 1, 4, 64),
+    (140000, 96, 8, 64, 64),
+]
+
+
+@pytest.mark.parametrize("N,M,G,H,n", LONG_SCORE_CASES)
+def test_score_mamba_long_sequences(N, M, G, H, n):
+    """Eq. 4 (Decoupled Content Alignment) on long sequences, every token against the oracle."""
+    g = torch.Generator().manual_seed(N + M)
+    _say("score_mamba long N=%d M=%d G=%d H=%d n=%d" % (N, M, G, H, n))
+    Bv = (torch.randn(N, G, n, generator=g) / n ** 0.5).to(torch.bfloat16)
+    Ct = torch.randn(M, G, n, generator=g).to(torch.bfloat16)
+    dtv = torch.nn.functional.softplus(torch.randn(N, H, generator=g))
+    s = strd.score_mamba(_dev(Bv), _dev(Ct), _dev(dtv))
+    assert_close(s.cpu().numpy(), oracle.score_mamba(f(Bv), f(Ct), f(dtv)), TOL[torch.bfloat16], "score_mamba", units=(0,))
+
+
 @pytest.mark.parametrize("seed", SEEDS)
 def test_scores_and_selection_random_shape(seed):
     """Both scores (Eq. 3 and Eq. 4) against the oracle, and the selection on the device's own
