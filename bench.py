@@ -553,9 +553,36 @@ def variants(torch, strd, synth, dev):
         nbytes = 4 * T * a.Hkv * a.d
         out["attn_decode_step_c3_" + tag] = {"T": T, "us": us, "GBps": nbytes / us * 1e-3,
                                              "frac_hbm": nbytes / us * 1e-3 / HBM_PEAK_GBS}
+    # packed batch: 16 clips of 8 frames (2048 vision + 64 text tokens, 25 %) scored, selected and
+    # compacted by one set of launches, against the same 16 sequences one call at a time
+    nseq, nv, mt = 16, 2048, 64
+    seqs = [(nv, mt, nv // 4)] * nseq
+    rows = nseq * (nv + mt)
+    xs = torch.randn(rows, m.H, m.P, device=dev).to(torch.bfloat16)
+    Bs = (torch.randn(rows, m.G, m.n, device=dev) / m.n ** 0.5).to(torch.bfloat16)
+    Cs = torch.randn(rows, m.G, m.n, device=dev).to(torch.bfloat16)
+    dts = torch.rand(rows, m.H, device=dev) + 0.1
+    hs = torch.randn(rows, wm.d_model, device=dev).to(torch.bfloat16)
+
+    def packed():
+        sc = strd.score_mamba_varlen(Bs, Cs, dts, seqs)
+        ix = strd.select_topk_varlen(sc, seqs)
+        strd.compact_varlen([xs, Bs, Cs, dts, hs], ix, seqs)
+
+    def one_by_one():
+        for b in range(nseq):
+            r0 = b * (nv + mt)
+            sc = strd.score_mamba(Bs[r0:r0 + nv], Cs[r0 + nv:r0 + nv + mt], dts[r0:r0 + nv])
+            ix = strd.select_topk(sc, nv // 4)
+            strd.compact_batch([t[r0:r0 + nv + mt] for t in (xs, Bs, Cs, dts, hs)], ix, nv, mt)
+
+    us_p, us_1 = 1e3 * time_events(torch, packed, iters=10), 1e3 * time_events(torch, one_by_one, iters=10)
+    out["reduce_16_clips_of_2048"] = {"packed_us": us_p, "one_call_per_sequence_us": us_1, "gain": us_1 / us_p,
+                                      "input_tokens_per_s_packed": rows / (us_p * 1e-6)}
     out["note"] = ("average-pool baseline of the reduction-type ablation on the residual stream; one decode token from "
                    "the state / the key-value rows a prefill leaves (25% budget vs none); device time per call from a "
-                   "graph of 20 calls; not part of the timed step")
+                   "graph of 20 calls; score + select + compact of a packed batch of short sequences (one set of "
+                   "launches) against one call per sequence, event-timed; not part of the timed step")
     return out
 
 

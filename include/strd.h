@@ -186,6 +186,58 @@ int strd_compact_batch(const strd_compact_item *items, int n_items, const int32_
                        int K, const int32_t *pos_in, int32_t *pos_out, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * Packed batches of sequences -- scoring, selection and compaction (Sec. 3.1,
+ * "Layer-wise Token Importance" and the token selection after it) for several
+ * sequences of different lengths in one set of launches.  Each sequence is
+ * reduced on its own, exactly as by the single-sequence calls above; the
+ * point is that short sequences, whose calls are bound by launch latency,
+ * share their launches.
+ *
+ * Layout.  The per-token tensors of the sequences lie one after the other
+ * along the token axis (no padding): sequence b is rows
+ * [row0_b, row0_b + N_b + M_b), row0_b = sum over earlier sequences of
+ * (N + M), its N_b vision rows first, then its M_b text rows.  `seqs` is a
+ * HOST array of `nseq` descriptors, read before the call returns.
+ *   scores  [dev] [nseq, ld] fp32: row b holds the N_b scores of sequence b
+ *           (entries past N_b are not touched); ld >= every N_b, ld % 4 == 0.
+ *   idx     [dev] [sum of K_b] int32: the kept vision tokens of sequence b,
+ *           ascending and local to the sequence (0 .. N_b - 1), start at
+ *           offset sum of earlier K.
+ *   compacted tensors: sequence b is rows [o_b, o_b + K_b + M_b),
+ *           o_b = sum over earlier sequences of (K + M).
+ *   pos_out [dev] [sum of (K_b + M_b)] int32: row number inside its own
+ *           sequence's N_b + M_b input rows (pos_in == NULL), or
+ *           pos_in[row0_b + that row]; pos_in [dev] [sum of (N_b + M_b)].
+ * Requires 1 <= nseq <= STRD_VARLEN_MAX, every N_b >= 1, M_b >= 1,
+ * 1 <= K_b <= N_b (the scores ignore K_b; select and compact use it), and for
+ * strd_select_topk_varlen every N_b <= strd_select_topk_varlen_max_n()
+ * (32768: one workgroup per sequence), else STRD_EINVAL / STRD_EUNSUPPORTED.
+ * The same alignment rules as the single-sequence calls apply to the packed
+ * base pointers.  Tie-breaking, NaN handling and error behaviour are those of
+ * the single-sequence calls.
+ * ------------------------------------------------------------------------- */
+#define STRD_VARLEN_MAX 64
+typedef struct strd_seq {
+    int32_t N; /* vision tokens */
+    int32_t M; /* text tokens (they follow the vision tokens) */
+    int32_t K; /* vision tokens to keep */
+} strd_seq;
+size_t strd_score_attn_varlen_workspace(const strd_seq *seqs, int nseq, int Hq, int Hkv, int d, strd_dtype io);
+int strd_score_attn_varlen(const void *q_all /* [dev] [rows, Hq, d] */, const void *k_all /* [dev] [rows, Hkv, d] */,
+                           float *scores, int ld, const strd_seq *seqs, int nseq, int Hq, int Hkv, int d,
+                           float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream);
+size_t strd_score_mamba_varlen_workspace(const strd_seq *seqs, int nseq, int H, int G, int n, strd_dtype io);
+int strd_score_mamba_varlen(const void *B_all /* [dev] [rows, G, n] */, const void *C_all /* [dev] [rows, G, n] */,
+                            const float *dt_all /* [dev] [rows, H] */, float *scores, int ld,
+                            const strd_seq *seqs, int nseq, int H, int G, int n, strd_dtype io, void *ws,
+                            size_t ws_bytes, void *stream);
+int strd_select_topk_varlen_max_n(void);
+int strd_select_topk_varlen(const float *scores, int ld, const strd_seq *seqs, int nseq, int32_t *idx,
+                            void *stream);
+int strd_compact_varlen(const strd_compact_item *items, int n_items, const int32_t *idx, const strd_seq *seqs,
+                        int nseq, const int32_t *pos_in, int32_t *pos_out, void *stream);
+
+/* ---------------------------------------------------------------------------
  * ssd_prefill -- Mamba-2 mixer over T tokens (Eqs. "ssm_state_update",
  * "ssm_output"), per head h with group g(h):
  *     S_t = exp(dt_t * A) * S_{t-1} + x_t (dt_t * b_t)^T ,   y_t = S_t c_t (+ D x_t)

@@ -37,6 +37,13 @@ _SIGNATURES = {
     "strd_select_topk_noalloc": (_int, [_vp, _int, _int, _vp, _vp]),
     "strd_compact": (_int, [_vp, _vp, _vp, _int, _int, _int, _i64, _vp, _vp, _vp]),
     "strd_compact_batch": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp]),
+    "strd_score_attn_varlen_workspace": (_sz, [_vp, _int, _int, _int, _int, _int]),
+    "strd_score_attn_varlen": (_int, [_vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _f32, _int, _vp, _sz, _vp]),
+    "strd_score_mamba_varlen_workspace": (_sz, [_vp, _int, _int, _int, _int, _int]),
+    "strd_score_mamba_varlen": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _int, _vp, _sz, _vp]),
+    "strd_select_topk_varlen_max_n": (_int, []),
+    "strd_select_topk_varlen": (_int, [_vp, _int, _vp, _int, _vp, _vp]),
+    "strd_compact_varlen": (_int, [_vp, _int, _vp, _vp, _int, _vp, _vp, _vp]),
     "strd_ssd_prefill_workspace": (_sz, [_int] * 6 + [_int]),
     "strd_ssd_prefill": (_int, [_vp] * 9 + [_int] * 6 + [_int, _vp, _sz, _vp]),
     "strd_ssd_prefill_gather": (_int, [_vp] * 10 + [_int] * 8 + [_int, _vp, _sz, _vp]),
@@ -273,6 +280,95 @@ def compact_batch(srcs: Sequence[torch.Tensor], idx: torch.Tensor, N: int, M: in
     _check(lib().strd_compact_batch(ctypes.cast(items, _vp), len(srcs), _ptr(idx), N, M, K, _ptr(pos_in),
                                     _ptr(pos_out), _stream()), "compact_batch")
     return list(outs), pos_out
+
+
+# ---- packed batches of sequences: `seqs` is a list of (N, M, K) per sequence ----------------
+class _Seq(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("M", ctypes.c_int32), ("K", ctypes.c_int32)]
+
+
+def _seq_array(seqs):
+    arr = (_Seq * len(seqs))()
+    for i, (n, m, k) in enumerate(seqs):
+        arr[i].N, arr[i].M, arr[i].K = int(n), int(m), int(k)
+    return arr
+
+
+def _varlen_ld(seqs, ld):
+    return (max(int(n) for n, _, _ in seqs) + 3) // 4 * 4 if ld is None else int(ld)
+
+
+def score_attn_varlen(q_all: torch.Tensor, k_all: torch.Tensor, seqs, scale: Optional[float] = None,
+                      ld: Optional[int] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores [nseq, ld] fp32 of a packed batch: q_all [rows,Hq,d], k_all [rows,Hkv,d]."""
+    _dev(q_all, k_all, out)
+    rows, Hq, d = q_all.shape
+    Hkv = k_all.shape[1]
+    if k_all.shape[0] != rows or k_all.shape[2] != d or q_all.dtype != k_all.dtype \
+            or rows != sum(int(n) + int(m) for n, m, _ in seqs):
+        raise StrdError("score_attn_varlen: q/k/seqs mismatch")
+    io, ld, arr = _io(q_all), _varlen_ld(seqs, ld), _seq_array(seqs)
+    if scale is None:
+        scale = d ** -0.5
+    if out is None:
+        out = torch.zeros(len(seqs), ld, dtype=torch.float32, device=q_all.device)
+    ws, nb = _ws(lib().strd_score_attn_varlen_workspace(ctypes.cast(arr, _vp), len(seqs), Hq, Hkv, d, io), q_all)
+    _check(lib().strd_score_attn_varlen(_ptr(q_all), _ptr(k_all), _ptr(out), ld, ctypes.cast(arr, _vp), len(seqs), Hq, Hkv,
+                                        d, scale, io, _ptr(ws), nb, _stream()), "score_attn_varlen")
+    return out
+
+
+def score_mamba_varlen(B_all: torch.Tensor, C_all: torch.Tensor, dt_all: torch.Tensor, seqs,
+                       ld: Optional[int] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores [nseq, ld] fp32 of a packed batch: B_all, C_all [rows,G,n], dt_all [rows,H] fp32."""
+    _dev(B_all, C_all, dt_all, out)
+    rows, G, n = B_all.shape
+    H = dt_all.shape[1]
+    if C_all.shape != B_all.shape or dt_all.shape[0] != rows or dt_all.dtype != torch.float32 \
+            or B_all.dtype != C_all.dtype or rows != sum(int(a) + int(m) for a, m, _ in seqs):
+        raise StrdError("score_mamba_varlen: B/C/dt/seqs mismatch")
+    io, ld, arr = _io(B_all), _varlen_ld(seqs, ld), _seq_array(seqs)
+    if out is None:
+        out = torch.zeros(len(seqs), ld, dtype=torch.float32, device=B_all.device)
+    ws, nb = _ws(lib().strd_score_mamba_varlen_workspace(ctypes.cast(arr, _vp), len(seqs), H, G, n, io), B_all)
+    _check(lib().strd_score_mamba_varlen(_ptr(B_all), _ptr(C_all), _ptr(dt_all), _ptr(out), ld, ctypes.cast(arr, _vp),
+                                         len(seqs), H, G, n, io, _ptr(ws), nb, _stream()), "score_mamba_varlen")
+    return out
+
+
+def select_topk_varlen(scores: torch.Tensor, seqs, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """idx [sum K] int32: per sequence, the K_b best of scores[b, :N_b], ascending, local to the sequence."""
+    _dev(scores, out)
+    if scores.dtype != torch.float32 or scores.dim() != 2 or scores.shape[0] != len(seqs):
+        raise StrdError("select_topk_varlen: scores must be fp32 [nseq, ld]")
+    arr = _seq_array(seqs)
+    if out is None:
+        out = torch.empty(sum(int(k) for _, _, k in seqs), dtype=torch.int32, device=scores.device)
+    _check(lib().strd_select_topk_varlen(_ptr(scores), scores.shape[1], ctypes.cast(arr, _vp), len(seqs), _ptr(out),
+                                         _stream()), "select_topk_varlen")
+    return out
+
+
+def compact_varlen(srcs: Sequence[torch.Tensor], idx: torch.Tensor, seqs, pos_in: Optional[torch.Tensor] = None,
+                   want_pos: bool = False):
+    """One-launch gather of several packed [rows, ...] tensors; returns (dsts [sum(K+M), ...], pos_out or None)."""
+    _dev(idx, pos_in, *srcs)
+    rows = sum(int(n) + int(m) for n, m, _ in seqs)
+    rows_out = sum(int(k) + int(m) for _, m, k in seqs)
+    if idx.dtype != torch.int32 or idx.shape[0] != sum(int(k) for _, _, k in seqs):
+        raise StrdError("compact_varlen: idx must be int32 [sum K]")
+    outs = [torch.empty((rows_out,) + tuple(t.shape[1:]), dtype=t.dtype, device=t.device) for t in srcs]
+    items = (_CompactItem * max(len(srcs), 1))()
+    for i, (t, o) in enumerate(zip(srcs, outs)):
+        if t.shape[0] != rows:
+            raise StrdError("compact_varlen: tensor %d has the wrong number of rows" % i)
+        items[i].src, items[i].dst = t.data_ptr(), o.data_ptr()
+        items[i].row_bytes = int(torch.Size(t.shape[1:]).numel()) * t.element_size()
+    pos_out = torch.empty(rows_out, dtype=torch.int32, device=idx.device) if (want_pos or pos_in is not None) else None
+    arr = _seq_array(seqs)
+    _check(lib().strd_compact_varlen(ctypes.cast(items, _vp), len(srcs), _ptr(idx), ctypes.cast(arr, _vp), len(seqs),
+                                     _ptr(pos_in), _ptr(pos_out), _stream()), "compact_varlen")
+    return outs, pos_out
 
 
 def ssd_prefill(x: torch.Tensor, dt: torch.Tensor, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,

@@ -4,6 +4,8 @@
 
 #include <string.h>
 
+#include <algorithm>
+
 #include "common.h"
 
 using namespace strd;
@@ -133,6 +135,113 @@ int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, i
     if ((src == nullptr) != (dst == nullptr)) return STRD_EINVAL;
     strd_compact_item it = {src, dst, row_bytes};
     return strd_compact_batch(&it, src ? 1 : 0, idx, N, M, K, pos_in, pos_out, stream);
+}
+
+// ------------------------------------------------------------------ packed batches ---------
+namespace {
+struct SeqPlan {
+    SeqTab tab;
+    int max_n = 0, max_m = 0, max_out = 0;
+    long long rows = 0, kept = 0, out_rows = 0;
+};
+// Validates the caller's descriptors and lays the sequences out.  K is checked only where it is used.
+bool plan_seqs(const strd_seq *seqs, int nseq, bool need_k, SeqPlan &p) {
+    if (!seqs || nseq < 1 || nseq > STRD_VARLEN_MAX) return false;
+    for (int b = 0; b < nseq; ++b) {
+        const strd_seq &q = seqs[b];
+        if (q.N < 1 || q.M < 1) return false;
+        if (need_k && (q.K < 1 || q.K > q.N)) return false;
+        const int k = need_k ? q.K : 0;
+        if (p.rows + q.N + q.M > 0x7FFFFFFFLL) return false;
+        p.tab.row0[b] = (int)p.rows;
+        p.tab.N[b] = q.N;
+        p.tab.M[b] = q.M;
+        p.tab.K[b] = k;
+        p.tab.koff[b] = (int)p.kept;
+        p.tab.ooff[b] = (int)p.out_rows;
+        p.rows += q.N + q.M;
+        p.kept += k;
+        p.out_rows += k + q.M;
+        p.max_n = std::max(p.max_n, q.N);
+        p.max_m = std::max(p.max_m, q.M);
+        p.max_out = std::max(p.max_out, k + q.M);
+    }
+    for (int b = nseq; b < STRD_VARLEN_MAX; ++b)
+        p.tab.row0[b] = p.tab.N[b] = p.tab.M[b] = p.tab.K[b] = p.tab.koff[b] = p.tab.ooff[b] = 0;
+    return true;
+}
+}  // namespace
+
+size_t strd_score_attn_varlen_workspace(const strd_seq *seqs, int nseq, int Hq, int Hkv, int d, strd_dtype io) {
+    SeqPlan p;
+    if (!plan_seqs(seqs, nseq, false, p) || Hq < 1 || Hkv < 1 || Hq % Hkv) return 0;
+    if (score_attn_mfma_supported(p.max_m, p.max_n, Hq, Hkv, d, io))
+        return score_attn_mfma_varlen_ws(nseq, p.max_m, p.max_n, Hq, Hkv);
+    return align_up((size_t)nseq * p.max_m * Hq * sizeof(float), 256);
+}
+
+int strd_score_attn_varlen(const void *q_all, const void *k_all, float *scores, int ld, const strd_seq *seqs, int nseq,
+                           int Hq, int Hkv, int d, float scale, strd_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    SeqPlan p;
+    if (!q_all || !k_all || !scores || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv || !io_ok(io) ||
+        !plan_seqs(seqs, nseq, false, p) || ld < p.max_n || ld % 4 || (long long)p.max_m * Hq > (1 << 30))
+        return STRD_EINVAL;
+    const bool mfma = score_attn_mfma_supported(p.max_m, p.max_n, Hq, Hkv, d, io);
+    if (mfma && !aligned16(q_all, k_all, scores, ws)) return STRD_EINVAL;
+    const size_t need = strd_score_attn_varlen_workspace(seqs, nseq, Hq, Hkv, d, io);
+    if (!ws || ws_bytes < need) return STRD_EWORKSPACE;
+    if (mfma)
+        return score_attn_mfma_varlen(q_all, k_all, scores, ld, p.tab, nseq, p.max_m, p.max_n, Hq, Hkv, d, scale, ws,
+                                      as_stream(stream));
+    return score_attn_general_varlen(q_all, k_all, scores, ld, p.tab, nseq, p.max_m, p.max_n, Hq, Hkv, d, scale, io, ws,
+                                     as_stream(stream));
+}
+
+size_t strd_score_mamba_varlen_workspace(const strd_seq *seqs, int nseq, int H, int G, int n, strd_dtype io) {
+    SeqPlan p;
+    if (!plan_seqs(seqs, nseq, false, p) || H < 1 || G < 1 || H % G) return 0;
+    return score_mamba_mfma_supported(p.max_m, p.max_n, H, G, n, io) ? align_up((size_t)p.rows * G * sizeof(float), 256) : 0;
+}
+
+int strd_score_mamba_varlen(const void *B_all, const void *C_all, const float *dt_all, float *scores, int ld,
+                            const strd_seq *seqs, int nseq, int H, int G, int n, strd_dtype io, void *ws, size_t ws_bytes,
+                            void *stream) {
+    SeqPlan p;
+    // b and c are one packed tensor each; the library reads vision rows of B_all and text rows of C_all
+    if (!B_all || !C_all || !dt_all || !scores || H < 1 || G < 1 || n < 1 || H % G || !io_ok(io) ||
+        !plan_seqs(seqs, nseq, false, p) || ld < p.max_n || ld % 4)
+        return STRD_EINVAL;
+    const bool mfma = score_mamba_mfma_supported(p.max_m, p.max_n, H, G, n, io);
+    if (mfma && !aligned16(B_all, C_all, dt_all, scores, ws)) return STRD_EINVAL;
+    const size_t need = strd_score_mamba_varlen_workspace(seqs, nseq, H, G, n, io);
+    if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
+    if (mfma)
+        return score_mamba_mfma_varlen(B_all, C_all, dt_all, scores, ld, p.tab, nseq, p.max_n, H, G, n, ws,
+                                       as_stream(stream));
+    return score_mamba_general_varlen(B_all, C_all, dt_all, scores, ld, p.tab, nseq, p.max_n, H, G, n, io,
+                                      as_stream(stream));
+}
+
+int strd_select_topk_varlen_max_n(void) { return select_topk_varlen_max_n(); }
+
+int strd_select_topk_varlen(const float *scores, int ld, const strd_seq *seqs, int nseq, int32_t *idx, void *stream) {
+    SeqPlan p;
+    if (!scores || !idx || !plan_seqs(seqs, nseq, true, p) || ld < p.max_n || ld % 4 || !aligned16(scores))
+        return STRD_EINVAL;
+    if (p.max_n > select_topk_varlen_max_n()) return STRD_EUNSUPPORTED;
+    return select_topk_varlen_launch(scores, ld, p.tab, nseq, p.max_n, idx, as_stream(stream));
+}
+
+int strd_compact_varlen(const strd_compact_item *items, int n_items, const int32_t *idx, const strd_seq *seqs, int nseq,
+                        const int32_t *pos_in, int32_t *pos_out, void *stream) {
+    SeqPlan p;
+    if (!idx || !plan_seqs(seqs, nseq, true, p)) return STRD_EINVAL;
+    if (n_items < 0 || n_items > STRD_COMPACT_MAX || (n_items > 0 && !items)) return STRD_EINVAL;
+    if (n_items == 0 && !pos_out) return STRD_EINVAL;
+    for (int i = 0; i < n_items; ++i)
+        if (!items[i].src || !items[i].dst || items[i].row_bytes <= 0 || items[i].row_bytes % 4) return STRD_EINVAL;
+    if (p.out_rows > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+    return compact_varlen_launch(items, n_items, idx, p.tab, nseq, p.max_out, pos_in, pos_out, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ ssd_prefill ------------

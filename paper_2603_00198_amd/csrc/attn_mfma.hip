@@ -60,7 +60,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 template <int D, int NW, int NC, int KC>
 __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_eu(2, NC ? 3 : 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
-    int Hq, int Hkv, float scale2, int nqb) {
+    int Hq, int Hkv, float scale2, int nqb, int xcd_map) {
     constexpr int KS = D / 16, DT = D / 32, kBM = 32 * NW;
     using TileT = Tile<D, NC ? NC : NW, KC>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -72,17 +72,20 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
     // the XCDs, all query heads and query blocks of one kv head go to one XCD, so its K and V stream
     // through one L2 (and the query heads of the group, issued back to back, share each chunk there)
     // instead of through all eight; otherwise heads are simply dealt round.  Longest blocks first.
-    int h, qb;
-    if (Hkv % kXcd == 0) {
-        const int xcd = blockIdx.x % kXcd, j = blockIdx.x / kXcd, per = Hkv / kXcd, gq = Hq / Hkv;
-        const int r = j / per;
-        h = (xcd + kXcd * (j % per)) * gq + r % gq;
-        qb = nqb - 1 - r / gq;
+    // xcd_map: 0, or 1 + log2(kv heads per XCD) + 8 * log2(query heads per kv head) -- shifts and
+    // masks only, so the indices stay in scalar registers.
+    int h, qb, kvh;
+    if (xcd_map) {
+        const int ps = (xcd_map - 1) & 7, gs = (xcd_map - 1) >> 3;
+        const int xcd = blockIdx.x % kXcd, j = blockIdx.x / kXcd, r = j >> ps;
+        kvh = xcd + kXcd * (j & ((1 << ps) - 1));
+        h = (kvh << gs) + (r & ((1 << gs) - 1));
+        qb = nqb - 1 - (r >> gs);
     } else {
         h = blockIdx.x % Hq;
         qb = nqb - 1 - blockIdx.x / Hq;
+        kvh = h / (Hq / Hkv);
     }
-    const int kvh = h / (Hq / Hkv);
     const int t0 = qb * kBM;
     const int tq = t0 + 32 * w + lc;             // this lane's query position
     // first query of the wave, in a scalar register so that tests on it are real branches (the wave
@@ -262,9 +265,13 @@ int launch(const void *q, const void *k, const void *v, void *o, int T, int Hq, 
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_mfma_kernel<D, NW, NC, KC>), smem))
         return STRD_EHIP;
     const int nqb = ceil_div(T, 32 * NW);
+    // XCD-aware order when the kv heads per XCD and the query heads per kv head are powers of two
+    const int per = Hkv / kXcd, gq = Hq / Hkv;
+    const bool pow2 = Hkv % kXcd == 0 && (per & (per - 1)) == 0 && (gq & (gq - 1)) == 0 && per <= 128;
+    const int xcd_map = pow2 ? 1 + __builtin_ctz(per) + 8 * __builtin_ctz(gq) : 0;
     attn_mfma_kernel<D, NW, NC, KC><<<nqb * Hq, (NW + NC) * kWave, smem, st>>>((const bf16_t *)q, (const bf16_t *)k,
                                                                         (const bf16_t *)v, (bf16_t *)o, T, Hq, Hkv,
-                                                                        scale * kLog2e, nqb);
+                                                                        scale * kLog2e, nqb, xcd_map);
     return launch_status();
 }
 

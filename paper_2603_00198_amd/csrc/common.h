@@ -34,6 +34,19 @@ __device__ __forceinline__ int xcd_swizzle(int b, int n) {
 }
 __host__ __forceinline__ int xcd_grid(int n) { return (n + kXcd - 1) / kXcd * kXcd; }
 
+// ---- packed batches of sequences (the *_varlen entry points) ---------------------------------
+// The per-token tensors of several sequences lie one after the other along the token axis:
+// sequence b is rows [row0[b], row0[b] + N[b] + M[b]), vision rows first.  The table travels in
+// the kernel arguments; a kernel instantiated with OneSeq takes its tensors as one sequence.
+constexpr int kMaxSeqs = STRD_VARLEN_MAX;
+struct OneSeq {};
+struct SeqTab {
+    int row0[kMaxSeqs], N[kMaxSeqs], M[kMaxSeqs], K[kMaxSeqs];
+    int koff[kMaxSeqs];  // retained vision tokens of the sequences before b (offset into the index list)
+    int ooff[kMaxSeqs];  // rows of the compacted tensors before b
+};
+template <class SEQ> constexpr bool is_varlen() { return std::is_same<SEQ, SeqTab>::value; }
+
 // ---- asynchronous global -> LDS tile copy (no VGPR staging) ---------------------------------
 // A tile is ROWS rows of VR 16-byte vectors, stored in LDS with PAD pad vectors per row (pitch
 // VR + PAD vectors, which keeps 16-byte row reads and transposing reads off each other's banks).
@@ -200,6 +213,21 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? STRD_OK : 
 // ---- entry points of the individual kernel files (all enqueue on `s`, return strd_status) ----
 int compact_launch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
                    const int32_t *pos_in, int32_t *pos_out, hipStream_t s);
+// packed batches: maxima over the sequences size the grids, the table says what each workgroup owns
+int compact_varlen_launch(const strd_compact_item *items, int n_items, const int32_t *idx, const SeqTab &tab, int nseq,
+                          int max_rows_out, const int32_t *pos_in, int32_t *pos_out, hipStream_t s);
+int select_topk_varlen_max_n();
+int select_topk_varlen_launch(const float *scores, int ld, const SeqTab &tab, int nseq, int max_n, int32_t *idx,
+                              hipStream_t s);
+int score_mamba_general_varlen(const void *B, const void *C, const float *dt, float *s, int ld, const SeqTab &tab, int nseq, int max_n,
+                               int H, int G, int n, strd_dtype io, hipStream_t st);
+int score_mamba_mfma_varlen(const void *B, const void *C, const float *dt, float *s, int ld, const SeqTab &tab, int nseq, int max_n,
+                            int H, int G, int n, void *ws, hipStream_t st);
+int score_attn_general_varlen(const void *q, const void *k, float *s, int ld, const SeqTab &tab, int nseq, int max_m,
+                              int max_n, int Hq, int Hkv, int d, float scale, strd_dtype io, void *ws, hipStream_t st);
+size_t score_attn_mfma_varlen_ws(int nseq, int max_m, int max_n, int Hq, int Hkv);
+int score_attn_mfma_varlen(const void *q, const void *k, float *s, int ld, const SeqTab &tab, int nseq, int max_m,
+                           int max_n, int Hq, int Hkv, int d, float scale, void *ws, hipStream_t st);
 size_t select_topk_ws(int N);
 int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws, hipStream_t s);
 int select_topk_static_max_n();

@@ -28,11 +28,14 @@ struct Batch {
     Item item[STRD_COMPACT_MAX + 1];
 };
 
+// Rows of one sequence: source rows count from src_row0, output rows from dst_row0 (both 0 for a
+// single sequence).
 template <typename Vec>
-__device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restrict__ idx, int N, int K, int rows_out) {
-    const Vec *__restrict__ src = reinterpret_cast<const Vec *>(it.src);
-    Vec *__restrict__ dst = reinterpret_cast<Vec *>(it.dst);
+__device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restrict__ idx, int N, int K, int rows_out,
+                                          size_t src_row0 = 0, size_t dst_row0 = 0) {
     const int vpr = it.vec_per_row;
+    const Vec *__restrict__ src = reinterpret_cast<const Vec *>(it.src) + src_row0 * vpr;
+    Vec *__restrict__ dst = reinterpret_cast<Vec *>(it.dst) + dst_row0 * vpr;
     const int row0 = blockIdx.x * it.rows_per_block;
     if (row0 >= rows_out) return;
     const int nrows = min(it.rows_per_block, rows_out - row0);
@@ -71,14 +74,30 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(Batch b, const int32_
     }
 }
 
+// Packed batch: blockIdx.z selects the sequence.  Positions are local to the sequence (row number
+// among its own N + M input rows), or pos_in of that row.
+__global__ __launch_bounds__(kThreads) void compact_varlen_kernel(Batch b, const int32_t *__restrict__ idx, SeqTab tab) {
+    const Item &it = b.item[blockIdx.y];
+    const int q = blockIdx.z;
+    const int N = tab.N[q], K = tab.K[q], rows_out = K + tab.M[q];
+    const int32_t *ix = idx + tab.koff[q];
+    if (it.identity) {
+        const int r = blockIdx.x * kThreads + threadIdx.x;
+        if (r < rows_out) reinterpret_cast<int32_t *>(it.dst)[tab.ooff[q] + r] = (r < K) ? ix[r] : (N + (r - K));
+    } else if (it.vec16) {
+        copy_rows<u32x4>(it, ix, N, K, rows_out, tab.row0[q], tab.ooff[q]);
+    } else {
+        copy_rows<uint32_t>(it, ix, N, K, rows_out, tab.row0[q], tab.ooff[q]);
+    }
+}
+
 }  // namespace
 
-int compact_launch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
-                   const int32_t *pos_in, int32_t *pos_out, hipStream_t s) {
-    const int rows_out = K + M;
-    if (rows_out == 0) return STRD_OK;
-    Batch b;
-    int n = 0, grid_x = 1;
+// Fills the launch table from the caller's items; returns the grid width for `rows_out` output rows.
+static int compact_plan(const strd_compact_item *items, int n_items, const int32_t *pos_in, int32_t *pos_out,
+                        int rows_out, Batch &b, int &n, int &grid_x) {
+    n = 0;
+    grid_x = 1;
     for (int i = 0; i < n_items; ++i) {
         const strd_compact_item &ci = items[i];
         Item it;
@@ -106,6 +125,29 @@ int compact_launch(const strd_compact_item *items, int n_items, const int32_t *i
         grid_x = max(grid_x, ceil_div(rows_out, pos_in ? it.rows_per_block : kThreads));
         b.item[n++] = it;
     }
+    return STRD_OK;
+}
+
+int compact_varlen_launch(const strd_compact_item *items, int n_items, const int32_t *idx, const SeqTab &tab, int nseq,
+                          int max_rows_out, const int32_t *pos_in, int32_t *pos_out, hipStream_t s) {
+    if (max_rows_out == 0 || nseq == 0) return STRD_OK;
+    Batch b;
+    int n, grid_x;
+    const int rc = compact_plan(items, n_items, pos_in, pos_out, max_rows_out, b, n, grid_x);
+    if (rc != STRD_OK) return rc;
+    if (n == 0) return STRD_OK;
+    compact_varlen_kernel<<<dim3(grid_x, n, nseq), kThreads, 0, s>>>(b, idx, tab);
+    return launch_status();
+}
+
+int compact_launch(const strd_compact_item *items, int n_items, const int32_t *idx, int N, int M, int K,
+                   const int32_t *pos_in, int32_t *pos_out, hipStream_t s) {
+    const int rows_out = K + M;
+    if (rows_out == 0) return STRD_OK;
+    Batch b;
+    int n, grid_x;
+    const int rc = compact_plan(items, n_items, pos_in, pos_out, rows_out, b, n, grid_x);
+    if (rc != STRD_OK) return rc;
     if (n == 0) return STRD_OK;
     compact_kernel<<<dim3(grid_x, n), kThreads, 0, s>>>(b, idx, N, K, rows_out);
     return launch_status();

@@ -23,11 +23,21 @@ __device__ __forceinline__ float wave_sum(float v) {
 // ------------------------------------------------------------------ score_attn -------------
 // Pass 1: one workgroup per (text row m, query head h): log-sum-exp of scale * q.k_i over the
 // N vision keys.  lse index = m * Hq + h.
-template <typename T>
+// SEQ = SeqTab (packed batch, blockIdx.y = sequence): q and k both point at the packed tensors,
+// lse has `lse_ld` entries per sequence.
+template <typename T, class SEQ>
 __global__ __launch_bounds__(kThreads) void attn_row_lse_kernel(const T *__restrict__ q, const T *__restrict__ k,
                                                                 float *__restrict__ lse, int N, int Hq, int Hkv,
-                                                                int d, float scale) {
+                                                                int d, float scale, SEQ seq, int lse_ld) {
     extern __shared__ float smem[];  // d floats of q, then 2 * waves
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        if ((int)blockIdx.x >= seq.M[b] * Hq) return;  // uniform
+        k += (size_t)seq.row0[b] * Hkv * d;
+        q += (size_t)(seq.row0[b] + N) * Hq * d;
+        lse += (size_t)b * lse_ld;
+    }
     const int row = blockIdx.x, h = row % Hq, hk = h / (Hq / Hkv);
     float *qs = smem;
     float *red = smem + d;
@@ -60,11 +70,21 @@ __global__ __launch_bounds__(kThreads) void attn_row_lse_kernel(const T *__restr
 }
 
 // Pass 2: one thread per vision token: sum over all (m, h) rows of exp(z - lse).
-template <typename T>
+template <typename T, class SEQ>
 __global__ __launch_bounds__(kThreads) void attn_col_sum_kernel(const T *__restrict__ q, const T *__restrict__ k,
                                                                 const float *__restrict__ lse,
                                                                 float *__restrict__ s, int M, int N, int Hq,
-                                                                int Hkv, int d, float scale) {
+                                                                int Hkv, int d, float scale, SEQ seq, int lse_ld,
+                                                                int ld) {
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        M = seq.M[b];
+        k += (size_t)seq.row0[b] * Hkv * d;
+        q += (size_t)(seq.row0[b] + N) * Hq * d;
+        lse += (size_t)b * lse_ld;
+        s += (size_t)b * ld;
+    }
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= N) return;
     const int rep = Hq / Hkv;
@@ -82,11 +102,20 @@ __global__ __launch_bounds__(kThreads) void attn_col_sum_kernel(const T *__restr
 
 // ------------------------------------------------------------------ score_mamba ------------
 // One thread per vision token: sum_g (sum_{h in g} dt_i^h) * sum_m |b_i^g . c_m^g|.
-template <typename T>
+template <typename T, class SEQ>
 __global__ __launch_bounds__(kThreads) void mamba_score_kernel(const T *__restrict__ Bv, const T *__restrict__ Ct,
                                                                const float *__restrict__ dtv,
                                                                float *__restrict__ s, int M, int N, int H, int G,
-                                                               int n) {
+                                                               int n, SEQ seq, int ld) {
+    if constexpr (is_varlen<SEQ>()) {  // blockIdx.y = sequence; Bv, Ct, dtv are the packed tensors
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        M = seq.M[b];
+        Bv += (size_t)seq.row0[b] * G * n;
+        Ct += (size_t)(seq.row0[b] + N) * G * n;
+        dtv += (size_t)seq.row0[b] * H;
+        s += (size_t)b * ld;
+    }
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= N) return;
     const int hpg = H / G;
@@ -206,18 +235,36 @@ __global__ __launch_bounds__(kThreads) void attn_row_kernel(const T *__restrict_
 // ------------------------------------------------------------------ host launchers ---------
 size_t score_attn_general_ws(int M, int Hq) { return align_up((size_t)M * Hq * sizeof(float), 256); }
 
+template <typename T, class SEQ>
+static void score_attn_launch(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale,
+                              float *lse, size_t sm, const SEQ &seq, int nseq, int ld, hipStream_t st) {
+    attn_row_lse_kernel<T, SEQ><<<dim3(M * Hq, nseq), kThreads, sm, st>>>((const T *)q, (const T *)k, lse, N, Hq, Hkv, d,
+                                                                         scale, seq, M * Hq);
+    attn_col_sum_kernel<T, SEQ><<<dim3(ceil_div(N, kThreads), nseq), kThreads, 0, st>>>((const T *)q, (const T *)k, lse, s,
+                                                                                      M, N, Hq, Hkv, d, scale, seq,
+                                                                                      M * Hq, ld);
+}
+
 int score_attn_general(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d,
                        float scale, strd_dtype io, void *ws, hipStream_t st) {
-    float *lse = (float *)ws;
     const size_t sm = (size_t)(d + 2 * (kThreads / kWave)) * sizeof(float);
     if (sm > 60000) return STRD_EUNSUPPORTED;
-    if (io == STRD_F32) {
-        attn_row_lse_kernel<float><<<M * Hq, kThreads, sm, st>>>((const float *)q, (const float *)k, lse, N, Hq, Hkv, d, scale);
-        attn_col_sum_kernel<float><<<ceil_div(N, kThreads), kThreads, 0, st>>>((const float *)q, (const float *)k, lse, s, M, N, Hq, Hkv, d, scale);
-    } else {
-        attn_row_lse_kernel<bf16_t><<<M * Hq, kThreads, sm, st>>>((const bf16_t *)q, (const bf16_t *)k, lse, N, Hq, Hkv, d, scale);
-        attn_col_sum_kernel<bf16_t><<<ceil_div(N, kThreads), kThreads, 0, st>>>((const bf16_t *)q, (const bf16_t *)k, lse, s, M, N, Hq, Hkv, d, scale);
-    }
+    if (io == STRD_F32)
+        score_attn_launch<float>(q, k, s, M, N, Hq, Hkv, d, scale, (float *)ws, sm, OneSeq(), 1, 0, st);
+    else
+        score_attn_launch<bf16_t>(q, k, s, M, N, Hq, Hkv, d, scale, (float *)ws, sm, OneSeq(), 1, 0, st);
+    return launch_status();
+}
+
+// Packed batch: grids sized for the longest sequence, lse of sequence b at ws + b * max_m * Hq floats.
+int score_attn_general_varlen(const void *q, const void *k, float *s, int ld, const SeqTab &tab, int nseq, int max_m,
+                              int max_n, int Hq, int Hkv, int d, float scale, strd_dtype io, void *ws, hipStream_t st) {
+    const size_t sm = (size_t)(d + 2 * (kThreads / kWave)) * sizeof(float);
+    if (sm > 60000) return STRD_EUNSUPPORTED;
+    if (io == STRD_F32)
+        score_attn_launch<float>(q, k, s, max_m, max_n, Hq, Hkv, d, scale, (float *)ws, sm, tab, nseq, ld, st);
+    else
+        score_attn_launch<bf16_t>(q, k, s, max_m, max_n, Hq, Hkv, d, scale, (float *)ws, sm, tab, nseq, ld, st);
     return launch_status();
 }
 
@@ -225,9 +272,23 @@ int score_mamba_general(const void *B, const void *C, const float *dt, float *s,
                         int G, int n, strd_dtype io, hipStream_t st) {
     const int grid = ceil_div(N, kThreads);
     if (io == STRD_F32)
-        mamba_score_kernel<float><<<grid, kThreads, 0, st>>>((const float *)B, (const float *)C, dt, s, M, N, H, G, n);
+        mamba_score_kernel<float, OneSeq><<<grid, kThreads, 0, st>>>((const float *)B, (const float *)C, dt, s, M, N, H, G, n,
+                                                                     OneSeq(), 0);
     else
-        mamba_score_kernel<bf16_t><<<grid, kThreads, 0, st>>>((const bf16_t *)B, (const bf16_t *)C, dt, s, M, N, H, G, n);
+        mamba_score_kernel<bf16_t, OneSeq><<<grid, kThreads, 0, st>>>((const bf16_t *)B, (const bf16_t *)C, dt, s, M, N, H, G,
+                                                                      n, OneSeq(), 0);
+    return launch_status();
+}
+
+int score_mamba_general_varlen(const void *B, const void *C, const float *dt, float *s, int ld, const SeqTab &tab, int nseq, int max_n,
+                               int H, int G, int n, strd_dtype io, hipStream_t st) {
+    const dim3 grid(ceil_div(max_n, kThreads), nseq);
+    if (io == STRD_F32)
+        mamba_score_kernel<float, SeqTab><<<grid, kThreads, 0, st>>>((const float *)B, (const float *)C, dt, s, 0, 0, H, G, n,
+                                                                     tab, ld);
+    else
+        mamba_score_kernel<bf16_t, SeqTab><<<grid, kThreads, 0, st>>>((const bf16_t *)B, (const bf16_t *)C, dt, s, 0, 0, H, G,
+                                                                      n, tab, ld);
     return launch_status();
 }
 

@@ -57,14 +57,26 @@ __device__ __forceinline__ size_t qrow_index(int r, int rep, int Hq, int kvh) {
 
 // ---------------------------------------------------------------------------------------------
 // pass 1: grid = row blocks (fastest) x kv heads x key slices
-template <int D>
+// SEQ = SeqTab (packed batch, blockIdx.y = sequence): q and k point at the packed tensors and every
+// sequence has `seq_stride` floats of pmax / psum of its own; the grid and the key slices are those of
+// the longest sequence, so a shorter one leaves slices empty (max = -inf, sum = 0).
+template <int D, class SEQ>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_stats_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                               float *__restrict__ pmax, float *__restrict__ psum, int M,
                                                               int N, int Hq, int Hkv, float scale2, int nrb,
-                                                              int keys_per_slice, int nunits) {
+                                                              int keys_per_slice, int nunits, SEQ seq, size_t seq_stride) {
     constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        M = seq.M[b];
+        k += (size_t)seq.row0[b] * Hkv * D;
+        q += (size_t)(seq.row0[b] + N) * Hq * D;
+        pmax += b * seq_stride;
+        psum += b * seq_stride;
+    }
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int rep = Hq / Hkv, R = M * rep;
@@ -198,9 +210,19 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 // combine: lse2[row] = log2 sum over slices.  A workgroup takes 16 rows; thread (j, r) = (tid / 16,
 // tid % 16) folds slices j, j + 16, ... of row r (16 adjacent rows per load: coalesced), then the 16
 // partial (max, sum) pairs of a row meet in LDS in a fixed order.
+template <class SEQ>
 __global__ __launch_bounds__(kThreads) void attn_lse_kernel(const float *__restrict__ pmax, const float *__restrict__ psum,
-                                                            float *__restrict__ lse2, int rows, int nslice) {
+                                                            float *__restrict__ lse2, int rows, int nslice, SEQ seq,
+                                                            int Hq, size_t seq_stride, int lse_ld) {
     __shared__ float sm[16][17], ss[16][17];
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.y;
+        rows = seq.M[b] * Hq;
+        if ((int)blockIdx.x * 16 >= rows) return;  // uniform
+        pmax += b * seq_stride;
+        psum += b * seq_stride;
+        lse2 += (size_t)b * lse_ld;
+    }
     const int j = threadIdx.x >> 4, rr = threadIdx.x & 15;
     const int r = min(blockIdx.x * 16 + rr, rows - 1);
     float m = -INFINITY, tot = 0.f;
@@ -227,13 +249,24 @@ __global__ __launch_bounds__(kThreads) void attn_lse_kernel(const float *__restr
 
 // ---------------------------------------------------------------------------------------------
 // pass 2: grid = kv heads (fastest) x key blocks
-template <int D>
+template <int D, class SEQ>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_colsum_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                                const float *__restrict__ lse2, float *__restrict__ part,
-                                                               int M, int N, int Hq, int Hkv, float scale2) {
+                                                               int M, int N, int Hq, int Hkv, float scale2, SEQ seq,
+                                                               int lse_ld, size_t part_stride) {
     constexpr int KS = D / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<D> &lds = *reinterpret_cast<Tile<D> *>(smem_raw);
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        M = seq.M[b];
+        if ((int)(blockIdx.x / Hkv) * (4 * 32 * kTW) >= N) return;  // uniform: key block past this sequence's keys
+        k += (size_t)seq.row0[b] * Hkv * D;
+        q += (size_t)(seq.row0[b] + N) * Hq * D;
+        lse2 += (size_t)b * lse_ld;
+        part += b * part_stride;
+    }
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     const int rep = Hq / Hkv, R = M * rep;
@@ -373,8 +406,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     if (key < N) part[(size_t)kvh * N + key] = col[0];
 }
 
+template <class SEQ>
 __global__ __launch_bounds__(kThreads) void attn_score_reduce_kernel(const float *__restrict__ part, float *__restrict__ s,
-                                                                     int N, int Hkv, float norm) {
+                                                                     int N, int Hkv, float norm, SEQ seq, int Hq,
+                                                                     size_t part_stride, int ld) {
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        norm = 1.f / ((float)seq.M[b] * (float)Hq);
+        part += b * part_stride;
+        s += (size_t)b * ld;
+    }
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= N) return;
     float t = 0.f;
@@ -384,7 +426,6 @@ __global__ __launch_bounds__(kThreads) void attn_score_reduce_kernel(const float
 
 struct Plan {
     int nrb, nslice, keys_per_slice;
-    size_t off_pmax, off_psum, off_lse, off_part, total;
 };
 
 Plan make_plan(int M, int N, int Hq, int Hkv) {
@@ -398,37 +439,44 @@ Plan make_plan(int M, int N, int Hq, int Hkv) {
     if (want < 1) want = 1;
     p.keys_per_slice = ceil_div(ceil_div(N, want), kRows) * kRows;
     p.nslice = ceil_div(N, p.keys_per_slice);
-    const size_t rows = (size_t)M * Hq;
-    size_t o = 0;
-    p.off_pmax = o; o += align_up(rows * p.nslice * sizeof(float), 256);
-    p.off_psum = o; o += align_up(rows * p.nslice * sizeof(float), 256);
-    p.off_lse = o;  o += align_up(rows * sizeof(float), 256);
-    p.off_part = o; o += align_up((size_t)Hkv * N * sizeof(float), 256);
-    p.total = o;
     return p;
 }
 
-template <int D>
-int run(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, float scale, void *ws, hipStream_t st) {
+// One sequence (SEQ = OneSeq, nseq = 1) or a packed batch: M and N are then the largest text and
+// vision counts of the batch, and every sequence has a plan's worth of workspace of its own.
+template <int D, class SEQ>
+int run(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, float scale, void *ws, const SEQ &seq,
+        int nseq, int ld, hipStream_t st) {
     const Plan p = make_plan(M, N, Hq, Hkv);
     const size_t smem = sizeof(Tile<D>);
-    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_stats_kernel<D>), smem) ||
-        !allow_dynamic_lds(reinterpret_cast<const void *>(&attn_colsum_kernel<D>), smem))
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&attn_stats_kernel<D, SEQ>), smem) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&attn_colsum_kernel<D, SEQ>), smem))
         return STRD_EHIP;
-    char *base = (char *)ws;
-    float *pmax = (float *)(base + p.off_pmax), *psum = (float *)(base + p.off_psum);
-    float *lse2 = (float *)(base + p.off_lse), *part = (float *)(base + p.off_part);
+    // per sequence: pmax | psum | lse | part, sequence after sequence inside each of the four regions
+    const size_t rows = (size_t)M * Hq;
+    const size_t stat_stride = rows * p.nslice, part_stride = (size_t)Hkv * N;
+    float *pmax = (float *)ws, *psum = pmax + stat_stride * nseq;
+    float *lse2 = psum + stat_stride * nseq, *part = lse2 + align_up(rows * nseq, 64);
     const float scale2 = scale * kLog2e;
-    const int rows = M * Hq;
     const int nunits = p.nrb * Hkv * p.nslice;
-    attn_stats_kernel<D><<<xcd_grid(nunits), kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, pmax, psum, M, N, Hq,
-                                                                   Hkv, scale2, p.nrb, p.keys_per_slice, nunits);
-    attn_lse_kernel<<<ceil_div(rows, 16), kThreads, 0, st>>>(pmax, psum, lse2, rows, p.nslice);
+    attn_stats_kernel<D, SEQ><<<dim3(xcd_grid(nunits), nseq), kThreads, smem, st>>>(
+        (const bf16_t *)q, (const bf16_t *)k, pmax, psum, M, N, Hq, Hkv, scale2, p.nrb, p.keys_per_slice, nunits, seq,
+        stat_stride);
+    attn_lse_kernel<SEQ><<<dim3(ceil_div((int)rows, 16), nseq), kThreads, 0, st>>>(pmax, psum, lse2, (int)rows, p.nslice, seq, Hq,
+                                                                                  stat_stride, (int)rows);
     const int nkb = ceil_div(N, 4 * 32 * kTW);
-    attn_colsum_kernel<D><<<nkb * Hkv, kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, lse2, part, M, N, Hq,
-                                                            Hkv, scale2);
-    attn_score_reduce_kernel<<<ceil_div(N, kThreads), kThreads, 0, st>>>(part, s, N, Hkv, 1.f / ((float)M * (float)Hq));
+    attn_colsum_kernel<D, SEQ><<<dim3(nkb * Hkv, nseq), kThreads, smem, st>>>((const bf16_t *)q, (const bf16_t *)k, lse2, part,
+                                                                              M, N, Hq, Hkv, scale2, seq, (int)rows,
+                                                                              part_stride);
+    attn_score_reduce_kernel<SEQ><<<dim3(ceil_div(N, kThreads), nseq), kThreads, 0, st>>>(
+        part, s, N, Hkv, 1.f / ((float)M * (float)Hq), seq, Hq, part_stride, ld);
     return launch_status();
+}
+
+size_t ws_bytes(int M, int N, int Hq, int Hkv, int nseq) {
+    const Plan p = make_plan(M, N, Hq, Hkv);
+    const size_t rows = (size_t)M * Hq;
+    return align_up((2 * rows * p.nslice * nseq + align_up(rows * nseq, 64) + (size_t)Hkv * N * nseq) * sizeof(float), 256);
 }
 
 }  // namespace
@@ -440,12 +488,22 @@ bool score_attn_mfma_supported(int M, int N, int Hq, int Hkv, int d, strd_dtype 
     return blocks1 < (1LL << 30) && blocks2 < (1LL << 30) && (long long)M * Hq < (1LL << 30);
 }
 
-size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv) { return make_plan(M, N, Hq, Hkv).total; }
+size_t score_attn_mfma_ws(int M, int N, int Hq, int Hkv) { return ws_bytes(M, N, Hq, Hkv, 1); }
+size_t score_attn_mfma_varlen_ws(int nseq, int max_m, int max_n, int Hq, int Hkv) {
+    return ws_bytes(max_m, max_n, Hq, Hkv, nseq);
+}
 
 int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq, int Hkv, int d, float scale, void *ws,
                     hipStream_t st) {
-    if (d == 128) return run<128>(q, k, s, M, N, Hq, Hkv, scale, ws, st);
-    if (d == 64) return run<64>(q, k, s, M, N, Hq, Hkv, scale, ws, st);
+    if (d == 128) return run<128>(q, k, s, M, N, Hq, Hkv, scale, ws, OneSeq(), 1, 0, st);
+    if (d == 64) return run<64>(q, k, s, M, N, Hq, Hkv, scale, ws, OneSeq(), 1, 0, st);
+    return STRD_EUNSUPPORTED;
+}
+
+int score_attn_mfma_varlen(const void *q, const void *k, float *s, int ld, const SeqTab &tab, int nseq, int max_m,
+                           int max_n, int Hq, int Hkv, int d, float scale, void *ws, hipStream_t st) {
+    if (d == 128) return run<128>(q, k, s, max_m, max_n, Hq, Hkv, scale, ws, tab, nseq, ld, st);
+    if (d == 64) return run<64>(q, k, s, max_m, max_n, Hq, Hkv, scale, ws, tab, nseq, ld, st);
     return STRD_EUNSUPPORTED;
 }
 

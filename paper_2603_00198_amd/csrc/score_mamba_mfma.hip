@@ -51,16 +51,27 @@ struct Tile {
 // That weight table is itself a [text row x token] contraction over the <= 16 heads of the group,
 // in the accumulator layout of G^T, so it is one more MFMA per tile; u and v are split into
 // bf16 high and low parts (three products) to keep about 16 bits of them.
-template <int NS, int CT, bool FULL>
+// SEQ = SeqTab (packed batch, blockIdx.z = sequence): Bv and Ct point at the packed b and c tensors,
+// the sequence's partials start at part + row0 * G.
+template <int NS, int CT, bool FULL, class SEQ = OneSeq>
 __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t *__restrict__ Bv,
                                                                     const bf16_t *__restrict__ Ct,
                                                                     const float *__restrict__ U,
                                                                     const float *__restrict__ V,
                                                                     float *__restrict__ part, int M, int N, int G,
-                                                                    int H) {
+                                                                    int H, SEQ seq) {
     constexpr int KS = NS / 16;  // k-steps of v_mfma_f32_32x32x16_bf16
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Tile<NS> &lds = *reinterpret_cast<Tile<NS> *>(smem_raw);
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.z;
+        N = seq.N[b];
+        M = seq.M[b];
+        if ((int)blockIdx.x * (128 * CT) >= N) return;  // uniform: a shorter sequence than the grid was sized for
+        Bv += (size_t)seq.row0[b] * G * NS;
+        Ct += (size_t)(seq.row0[b] + N) * G * NS;
+        part += (size_t)seq.row0[b] * G;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
@@ -185,10 +196,19 @@ __global__ __launch_bounds__(kThreads) void score_mamba_mfma_kernel(const bf16_t
 
 // s_i = 1/(M*H) * sum_h dt_i^h * a[g(h)][i].  16 adjacent lanes share a token and read its dt
 // row in 64-byte pieces (coalesced); their partial sums meet in a fixed butterfly order.
+template <class SEQ = OneSeq>
 __global__ __launch_bounds__(kThreads) void score_mamba_reduce_kernel(const float *__restrict__ part,
                                                                       const float *__restrict__ dtv,
                                                                       float *__restrict__ s, int N, int H, int G,
-                                                                      float norm) {
+                                                                      float norm, SEQ seq, int ld) {
+    if constexpr (is_varlen<SEQ>()) {  // blockIdx.y = sequence; dtv is the packed tensor, s has `ld` floats per sequence
+        const int b = blockIdx.y;
+        N = seq.N[b];
+        norm = 1.f / ((float)seq.M[b] * (float)H);
+        part += (size_t)seq.row0[b] * G;
+        dtv += (size_t)seq.row0[b] * H;
+        s += (size_t)b * ld;
+    }
     const int i = blockIdx.x * (kThreads / 16) + threadIdx.x / 16, j = threadIdx.x & 15;
     const int hpg = H / G;
     float tot = 0.f;
@@ -421,7 +441,7 @@ int launch_full(const void *B, const void *C, const float *U, const float *V, fl
     float *part = (float *)ws;
     const dim3 grid(ceil_div(N, 128 * CT), G);
     score_mamba_mfma_kernel<NS, CT, true><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, U, V, part,
-                                                                        M, N, G, H);
+                                                                        M, N, G, H, OneSeq());
     score_mamba_full_reduce_kernel<<<ceil_div(N, kThreads), kThreads, 0, st>>>(part, s, N, G,
                                                                              1.f / ((float)M * (float)H));
     return launch_status();
@@ -436,13 +456,35 @@ int launch(const void *B, const void *C, const float *dt, float *s, int M, int N
     float *part = (float *)ws;
     const dim3 grid(ceil_div(N, 128 * CT), G);
     score_mamba_mfma_kernel<NS, CT, false><<<grid, kThreads, smem, st>>>((const bf16_t *)B, (const bf16_t *)C, nullptr,
-                                                                         nullptr, part, M, N, G, H);
+                                                                         nullptr, part, M, N, G, H, OneSeq());
     score_mamba_reduce_kernel<<<ceil_div(N, kThreads / 16), kThreads, 0, st>>>(part, dt, s, N, H, G,
-                                                                          1.f / ((float)M * (float)H));
+                                                                          1.f / ((float)M * (float)H), OneSeq(), 0);
+    return launch_status();
+}
+
+template <int NS>
+int launch_varlen(const void *B, const void *C, const float *dt, float *s, int ld, const SeqTab &tab, int nseq, int max_n, int H, int G,
+                  void *ws, hipStream_t st) {
+    const size_t smem = sizeof(Tile<NS>);
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&score_mamba_mfma_kernel<NS, 1, false, SeqTab>), smem))
+        return STRD_EHIP;
+    float *part = (float *)ws;
+    score_mamba_mfma_kernel<NS, 1, false, SeqTab><<<dim3(ceil_div(max_n, 128), G, nseq), kThreads, smem, st>>>(
+        (const bf16_t *)B, (const bf16_t *)C, nullptr, nullptr, part, 0, 0, G, H, tab);
+    score_mamba_reduce_kernel<SeqTab><<<dim3(ceil_div(max_n, kThreads / 16), nseq), kThreads, 0, st>>>(part, dt, s, 0, H, G,
+                                                                                               0.f, tab, ld);
     return launch_status();
 }
 
 }  // namespace
+
+// Packed batch on the matrix-core tile kernel: partials of sequence b at ws + row0[b] * G floats.
+int score_mamba_mfma_varlen(const void *B, const void *C, const float *dt, float *s, int ld, const SeqTab &tab, int nseq, int max_n,
+                            int H, int G, int n, void *ws, hipStream_t st) {
+    if (n == 128) return launch_varlen<128>(B, C, dt, s, ld, tab, nseq, max_n, H, G, ws, st);
+    if (n == 64) return launch_varlen<64>(B, C, dt, s, ld, tab, nseq, max_n, H, G, ws, st);
+    return STRD_EUNSUPPORTED;
+}
 
 bool score_mamba_mfma_supported(int M, int N, int H, int G, int n, strd_dtype io) {
     (void)M; (void)H;

@@ -153,9 +153,18 @@ __device__ __forceinline__ void pick_bin(const uint32_t *hist, ScanScratch &sc, 
 }
 
 // TILES > 0: N <= TILES * kTile and every key stays in registers.  TILES == 0: streaming.
-template <int TILES>
+// SEQ = SeqTab: one workgroup per sequence of a packed batch (scores of sequence b start at
+// scores + b * ld, its indices at idx + koff[b]; N and K are the table's).
+template <int TILES, class SEQ = OneSeq>
 __global__ __launch_bounds__(kThreads) void select_topk_kernel(const float *__restrict__ scores, int N, int K,
-                                                               int32_t *__restrict__ idx) {
+                                                               int32_t *__restrict__ idx, SEQ seq, int ld) {
+    if constexpr (is_varlen<SEQ>()) {
+        const int b = blockIdx.x;
+        N = seq.N[b];
+        K = seq.K[b];
+        scores += (size_t)b * ld;
+        idx += seq.koff[b];
+    }
     extern __shared__ __attribute__((aligned(16))) uint32_t hist[];  // [kBins][kCopies]
     __shared__ ScanScratch scan;
     __shared__ uint32_t found[3][3];         // (bin, rank inside the bin, keys in the bin) of each pass
@@ -503,6 +512,21 @@ size_t select_topk_ws(int N) {
     return (N > 8 * kTile && N <= kWideMax * kTile) ? align_up(sizeof(WideWs), 256) : 0;
 }
 
+int select_topk_varlen_max_n() { return 8 * kTile; }
+
+int select_topk_varlen_launch(const float *scores, int ld, const SeqTab &tab, int nseq, int max_n, int32_t *idx,
+                              hipStream_t s) {
+    const size_t smem = (size_t)kBins * kCopies * sizeof(uint32_t);
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<2, SeqTab>), smem) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<8, SeqTab>), smem))
+        return STRD_EHIP;
+    if (max_n <= 2 * kTile)
+        select_topk_kernel<2, SeqTab><<<nseq, kThreads, smem, s>>>(scores, 0, 0, idx, tab, ld);
+    else
+        select_topk_kernel<8, SeqTab><<<nseq, kThreads, smem, s>>>(scores, 0, 0, idx, tab, ld);
+    return launch_status();
+}
+
 int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws, hipStream_t s) {
     if (select_topk_ws(N)) {
         WideWs *w = reinterpret_cast<WideWs *>(ws);
@@ -521,11 +545,11 @@ int select_topk_launch(const float *scores, int N, int K, int32_t *idx, void *ws
         !allow_dynamic_lds(reinterpret_cast<const void *>(&select_topk_kernel<0>), smem))
         return STRD_EHIP;
     if (N <= 2 * kTile)
-        select_topk_kernel<2><<<1, kThreads, smem, s>>>(scores, N, K, idx);
+        select_topk_kernel<2><<<1, kThreads, smem, s>>>(scores, N, K, idx, OneSeq(), 0);
     else if (N <= 8 * kTile)
-        select_topk_kernel<8><<<1, kThreads, smem, s>>>(scores, N, K, idx);
+        select_topk_kernel<8><<<1, kThreads, smem, s>>>(scores, N, K, idx, OneSeq(), 0);
     else
-        select_topk_kernel<0><<<1, kThreads, smem, s>>>(scores, N, K, idx);
+        select_topk_kernel<0><<<1, kThreads, smem, s>>>(scores, N, K, idx, OneSeq(), 0);
     return launch_status();
 }
 

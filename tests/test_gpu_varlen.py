@@ -1,0 +1,138 @@
+"""Packed batches of sequences of different lengths through the C ABI: scores, selection and
+compaction of every sequence against the CPU oracle applied to that sequence alone (Sec. 3.1:
+each sequence is reduced on its own; only the launches are shared).  Needs a GPU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_00198_amd as strd
+from paper_2603_00198_amd import synth
+from util import TOL, assert_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+f = synth.np64
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# (N, M, K) per sequence: one token, ragged tiles, a sequence much longer than the others,
+# every token kept, one text row
+BATCHES = {
+    "mixed": [(2048, 64, 512), (300, 17, 300), (5000, 128, 1250), (1, 1, 1), (4099, 33, 1000), (129, 1, 7)],
+    "long_and_short": [(20000, 200, 5000), (257, 40, 64), (8193, 96, 2048)],
+    "single": [(1500, 31, 400)],
+}
+MAMBA_SHAPES = {"bf16": (128, 8, 128, torch.bfloat16), "bf16_n64": (8, 2, 64, torch.bfloat16),
+                "f32": (8, 1, 16, torch.float32), "bf16_simt": (6, 3, 40, torch.bfloat16)}
+ATTN_SHAPES = {"bf16": (32, 8, 128, torch.bfloat16), "bf16_d64": (4, 4, 64, torch.bfloat16),
+               "f32": (4, 2, 64, torch.float32), "bf16_simt": (6, 2, 48, torch.bfloat16)}
+
+
+def _rows(seqs):
+    r0, out = 0, []
+    for n, m, _ in seqs:
+        out.append((r0, r0 + n, r0 + n + m))
+        r0 += n + m
+    return out, r0
+
+
+@pytest.mark.parametrize("shape", list(MAMBA_SHAPES))
+@pytest.mark.parametrize("batch", list(BATCHES))
+def test_score_mamba_varlen(batch, shape):
+    """Eq. 4 per sequence of a packed batch."""
+    seqs = BATCHES[batch]
+    H, G, n, dtype = MAMBA_SHAPES[shape]
+    spans, rows = _rows(seqs)
+    g = torch.Generator().manual_seed(len(batch) * 131 + H)
+    _say("score_mamba_varlen %s %s rows=%d" % (batch, shape, rows))
+    B = (torch.randn(rows, G, n, generator=g) / n ** 0.5).to(dtype)
+    C = torch.randn(rows, G, n, generator=g).to(dtype)
+    dt = torch.nn.functional.softplus(torch.randn(rows, H, generator=g))
+    s = strd.score_mamba_varlen(B.to(DEV), C.to(DEV), dt.to(DEV), seqs).cpu().numpy()
+    for b, (v0, t0, t1) in enumerate(spans):
+        want = oracle.score_mamba(f(B[v0:t0]), f(C[t0:t1]), f(dt[v0:t0]))
+        assert_close(s[b, :t0 - v0], want, TOL[dtype], "sequence %d" % b, units=(0,))
+        assert not s[b, t0 - v0:].any()  # entries past N_b are left alone (the binding hands in zeros)
+
+
+@pytest.mark.parametrize("shape", list(ATTN_SHAPES))
+@pytest.mark.parametrize("batch", list(BATCHES))
+def test_score_attn_varlen(batch, shape):
+    """Eq. 3 per sequence of a packed batch; the scores of a sequence sum to 1."""
+    seqs = BATCHES[batch]
+    Hq, Hkv, d, dtype = ATTN_SHAPES[shape]
+    spans, rows = _rows(seqs)
+    g = torch.Generator().manual_seed(len(batch) * 137 + Hq)
+    _say("score_attn_varlen %s %s rows=%d" % (batch, shape, rows))
+    q = torch.randn(rows, Hq, d, generator=g).to(dtype)
+    k = torch.randn(rows, Hkv, d, generator=g).to(dtype)
+    s = strd.score_attn_varlen(q.to(DEV), k.to(DEV), seqs).cpu().numpy()
+    for b, (v0, t0, t1) in enumerate(spans):
+        want = oracle.score_attn(f(q[t0:t1]), f(k[v0:t0]))
+        assert_close(s[b, :t0 - v0], want, TOL[dtype], "sequence %d" % b, units=(0,))
+        assert abs(float(s[b, :t0 - v0].astype(np.float64).sum()) - 1.0) < 1e-3
+        assert not s[b, t0 - v0:].any()
+
+
+@pytest.mark.parametrize("batch", list(BATCHES))
+def test_select_and_compact_varlen(batch):
+    """Selection per sequence, index for index, against the oracle on the same scores (ties included),
+    then the gather of two tensors and the position map, bit for bit."""
+    seqs = BATCHES[batch]
+    spans, rows = _rows(seqs)
+    rng = np.random.default_rng(len(batch))
+    ld = (max(n for n, _, _ in seqs) + 3) // 4 * 4 + 8
+    scores = np.zeros((len(seqs), ld), dtype=np.float32)
+    for b, (n, _, _) in enumerate(seqs):
+        scores[b, :n] = rng.choice(np.float32([0.25, 0.5, 0.75, 1.0, 1.5]), n) if b % 2 else rng.random(n, dtype=np.float32)
+        scores[b, n:] = 9.0  # must never be looked at
+    _say("select_topk_varlen / compact_varlen %s" % batch)
+    idx = strd.select_topk_varlen(torch.from_numpy(scores).to(DEV), seqs)
+    got = idx.cpu().numpy()
+    k0, want_rows, want_pos = 0, [], []
+    for b, ((n, m, k), (v0, t0, t1)) in enumerate(zip(seqs, spans)):
+        want = oracle.select_topk(scores[b, :n].astype(np.float64), k)
+        np.testing.assert_array_equal(got[k0:k0 + k], want)
+        k0 += k
+        want_rows += [v0 + int(i) for i in want] + list(range(t0, t1))
+        want_pos += [int(i) for i in want] + list(range(n, n + m))
+    g = torch.Generator().manual_seed(7)
+    hid = torch.randn(rows, 96, generator=g).to(torch.bfloat16).to(DEV)
+    dt = torch.randn(rows, 5, generator=g).to(DEV)  # 20-byte rows: the 4-byte vector form
+    pos_in = torch.randperm(rows, generator=g).to(torch.int32).to(DEV)
+    (h2, d2), pos = strd.compact_varlen([hid, dt], idx, seqs, want_pos=True)
+    sel = torch.tensor(want_rows, device=DEV)
+    assert torch.equal(h2, hid[sel]) and torch.equal(d2, dt[sel])
+    np.testing.assert_array_equal(pos.cpu().numpy(), np.int32(want_pos))
+    _, pos2 = strd.compact_varlen([hid], idx, seqs, pos_in=pos_in)
+    assert torch.equal(pos2, pos_in[sel])
+
+
+def test_varlen_pipeline_matches_the_single_sequence_calls():
+    """score -> select -> compact of a packed batch gives, sequence by sequence, what the
+    single-sequence entry points give (same kernels on the Mamba side: bit for bit)."""
+    seqs = BATCHES["mixed"]
+    H, G, n = 128, 8, 128
+    spans, rows = _rows(seqs)
+    g = torch.Generator().manual_seed(99)
+    B = (torch.randn(rows, G, n, generator=g) / n ** 0.5).to(torch.bfloat16).to(DEV)
+    C = torch.randn(rows, G, n, generator=g).to(torch.bfloat16).to(DEV)
+    dt = torch.nn.functional.softplus(torch.randn(rows, H, generator=g)).to(DEV)
+    x = torch.randn(rows, 64, generator=g).to(torch.bfloat16).to(DEV)
+    s = strd.score_mamba_varlen(B, C, dt, seqs)
+    idx = strd.select_topk_varlen(s, seqs)
+    (x2,), _ = strd.compact_varlen([x], idx, seqs)
+    k0 = o0 = 0
+    for b, ((nv, m, k), (v0, t0, t1)) in enumerate(zip(seqs, spans)):
+        s1 = strd.score_mamba(B[v0:t0].contiguous(), C[t0:t1].contiguous(), dt[v0:t0].contiguous())
+        assert torch.equal(s[b, :nv], s1)
+        i1 = strd.select_topk(s1, k)
+        assert torch.equal(idx[k0:k0 + k], i1)
+        x1 = strd.compact(x[v0:t1].contiguous(), i1, nv, m)
+        assert torch.equal(x2[o0:o0 + k + m], x1)
+        k0 += k
+        o0 += k + m

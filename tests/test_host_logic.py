@@ -211,6 +211,52 @@ def test_entry_points_refuse_inconsistent_arguments_on_the_host():
             assert rc == EINVAL, "%s accepted argument %d = %r (returned %d)" % (name, pos, value, rc)
 
 
+def test_packed_batch_entry_points_validate_their_descriptors_on_the_host():
+    """The sequence descriptors of the *_varlen calls are a host array: counts, K <= N, the score
+    row length and the limit on sequences per call are checked before anything is launched."""
+    if torch.cuda.is_available():
+        pytest.skip("placeholder pointers: only run without a GPU")
+    import ctypes
+    L = binding.lib()
+    P, BIG, BF16 = 0x1000, 1 << 40, 1
+    EINVAL, EUNSUPPORTED, EHIP = -1, -2, -4
+
+    def seqs(*t):
+        arr = (binding._Seq * len(t))()
+        for i, (n, m, k) in enumerate(t):
+            arr[i].N, arr[i].M, arr[i].K = n, m, k
+        return ctypes.cast(arr, ctypes.c_void_p), len(t), arr
+
+    good, ng, keep = seqs((100, 8, 10), (37, 3, 37))
+    mamba = lambda sq, nsq, ld=100: L.strd_score_mamba_varlen(P, P, P, P, ld, sq, nsq, 8, 2, 64, BF16, P, BIG, None)
+    attn = lambda sq, nsq, ld=100: L.strd_score_attn_varlen(P, P, P, ld, sq, nsq, 4, 2, 64, 0.125, BF16, P, BIG, None)
+    topk = lambda sq, nsq, ld=100: L.strd_select_topk_varlen(P, ld, sq, nsq, P, None)
+    item = (binding._CompactItem * 1)()
+    item[0].src, item[0].dst, item[0].row_bytes = P, P, 64
+    comp = lambda sq, nsq: L.strd_compact_varlen(ctypes.cast(item, ctypes.c_void_p), 1, P, sq, nsq, None, None, None)
+    for call in (mamba, attn, topk, comp):
+        assert call(good, ng) == EHIP            # consistent: past validation, then no GPU
+        assert call(None, ng) == EINVAL
+        assert call(good, 0) == EINVAL
+        assert call(good, 65) == EINVAL          # STRD_VARLEN_MAX sequences per call
+        for bad in ((0, 8, 1), (100, 0, 10)):
+            sq, nsq, k2 = seqs((100, 8, 10), bad)
+            assert call(sq, nsq) == EINVAL, bad
+    for call in (mamba, attn, topk):
+        assert call(good, ng, 96) == EINVAL      # shorter than the longest sequence
+        assert call(good, ng, 102) == EINVAL     # not a multiple of 4
+    for bad in ((100, 8, 0), (100, 8, 101)):     # K is checked where it is used ...
+        sq, nsq, k2 = seqs(bad)
+        assert topk(sq, nsq) == EINVAL and comp(sq, nsq) == EINVAL
+        assert mamba(sq, nsq) == EHIP and attn(sq, nsq) == EHIP  # ... and ignored by the scores
+    sq, nsq, k2 = seqs((40000, 8, 10))
+    assert topk(sq, nsq, 40000) == EUNSUPPORTED   # one workgroup per sequence: at most 32768 scores each
+    assert L.strd_select_topk_varlen_max_n() == 32768
+    assert L.strd_score_mamba_varlen_workspace(good, ng, 8, 2, 64, BF16) >= (100 + 8 + 37 + 3) * 2 * 4
+    assert L.strd_score_mamba_varlen_workspace(good, ng, 8, 2, 40, BF16) == 0
+    assert L.strd_score_attn_varlen_workspace(good, ng, 4, 2, 64, BF16) > 0
+
+
 def test_matrix_core_shapes_refuse_misaligned_tensors_and_report_their_kernel_path():
     """16-byte vectors are moved straight from the caller's pointers on the matrix-core shapes: a
     misaligned tensor is refused on the host.  Which kernel a shape runs is answered without a GPU."""
