@@ -30,30 +30,33 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 KERNEL_STEP = 64               # tokens per step of the scan kernel, whatever `chunk` the caller names
 TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
-KERNEL_SOURCES = {"ssd_prefill": "ssd_mfma.hip", "attn_prefill": "attn_mfma.hip"}
 
 
-def kernel_source_hash(kernel):
+def source_hash(file_name):
     import hashlib
-    path = os.path.join(ROOT, "paper_2603_00198_amd", "csrc", KERNEL_SOURCES[kernel])
-    return hashlib.sha1(open(path, "rb").read()).hexdigest()[:12]
+    path = os.path.join(ROOT, "paper_2603_00198_amd", "csrc", file_name)
+    try:
+        return hashlib.sha1(open(path, "rb").read()).hexdigest()[:12]
+    except OSError:
+        return None
 
 
 def measured_traffic(workload, budget, kernel):
     """HBM bytes per launch of the mixer kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs
     summarised in profiles/hbm_traffic.md (counters cannot be read from inside this process).  A row
-    counts only while the kernel's source is the one that was profiled; otherwise None."""
+    names the source file of the kernel that was profiled and counts only while that file is unchanged;
+    otherwise None."""
     try:
         rows = open(TRAFFIC_TABLE).read().splitlines()
     except OSError:
         return None
     for line in rows:
         cells = [c.strip() for c in line.strip().strip("|").split("|")]
-        if len(cells) >= 6 and cells[0] == workload and cells[2] == kernel:
+        if len(cells) >= 7 and cells[0] == workload and cells[2] == kernel:
             try:
-                if abs(float(cells[1]) - budget) > 1e-9 or cells[5] != kernel_source_hash(kernel):
+                if abs(float(cells[1]) - budget) > 1e-9 or cells[6] != source_hash(cells[3]):
                     continue
-                return float(cells[3]) + float(cells[4])
+                return float(cells[4]) + float(cells[5])
             except ValueError:
                 continue
     return None
@@ -672,6 +675,26 @@ def block_stack(torch, strd, synth, dev, iters=5):
                 "reducing blocks, mixer, gated norm, out-projection + residual; no MLP blocks"}))
 
 
+def matrix_core_rate(torch, strd, dev):
+    """TFLOP/s of back-to-back bf16 32x32x16 products on register-resident operands (no loads, no LDS),
+    with constant and with random operands: what the matrix cores of THIS chip sustain at the clock
+    its power management allows, beside the published 2.5 PFLOP/s the roofline fractions are taken of."""
+    out = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    res = {}
+    for tag, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        strd.mfma_rate_probe(512, 2000, rnd, out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        strd.mfma_rate_probe(512, 10000, rnd, out)
+        e1.record()
+        torch.cuda.synchronize()
+        res[tag + "_TFLOPs"] = 512 * 4 * 10000 * 32 * 32768 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    res["note"] = ("strd_mfma_rate_probe: 2 waves per SIMD issuing only products; real activations look like the random "
+                   "case to the multipliers, and the clock under full-rate products follows the power they draw")
+    return res
+
+
 def median(vals):
     v = sorted(vals)
     n = len(v)
@@ -898,6 +921,7 @@ def main():
             del olayer
             torch.cuda.empty_cache()
         line.setdefault("next_rows", {})["variants"] = variants(torch, strd, synth, dev)
+        line["matrix_core_rate_probe"] = matrix_core_rate(torch, strd, dev)
     if not args.no_cpu_baseline:
         line["cpu_baseline"]["single_thread_c1"] = cpu_single_thread_c1(torch, synth)
     print(json.dumps(line))

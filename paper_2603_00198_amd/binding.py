@@ -37,6 +37,7 @@ _SIGNATURES = {
     "strd_select_topk_noalloc": (_int, [_vp, _int, _int, _vp, _vp]),
     "strd_compact": (_int, [_vp, _vp, _vp, _int, _int, _int, _i64, _vp, _vp, _vp]),
     "strd_compact_batch": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp]),
+    "strd_mfma_rate_probe": (_int, [_vp, _int, _int, _int, _vp]),
     "strd_score_attn_varlen_workspace": (_sz, [_vp, _int, _int, _int, _int, _int]),
     "strd_score_attn_varlen": (_int, [_vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _f32, _int, _vp, _sz, _vp]),
     "strd_score_mamba_varlen_workspace": (_sz, [_vp, _int, _int, _int, _int, _int]),
@@ -280,6 +281,16 @@ def compact_batch(srcs: Sequence[torch.Tensor], idx: torch.Tensor, N: int, M: in
     _check(lib().strd_compact_batch(ctypes.cast(items, _vp), len(srcs), _ptr(idx), N, M, K, _ptr(pos_in),
                                     _ptr(pos_out), _stream()), "compact_batch")
     return list(outs), pos_out
+
+
+def mfma_rate_probe(workgroups: int, iters: int, random_operands: bool, out: Optional[torch.Tensor] = None,
+                    device="cuda") -> torch.Tensor:
+    """Launches the matrix-core rate probe (a measurement aid): workgroups * 4 * iters * 32 * 32768 flop."""
+    if out is None:
+        out = torch.empty(workgroups * 256, dtype=torch.float32, device=device)
+    _dev(out)
+    _check(lib().strd_mfma_rate_probe(_ptr(out), workgroups, iters, int(bool(random_operands)), _stream()), "mfma_rate_probe")
+    return out
 
 
 # ---- packed batches of sequences: `seqs` is a list of (N, M, K) per sequence ----------------

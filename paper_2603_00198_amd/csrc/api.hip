@@ -137,6 +137,12 @@ int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, i
     return strd_compact_batch(&it, src ? 1 : 0, idx, N, M, K, pos_in, pos_out, stream);
 }
 
+// ------------------------------------------------------------------ measurement aid --------
+int strd_mfma_rate_probe(float *out, int workgroups, int iters, int random_operands, void *stream) {
+    if (!out || workgroups < 1 || iters < 1 || workgroups > (1 << 20)) return STRD_EINVAL;
+    return mfma_rate_probe(out, workgroups, iters, random_operands, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ packed batches ---------
 namespace {
 struct SeqPlan {

@@ -163,3 +163,12 @@ def test_attn_decode_step_errors():
     kv = torch.zeros(10, 2, 32, device=DEV)
     with pytest.raises(strd.StrdError):
         strd.attn_decode_step(q, kv, kv)                       # d = 32: unsupported
+
+
+def test_matrix_core_rate_probe_counts_its_products():
+    """The measurement aid of the benchmark: with every operand 1.0 each of the 64 accumulator entries
+    of a lane ends at iters * 8 products * 16 = iters * 128, so the lane's checksum is iters * 8192."""
+    out = strd.mfma_rate_probe(8, 50, False)
+    assert out.shape == (8 * 256,) and bool((out == 50 * 8192).all())
+    rnd = strd.mfma_rate_probe(8, 50, True)
+    assert bool(torch.isfinite(rnd).all()) and float(rnd.abs().max()) > 0

@@ -211,6 +211,13 @@ def test_entry_points_refuse_inconsistent_arguments_on_the_host():
             assert rc == EINVAL, "%s accepted argument %d = %r (returned %d)" % (name, pos, value, rc)
 
 
+def test_rate_probe_refuses_empty_launches():
+    L = binding.lib()
+    assert L.strd_mfma_rate_probe(None, 4, 10, 0, None) == -1
+    assert L.strd_mfma_rate_probe(0x1000, 0, 10, 0, None) == -1
+    assert L.strd_mfma_rate_probe(0x1000, 4, 0, 1, None) == -1
+
+
 def test_packed_batch_entry_points_validate_their_descriptors_on_the_host():
     """The sequence descriptors of the *_varlen calls are a host array: counts, K <= N, the score
     row length and the limit on sequences per call are checked before anything is launched."""
