@@ -259,6 +259,10 @@ int strd_compact_varlen(const strd_compact_item *items, int n_items, const int32
  * otherwise unused: it does NOT select the tiling.  The kernels always cut time into
  * 64-token steps and carry the state across them on chip, so results do not depend on
  * `chunk` at all.  S_out of one call fed as S_in of the next continues the same scan.
+ *   ws  [dev] strd_ssd_prefill_workspace(T, ...) bytes: 0 for short sequences; for long ones the
+ *       sequence is cut into segments that run side by side, and the local end state and total
+ *       decay of every segment but the last pass through the workspace ((segments - 1) * H * P * n
+ *       + segments * H floats).  Too small or NULL when needed: STRD_EWORKSPACE.
  * Requires T >= 0, H % G == 0.
  * ------------------------------------------------------------------------- */
 size_t strd_ssd_prefill_workspace(int T, int H, int P, int G, int n, int chunk, strd_dtype io);
@@ -272,7 +276,8 @@ int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void 
  * uncompacted x, dt, B, C (N + M rows each).  Equal, bit for bit, to compacting the four
  * tensors with strd_compact and calling strd_ssd_prefill, minus that HBM round trip.
  *   idx [dev] [K] int32, ascending, each in [0, N)     y [dev] [K+M, H, P] (dense)
- * Only shapes the matrix-core kernel covers (bf16, n in {64, 128}, P % 32 == 0, K + M >= 1);
+ *   ws  [dev] strd_ssd_prefill_workspace(K + M, ...) bytes, as for the dense call on K + M tokens.
+ * Only shapes the matrix-core kernels cover (bf16, n in {64, 128}, P % 32 == 0, K + M >= 1);
  * anything else gives STRD_EUNSUPPORTED (compact, then call strd_ssd_prefill). */
 int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, const void *B, const void *C,
                             const float *D, const float *S_in, const int32_t *idx, void *y, float *S_out,
