@@ -14,6 +14,12 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libstrd.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# A change of flags or toolchain has to keep two properties of the generated code, both checked by
+# tests/test_host_logic.py from the compiler's resource report: the kernels that split LDS reads into
+# issue and wait (ssd_mfma.hip, ssd_seg_mfma.hip, attn_mfma.hip) must fit their register budget with
+# no scratch, no spilled VGPR / SGPR and no accumulation registers -- a register moved between the two
+# halves of a split read would carry stale data; and matrix products must take their operands from
+# ordinary VGPRs (-amdgpu-mfma-vgpr-form), which those budgets assume.
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
