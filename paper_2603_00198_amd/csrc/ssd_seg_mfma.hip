@@ -74,12 +74,18 @@ struct SegArgs {
 
 template <int NS, int NC>
 struct LdsS {
-    using BT = AsyncTile<kQ, NS / 8, 1, 2, true>;  // one B or C tile, filled by one wave, 2 pad vectors per row
-    using XT = AsyncTile<kQ, NC * 4, 1, 1, true>;  // x tile of the workgroup's channels, 1 pad vector per row
-    static constexpr int kCP = BT::kPitch;         // bf16 elements per row of the B / C tiles
+    // One B and one C tile, each filled by one wave, 1 pad vector per row: a pitch of 68 words, i.e. 4
+    // modulo the 64 banks, so that the 16 rows a quarter wave reads 16 bytes of (or a half wave 8 bytes
+    // of) cover all banks once.  The transposing reads of the B tile (8 rows x 32 bytes per half wave) stay
+    // off each other's banks because a half wave takes every other row (state_tok below).
+    using BT = AsyncTile<kQ, NS / 8, 1, 1, true>;
+    using CT = BT;
+    using XT = AsyncTile<kQ, NC * 4, 1, 1, true>;  // x tile of the workgroup's channels, 1 pad vector per row (2 changed nothing)
+    static constexpr int kBP = BT::kPitch;         // bf16 elements per row of the B tiles
+    static constexpr int kCP = CT::kPitch;         // ... of the C tiles
     static constexpr int kXP = XT::kPitch;         // ... of the x tiles
     struct alignas(16) TileBC {
-        bf16_t c[BT::kBytes / 2];
+        bf16_t c[CT::kBytes / 2];
         bf16_t b[BT::kBytes / 2];
     };
     struct alignas(16) TileX {
@@ -128,12 +134,20 @@ constexpr int vm_wait_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n 
 
 // The four token-contracted fragments of the x tile for a slab of 32 channels at column c0
 // ([kr = token half][pt = channel half]).  Issued early (issue_x_frags), usable after take_x_frags.
+// `row`: the row of a 16-token block whose 8-byte piece this lane passes (4 lb + lr / 4 for the order above).
 template <int PITCH>
-__device__ __forceinline__ void issue_x_frags(const bf16_t *xt, int c0, int lr, int lb, strd_s16x4 (&r)[8]) {
+__device__ __forceinline__ void issue_x_frags(const bf16_t *xt, int c0, int row, int lr, strd_s16x4 (&r)[8]) {
     constexpr int R = PITCH * 2;  // row pitch in bytes
     lds_issue_tr8<0, 16 * R, 32, 16 * R + 32, 32 * R, 48 * R, 32 * R + 32, 48 * R + 32>(
-        xt + (4 * lb + (lr >> 2)) * PITCH + c0 + 4 * (lr & 3), r);
+        xt + row * PITCH + c0 + 4 * (lr & 3), r);
 }
+// The state update (e) contracts over the tokens of a step, in any order as long as b, x and the
+// weights w agree on it.  Its k slot (lb, j) of a 16-token block is token 8 (lb & 1) + 2 j + (lb >> 1):
+// the two lane groups of a half wave then pass the even (or the odd) rows of the block to a
+// transposing read, 8 rows two apart, which at a row pitch of 4 (B tile) or 36 (x tile) words modulo 64
+// start 8 banks apart -- no two of them share a bank.  ((c) keeps the order above: its weights come out
+// of the accumulators of (a) in that order.)
+__device__ __forceinline__ int state_tok(int lb, int j) { return 8 * (lb & 1) + 2 * j + (lb >> 1); }
 __device__ __forceinline__ void take_x_frags(strd_s16x4 (&r)[8], bf16x8 (&xf)[2][2]) {
     lds_settle8(r);
     xf[0][0] = tr_pair(r[0], r[1]);
@@ -173,10 +187,11 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
         const bf16_t *xt = lds.xr[i % kRX].x;
         // ---- LDS reads that do not depend on the arithmetic of the step are requested first ----
         // x fragments and the first b^T fragments (transposing reads, for (e)); weights; c rows
-        constexpr int R = L::kCP * 2;
+        constexpr int R = L::kBP * 2;
         strd_s16x4 xr8[8], ba[8], bb[8];
-        issue_x_frags<L::kXP>(xt, xcol, lr, lb, xr8);
-        const bf16_t *bbase = &tb.b[(4 * lb + (lr >> 2)) * L::kCP + 4 * (lr & 3)];
+        const int trow = state_tok(lb, lr >> 2);  // the row of a 16-token block this lane passes to a transposing read
+        issue_x_frags<L::kXP>(xt, xcol, trow, lr, xr8);
+        const bf16_t *bbase = &tb.b[trow * L::kBP + 4 * (lr & 3)];
         // state tile d of a group of four: columns + 16 d of the b tile; rows + 0, 16 (token half 0: slots
         // 0-3, 4-7), + 32, 48 (token half 1); ba: tiles 0, 1; bb: tiles 2, 3
         lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(bbase, ba);
@@ -185,7 +200,9 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
 #pragma unroll
         for (int kr = 0; kr < 2; ++kr)
 #pragma unroll
-            for (int hi = 0; hi < 2; ++hi) wv[kr][hi] = *reinterpret_cast<const f32x4 *>(&sc.w[32 * kr + 16 * hi + 4 * lb]);
+            for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) wv[kr][hi][e] = sc.w[32 * kr + 16 * hi + state_tok(lb, e)];
         const float dq = sc.carry[kQ - 1];
         // (d): Y^T[p, t] = sum_n S[p, n] c_t[n] (the factor 2^(l_t) is applied where the outputs are summed).
         // A operand straight from the accumulators: the lane holds rows 4 lb .. 4 lb + 3 of state tiles
@@ -350,7 +367,7 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int jt = 0; jt <= TB; ++jt)
-                bf[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kCP + 32 * ks + 8 * lb]);
+                bf[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kBP + 32 * ks + 8 * lb]);
             cfa[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * TA + lr) * L::kCP + 32 * ks + 8 * lb]);
             cfb[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * TB + lr) * L::kCP + 32 * ks + 8 * lb]);
         }
@@ -372,7 +389,7 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
         // before (published by the barrier that ended it) are requested
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) issue_x_frags<L::kXP>(xt, 32 * c, lr, lb, xr8[c]);
+        for (int c = 0; c < NC; ++c) issue_x_frags<L::kXP>(xt, 32 * c, 4 * lb + (lr >> 2), lr, xr8[c]);
         if (prev) emit_read(i - 1);
         // what (b) needs from the scan of the head
         const float el_a = sc.ell[16 * TA + lr], el_b = sc.ell[16 * TB + lr];
