@@ -74,12 +74,17 @@ struct SegArgs {
 
 template <int NS, int NC>
 struct LdsS {
-    // One B and one C tile, each filled by one wave, 1 pad vector per row: a pitch of 68 words, i.e. 4
-    // modulo the 64 banks, so that the 16 rows a quarter wave reads 16 bytes of (or a half wave 8 bytes
-    // of) cover all banks once.  The transposing reads of the B tile (8 rows x 32 bytes per half wave) stay
-    // off each other's banks because a half wave takes every other row (state_tok below).
-    using BT = AsyncTile<kQ, NS / 8, 1, 1, true>;
-    using CT = BT;
+    // One B and one C tile, each filled by one wave.  Pitches by measurement (bytes per clock and CU of the
+    // read patterns below in a loop of their own, row pitch in 4-byte words modulo the 64 banks):
+    //   16-byte reads, lane = (row lane % 16, piece lane / 16):            8: 180    4: 117
+    //   transposing reads, 8 consecutive rows per half wave:              8: 118    4: 108
+    //   transposing reads, every other row (state_tok below):             8: 123    4: 130
+    //   8-byte reads of 16 rows, one instruction each:                    8: 115    4: 144
+    //   the same two at a time (ds_read2_b64, what the compiler makes):   8:  32    4:  64
+    // B tile (16-byte row reads in (a), transposing reads in (e)): 2 pad vectors, pitch 72 = 8 mod 64.
+    // C tile (16-byte row reads in (a), 8-byte row reads in (d), issued one by one): 1 pad vector, 68 = 4.
+    using BT = AsyncTile<kQ, NS / 8, 1, 2, true>;
+    using CT = AsyncTile<kQ, NS / 8, 1, 1, true>;
     using XT = AsyncTile<kQ, NC * 4, 1, 1, true>;  // x tile of the workgroup's channels, 1 pad vector per row (2 changed nothing)
     static constexpr int kBP = BT::kPitch;         // bf16 elements per row of the B tiles
     static constexpr int kCP = CT::kPitch;         // ... of the C tiles
@@ -156,6 +161,37 @@ __device__ __forceinline__ void take_x_frags(strd_s16x4 (&r)[8], bf16x8 (&xf)[2]
     xf[1][1] = tr_pair(r[6], r[7]);
 }
 
+// The 8-byte pieces of one c row that a lane needs as B operand of (d): elements 32 ks + 4 lb .. + 3 and
+// the same 16 further on, for every k-step -- 2 KS plain reads 32 bytes apart, requested together and
+// waited for separately (same contract as lds_issue_tr8 / lds_settle8).
+template <int KS>
+__device__ __forceinline__ void issue_c_pieces(const bf16_t *p, strd_s16x4 (&r)[2 * KS]) {
+    static_assert(KS == 2 || KS == 4, "state sizes 64 and 128");
+    const uint32_t a = lds_offset(p);
+    if constexpr (KS == 4)
+        asm volatile(
+            "ds_read_b64 %0, %8\n\tds_read_b64 %1, %8 offset:32\n\tds_read_b64 %2, %8 offset:64\n\t"
+            "ds_read_b64 %3, %8 offset:96\n\tds_read_b64 %4, %8 offset:128\n\tds_read_b64 %5, %8 offset:160\n\t"
+            "ds_read_b64 %6, %8 offset:192\n\tds_read_b64 %7, %8 offset:224"
+            : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
+            : "v"(a)
+            : "memory");
+    else
+        asm volatile(
+            "ds_read_b64 %0, %4\n\tds_read_b64 %1, %4 offset:32\n\tds_read_b64 %2, %4 offset:64\n\t"
+            "ds_read_b64 %3, %4 offset:96"
+            : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+            : "v"(a)
+            : "memory");
+}
+template <int KS>
+__device__ __forceinline__ void settle_c_pieces(strd_s16x4 (&r)[2 * KS]) {
+    if constexpr (KS == 4)
+        lds_settle8(r);
+    else
+        lds_settle4(r);
+}
+
 // ---- compute wave: the slab of 32 channels at column 32 * cw of the workgroup's x tile: (d), (e) ----
 template <int NS, int NC, bool GATHER>
 __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a, int cw, int h, int pin, int nloc,
@@ -215,14 +251,18 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
         for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) sb[pt][ks] = cat8(to_bf16x4(sacc[2 * ks][pt]), to_bf16x4(sacc[2 * ks + 1][pt]));
+        // (the 8-byte pieces are read by instructions of their own, a query block ahead: paired into
+        // ds_read2_b64, as the compiler does with ordinary loads, they run at less than half the rate)
+        strd_s16x4 cr[2][2 * KS];
+        const bf16_t *cbase = &tb.c[lr * L::kCP + 4 * lb];
+        issue_c_pieces<KS>(cbase, cr[0]);
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
             bf16x8 cf[KS];
+            settle_c_pieces<KS>(cr[tt & 1]);
+            if (tt < 3) issue_c_pieces<KS>(cbase + 16 * (tt + 1) * L::kCP, cr[(tt + 1) & 1]);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16_t *row = &tb.c[(16 * tt + lr) * L::kCP + 32 * ks + 4 * lb];
-                cf[ks] = cat8(*reinterpret_cast<const bf16x4 *>(row), *reinterpret_cast<const bf16x4 *>(row + 16));
-            }
+            for (int ks = 0; ks < KS; ++ks) cf[ks] = tr_pair(cr[tt & 1][2 * ks], cr[tt & 1][2 * ks + 1]);
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt) {
                 f32x4 yin = {0.f, 0.f, 0.f, 0.f};
@@ -565,7 +605,7 @@ __device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a,
 template <int NS, int NC, int WHAT, bool GATHER>
 __device__ __forceinline__ void copy_wave(LdsS<NS, NC> &lds, const SegArgs &a, int col_bytes, int tok0, int nloc) {
     using L = LdsS<NS, NC>;
-    using TT = typename std::conditional<WHAT == 0, typename L::XT, typename L::BT>::type;
+    using TT = typename std::conditional<WHAT == 0, typename L::XT, typename std::conditional<WHAT == 1, typename L::BT, typename L::CT>::type>::type;
     const int lane = threadIdx.x & 63;
     __builtin_amdgcn_s_setprio(3);
     const char *src = reinterpret_cast<const char *>(WHAT == 0 ? a.x : WHAT == 1 ? a.B : a.C);
