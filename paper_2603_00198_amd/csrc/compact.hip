@@ -26,17 +26,33 @@ struct Item {
 };
 struct Batch {
     Item item[STRD_COMPACT_MAX + 1];
+    int first_block[STRD_COMPACT_MAX + 2];  // workgroups [first_block[i], first_block[i + 1]) belong to item i
+    int n_items;
+    int grid;  // workgroups of all items together
 };
+// The item a workgroup belongs to and its number among that item's workgroups (uniform).
+// (entries past the last item hold INT_MAX: all bounds are fetched at once and compared without a branch)
+__device__ __forceinline__ int item_of(const Batch &b, int block, int &local) {
+    int i = 0, first = 0;
+#pragma unroll
+    for (int j = 1; j <= STRD_COMPACT_MAX; ++j) {
+        const bool past = block >= b.first_block[j];
+        i += past ? 1 : 0;
+        first = past ? b.first_block[j] : first;
+    }
+    local = block - first;
+    return i;
+}
 
 // Rows of one sequence: source rows count from src_row0, output rows from dst_row0 (both 0 for a
 // single sequence).
 template <typename Vec>
 __device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restrict__ idx, int N, int K, int rows_out,
-                                          size_t src_row0 = 0, size_t dst_row0 = 0) {
+                                          int block, size_t src_row0 = 0, size_t dst_row0 = 0) {
     const int vpr = it.vec_per_row;
     const Vec *__restrict__ src = reinterpret_cast<const Vec *>(it.src) + src_row0 * vpr;
     Vec *__restrict__ dst = reinterpret_cast<Vec *>(it.dst) + dst_row0 * vpr;
-    const int row0 = blockIdx.x * it.rows_per_block;
+    const int row0 = block * it.rows_per_block;
     if (row0 >= rows_out) return;
     const int nrows = min(it.rows_per_block, rows_out - row0);
     const int total = nrows * vpr;
@@ -63,14 +79,16 @@ __device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restr
 
 __global__ __launch_bounds__(kThreads) void compact_kernel(Batch b, const int32_t *__restrict__ idx, int N, int K,
                                                            int rows_out) {
-    const Item &it = b.item[blockIdx.y];
+    // one grid dimension for all tensors: every tensor gets exactly the workgroups its rows need
+    int block;
+    const Item &it = b.item[item_of(b, blockIdx.x, block)];
     if (it.identity) {
-        const int r = blockIdx.x * kThreads + threadIdx.x;
+        const int r = block * kThreads + threadIdx.x;
         if (r < rows_out) reinterpret_cast<int32_t *>(it.dst)[r] = (r < K) ? idx[r] : (N + (r - K));
     } else if (it.vec16) {
-        copy_rows<u32x4>(it, idx, N, K, rows_out);
+        copy_rows<u32x4>(it, idx, N, K, rows_out, block);
     } else {
-        copy_rows<uint32_t>(it, idx, N, K, rows_out);
+        copy_rows<uint32_t>(it, idx, N, K, rows_out, block);
     }
 }
 
@@ -85,9 +103,9 @@ __global__ __launch_bounds__(kThreads) void compact_varlen_kernel(Batch b, const
         const int r = blockIdx.x * kThreads + threadIdx.x;
         if (r < rows_out) reinterpret_cast<int32_t *>(it.dst)[tab.ooff[q] + r] = (r < K) ? ix[r] : (N + (r - K));
     } else if (it.vec16) {
-        copy_rows<u32x4>(it, ix, N, K, rows_out, tab.row0[q], tab.ooff[q]);
+        copy_rows<u32x4>(it, ix, N, K, rows_out, blockIdx.x, tab.row0[q], tab.ooff[q]);
     } else {
-        copy_rows<uint32_t>(it, ix, N, K, rows_out, tab.row0[q], tab.ooff[q]);
+        copy_rows<uint32_t>(it, ix, N, K, rows_out, blockIdx.x, tab.row0[q], tab.ooff[q]);
     }
 }
 
@@ -112,6 +130,7 @@ static int compact_plan(const strd_compact_item *items, int n_items, const int32
         it.rows_per_block = (kThreads * kVecPerThread) / it.vec_per_row;
         if (it.rows_per_block < 1) it.rows_per_block = 1;
         grid_x = max(grid_x, ceil_div(rows_out, it.rows_per_block));
+        b.first_block[n + 1] = ceil_div(rows_out, it.rows_per_block);
         b.item[n++] = it;
     }
     if (pos_out) {
@@ -123,8 +142,21 @@ static int compact_plan(const strd_compact_item *items, int n_items, const int32
         it.vec_per_row = 1;
         it.rows_per_block = kThreads * 8;
         grid_x = max(grid_x, ceil_div(rows_out, pos_in ? it.rows_per_block : kThreads));
+        b.first_block[n + 1] = ceil_div(rows_out, pos_in ? it.rows_per_block : kThreads);
         b.item[n++] = it;
     }
+    // per-item counts -> running totals (used by the single-sequence launch, which has one grid dimension)
+    b.first_block[0] = 0;
+    long long total = 0;
+    for (int i = 0; i < n; ++i) {
+        total += b.first_block[i + 1];
+        if (total > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+        b.first_block[i + 1] = (int)total;
+    }
+    const int grid = b.first_block[n];
+    for (int i = n; i <= STRD_COMPACT_MAX + 1; ++i) b.first_block[i] = 0x7FFFFFFF;
+    b.n_items = n;
+    b.grid = grid;
     return STRD_OK;
 }
 
@@ -149,7 +181,7 @@ int compact_launch(const strd_compact_item *items, int n_items, const int32_t *i
     const int rc = compact_plan(items, n_items, pos_in, pos_out, rows_out, b, n, grid_x);
     if (rc != STRD_OK) return rc;
     if (n == 0) return STRD_OK;
-    compact_kernel<<<dim3(grid_x, n), kThreads, 0, s>>>(b, idx, N, K, rows_out);
+    compact_kernel<<<b.grid, kThreads, 0, s>>>(b, idx, N, K, rows_out);
     return launch_status();
 }
 
