@@ -83,6 +83,7 @@ LONG_SCORE_CASES = [
     (16411, 37, 8, 128, 128),
     (40000, 200, 8, 128, 128),
     (17000, 600, 8, 128, 128),
+    (16500, 1300, 8, 128, 128),   # three passes over the text rows
     (33001, 1150, 8, 24, 64),
     (66000, 129, 2, 32, 128),
     (131075, 64, 1, 4, 64),

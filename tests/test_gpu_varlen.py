@@ -136,3 +136,36 @@ def test_varlen_pipeline_matches_the_single_sequence_calls():
         assert torch.equal(x2[o0:o0 + k + m], x1)
         k0 += k
         o0 += k + m
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_packed_batches(seed):
+    """Seeded random batches (1 to 64 sequences, lengths from 1 to a few thousand tokens) through the
+    packed pipeline: scores against the oracle per sequence, selection and compaction bit for bit."""
+    rng = np.random.default_rng(500 + seed)
+    nseq = int(rng.choice([1, 2, 7, 33, 64]))
+    seqs = []
+    for _ in range(nseq):
+        n = int(rng.integers(1, 3000 if nseq <= 7 else 400))
+        seqs.append((n, int(rng.integers(1, 50)), int(rng.integers(1, n + 1))))
+    H, G, n_state = (16, 2, 64) if seed % 2 else (8, 8, 128)
+    spans, rows = _rows(seqs)
+    g = torch.Generator().manual_seed(500 + seed)
+    _say("random packed batch seed=%d nseq=%d rows=%d" % (seed, nseq, rows))
+    B = (torch.randn(rows, G, n_state, generator=g) / n_state ** 0.5).to(torch.bfloat16)
+    C = torch.randn(rows, G, n_state, generator=g).to(torch.bfloat16)
+    dt = torch.nn.functional.softplus(torch.randn(rows, H, generator=g))
+    hid = torch.randn(rows, 24, generator=g).to(torch.bfloat16).to(DEV)
+    s = strd.score_mamba_varlen(B.to(DEV), C.to(DEV), dt.to(DEV), seqs)
+    idx = strd.select_topk_varlen(s, seqs)
+    (h2,), pos = strd.compact_varlen([hid], idx, seqs, want_pos=True)
+    s_np, i_np = s.cpu().numpy(), idx.cpu().numpy()
+    k0, want_rows = 0, []
+    for b, ((nv, m, k), (v0, t0, t1)) in enumerate(zip(seqs, spans)):
+        assert_close(s_np[b, :nv], oracle.score_mamba(f(B[v0:t0]), f(C[t0:t1]), f(dt[v0:t0])), TOL[torch.bfloat16],
+                     "sequence %d" % b, units=(0,))
+        want = oracle.select_topk(s_np[b, :nv].astype(np.float64), k)
+        np.testing.assert_array_equal(i_np[k0:k0 + k], want)
+        k0 += k
+        want_rows += [v0 + int(i) for i in want] + list(range(t0, t1))
+    assert torch.equal(h2, hid[torch.tensor(want_rows, device=DEV)])
