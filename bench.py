@@ -582,6 +582,20 @@ def variants(torch, strd, synth, dev):
     us_p, us_1 = 1e3 * time_events(torch, packed, iters=10), 1e3 * time_events(torch, one_by_one, iters=10)
     out["reduce_16_clips_of_2048"] = {"packed_us": us_p, "one_call_per_sequence_us": us_1, "gain": us_1 / us_p,
                                       "input_tokens_per_s_packed": rows / (us_p * 1e-6)}
+    # the in-projection of a Mamba-2 block at c4 (33 024 tokens, 4096 -> 18 560): the library product and
+    # the kernel of this library that needs no handle
+    w4 = synth.WORKLOADS["c4"]
+    nd = 2 * w4.mamba.H * w4.mamba.P + 2 * w4.mamba.G * w4.mamba.n + w4.mamba.H
+    u = torch.randn(w4.T, w4.d_model, device=dev).to(torch.bfloat16)
+    wp = (torch.randn(w4.d_model, nd, device=dev) / w4.d_model ** 0.5).to(torch.bfloat16)
+    po = torch.empty(w4.T, nd, dtype=torch.bfloat16, device=dev)
+    flops = 2.0 * w4.T * w4.d_model * nd
+    ms_lib = time_events(torch, lambda: strd.linear(u, wp, out=po), iters=5)
+    ms_own = time_events(torch, lambda: strd.linear_mfma(u, wp, out=po), iters=5)
+    out["in_projection_c4"] = {"T": w4.T, "Kd": w4.d_model, "Nd": nd, "library_ms": ms_lib, "own_kernel_ms": ms_own,
+                               "library_TFLOPs": flops / ms_lib * 1e-9, "own_kernel_TFLOPs": flops / ms_own * 1e-9,
+                               "own_kernel_frac_of_bf16_peak": flops / ms_own * 1e-9 / MFMA_BF16_PEAK_TFLOPS}
+    del u, wp, po
     out["note"] = ("average-pool baseline of the reduction-type ablation on the residual stream; one decode token from "
                    "the state / the key-value rows a prefill leaves (25% budget vs none); device time per call from a "
                    "graph of 20 calls; score + select + compact of a packed batch of short sequences (one set of "
@@ -664,6 +678,9 @@ def block_stack(torch, strd, synth, dev, iters=5):
     parts["gated_rmsnorm_us"] = 1e3 * time_events(torch, lambda: strd.gated_rmsnorm(y2, z, wt["gnorm_w"], s.G), iters=iters)
     g = strd.gated_rmsnorm(y2, z, wt["gnorm_w"], s.G)
     parts["out_proj_us"] = 1e3 * time_events(torch, lambda: strd.linear(g, wt["W_out"], residual=h1), iters=iters)
+    parts["in_proj_own_kernel_us"] = 1e3 * time_events(
+        torch, lambda: (strd.linear_mfma(u, wt["W_z"]), strd.linear_mfma(u, wt["W_xbcdt"])), iters=iters)
+    parts["out_proj_own_kernel_us"] = 1e3 * time_events(torch, lambda: strd.linear_mfma(g, wt["W_out"], residual=h1), iters=iters)
     eb = 2
     glue_bytes = {"rmsnorm": 2 * w.T * w.d_model * eb, "conv1d_silu": 2 * w.T * (d_inner + 2 * gn) * eb,
                   "gated_rmsnorm": 3 * w.T * d_inner * eb}

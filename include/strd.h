@@ -319,9 +319,20 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
  *                 The one entry point that retains something: the first call on a process creates a
  *                 rocBLAS handle (which allocates device workspace of its own) and keeps it until the
  *                 process ends; calls are serialised on it.  Not for callers that must not allocate.
+ * linear_mfma:    the same product by a kernel of this library (bf16 matrix cores, fp32 accumulation,
+ *                 one rounding to bf16 after the optional residual is added in fp32): no handle, no
+ *                 allocation, nothing kept between calls.  bf16 only, Kd a multiple of 64, Nd a multiple
+ *                 of 8, x and w below 4 GiB each, all pointers 16-byte aligned (STRD_EINVAL if not);
+ *                 other shapes return STRD_EUNSUPPORTED (strd_linear_mfma_supported answers that from
+ *                 the shape alone: 1 or 0).  `residual` may be `out`.  On the large projections of a
+ *                 block it reaches about 5/6 of the library product's rate, so strd_linear stays the
+ *                 default for them; this call is for callers that cannot take a library handle.
  * ------------------------------------------------------------------------- */
 int strd_linear(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
                 strd_dtype io, void *stream);
+int strd_linear_mfma(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
+                     strd_dtype io, void *stream);
+int strd_linear_mfma_supported(int T, int Kd, int Nd, strd_dtype io);
 int strd_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, void *stream);
 int strd_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D,
                        int groups, float eps, strd_dtype io, void *stream);

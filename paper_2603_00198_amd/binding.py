@@ -51,6 +51,8 @@ _SIGNATURES = {
     "strd_attn_prefill_workspace": (_sz, [_int] * 4 + [_int]),
     "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
     "strd_linear": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _vp]),
+    "strd_linear_mfma": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _vp]),
+    "strd_linear_mfma_supported": (_int, [_int, _int, _int, _int]),
     "strd_rmsnorm": (_int, [_vp, _vp, _vp, _int, _int, _f32, _int, _vp]),
     "strd_gated_rmsnorm": (_int, [_vp, _vp, _int, _vp, _vp, _int, _int, _int, _f32, _int, _vp]),
     "strd_conv1d_silu": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp] + [_int] * 4 + [_int, _vp]),
@@ -544,6 +546,24 @@ def linear(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = 
     out = out if out is not None else torch.empty((T, Nd), dtype=x.dtype, device=x.device)
     _check(lib().strd_linear(_ptr(x), _ptr(w), _ptr(residual), _ptr(out), T, Kd, Nd, _io(x), _stream()), "linear")
     return out
+
+
+def linear_mfma(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The same product by the library's own matrix-core kernel (bf16; no handle, no allocation)."""
+    _dev(x, w, residual, out)
+    T, Kd = x.shape
+    Nd = w.shape[1]
+    if w.shape[0] != Kd or w.dtype != x.dtype or (residual is not None and (residual.shape != (T, Nd) or
+                                                                             residual.dtype != x.dtype)):
+        raise StrdError("linear_mfma: x [T,Kd], w [Kd,Nd], residual [T,Nd], one dtype")
+    out = out if out is not None else torch.empty((T, Nd), dtype=x.dtype, device=x.device)
+    _check(lib().strd_linear_mfma(_ptr(x), _ptr(w), _ptr(residual), _ptr(out), T, Kd, Nd, _io(x), _stream()), "linear_mfma")
+    return out
+
+
+def linear_mfma_supported(T: int, Kd: int, Nd: int, dtype: torch.dtype) -> bool:
+    return bool(lib().strd_linear_mfma_supported(T, Kd, Nd, 1 if dtype == torch.bfloat16 else 0))
 
 
 def rmsnorm(x: torch.Tensor, w: torch.Tensor, eps: float = 1e-5, out: Optional[torch.Tensor] = None) -> torch.Tensor:

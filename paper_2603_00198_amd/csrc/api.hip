@@ -390,6 +390,17 @@ int strd_linear(const void *x, const void *w, const void *residual, void *out, i
     return linear_rocblas(x, w, residual, out, T, Kd, Nd, io, as_stream(stream));
 }
 
+int strd_linear_mfma_supported(int T, int Kd, int Nd, strd_dtype io) { return linear_mfma_supported(T, Kd, Nd, io) ? 1 : 0; }
+
+int strd_linear_mfma(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd, strd_dtype io,
+                     void *stream) {
+    if (T < 0 || Kd < 1 || Nd < 1 || !io_ok(io) || !w || (T > 0 && (!x || !out))) return STRD_EINVAL;
+    if (T == 0) return STRD_OK;
+    if (!linear_mfma_supported(T, Kd, Nd, io)) return STRD_EUNSUPPORTED;
+    if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)residual | (uintptr_t)out) & 15) return STRD_EINVAL;
+    return linear_mfma(x, w, residual, out, T, Kd, Nd, as_stream(stream));
+}
+
 // ------------------------------------------------------------------ variants ---------------
 int strd_avgpool(const void *src, void *dst, int N, int M, int K, int D, strd_dtype io, const int32_t *pos_in,
                  int32_t *pos_out, void *stream) {

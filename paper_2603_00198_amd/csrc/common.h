@@ -253,6 +253,8 @@ int score_attn_mfma(const void *q, const void *k, float *s, int M, int N, int Hq
                     hipStream_t st);
 int linear_rocblas(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd, strd_dtype io,
                    hipStream_t st);
+bool linear_mfma_supported(int T, int Kd, int Nd, strd_dtype io);
+int linear_mfma(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd, hipStream_t st);
 int glue_conv_max_width();
 int glue_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, hipStream_t st);
 int glue_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D, int groups,

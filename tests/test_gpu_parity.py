@@ -522,6 +522,31 @@ def test_linear_parity(T, Kd, Nd, dtype):
     assert_close(synth.np64(acc), synth.np64(x) @ synth.np64(w) + synth.np64(r), tol, "linear in place")
 
 
+@pytest.mark.parametrize("T,Kd,Nd", [(1, 64, 8), (37, 320, 136), (300, 64, 264), (513, 1024, 2056), (2049, 512, 520)])
+def test_linear_mfma_parity(T, Kd, Nd):
+    """The library's own projection kernel against the dense product in fp64: one tile and several, ragged
+    last token and column tiles, one stage and an odd number of stages, the residual separately and in place."""
+    _say("linear_mfma T=%d Kd=%d Nd=%d" % (T, Kd, Nd))
+    g = torch.Generator(device=DEV).manual_seed(3 * T + Kd)
+    dtype = torch.bfloat16
+    x = torch.randn(T, Kd, generator=g, device=DEV).to(dtype)
+    w = (torch.randn(Kd, Nd, generator=g, device=DEV) / Kd ** 0.5).to(dtype)
+    r = torch.randn(T, Nd, generator=g, device=DEV).to(dtype)
+    want = synth.np64(x) @ synth.np64(w)
+    tol = TOL[dtype]
+    out = torch.full((T + 1, Nd), 7.0, dtype=dtype, device=DEV)       # one guard row after the output
+    strd.linear_mfma(x, w, out=out[:T])
+    assert_close(synth.np64(out[:T]), want, tol, "linear_mfma")
+    assert (out[T] == 7.0).all(), "wrote past the last token"
+    assert_close(synth.np64(strd.linear_mfma(x, w, r)), want + synth.np64(r), tol, "linear_mfma + residual")
+    acc = r.clone()
+    strd.linear_mfma(x, w, acc, out=acc)                               # residual stream updated in place
+    assert_close(synth.np64(acc), want + synth.np64(r), tol, "linear_mfma in place")
+    # one rounding after fp32 accumulation: within one bf16 step of the exact value, element by element
+    got = synth.np64(strd.linear_mfma(x, w))
+    assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-3).all()
+
+
 def test_glue_refuses_misaligned_or_inconsistent_arguments():
     x = torch.randn(8, 30, device=DEV, dtype=torch.bfloat16)
     with pytest.raises(strd.StrdError):

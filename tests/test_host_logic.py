@@ -144,13 +144,13 @@ def test_synthetic_inputs_are_seeded_and_shaped():
 
 
 def test_kernels_with_split_lds_reads_do_not_spill():
-    """ssd_mfma.hip, ssd_seg_mfma.hip and attn_mfma.hip issue LDS reads from inline assembly and wait for them later;
+    """ssd_mfma.hip, ssd_seg_mfma.hip, attn_mfma.hip and linear_mfma.hip issue LDS reads from inline assembly and wait for them later;
     between the two the compiler believes the destination registers hold their values.  A spill of
     such a register before the wait would save garbage, so these kernels must fit their register
     budget without scratch memory.  The compiler's own resource report is the check."""
     import subprocess
     from paper_2603_00198_amd import build as strd_build
-    for name in ("ssd_mfma.hip", "ssd_seg_mfma.hip", "attn_mfma.hip"):
+    for name in ("ssd_mfma.hip", "ssd_seg_mfma.hip", "attn_mfma.hip", "linear_mfma.hip"):
         src = os.path.join(strd_build.CSRC, name)
         cmd = [strd_build.HIPCC] + strd_build.FLAGS + ["--cuda-device-only", "-c", src, "-o", os.devnull,
                                                        "-Rpass-analysis=kernel-resource-usage"]
@@ -197,6 +197,7 @@ def test_entry_points_refuse_inconsistent_arguments_on_the_host():
                               {0: None, 1: None, 2: None, 3: None, 4: -1, 5: 3, 6: 0, 7: 0, 8: -1.0, 9: 7}),
         "strd_rmsnorm": ([P, P, P, 8, 64, 1e-5, BF16, None], {0: None, 1: None, 2: None, 3: -1, 4: 0, 5: -1.0, 6: 7}),
         "strd_avgpool": ([P, P, 100, 4, 10, 64, BF16, None, None, None], {1: None, 2: -1, 3: -1, 4: 101, 6: 7}),
+        "strd_linear_mfma": ([P, P, None, P, 100, 128, 264, BF16, None], {0: None, 1: None, 3: None, 4: -1, 5: 0, 6: 0, 7: 7}),
         "strd_attn_decode_step": ([P, P, P, P, 100, 4, 2, 64, 0.125, BF16, P, BIG, None], {0: None, 3: None, 4: 0, 5: 3, 9: 7}),
     }
     for name, (good, bad) in cases.items():
@@ -276,6 +277,16 @@ def test_matrix_core_shapes_refuse_misaligned_tensors_and_report_their_kernel_pa
     assert L.strd_attn_prefill(P, P, P + 8, P, 64, 4, 2, 128, 0.09, BF16, P, BIG, None) == EINVAL
     assert L.strd_select_topk(P + 4, 100, 10, P, None, 0, None) == EINVAL
     assert L.strd_select_topk_noalloc(P + 4, 100, 10, P, None) == EINVAL
+    # the library's own projection kernel: misaligned tensors, and the shapes it is not tiled for
+    EUNSUPPORTED = -2
+    assert L.strd_linear_mfma(P + 8, P, None, P, 100, 128, 264, BF16, None) == EINVAL
+    assert L.strd_linear_mfma(P, P, P + 2, P, 100, 128, 264, BF16, None) == EINVAL
+    assert L.strd_linear_mfma(P, P, None, P, 100, 100, 264, BF16, None) == EUNSUPPORTED   # Kd not a multiple of 64
+    assert L.strd_linear_mfma(P, P, None, P, 100, 128, 100, BF16, None) == EUNSUPPORTED   # Nd not a multiple of 8
+    assert L.strd_linear_mfma(P, P, None, P, 100, 128, 264, F32, None) == EUNSUPPORTED    # bf16 only
+    assert L.strd_linear_mfma(P, P, None, P, 0, 128, 264, BF16, None) == 0                # nothing to do
+    assert L.strd_linear_mfma_supported(33024, 4096, 18560, BF16) == 1
+    assert L.strd_linear_mfma_supported(1 << 20, 4096, 8, BF16) == 0                      # x of 8 GiB: 32-bit copy offsets
     kp = strd.kernel_path
     bf, f32 = torch.bfloat16, torch.float32
     assert kp("score_attn", 256, 32768, 32, 8, 128) == strd.PATH_MFMA
