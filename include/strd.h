@@ -11,9 +11,9 @@
  *     tensors are token-major, contiguous, batch 1.
  *   - Pointers marked [dev] are device pointers owned by the caller; [host] are
  *     host pointers.  The library allocates, frees and retains no device memory, with
- *     one exception that is stated where it applies: strd_linear hands its product to
- *     rocBLAS and keeps that library's handle (and whatever it allocates) for the life
- *     of the process.
+ *     one exception that is stated where it applies: strd_linear hands the products its
+ *     own kernel is not built for to rocBLAS and keeps that library's handle (and whatever
+ *     it allocates) for the life of the process.
  *   - `io` is the element type of the tensors declared `const void*` / `void*`
  *     (STRD_F32 or STRD_BF16); accumulation, exponentials, decay, state and scores
  *     are always fp32.
@@ -315,23 +315,28 @@ int strd_attn_prefill(const void *q, const void *k, const void *v, void *o, int 
  * softplus_dt:    dt[t,h] = log(1 + exp(raw[t, col0+h] + bias[h])), raw rows of pitch ld in the io
  *                 dtype, bias [H] fp32 or NULL, dt [T,H] fp32.
  * linear:         out[T,Nd] = x[T,Kd] . w[Kd,Nd] (+ residual[T,Nd], which may be `out` itself): the
- *                 projections of a block, a plain dense product handed to rocBLAS (fp32 accumulation).
- *                 The one entry point that retains something: the first call on a process creates a
- *                 rocBLAS handle (which allocates device workspace of its own) and keeps it until the
- *                 process ends; calls are serialised on it.  Not for callers that must not allocate.
- * linear_mfma:    the same product by a kernel of this library (bf16 matrix cores, fp32 accumulation,
- *                 one rounding to bf16 after the optional residual is added in fp32): no handle, no
- *                 allocation, nothing kept between calls.  bf16 only, Kd a multiple of 64, Nd a multiple
- *                 of 8, x and w below 4 GiB each, all pointers 16-byte aligned (STRD_EINVAL if not);
- *                 other shapes return STRD_EUNSUPPORTED (strd_linear_mfma_supported answers that from
- *                 the shape alone: 1 or 0).  `residual` may be `out`.  On the large projections of a
- *                 block it reaches about 5/6 of the library product's rate, so strd_linear stays the
- *                 default for them; this call is for callers that cannot take a library handle.
+ *                 projections of a block, fp32 accumulation, the residual added in fp32 before the one
+ *                 rounding.  Large bf16 products (see linear_mfma; at least one 256 x 256 output tile per
+ *                 CU, 16-byte aligned pointers) run on the library's own kernel; everything else (fp32,
+ *                 other shapes, small products) is handed to rocBLAS.  That second path is the one place
+ *                 where something is retained: its first use in a process creates a rocBLAS handle (which
+ *                 allocates device workspace of its own) and keeps it until the process ends; calls are
+ *                 serialised on it.  Callers that must not allocate use strd_linear_mfma.
+ * linear_library: the same product by rocBLAS whatever the shape (what strd_linear falls back to; kept as an
+ *                 entry point so that the two can be timed side by side).
+ * linear_mfma:    the same product by the library's own kernel only (bf16 matrix cores): no handle, no
+ *                 allocation, nothing kept between calls.  bf16, Kd a multiple of 64, Nd a multiple of 8,
+ *                 x and w below 4 GiB each, all pointers 16-byte aligned (STRD_EINVAL if not); other shapes
+ *                 return STRD_EUNSUPPORTED (strd_linear_mfma_supported answers that from the shape alone:
+ *                 1 or 0).  `residual` may be `out`.  Any size is computed correctly; below one output tile
+ *                 per CU most of the chip idles.
  * ------------------------------------------------------------------------- */
 int strd_linear(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
                 strd_dtype io, void *stream);
 int strd_linear_mfma(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
                      strd_dtype io, void *stream);
+int strd_linear_library(const void *x, const void *w, const void *residual, void *out, int T, int Kd, int Nd,
+                        strd_dtype io, void *stream);
 int strd_linear_mfma_supported(int T, int Kd, int Nd, strd_dtype io);
 int strd_rmsnorm(const void *x, const void *w, void *out, int T, int d, float eps, strd_dtype io, void *stream);
 int strd_gated_rmsnorm(const void *y, const void *z, int ldz, const void *w, void *out, int T, int D,

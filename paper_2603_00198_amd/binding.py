@@ -52,6 +52,7 @@ _SIGNATURES = {
     "strd_attn_prefill": (_int, [_vp] * 4 + [_int] * 4 + [_f32, _int, _vp, _sz, _vp]),
     "strd_linear": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _vp]),
     "strd_linear_mfma": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _vp]),
+    "strd_linear_library": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _vp]),
     "strd_linear_mfma_supported": (_int, [_int, _int, _int, _int]),
     "strd_rmsnorm": (_int, [_vp, _vp, _vp, _int, _int, _f32, _int, _vp]),
     "strd_gated_rmsnorm": (_int, [_vp, _vp, _int, _vp, _vp, _int, _int, _int, _f32, _int, _vp]),
@@ -536,7 +537,7 @@ def _rows(t: torch.Tensor, what: str) -> int:
 
 def linear(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = None,
            out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """x [T,Kd] . w [Kd,Nd] (+ residual [T,Nd]); a plain library product."""
+    """x [T,Kd] . w [Kd,Nd] (+ residual [T,Nd]): the library's own kernel for large bf16 products, rocBLAS otherwise."""
     _dev(x, w, residual, out)
     T, Kd = x.shape
     Nd = w.shape[1]
@@ -548,18 +549,28 @@ def linear(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = 
     return out
 
 
-def linear_mfma(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = None,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """The same product by the library's own matrix-core kernel (bf16; no handle, no allocation)."""
+def _linear_by(entry: str, x, w, residual, out):
     _dev(x, w, residual, out)
     T, Kd = x.shape
     Nd = w.shape[1]
     if w.shape[0] != Kd or w.dtype != x.dtype or (residual is not None and (residual.shape != (T, Nd) or
                                                                              residual.dtype != x.dtype)):
-        raise StrdError("linear_mfma: x [T,Kd], w [Kd,Nd], residual [T,Nd], one dtype")
+        raise StrdError("%s: x [T,Kd], w [Kd,Nd], residual [T,Nd], one dtype" % entry)
     out = out if out is not None else torch.empty((T, Nd), dtype=x.dtype, device=x.device)
-    _check(lib().strd_linear_mfma(_ptr(x), _ptr(w), _ptr(residual), _ptr(out), T, Kd, Nd, _io(x), _stream()), "linear_mfma")
+    _check(getattr(lib(), "strd_" + entry)(_ptr(x), _ptr(w), _ptr(residual), _ptr(out), T, Kd, Nd, _io(x), _stream()), entry)
     return out
+
+
+def linear_mfma(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The same product by the library's own matrix-core kernel only (bf16; no handle, no allocation)."""
+    return _linear_by("linear_mfma", x, w, residual, out)
+
+
+def linear_library(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor] = None,
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The same product by rocBLAS whatever the shape (to time the two side by side)."""
+    return _linear_by("linear_library", x, w, residual, out)
 
 
 def linear_mfma_supported(T: int, Kd: int, Nd: int, dtype: torch.dtype) -> bool:

@@ -3,6 +3,8 @@ softplus on dt; gated RMS norm) or the attention glue, the mixer on the survivin
 out-projection added to the residual stream.  A reducing block scores with its own projected
 b, c, dt (or q, k) -- after the convolution -- keeps the top K vision tokens and compacts what the
 rest of the block and the later blocks read, the residual stream included (paper Sec. 3.1, 3.2).
+Projections whose outputs nothing reads before the selection (the gate z; the queries and values of
+the vision tokens) are taken after it, of the kept rows only.
 
 The paper builds on the Mamba-2 block and a standard pre-norm attention block without restating
 them; the attention block here carries no positional encoding.  Orchestration only: every tensor
@@ -24,7 +26,6 @@ def mamba_block(hidden: torch.Tensor, N: int, M: int, wt: Dict[str, torch.Tensor
     T = N + M
     d_inner, gn = s.H * s.P, s.G * s.n
     u = strd.rmsnorm(hidden, wt["norm_w"], eps)
-    z = strd.linear(u, wt["W_z"])
     xbcdt = strd.linear(u, wt["W_xbcdt"])
     x, B, C = strd.conv1d_silu(xbcdt, wt["conv_w"], wt["conv_b"], d_inner, gn)
     dt = strd.softplus_dt(xbcdt[:, d_inner + 2 * gn:], wt["dt_bias"])
@@ -33,9 +34,12 @@ def mamba_block(hidden: torch.Tensor, N: int, M: int, wt: Dict[str, torch.Tensor
     if K is not None and K < N:
         scores = strd.score_mamba(B[:N], C[N:], dt[:N])
         idx = strd.select_topk(scores, K)
-        (x, B, C, dt, z, hidden), _ = strd.compact_batch([x, B, C, dt, z, hidden], idx, N, M)
+        # the gate z is read only after the scan: its projection is a row-wise product, so it is taken of the
+        # kept rows of u alone (the same values as projecting every row and compacting, at K + M rows' cost)
+        (x, B, C, dt, u, hidden), _ = strd.compact_batch([x, B, C, dt, u, hidden], idx, N, M)
         info = {"scores": scores, "idx": idx}
         N, T = K, K + M
+    z = strd.linear(u, wt["W_z"])
     y, _ = strd.ssd_prefill(x, dt, wt["A"], B, C, wt["D"], chunk=s.chunk, want_state=False)
     gated = strd.gated_rmsnorm(y.view(T, d_inner), z, wt["gnorm_w"], s.G, eps)
     return strd.linear(gated, wt["W_out"], residual=hidden), N, info
@@ -45,16 +49,20 @@ def attn_block(hidden: torch.Tensor, N: int, M: int, wt: Dict[str, torch.Tensor]
                K: Optional[int] = None, eps: float = 1e-5) -> Tuple[torch.Tensor, int, Dict[str, torch.Tensor]]:
     T = N + M
     u = strd.rmsnorm(hidden, wt["norm_w"], eps)
-    q = strd.linear(u, wt["W_q"]).view(T, s.Hq, s.d)
     k = strd.linear(u, wt["W_k"]).view(T, s.Hkv, s.d)
-    v = strd.linear(u, wt["W_v"]).view(T, s.Hkv, s.d)
     info: Dict[str, torch.Tensor] = {}
     if K is not None and K < N:
-        scores = strd.score_attn(q[N:], k[:N])
+        # the score needs the keys of every vision token but the queries of the text rows only; the queries
+        # and values of the vision tokens are projected after the selection, of the kept rows of u alone
+        # (row-wise products: the same values as projecting every row and compacting)
+        q_txt = strd.linear(u[N:], wt["W_q"]).view(M, s.Hq, s.d)
+        scores = strd.score_attn(q_txt, k[:N])
         idx = strd.select_topk(scores, K)
-        (q, k, v, hidden), _ = strd.compact_batch([q, k, v, hidden], idx, N, M)
+        (k, u, hidden), _ = strd.compact_batch([k, u, hidden], idx, N, M)
         info = {"scores": scores, "idx": idx}
         N, T = K, K + M
+    q = strd.linear(u, wt["W_q"]).view(T, s.Hq, s.d)
+    v = strd.linear(u, wt["W_v"]).view(T, s.Hkv, s.d)
     o = strd.attn_prefill(q, k, v)
     return strd.linear(o.view(T, s.Hq * s.d), wt["W_o"], residual=hidden), N, info
 

@@ -547,6 +547,25 @@ def test_linear_mfma_parity(T, Kd, Nd):
     assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-3).all()
 
 
+def test_linear_picks_its_kernel_by_size_and_both_agree():
+    """strd_linear runs the library's own kernel from one 256 x 256 output tile per CU up and rocBLAS below;
+    both paths against the dense product in fp64 on a shape of 17 x 16 tiles, with the residual in place."""
+    T, Kd, Nd = 4352, 256, 4096
+    _say("linear dispatch T=%d Kd=%d Nd=%d" % (T, Kd, Nd))
+    g = torch.Generator(device=DEV).manual_seed(11)
+    x = torch.randn(T, Kd, generator=g, device=DEV).to(torch.bfloat16)
+    w = (torch.randn(Kd, Nd, generator=g, device=DEV) / Kd ** 0.5).to(torch.bfloat16)
+    r = torch.randn(T, Nd, generator=g, device=DEV).to(torch.bfloat16)
+    want = synth.np64(x) @ synth.np64(w) + synth.np64(r)
+    tol = TOL[torch.bfloat16]
+    for name, fn in (("linear", strd.linear), ("linear_mfma", strd.linear_mfma), ("linear_library", strd.linear_library)):
+        acc = r.clone()
+        fn(x, w, acc, out=acc)
+        assert_close(synth.np64(acc), want, tol, name)
+    # the dispatching call and the own kernel are the same launch: identical bits
+    assert torch.equal(strd.linear(x, w, r), strd.linear_mfma(x, w, r))
+
+
 def test_glue_refuses_misaligned_or_inconsistent_arguments():
     x = torch.randn(8, 30, device=DEV, dtype=torch.bfloat16)
     with pytest.raises(strd.StrdError):

@@ -198,6 +198,7 @@ def test_entry_points_refuse_inconsistent_arguments_on_the_host():
         "strd_rmsnorm": ([P, P, P, 8, 64, 1e-5, BF16, None], {0: None, 1: None, 2: None, 3: -1, 4: 0, 5: -1.0, 6: 7}),
         "strd_avgpool": ([P, P, 100, 4, 10, 64, BF16, None, None, None], {1: None, 2: -1, 3: -1, 4: 101, 6: 7}),
         "strd_linear_mfma": ([P, P, None, P, 100, 128, 264, BF16, None], {0: None, 1: None, 3: None, 4: -1, 5: 0, 6: 0, 7: 7}),
+        "strd_linear": ([P, P, None, P, 4352, 256, 4096, BF16, None], {0: None, 1: None, 3: None, 4: -1, 5: 0, 6: 0, 7: 7}),
         "strd_attn_decode_step": ([P, P, P, P, 100, 4, 2, 64, 0.125, BF16, P, BIG, None], {0: None, 3: None, 4: 0, 5: 3, 9: 7}),
     }
     for name, (good, bad) in cases.items():
