@@ -3,13 +3,18 @@
 // produced and consumed tile by tile with a running max and sum per query.
 //
 // One workgroup = NW waves = one query head x 32 * NW consecutive query positions; wave w owns 32
-// of them.  Tiles are computed transposed (v_mfma_f32_32x32x16_bf16):
+// of them as two tiles of 16.  Tiles are computed transposed (v_mfma_f32_16x16x32_bf16):
 //     S^T[key, t] = K_tile . Q^T        A = key rows from LDS, B = query fragments in registers
 //     O^T[d,  t] += V_tile^T . P^T      A = V read with the transposing LDS load, B = P^T
-// so a lane owns one query column: its running max, running sum and the rescale factor are
-// per-lane scalars, and the fp32 score accumulators of a 32-key tile, converted to bf16, are
-// already laid out as the B operand of the second product (8 consecutive accumulator registers
-// = the 8 contraction slots of a lane; V is read with the matching key permutation).
+// so a lane owns one query column of each tile: its running max, running sum and the rescale
+// factor are per-lane scalars (shared by the four lane groups that hold different keys of the
+// query), and the fp32 score accumulators of two 16-key tiles, converted to bf16, are already
+// laid out as the B operand of the second product: lane group lb holds keys 4 lb .. 4 lb + 3 of
+// both tiles, i.e. the 8 contraction slots of a 32-key step in the order (4 lb + s, 16 + 4 lb + s),
+// and V is read with the matching key permutation.
+// The 16 x 16 x 32 form of the product is deliberate: with 32 x 32 x 16 products (half as many
+// operand reads) the asynchronous K / V copies and the matrix pipe do not overlap -- the same
+// kernel took 18 % longer at 33 K tokens.
 // K and V stream through LDS in chunks of KC keys, double-buffered, shared by the waves; the next
 // chunk is copied global -> LDS asynchronously (no register staging) during the current one.
 // Two shapes: 4 waves that request their own copies and 64-key chunks (two workgroups per CU) for
@@ -23,37 +28,30 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.f;  // log2 of how far a probability may exceed 1 before the reference moves
 
-// K rows are read 16 bytes per lane, 16 rows per quarter wave: conflict-free when the row pitch is
-// 4 words modulo 64 (one pad vector).  V is read with the transposing load, 4 rows x 64 bytes per
-// half wave: conflict-free when the pitch is 16 words modulo 64 (four pad vectors, never copied).
+// K rows are read 16 bytes per lane, lane = (row lane % 16, piece lane / 16), V with the transposing load,
+// 8 consecutive rows per half wave: both run fastest at a row pitch of 8 words modulo 32 (two pad
+// vectors, never copied): 180 and 118 bytes per clock and CU, against 117 and 108 with one pad vector.
 // NC = number of waves that fill the tiles.
 template <int D, int NC, int KC>
 struct Tile {
-    using A = AsyncTile<KC, D / 8, NC>;
-    using AV = AsyncTile<KC, D / 8, NC, 4, true>;
+    using A = AsyncTile<KC, D / 8, NC, 2, true>;
     static constexpr int kPitch = A::kPitch;
-    static constexpr int kPitchV = AV::kPitch;
     struct alignas(16) Half {
         bf16_t e[A::kBytes / 2];
         __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitch + c; }
     };
-    struct alignas(16) HalfV {
-        bf16_t e[AV::kBytes / 2];
-        __device__ __forceinline__ const bf16_t *at(int r, int c) const { return e + r * kPitchV + c; }
-    };
     Half k[2];
-    HalfV v[2];
+    Half v[2];
 };
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
 // NW computing waves and NC copy waves; NC = 0: the computing waves request the copies themselves.
@@ -61,11 +59,11 @@ template <int D, int NW, int NC, int KC>
 __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_eu(2, NC ? 3 : 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v, bf16_t *__restrict__ o, int T,
     int Hq, int Hkv, float scale2, int nqb, int xcd_map) {
-    constexpr int KS = D / 16, DT = D / 32, kBM = 32 * NW;
+    constexpr int KS = D / 32, DT = D / 16, kBM = 32 * NW;
     using TileT = Tile<D, NC ? NC : NW, KC>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     TileT &lds = *reinterpret_cast<TileT *>(smem_raw);
-    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lr = lane & 15, lb = lane >> 4;
     const float lazy_raw = kLazy / scale2;  // the slack of the softmax reference, in raw score units
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, in a scalar register
     // Workgroup b runs on XCD b % 8, each with an L2 of its own.  When the kv heads divide evenly over
@@ -87,7 +85,7 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
         kvh = h / (Hq / Hkv);
     }
     const int t0 = qb * kBM;
-    const int tq = t0 + 32 * w + lc;             // this lane's query position
+    const int tq0 = t0 + 32 * w + lr, tq1 = tq0 + 16;  // this lane's query positions (tiles 0 and 1)
     // first query of the wave, in a scalar register so that tests on it are real branches (the wave
     // index comes from threadIdx, which the compiler cannot prove uniform)
     const int wq0 = __builtin_amdgcn_readfirstlane(t0 + 32 * w);
@@ -102,7 +100,6 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
     // requests its share.  The slots of a lane are recomputed for every chunk (a few integer
     // operations) rather than held in registers.
     using AT = typename TileT::A;
-    using ATV = typename TileT::AV;
     const int cw = NC ? w - NW : w;
     const uint32_t kv_row = (uint32_t)Hkv * D * 2;
     const uint32_t kv_col = (uint32_t)kvh * D * 2;
@@ -116,11 +113,11 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
             AT::issue(reinterpret_cast<const char *>(k) + off, &lds.k[b], cw, i);
         }
 #pragma unroll
-        for (int i = 0; i < ATV::kIssues; ++i) {
+        for (int i = 0; i < AT::kIssues; ++i) {
             int row, cv;
-            ATV::slot(cw, lane, i, row, cv);
+            AT::slot(cw, lane, i, row, cv);
             const uint32_t off = (uint32_t)min(next_chunk * KC + row, T - 1) * kv_row + kv_col + (uint32_t)cv * 16;
-            ATV::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], cw, i);
+            AT::issue(reinterpret_cast<const char *>(v) + off, &lds.v[b], cw, i);
         }
         ++next_chunk;
     };
@@ -136,24 +133,26 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
         return;
     }
 
-    bf16x8 bq[KS];
+    // query fragments: B operand, column = query lr of the tile, k slots d = 32 ks + 8 lb ..
+    bf16x8 bq[2][KS];
     {
-        const bf16_t *qp = q + ((size_t)min(tq, T - 1) * Hq + h) * D;
+        const bf16_t *qp0 = q + ((size_t)min(tq0, T - 1) * Hq + h) * D + 8 * lb;
+        const bf16_t *qp1 = q + ((size_t)min(tq1, T - 1) * Hq + h) * D + 8 * lb;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks + 8 * half);
+        for (int ks = 0; ks < KS; ++ks) {
+            bq[0][ks] = *reinterpret_cast<const bf16x8 *>(qp0 + 32 * ks);
+            bq[1][ks] = *reinterpret_cast<const bf16x8 *>(qp1 + 32 * ks);
+        }
     }
 
-    f32x16 oacc[DT];
+    // O^T tiles: oacc[dt][qt][r] = channel 16 dt + 4 lb + r of query (qt, lr)
+    f32x4 oacc[DT][2];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
-    float m_run = -INFINITY, m_neg = 0.f, l_run = 0.f;  // l_run: this lane half's share of the row sum
+    for (int dt = 0; dt < DT; ++dt) oacc[dt][0] = oacc[dt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // per query tile; l_run: this lane group's share of the row sum
+    float m_run[2] = {-INFINITY, -INFINITY}, m_neg[2] = {0.f, 0.f}, l_run[2] = {0.f, 0.f};
 
-    // lane-dependent parts of the transposed V read
-    const int vb = lane >> 4, vr = lane & 15;
-    const int v_krow = 4 * (vb >> 1) + (vr >> 2), v_col = 16 * (vb & 1) + 4 * (vr & 3);
-
+    constexpr int kRowB = TileT::kPitch * 2;  // row pitch of the tiles in bytes
     if (NC == 0) {
         stage(0);
         async_tile_wait();
@@ -166,76 +165,109 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
         for (int kt = 0; kt < KC / 32; ++kt) {
             const int kb = chunk * KC + 32 * kt;
             if (kb <= wmax) {  // uniform per wave
-                // all key fragments of the tile first (one LDS round trip, not one per product)
-                bf16x8 kf[KS];
+                // all key fragments of the 32 keys first (one LDS round trip, not one per product):
+                // A operand, row = key lr of a 16-key tile, k slots d = 32 ks + 8 lb ..
+                bf16x8 kf[2][KS];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    kf[ks] = *reinterpret_cast<const bf16x8 *>(lds.k[cur].at(32 * kt + lc, 16 * ks + 8 * half));
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        kf[j][ks] = *reinterpret_cast<const bf16x8 *>(lds.k[cur].at(32 * kt + 16 * j + lr, 32 * ks + 8 * lb));
                 __builtin_amdgcn_sched_barrier(0);
-                f32x16 sacc;
+                // sacc[qt][j][r] = score of key kb + 16 j + 4 lb + r for query (qt, lr)
+                f32x4 sacc[2][2];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+                for (int qt = 0; qt < 2; ++qt) sacc[qt][0] = sacc[qt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
                 // products first: the other wave of the SIMD is most likely in its softmax, and a
                 // matrix instruction that waits behind its vector instructions leaves the matrix pipe idle
                 __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) sacc = mfma32(kf[ks], bq[ks], sacc);
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int qt = 0; qt < 2; ++qt) sacc[qt][j] = mfma16(kf[j][ks], bq[qt][ks], sacc[qt][j]);
                 __builtin_amdgcn_s_setprio(0);
-                // the transposed V fragments of the tile are requested now and arrive during the softmax
-                constexpr int kHi = 8 * TileT::kPitchV * 2;  // byte offset of the second 4 keys of a slot group
-                strd_s16x4 vr8[2][(DT + 3) / 4][8];
+                // the transposed V fragments are requested now and arrive during the softmax: lane group lb
+                // passes rows 4 lb + lr / 4 (then + 16) and columns 4 (lr % 4) of a 16-channel tile and
+                // receives, for channel lr, the keys 4 lb .. 4 lb + 3 (then 16 + 4 lb ..): the slot order of P
+                // (64 channels now; the other 64 are requested after the softmax, when the score registers are free)
+                strd_s16x4 vr8[DT / 4][8];
+                const bf16_t *vp = lds.v[cur].at(32 * kt + 4 * lb + (lr >> 2), 4 * (lr & 3));
+                lds_issue_tr8<0, 16 * kRowB, 32, 16 * kRowB + 32, 64, 16 * kRowB + 64, 96, 16 * kRowB + 96>(vp, vr8[0]);
+                if (kb + 31 > wq0) {  // uniform: some (key, query) pair of the block is masked
+                    asm volatile("" ::);  // keeps this a branch: folded into selects it would run for every block
 #pragma unroll
-                for (int ks2 = 0; ks2 < 2; ++ks2) {
-                    const bf16_t *vp = lds.v[cur].at(32 * kt + 16 * ks2 + v_krow, v_col);
+                    for (int j = 0; j < 2; ++j)
 #pragma unroll
-                    for (int dp = 0; dp < DT; dp += 4)
-                        lds_issue_tr8<0, kHi, 64, 64 + kHi, 128, 128 + kHi, 192, 192 + kHi>(vp + 32 * dp, vr8[ks2][dp / 4]);
+                        for (int r = 0; r < 4; ++r) {
+                            const int key = kb + 16 * j + 4 * lb + r;
+                            if (key > tq0) sacc[0][j][r] = -INFINITY;
+                            if (key > tq1) sacc[1][j][r] = -INFINITY;
+                        }
                 }
-                if (kb + 31 > wq0) {  // uniform: some (key, query) pair of the tile is masked
+                float tm[2];  // max of this lane's 8 raw scores per query tile
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (kb + 8 * (i / 4) + 4 * half + (i % 4) > tq) sacc[i] = -INFINITY;
+                for (int qt = 0; qt < 2; ++qt) {
+                    float t = sacc[qt][0][0];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) t = fmaxf(t, sacc[qt][j][r]);
+                    tm[qt] = t;
                 }
-                float tm = -INFINITY;  // max of this lane half's 16 raw scores
-#pragma unroll
-                for (int i = 0; i < 16; ++i) tm = fmaxf(tm, sacc[i]);
-                // m_run (raw units) is the reference the exponentials are taken against, common to both
-                // lane halves of a query.  Softmax does not care which reference is used, so it follows
-                // the running max lazily: it moves (and the accumulators are rescaled, and the halves
+                // m_run (raw units) is the reference the exponentials are taken against, common to the four
+                // lane groups of a query.  Softmax does not care which reference is used, so it follows
+                // the running max lazily: it moves (and the accumulators are rescaled, and the groups
                 // talk) only when some lane sees a score more than 2^kLazy above it; until then the
                 // probabilities are merely allowed to reach 2^kLazy instead of 1.
-                if (__any(tm > m_run + lazy_raw)) {
-                    tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
-                    const float nm = fmaxf(m_run, tm);  // finite: key 0 is visible to every query
-                    const float corr = ex2((m_run - nm) * scale2);
-                    l_run *= corr;
+                if (__any(tm[0] > m_run[0] + lazy_raw || tm[1] > m_run[1] + lazy_raw)) {
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
+                    for (int qt = 0; qt < 2; ++qt) {
+                        float t = tm[qt];
+                        t = fmaxf(t, __shfl_xor(t, 16, kWave));
+                        t = fmaxf(t, __shfl_xor(t, 32, kWave));
+                        const float nm = fmaxf(m_run[qt], t);  // finite: key 0 is visible to every query
+                        const float corr = ex2((m_run[qt] - nm) * scale2);
+                        l_run[qt] *= corr;
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[dt][i] *= corr;
-                    m_run = nm;
-                    m_neg = -nm * scale2;
+                        for (int dt = 0; dt < DT; ++dt) oacc[dt][qt] *= corr;
+                        m_run[qt] = nm;
+                        m_neg[qt] = -nm * scale2;
+                    }
                 }
-                float ps = 0.f;
                 bf16x8 pf[2];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = ex2(fmaf(sacc[i], scale2, m_neg));  // 2^((s - m) * scale * log2 e)
-                    ps += p;
-                    pf[i >> 3][i & 7] = (bf16_t)p;
+                for (int qt = 0; qt < 2; ++qt) {
+                    float ps = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float p = ex2(fmaf(sacc[qt][j][r], scale2, m_neg[qt]));  // 2^((s - m) * scale * log2 e)
+                            ps += p;
+                            pf[qt][4 * j + r] = (bf16_t)p;
+                        }
+                    l_run[qt] += ps;
                 }
-                l_run += ps;
+#pragma unroll
+                for (int dp = 1; dp < DT / 4; ++dp)
+                    lds_issue_tr8<0, 16 * kRowB, 32, 16 * kRowB + 32, 64, 16 * kRowB + 64, 96, 16 * kRowB + 96>(vp + 64 * dp, vr8[dp]);
                 __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-                for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-                    for (int dp = 0; dp < DT; dp += 4) {
-                        strd_s16x4(&r)[8] = vr8[ks2][dp / 4];
+                for (int dp = 0; dp < DT / 4; ++dp) {
+                    strd_s16x4(&r)[8] = vr8[dp];
+                    if (dp + 1 < DT / 4)
+                        lds_settle8_but<8 * (DT / 4 - 1)>(r);  // LDS reads return in order: the later batch may still travel
+                    else
                         lds_settle8(r);
 #pragma unroll
-                        for (int dd = 0; dd < 4; ++dd)
-                            if (dp + dd < DT) oacc[dp + dd] = mfma32(tr_pair(r[2 * dd], r[2 * dd + 1]), pf[ks2], oacc[dp + dd]);
+                    for (int dd = 0; dd < 4; ++dd) {
+                        const bf16x8 vf = tr_pair(r[2 * dd], r[2 * dd + 1]);
+                        oacc[4 * dp + dd][0] = mfma16(vf, pf[0], oacc[4 * dp + dd][0]);
+                        oacc[4 * dp + dd][1] = mfma16(vf, pf[1], oacc[4 * dp + dd][1]);
                     }
+                }
                 __builtin_amdgcn_s_setprio(0);
             }
         }
@@ -243,19 +275,23 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
         lds_barrier();  // chunk + 1 has landed, every wave is done with this one
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    if (tq < T) {
-        const float inv = 1.f / l_tot;
-        bf16_t *op = o + ((size_t)tq * Hq + h) * D;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+    for (int qt = 0; qt < 2; ++qt) {
+        float l_tot = l_run[qt];
+        l_tot += __shfl_xor(l_tot, 16, kWave);
+        l_tot += __shfl_xor(l_tot, 32, kWave);
+        const int tq = qt ? tq1 : tq0;
+        if (tq < T) {
+            const float inv = 1.f / l_tot;
+            bf16_t *op = o + ((size_t)tq * Hq + h) * D + 4 * lb;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
+            for (int dt = 0; dt < DT; ++dt) {
                 bf16x4 out;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) out[e] = (bf16_t)(oacc[dt][4 * i4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(op + 32 * dt + 8 * i4 + 4 * half) = out;
+                for (int e = 0; e < 4; ++e) out[e] = (bf16_t)(oacc[dt][qt][e] * inv);
+                *reinterpret_cast<bf16x4 *>(op + 16 * dt) = out;
             }
+        }
     }
 }
 

@@ -161,6 +161,15 @@ __device__ __forceinline__ void lds_settle8(strd_s16x4 (&r)[8]) {
                  :
                  : "memory");
 }
+// The same with up to N later LDS operations of the wave still outstanding (they return in order).
+template <int N>
+__device__ __forceinline__ void lds_settle8_but(strd_s16x4 (&r)[8]) {
+    static_assert(N >= 0 && N < 16, "lgkmcnt has 4 bits");
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+                 : "i"(N)
+                 : "memory");
+}
 __device__ __forceinline__ strd_bf16x8 tr_pair(strd_s16x4 lo, strd_s16x4 hi) {
     return __builtin_shufflevector(__builtin_bit_cast(strd_bf16x4, lo), __builtin_bit_cast(strd_bf16x4, hi), 0, 1, 2, 3,
                                    4, 5, 6, 7);
