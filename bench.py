@@ -698,12 +698,13 @@ def matrix_core_rate(torch, strd, dev):
     its power management allows, beside the published 2.5 PFLOP/s the roofline fractions are taken of."""
     out = torch.empty(512 * 256, dtype=torch.float32, device=dev)
     res = {}
-    for tag, rnd in (("constant_operands", 0), ("random_operands", 1)):
-        strd.mfma_rate_probe(512, 2000, rnd, out)
+    for tag, rnd, small in (("constant_operands", 0, False), ("random_operands", 1, False),
+                            ("random_operands_16x16x32", 1, True)):
+        strd.mfma_rate_probe(512, 2000, rnd, out, small_products=small)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        strd.mfma_rate_probe(512, 10000, rnd, out)
+        strd.mfma_rate_probe(512, 10000, rnd, out, small_products=small)
         e1.record()
         torch.cuda.synchronize()
         res[tag + "_TFLOPs"] = 512 * 4 * 10000 * 32 * 32768 / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -65,12 +65,13 @@ int strd_version(void);
 
 /* Measurement aid (used by the benchmark, not by the path; for callers that want to know what
  * the matrix cores of their chip sustain): `workgroups` x 4 waves each issue `iters` x 32
- * independent v_mfma_f32_32x32x16_bf16 products on register-resident operands -- random bf16
- * values in +-[1, 2) if random_operands != 0, else 1.0 everywhere -- and write one float per thread
- * to out [dev] [workgroups * 256] (a checksum, so that nothing is optimised away).  One launch is
- * workgroups * 4 * iters * 32 * 32768 flop; time it with events on `stream`.
- * STRD_EINVAL for out == NULL, workgroups < 1 or iters < 1. */
-int strd_mfma_rate_probe(float *out, int workgroups, int iters, int random_operands, void *stream);
+ * independent v_mfma_f32_32x32x16_bf16 products on register-resident operands and write one
+ * float per thread to out [dev] [workgroups * 256] (a checksum, so that nothing is optimised
+ * away).  `mode` bit 0: random bf16 operands in +-[1, 2) instead of 1.0 everywhere; bit 1: the
+ * 16 x 16 x 32 form of the instruction, twice as many products of half the size.  One launch is
+ * workgroups * 4 * iters * 32 * 32768 flop in either form; time it with events on `stream`.
+ * STRD_EINVAL for out == NULL, workgroups < 1, iters < 1 or mode outside 0..3. */
+int strd_mfma_rate_probe(float *out, int workgroups, int iters, int mode, void *stream);
 
 /* Which device kernel a call with these sizes runs: STRD_PATH_MFMA (bf16 matrix cores),
  * STRD_PATH_SIMT (fp32 arithmetic on the vector units: fp32 tensors, and bf16 shapes outside

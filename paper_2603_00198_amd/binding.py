@@ -287,12 +287,14 @@ def compact_batch(srcs: Sequence[torch.Tensor], idx: torch.Tensor, N: int, M: in
 
 
 def mfma_rate_probe(workgroups: int, iters: int, random_operands: bool, out: Optional[torch.Tensor] = None,
-                    device="cuda") -> torch.Tensor:
-    """Launches the matrix-core rate probe (a measurement aid): workgroups * 4 * iters * 32 * 32768 flop."""
+                    device="cuda", small_products: bool = False) -> torch.Tensor:
+    """Launches the matrix-core rate probe (a measurement aid): workgroups * 4 * iters * 32 * 32768 flop, as
+    32 x 32 x 16 products or (small_products) twice as many 16 x 16 x 32 ones."""
     if out is None:
         out = torch.empty(workgroups * 256, dtype=torch.float32, device=device)
     _dev(out)
-    _check(lib().strd_mfma_rate_probe(_ptr(out), workgroups, iters, int(bool(random_operands)), _stream()), "mfma_rate_probe")
+    mode = int(bool(random_operands)) | (2 if small_products else 0)
+    _check(lib().strd_mfma_rate_probe(_ptr(out), workgroups, iters, mode, _stream()), "mfma_rate_probe")
     return out
 
 

@@ -138,9 +138,9 @@ int strd_compact(const void *src, const int32_t *idx, void *dst, int N, int M, i
 }
 
 // ------------------------------------------------------------------ measurement aid --------
-int strd_mfma_rate_probe(float *out, int workgroups, int iters, int random_operands, void *stream) {
-    if (!out || workgroups < 1 || iters < 1 || workgroups > (1 << 20)) return STRD_EINVAL;
-    return mfma_rate_probe(out, workgroups, iters, random_operands, as_stream(stream));
+int strd_mfma_rate_probe(float *out, int workgroups, int iters, int mode, void *stream) {
+    if (!out || workgroups < 1 || iters < 1 || workgroups > (1 << 20) || mode < 0 || mode > 3) return STRD_EINVAL;
+    return mfma_rate_probe(out, workgroups, iters, mode, as_stream(stream));
 }
 
 // ------------------------------------------------------------------ packed batches ---------

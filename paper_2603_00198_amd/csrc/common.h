@@ -301,7 +301,7 @@ int ssd_mfma(const void *x, const float *dt, const float *A, const void *B, cons
              const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G,
              int n, hipStream_t st);
 
-int mfma_rate_probe(float *out, int workgroups, int iters, int random_operands, hipStream_t st);
+int mfma_rate_probe(float *out, int workgroups, int iters, int mode, hipStream_t st);
 bool attn_general_supported(int d);
 int attn_general(const void *q, const void *k, const void *v, void *o, int T, int Hq, int Hkv, int d,
                  float scale, strd_dtype io, hipStream_t st);

@@ -1,6 +1,7 @@
 // Measurement aid, not part of the path: the rate at which this chip issues dense bf16 products
-// (v_mfma_f32_32x32x16_bf16) from registers, with nothing else in the way -- no loads, no LDS,
-// four independent accumulators per wave.  The published peak (2.5 PFLOP/s) assumes the nominal
+// (v_mfma_f32_32x32x16_bf16, or twice as many v_mfma_f32_16x16x32_bf16: the same flops per
+// iteration) from registers, with nothing else in the way -- no loads, no LDS, four (eight)
+// independent accumulators per wave.  The published peak (2.5 PFLOP/s) assumes the nominal
 // clock; under full-rate products the clock follows the power the operands draw, and random bf16
 // operands (what real activations look like to the multipliers) draw far more than constants.
 // The benchmark reports both rates beside the fraction of the published peak, so that a kernel's
@@ -12,11 +13,13 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kFrags = 8;  // operand fragments of each kind a wave rotates through
 
+template <bool SMALL>
 __global__ __launch_bounds__(kThreads) void mfma_rate_kernel(float *__restrict__ out, int iters, int random_operands) {
     bf16x8 a[kFrags], b[kFrags];
     const unsigned id = blockIdx.x * kThreads + threadIdx.x;
@@ -35,31 +38,52 @@ __global__ __launch_bounds__(kThreads) void mfma_rate_kernel(float *__restrict__
         a[f] = __builtin_bit_cast(bf16x8, ra);
         b[f] = __builtin_bit_cast(bf16x8, rb);
     }
-    f32x16 acc[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int f = 0; f < kFrags; ++f)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], b[(f + 2 * j + 1) % kFrags], acc[j], 0, 0, 0);
-    }
     float t = 0.f;
+    if constexpr (SMALL) {
+        f32x4 acc[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) t += acc[j][i];
+            for (int f = 0; f < kFrags; ++f)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[f], b[(f + j + 1) % kFrags], acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t += acc[j][i];
+    } else {
+        f32x16 acc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int f = 0; f < kFrags; ++f)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], b[(f + 2 * j + 1) % kFrags], acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t += acc[j][i];
+    }
     out[id] = t;
 }
 
 }  // namespace
 
-// flops of one launch: workgroups x 4 waves x iters x 32 products x 32768
-int mfma_rate_probe(float *out, int workgroups, int iters, int random_operands, hipStream_t st) {
-    mfma_rate_kernel<<<workgroups, kThreads, 0, st>>>(out, iters, random_operands);
+// flops of one launch: workgroups x 4 waves x iters x 32 products x 32768 (64 products x 16384 in the small form).
+// mode: bit 0 = random operands, bit 1 = the 16 x 16 x 32 form of the product
+int mfma_rate_probe(float *out, int workgroups, int iters, int mode, hipStream_t st) {
+    if (mode & 2)
+        mfma_rate_kernel<true><<<workgroups, kThreads, 0, st>>>(out, iters, mode & 1);
+    else
+        mfma_rate_kernel<false><<<workgroups, kThreads, 0, st>>>(out, iters, mode & 1);
     return launch_status();
 }
 

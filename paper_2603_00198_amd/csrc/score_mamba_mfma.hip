@@ -237,17 +237,22 @@ __global__ __launch_bounds__(kThreads) void score_mamba_full_reduce_kernel(const
 // at most one workgroup per CU).  The group's text rows are copied into LDS once (up to
 // kResBytes of them at a time), after which the waves share nothing: each takes token tiles of
 // 32*CT tokens in turn, loads their b fragments and the group's dt values straight from global
-// memory, and runs through all text rows with no barrier.  Products for the next 32 text rows
-// are issued before the previous accumulators are folded, so the |acc| additions run under the
-// matrix-core work.  It writes a[g][i] = (sum_{h in g} dt_i^h) * sum_m |b_i^g . c_m^g|; the sum over
-// groups and the scale are a second, small kernel.  The workgroups of one slice are dealt to one
-// XCD, so that the dt rows (each group reads its own 4*H/G bytes of every row) meet in one L2.
+// memory, and runs through all text rows with no barrier.  Products are v_mfma_f32_16x16x32_bf16
+// (A = 16 text rows, B = 16 tokens; on this chip the small form of the instruction sustains a higher
+// rate than 32x32x16 at the same flops), one row tile at a time against every token tile of the wave:
+// independent accumulator chains, and while they run the accumulators of the row tile before are
+// folded, so the |acc| additions sit under the matrix-core work.  It writes
+// a[g][i] = (sum_{h in g} dt_i^h) * sum_m |b_i^g . c_m^g|; the sum over groups and the scale are a
+// second, small kernel.  The workgroups of one slice are dealt to one XCD, so that the dt rows
+// (each group reads its own 4*H/G bytes of every row) meet in one L2.
 typedef int strd_i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kResThreads = 512;
 constexpr int kResBytes = 156 * 1024;  // LDS for text rows (160 KB per CU less a little for the runtime)
+constexpr int kResPad = 2;             // pad vectors per text row: pitch = 8 words mod 32, the fast one for 16 rows x 4 pieces
 
 template <int NS>
-constexpr int res_max_rows() { return kResBytes / ((NS / 8 + 1) * 16) / 32 * 32; }
+constexpr int res_max_rows() { return kResBytes / ((NS / 8 + kResPad) * 16) / 32 * 32; }
 
 template <int NS, int CT>
 __global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16_t *__restrict__ Bv,
@@ -255,11 +260,12 @@ __global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16
                                                                       const float *__restrict__ dtv,
                                                                       float *__restrict__ part, int M, int N, int G,
                                                                       int H, int slices, int slice_len) {
-    constexpr int KS = NS / 16, VR = NS / 8, VP = VR + 1, kPitch = VP * 8, kRows = res_max_rows<NS>();
+    constexpr int KS = NS / 32, NT = 2 * CT;  // k-steps of a product; 16-token tiles per wave tile
+    constexpr int VR = NS / 8, VP = VR + kResPad, kPitch = VP * 8, kRows = res_max_rows<NS>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     const bf16_t *text = reinterpret_cast<const bf16_t *>(smem_raw);
 
-    const int tid = threadIdx.x, lane = tid & 63, lc = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lr = lane & 15, lb = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     int slice, g;
     if (slices % kXcd == 0) {  // workgroup b runs on XCD b % 8: keep the groups of a slice together
@@ -276,7 +282,7 @@ __global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16
 
     for (int m0 = 0; m0 < M; m0 += kRows) {
         const int rows = min(kRows, M - m0);  // valid text rows of this pass
-        const int nmt = (rows + 31) / 32;  // 32-row products
+        const int nmt = (rows + 31) / 32;  // blocks of 32 text rows
         if (m0 > 0) __syncthreads();  // every wave is done with the previous rows
         // rows past the last one are zeros, so their products add nothing
         const int slots = nmt * 32 * VP;
@@ -294,104 +300,119 @@ __global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16
         async_tile_wait();
         __syncthreads();
 
-        // b fragments of a tile: lane = token column, 8 consecutive k (lanes past the end repeat the last token)
-        auto load_b = [&](int tt, bf16x8(&bf)[CT][KS]) {
+        // b fragments of a wave tile: B operand, column = token lr of a 16-token tile, k slots 32 ks + 8 lb ..
+        // (lanes past the end repeat the last token)
+        auto load_b = [&](int tt, bf16x8(&bf)[NT][KS]) {
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                const int t = min(t_begin + tt * (32 * CT) + 32 * ct + lc, N - 1);
-                const bf16_t *bp = Bv + ((size_t)t * G + g) * NS + 8 * half;
+            for (int nt = 0; nt < NT; ++nt) {
+                const int t = min(t_begin + tt * (32 * CT) + 16 * nt + lr, N - 1);
+                const bf16_t *bp = Bv + ((size_t)t * G + g) * NS + 8 * lb;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) bf[ct][ks] = *reinterpret_cast<const bf16x8 *>(bp + 16 * ks);
+                for (int ks = 0; ks < KS; ++ks) bf[nt][ks] = *reinterpret_cast<const bf16x8 *>(bp + 32 * ks);
             }
         };
-        bf16x8 bfr[CT][KS];
+        bf16x8 bfr[NT][KS];
         load_b(w, bfr);
+        // last pass: the dt values of the group; each lane group sums a quarter of them.  With 16 heads per
+        // group (rows of 16*G floats from a 16-byte aligned base: float4 loads) the values of a tile are
+        // requested a whole tile before they are used: those of the first tile here, those of the next
+        // tile where the current ones have been consumed.
+        const bool last = m0 + kRows >= M;
+        const bool dt16 = hpg == 16;
+        float4 dq[NT];
+        auto load_dt = [&](int tt) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                dq[nt] = *reinterpret_cast<const float4 *>(
+                    dtv + (size_t)min(t_begin + tt * (32 * CT) + 16 * nt + lr, N - 1) * H + g * 16 + lb * 4);
+        };
+        if (last && dt16) load_dt(w);
         for (int tt = w; tt < ntile; tt += kResThreads / kWave) {
             const int tok0 = t_begin + tt * (32 * CT);
             // the fragments of this wave's next tile are requested now and used after this tile's
             // products (past the last tile they re-read the sequence's last token and are dropped)
-            bf16x8 bnx[CT][KS];
+            bf16x8 bnx[NT][KS];
             load_b(tt + kResThreads / kWave, bnx);
-            // last pass: the dt values of the group; each half of the wave sums one half of them.
-            // With 16 heads per group the loads are issued here and used after the products.
-            const bool last = m0 + kRows >= M;
-            const bool dt16 = hpg == 16;  // rows of 16*G floats from a 16-byte aligned base: float4 loads
-            float4 dq[CT][2];
-            if (last && dt16) {
+            // Per 16 text rows (one row tile): its products with every token tile, k-step by k-step, four
+            // independent accumulator chains; meanwhile the accumulators of the row tile before are folded.
+            // Each piece of a text row is replaced by the piece of the row 32 further on right after its
+            // last product, a whole round of the other row tile's products before it is needed again.
+            float part_sum[NT];
+            f32x4 acc[NT];
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    const float4 *d4 = reinterpret_cast<const float4 *>(
-                        dtv + (size_t)min(tok0 + 32 * ct + lc, N - 1) * H + g * 16 + half * 8);
-                    dq[ct][0] = d4[0];
-                    dq[ct][1] = d4[1];
-                }
+            for (int nt = 0; nt < NT; ++nt) {
+                part_sum[nt] = 0.f;
+                acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-            // Per 32 text rows: the products of token block 0 while the accumulator of the last
-            // block (previous rows) is folded, then block 1 while block 0 is folded, ...  Each of
-            // the KS pieces of a text row is replaced by the piece of the row 32 further on right
-            // after its last product, a whole block of products before it is needed.
-            float part_sum[CT];
-            f32x16 acc[CT];
+            // A operand: row = text row lr of a 16-row tile, k slots 32 ks + 8 lb ..
+            const bf16_t *ap = text + lr * kPitch + 8 * lb;
+            bf16x8 a[2][KS];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                part_sum[ct] = 0.f;
+            for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[ct][i] = 0.f;
-            }
-            const bf16_t *ap = text + lc * kPitch + 8 * half;
-            bf16x8 a[KS];
+                for (int ks = 0; ks < KS; ++ks) a[rt][ks] = *reinterpret_cast<const bf16x8 *>(ap + 16 * rt * kPitch + 32 * ks);
+            auto fold = [&]() {  // the accumulators of a row tile whose products are complete (zeros the first time)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) a[ks] = *reinterpret_cast<const bf16x8 *>(ap + 16 * ks);
-            auto fold = [&](int ct) {
-                float t = 0.f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) t += fabsf(acc[ct][i]);
-                part_sum[ct] += t;
+                for (int nt = 0; nt < NT; ++nt)
+                    part_sum[nt] += (fabsf(acc[nt][0]) + fabsf(acc[nt][1])) + (fabsf(acc[nt][2]) + fabsf(acc[nt][3]));
             };
             for (int mt = 0; mt < nmt; ++mt) {
                 const bf16_t *np = ap + (size_t)min(mt + 1, nmt - 1) * 32 * kPitch;
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    f32x16 c;
+                for (int rt = 0; rt < 2; ++rt) {
+                    f32x4 c[NT];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) c[i] = 0.f;
+                    for (int nt = 0; nt < NT; ++nt) c[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bfr[ct][ks], c, 0, 0, 0);
-                        if (ct == CT - 1) a[ks] = *reinterpret_cast<const bf16x8 *>(np + 16 * ks);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            c[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt][ks], bfr[nt][ks], c[nt], 0, 0, 0);
+                        a[rt][ks] = *reinterpret_cast<const bf16x8 *>(np + 16 * rt * kPitch + 32 * ks);
                     }
-                    fold(ct == 0 ? CT - 1 : ct - 1);  // a block whose products are complete (zeros the first time)
+                    fold();
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
+                    for (int i = 0; i < NT * KS; ++i) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        if (ct == CT - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 16 / KS, 0);
+                        if (i % NT == NT - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
                     }
-                    acc[ct] = c;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[nt] = c[nt];
                 }
             }
-            fold(CT - 1);
+            fold();
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) bfr[ct][ks] = bnx[ct][ks];
+                for (int ks = 0; ks < KS; ++ks) bfr[nt][ks] = bnx[nt][ks];
+            float dsum[NT];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                float col = part_sum[ct] + __shfl_xor(part_sum[ct], 32, kWave);
-                const int t = tok0 + 32 * ct + lc;
+            for (int nt = 0; nt < NT; ++nt) {
+                dsum[nt] = 0.f;
+                if (last) {
+                    if (dt16) {
+                        dsum[nt] = (dq[nt].x + dq[nt].y) + (dq[nt].z + dq[nt].w);
+                    } else {
+                        const float *dp = dtv + (size_t)min(tok0 + 16 * nt + lr, N - 1) * H + g * hpg;
+                        for (int j = lb; j < hpg; j += 4) dsum[nt] += dp[j];
+                    }
+                }
+            }
+            if (last && dt16) load_dt(tt + kResThreads / kWave);  // (past the last tile: the last token again, dropped)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                // the four lane groups hold different text rows of the same token
+                float col = part_sum[nt] + __shfl_xor(part_sum[nt], 16, kWave);
+                col += __shfl_xor(col, 32, kWave);
+                const int t = tok0 + 16 * nt + lr;
                 float *dst = part + (size_t)g * N + t;
-                const bool mine = half == 0 && t < t_end;
+                const bool mine = lb == 0 && t < t_end;
                 if (m0 > 0 && mine) col += *dst;
                 if (last) {
-                    float a = 0.f;
-                    if (dt16) {
-                        a = ((dq[ct][0].x + dq[ct][0].y) + (dq[ct][0].z + dq[ct][0].w)) +
-                            ((dq[ct][1].x + dq[ct][1].y) + (dq[ct][1].z + dq[ct][1].w));
-                    } else {
-                        const float *dp = dtv + (size_t)min(t, N - 1) * H + g * hpg;
-                        for (int j = half; j < hpg; j += 2) a += dp[j];
-                    }
-                    col *= a + __shfl_xor(a, 32, kWave);
+                    float a = dsum[nt] + __shfl_xor(dsum[nt], 16, kWave);
+                    a += __shfl_xor(a, 32, kWave);
+                    col *= a;
                 }
                 if (mine) *dst = col;
             }
@@ -420,7 +441,7 @@ template <int NS, int CT>
 int launch_res(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, void *ws,
                hipStream_t st) {
     const int rows = std::min(res_max_rows<NS>(), (M + 31) / 32 * 32);
-    const size_t smem = (size_t)rows * (NS / 8 + 1) * 16;
+    const size_t smem = (size_t)rows * (NS / 8 + kResPad) * 16;
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(&score_mamba_res_kernel<NS, CT>), smem)) return STRD_EHIP;
     int slices, slice_len;
     res_plan(N, G, CT, &slices, &slice_len);
@@ -497,9 +518,8 @@ int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, in
                      void *ws, hipStream_t st) {
     // Long sequences: text rows resident in LDS, one workgroup per CU.  It pays once every wave
     // has a few token tiles of its own (one slice = N / (256 / G) tokens, shared by 8 waves).
+    // (Wave tiles of 32 tokens: with 64 the kernel is no faster and, at n = 128, out of registers.)
     const long long per_slice = (long long)N / std::max(1, 256 / G);
-    if (per_slice >= 4096)
-        return n == 128 ? launch_res<128, 2>(B, C, dt, s, M, N, H, G, ws, st) : launch_res<64, 2>(B, C, dt, s, M, N, H, G, ws, st);
     if (per_slice >= 512)
         return n == 128 ? launch_res<128, 1>(B, C, dt, s, M, N, H, G, ws, st) : launch_res<64, 1>(B, C, dt, s, M, N, H, G, ws, st);
     // wide token tiles once there are enough of them to fill 256 CUs several times over

@@ -172,3 +172,6 @@ def test_matrix_core_rate_probe_counts_its_products():
     assert out.shape == (8 * 256,) and bool((out == 50 * 8192).all())
     rnd = strd.mfma_rate_probe(8, 50, True)
     assert bool(torch.isfinite(rnd).all()) and float(rnd.abs().max()) > 0
+    # the 16 x 16 x 32 form: 32 accumulator entries per lane, each iters * 8 products * 32
+    small = strd.mfma_rate_probe(8, 50, False, small_products=True)
+    assert bool((small == 50 * 8192).all())

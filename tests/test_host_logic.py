@@ -218,6 +218,7 @@ def test_rate_probe_refuses_empty_launches():
     assert L.strd_mfma_rate_probe(None, 4, 10, 0, None) == -1
     assert L.strd_mfma_rate_probe(0x1000, 0, 10, 0, None) == -1
     assert L.strd_mfma_rate_probe(0x1000, 4, 0, 1, None) == -1
+    assert L.strd_mfma_rate_probe(0x1000, 4, 10, 4, None) == -1
 
 
 def test_packed_batch_entry_points_validate_their_descriptors_on_the_host():
