@@ -230,3 +230,33 @@ def test_variants_at_benchmark_shapes():
     vc = torch.randn(T, a.Hkv, a.d, generator=g, device=DEV).to(torch.bfloat16)
     o = strd.attn_decode_step(q, kc, vc)
     assert_close(f(o), oracle.attn_decode_step(f(q), f(kc), f(vc)), TOLB, "attn decode c3 reduced cache", units=(0,))
+
+
+def test_c4_block_projections_sampled():
+    """The projections of a c4 block at their full size (33 024 tokens; 4096 -> 18 560 in, 8192 -> 4096 out with the
+    residual), as `bench.py --block-stack` launches them: the library's own kernel through strd_linear.  Sampled
+    elements, the edges of the output and whole rows against the dense product in fp64; the same call by rocBLAS
+    within the same tolerance."""
+    w = synth.WORKLOADS["c4"]
+    T = w.T
+    g = torch.Generator(device="cpu").manual_seed(7)
+    rng = np.random.default_rng(7)
+    for Kd, Nd, with_res in ((w.d_model, 18560, False), (2 * w.d_model, w.d_model, True)):
+        _say("c4 projection: T=%d Kd=%d Nd=%d residual=%s" % (T, Kd, Nd, with_res))
+        assert strd.linear_mfma_supported(T, Kd, Nd, torch.bfloat16)
+        x = torch.randn(T, Kd, generator=g).to(torch.bfloat16).to(DEV)
+        wt = (torch.randn(Kd, Nd, generator=g) / Kd ** 0.5).to(torch.bfloat16).to(DEV)
+        r = torch.randn(T, Nd, generator=g).to(torch.bfloat16).to(DEV) if with_res else None
+        out = strd.linear(x, wt, r)
+        assert torch.equal(out, strd.linear_mfma(x, wt, r))            # the size picks the library's own kernel
+        ts = np.concatenate([rng.integers(0, T, 400), [0, 255, 256, T - 257, T - 256, T - 1]])
+        ns = np.concatenate([rng.integers(0, Nd, 400), [0, 255, 256, Nd - 257, Nd - 9, Nd - 1]])
+        ti, ni = torch.from_numpy(ts).long().to(DEV), torch.from_numpy(ns).long().to(DEV)
+        want = f(x[ti]) @ f(wt[:, ni])                                  # [406, 406]: every sampled row x every sampled column
+        if with_res:
+            want = want + f(r[ti][:, ni])
+        assert_close(f(out[ti][:, ni]), want, TOLB, "sampled block")
+        whole = f(x[ti[-3:]]) @ f(wt) + (f(r[ti[-3:]]) if with_res else 0.0)
+        assert_close(f(out[ti[-3:]]), whole, TOLB, "whole rows")
+        assert_close(f(strd.linear_library(x, wt, r)[ti][:, ni]), want, TOLB, "the same by the library product")
+        del x, wt, r, out
