@@ -28,6 +28,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -236,19 +237,21 @@ __global__ __launch_bounds__((NW + NC) * kWave) __attribute__((amdgpu_waves_per_
                         m_neg[qt] = -nm * scale2;
                     }
                 }
+                // The row sum is taken of the probabilities as they enter the second product, i.e. rounded to
+                // bf16 (numerator and denominator then carry the same rounding), two at a time.
                 bf16x8 pf[2];
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt) {
-                    float ps = 0.f;
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const float p = ex2(fmaf(sacc[qt][j][r], scale2, m_neg[qt]));  // 2^((s - m) * scale * log2 e)
-                            ps += p;
-                            pf[qt][4 * j + r] = (bf16_t)p;
-                        }
-                    l_run[qt] += ps;
+                        for (int r = 0; r < 4; ++r)
+                            pf[qt][4 * j + r] = (bf16_t)ex2(fmaf(sacc[qt][j][r], scale2, m_neg[qt]));  // 2^((s - m) * scale * log2 e)
+                    float ps = l_run[qt];
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2)
+                        ps = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pf[qt][e], pf[qt][e + 1]}, bf16x2{(bf16_t)1.f, (bf16_t)1.f}, ps, false);
+                    l_run[qt] = ps;
                 }
 #pragma unroll
                 for (int dp = 1; dp < DT / 4; ++dp)
