@@ -522,10 +522,12 @@ def test_linear_parity(T, Kd, Nd, dtype):
     assert_close(synth.np64(acc), synth.np64(x) @ synth.np64(w) + synth.np64(r), tol, "linear in place")
 
 
-@pytest.mark.parametrize("T,Kd,Nd", [(1, 64, 8), (37, 320, 136), (300, 64, 264), (513, 1024, 2056), (2049, 512, 520)])
+@pytest.mark.parametrize("T,Kd,Nd", [(1, 64, 8), (37, 320, 136), (300, 64, 264), (257, 128, 24), (40, 192, 512), (513, 1024, 2056),
+                                     (2049, 512, 520)])
 def test_linear_mfma_parity(T, Kd, Nd):
     """The library's own projection kernel against the dense product in fp64: one tile and several, ragged
-    last token and column tiles, one stage and an odd number of stages, the residual separately and in place."""
+    last token and column tiles, every length of the copy ring's start-up and tail (2, 4, 6 stages of 32 and
+    more), the residual separately and in place."""
     _say("linear_mfma T=%d Kd=%d Nd=%d" % (T, Kd, Nd))
     g = torch.Generator(device=DEV).manual_seed(3 * T + Kd)
     dtype = torch.bfloat16
