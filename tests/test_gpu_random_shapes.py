@@ -241,3 +241,28 @@ def test_score_mamba_full_random_shape(seed):
     got = strd.score_mamba_full(_dev(Ball[:N].contiguous()), _dev(Call[N:].contiguous()), _dev(dt), _dev(A))
     want = oracle.score_mamba_full(f(Ball), f(Call), f(dt), f(A), N)
     assert_close(got.cpu().numpy(), want, TOL[torch.bfloat16], "score_mamba_full", units=(0,))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_linear_mfma_random_shape(seed):
+    """The library's own projection kernel on token counts, input widths (multiples of 64) and output
+    widths (multiples of 8) drawn together: ragged last tiles in both directions, any number of
+    k stages, with and without the residual.  Checked against the dense product in fp64."""
+    rng = np.random.default_rng(8000 + seed)
+    g = torch.Generator().manual_seed(8000 + seed)
+    T = int(rng.integers(1, 1400))
+    Kd = 64 * int(rng.integers(1, 20))
+    Nd = 8 * int(rng.integers(1, 130))
+    with_res = bool(rng.integers(2))
+    _say("linear_mfma random T=%d Kd=%d Nd=%d residual=%s" % (T, Kd, Nd, with_res))
+    assert strd.linear_mfma_supported(T, Kd, Nd, torch.bfloat16)
+    x = torch.randn(T, Kd, generator=g).to(torch.bfloat16)
+    w = (torch.randn(Kd, Nd, generator=g) / Kd ** 0.5).to(torch.bfloat16)
+    r = torch.randn(T, Nd, generator=g).to(torch.bfloat16) if with_res else None
+    want = f(x) @ f(w) + (f(r) if with_res else 0.0)
+    out = torch.full((T + 1, Nd), 7.0, dtype=torch.bfloat16, device=DEV)      # one guard row after the output
+    strd.linear_mfma(_dev(x), _dev(w), _dev(r) if with_res else None, out=out[:T])
+    assert_close(f(out[:T]), want, TOL[torch.bfloat16], "linear_mfma")
+    assert (out[T] == 7.0).all(), "wrote past the last token"
+    # the dispatching call gives the same values whichever kernel it picks (rocBLAS at these sizes)
+    assert_close(f(strd.linear(_dev(x), _dev(w), _dev(r) if with_res else None)), want, TOL[torch.bfloat16], "linear")
