@@ -18,7 +18,7 @@ inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
 // pays, one workgroup per (head, 32 channels) over the whole sequence (ssd_mfma) otherwise.
 inline bool use_seg(int T, int rows, int H, int P, int G, int n, strd_dtype io) {
     return ssd_seg_supported(T, rows, H, P, G, n, io) &&
-           (ssd_seg_preferred(T, H, P) || !ssd_mfma_supported(T, rows, H, P, G, n, io));
+           (ssd_seg_preferred(T, H, P, G) || !ssd_mfma_supported(T, rows, H, P, G, n, io));
 }
 // The kernels read and write 16-byte vectors straight from the caller's pointers.
 template <typename... P>
@@ -254,7 +254,7 @@ int strd_compact_varlen(const strd_compact_item *items, int n_items, const int32
 size_t strd_ssd_prefill_workspace(int T, int H, int P, int G, int n, int chunk, strd_dtype io) {
     (void)chunk;
     if (T < 1 || H < 1 || P < 1 || G < 1 || n < 1 || H % G) return 0;
-    return use_seg(T, T, H, P, G, n, io) ? ssd_seg_ws(T, H, P, n) : 0;
+    return use_seg(T, T, H, P, G, n, io) ? ssd_seg_ws(T, H, P, G, n) : 0;
 }
 
 int strd_ssd_prefill(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
@@ -288,7 +288,7 @@ int strd_ssd_prefill_gather(const void *x, const float *dt, const float *A, cons
     // the same choice of kernel as strd_ssd_prefill makes for K + M tokens: the results must be the same bits
     const bool old = !use_seg((int)T, (int)T, H, P, G, n, io) || !ssd_seg_supported((int)T, N + M, H, P, G, n, io);
     if (old && !ssd_mfma_supported((int)T, N + M, H, P, G, n, io)) return STRD_EUNSUPPORTED;
-    const size_t need = old ? 0 : ssd_seg_ws((int)T, H, P, n);
+    const size_t need = old ? 0 : ssd_seg_ws((int)T, H, P, G, n);
     if (need && (!ws || ws_bytes < need)) return STRD_EWORKSPACE;
     if (K == 0) {  // only the text rows survive: a dense scan over the tail of the tensors
         const size_t es = 2;

@@ -291,8 +291,8 @@ size_t score_mamba_mfma_ws(int N, int G);
 int score_mamba_mfma(const void *B, const void *C, const float *dt, float *s, int M, int N, int H, int G, int n,
                      void *ws, hipStream_t st);
 bool ssd_seg_supported(int T, int rows, int H, int P, int G, int n, strd_dtype io);
-size_t ssd_seg_ws(int T, int H, int P, int n);
-bool ssd_seg_preferred(int T, int H, int P);
+size_t ssd_seg_ws(int T, int H, int P, int G, int n);
+bool ssd_seg_preferred(int T, int H, int P, int G);
 int ssd_seg(const void *x, const float *dt, const float *A, const void *B, const void *C, const float *D,
             const float *S_in, void *y, float *S_out, const int32_t *idx, int N, int K, int T, int H, int P, int G, int n,
             void *ws, hipStream_t st);

@@ -51,10 +51,9 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 64;       // tokens per step
-constexpr int kRB = 3;       // B / C tiles in LDS (requested kRB - 1 steps ahead)
-constexpr int kRX = 3;       // x tiles in LDS
 constexpr int kRD = 4;       // dt rows in LDS (requested kRD - 1 steps ahead)
-constexpr int threads_for(int NC) { return 64 * (NC + 6); }  // compute waves + 2 G waves + 3 copy waves + helper
+// per head NC compute waves + 2 G waves; 3 copy waves + helper per workgroup
+constexpr int threads_for(int NC, int NH) { return 64 * (NH * (NC + 2) + 4); }
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct SegArgs {
@@ -72,8 +71,10 @@ struct SegArgs {
     int wg_per_seg;       // H * P / (32 * NC)
 };
 
-template <int NS, int NC>
+template <int NS, int NC, int NH>
 struct LdsS {
+    static constexpr int kRB = NH == 1 ? 3 : 2;  // B / C tiles in LDS (requested kRB - 1 steps ahead)
+    static constexpr int kRX = NH == 1 ? 3 : 2;  // x tiles in LDS
     // One B and one C tile, each filled by one wave.  Pitches by measurement (bytes per clock and CU of the
     // read patterns below in a loop of their own, row pitch in 4-byte words modulo the 64 banks):
     //   16-byte reads, lane = (row lane % 16, piece lane / 16):            8: 180    4: 117
@@ -85,7 +86,7 @@ struct LdsS {
     // C tile (16-byte row reads in (a), 8-byte row reads in (d), issued one by one): 1 pad vector, 68 = 4.
     using BT = AsyncTile<kQ, NS / 8, 1, 2, true>;
     using CT = AsyncTile<kQ, NS / 8, 1, 1, true>;
-    using XT = AsyncTile<kQ, NC * 4, 1, 1, true>;  // x tile of the workgroup's channels, 1 pad vector per row (2 changed nothing)
+    using XT = AsyncTile<kQ, NH * NC * 4, 1, 1, true>;  // x tile of the workgroup's channels, 1 pad vector per row (2 changed nothing)
     static constexpr int kBP = BT::kPitch;         // bf16 elements per row of the B tiles
     static constexpr int kCP = CT::kPitch;         // ... of the C tiles
     static constexpr int kXP = XT::kPitch;         // ... of the x tiles
@@ -106,14 +107,14 @@ struct LdsS {
     static constexpr int fw_at(int W) { return W <= 1 ? 0 : W == 2 ? 16 : 48; }
     TileBC bc[kRB];
     TileX xr[kRX];
-    float dt[kRD][kQ];
-    Scan scan[2];
-    bf16x4 yin[2][8 * NC][64];  // carried part of the outputs of step i, [i % 2][query block * 2 NC + channel tile][lane]
+    float dt[NH][kRD][kQ];
+    Scan scan[NH][2];
+    bf16x4 yin[2][NH][8 * NC][64];  // carried part of the outputs of step i, [i % 2][head][query block * 2 NC + channel tile][lane]
     uint32_t rowtab[4][kQ];  // gather mode: source row of every token of local step i, i % 4 = slot
     int32_t rawidx[4][kQ];   // gather mode: entries of the kept-index list for local step i, i % 4 = slot
 };
 
-static_assert(sizeof(LdsS<128, 2>) <= 160 * 1024, "one workgroup must fit the 160 KB of LDS of a CU");
+static_assert(sizeof(LdsS<128, 2, 1>) <= 160 * 1024 && sizeof(LdsS<128, 2, 2>) <= 160 * 1024, "one workgroup must fit the 160 KB of LDS of a CU");
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -193,14 +194,15 @@ __device__ __forceinline__ void settle_c_pieces(strd_s16x4 (&r)[2 * KS]) {
 }
 
 // ---- compute wave: the slab of 32 channels at column 32 * cw of the workgroup's x tile: (d), (e) ----
-template <int NS, int NC, bool GATHER>
-__device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a, int cw, int h, int pin, int nloc,
+template <int NS, int NC, int NH, bool GATHER>
+__device__ __forceinline__ void compute_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, int hh, int cw, int h, int pin, int nloc,
                                              const float *s_src, float *s_dst) {
-    using L = LdsS<NS, NC>;
+    using L = LdsS<NS, NC, NH>;
     constexpr int KS = NS / 32;  // k-steps of the products contracted over n
     constexpr int NT = NS / 16;  // 16-row tiles of the state
     const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
-    const int xcol = 32 * cw;  // first column of the slab in the x tile
+    const int xcol = 32 * (NC * hh + cw);  // first column of the slab in the x tile
+    const int scol = 32 * cw;              // ... in the head
 
     // state: S^T[n][p] tiles, rows n = 16 nt + 4 lb + i, columns p = pin + 32 cw + 16 pt + lr
     f32x4 sacc[NT][2];
@@ -209,7 +211,7 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt) {
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (s_src) v = *reinterpret_cast<const f32x4 *>(s_src + ((size_t)h * a.P + pin + xcol + 16 * pt + lr) * NS + 16 * nt + 4 * lb);
+            if (s_src) v = *reinterpret_cast<const f32x4 *>(s_src + ((size_t)h * a.P + pin + scol + 16 * pt + lr) * NS + 16 * nt + 4 * lb);
             sacc[nt][pt] = v;
         }
 
@@ -218,27 +220,33 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
     __syncthreads();              // scan of the first step
 
     for (int i = 0; i < nloc; ++i) {
-        const typename L::Scan &sc = lds.scan[i & 1];
-        const typename L::TileBC &tb = lds.bc[i % kRB];
-        const bf16_t *xt = lds.xr[i % kRX].x;
-        // ---- LDS reads that do not depend on the arithmetic of the step are requested first ----
-        // x fragments and the first b^T fragments (transposing reads, for (e)); weights; c rows
+        const typename L::Scan &sc = lds.scan[hh][i & 1];
+        const typename L::TileBC &tb = lds.bc[i % L::kRB];
+        const bf16_t *xt = lds.xr[i % L::kRX].x;
+        // ---- LDS reads that do not depend on the arithmetic of the step are requested first: x fragments
+        // and the first b^T fragments (transposing reads, for (e)), the weights.  With three waves on a SIMD
+        // (NH = 2) the registers do not allow that, and the other waves cover the round trip: there these
+        // reads are requested after (d).
         constexpr int R = L::kBP * 2;
+        constexpr bool kEarly = NH == 1;
         strd_s16x4 xr8[8], ba[8], bb[8];
         const int trow = state_tok(lb, lr >> 2);  // the row of a 16-token block this lane passes to a transposing read
-        issue_x_frags<L::kXP>(xt, xcol, trow, lr, xr8);
         const bf16_t *bbase = &tb.b[trow * L::kBP + 4 * (lr & 3)];
-        // state tile d of a group of four: columns + 16 d of the b tile; rows + 0, 16 (token half 0: slots
-        // 0-3, 4-7), + 32, 48 (token half 1); ba: tiles 0, 1; bb: tiles 2, 3
-        lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(bbase, ba);
-        lds_issue_tr8<64, 16 * R + 64, 32 * R + 64, 48 * R + 64, 96, 16 * R + 96, 32 * R + 96, 48 * R + 96>(bbase, bb);
         f32x4 wv[2][2];
+        auto request_e = [&]() __attribute__((always_inline)) {
+            issue_x_frags<L::kXP>(xt, xcol, trow, lr, xr8);
+            // state tile d of a group of four: columns + 16 d of the b tile; rows + 0, 16 (token half 0: slots
+            // 0-3, 4-7), + 32, 48 (token half 1); ba: tiles 0, 1; bb: tiles 2, 3
+            lds_issue_tr8<0, 16 * R, 32 * R, 48 * R, 32, 16 * R + 32, 32 * R + 32, 48 * R + 32>(bbase, ba);
+            lds_issue_tr8<64, 16 * R + 64, 32 * R + 64, 48 * R + 64, 96, 16 * R + 96, 32 * R + 96, 48 * R + 96>(bbase, bb);
 #pragma unroll
-        for (int kr = 0; kr < 2; ++kr)
+            for (int kr = 0; kr < 2; ++kr)
 #pragma unroll
-            for (int hi = 0; hi < 2; ++hi)
+                for (int hi = 0; hi < 2; ++hi)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) wv[kr][hi][e] = sc.w[32 * kr + 16 * hi + state_tok(lb, e)];
+                    for (int e = 0; e < 4; ++e) wv[kr][hi][e] = sc.w[32 * kr + 16 * hi + state_tok(lb, e)];
+        };
+        if constexpr (kEarly) request_e();
         const float dq = sc.carry[kQ - 1];
         // (d): Y^T[p, t] = sum_n S[p, n] c_t[n] (the factor 2^(l_t) is applied where the outputs are summed).
         // A operand straight from the accumulators: the lane holds rows 4 lb .. 4 lb + 3 of state tiles
@@ -268,7 +276,7 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
                 f32x4 yin = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) yin = mfma16(sb[pt][ks], cf[ks], yin);
-                lds.yin[i & 1][tt * (2 * NC) + 2 * cw + pt][lane] = to_bf16x4(yin);  // to the G wave of query block tt
+                lds.yin[i & 1][hh][tt * (2 * NC) + 2 * cw + pt][lane] = to_bf16x4(yin);  // to the G wave of query block tt
             }
             // a quarter of the state's decay per query block
 #pragma unroll
@@ -277,6 +285,7 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
                 for (int pt = 0; pt < 2; ++pt) sacc[nt][pt] *= dq;
         }
         // (e): S^T = 2^(l_Q) S^T + b^T (w x).  The x fragments, weighted in registers, are the B operand.
+        if constexpr (!kEarly) request_e();
         bf16x8 xf[2][2], xwf[2][2];
         take_x_frags(xr8, xf);  // waits for every read requested above
 #pragma unroll
@@ -316,7 +325,7 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
-                *reinterpret_cast<f32x4 *>(s_dst + ((size_t)h * a.P + pin + xcol + 16 * pt + lr) * NS + 16 * nt + 4 * lb) =
+                *reinterpret_cast<f32x4 *>(s_dst + ((size_t)h * a.P + pin + scol + 16 * pt + lr) * NS + 16 * nt + 4 * lb) =
                     sacc[nt][pt];
     }
 }
@@ -324,9 +333,10 @@ __device__ __forceinline__ void compute_wave(LdsS<NS, NC> &lds, const SegArgs &a
 // ---- G wave GW: (a), (b), (c) and the outputs of the query blocks {0, 3} (GW = 0) or {1, 2} (GW = 1) ----
 // The outputs of a step leave one step late: (a)-(c) of step i are summed up in registers during step i,
 // the carried part arrives from the compute waves with the barrier that ends the step.
-template <int NS, int NC, int GW, bool GATHER>
-__device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int h, int chan0, int tok0, int nloc) {
-    using L = LdsS<NS, NC>;
+template <int NS, int NC, int NH, int GW, bool GATHER>
+__device__ __forceinline__ void g_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, int hh, int h, int chan0, int tok0, int nloc) {
+    using L = LdsS<NS, NC, NH>;
+    const int xc0 = 32 * NC * hh;  // first column of the head in the x tile
     constexpr int KS = NS / 32;
     constexpr int PT = 2 * NC;                                  // 16-channel tiles of the workgroup
     constexpr int TA = GW == 0 ? 0 : 1, TB = GW == 0 ? 3 : 2;  // the two query blocks of this wave
@@ -350,12 +360,12 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
     auto emit_read = [&](int j) __attribute__((always_inline)) {
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
-            ia[pt] = lds.yin[j & 1][TA * PT + pt][lane];
-            ib[pt] = lds.yin[j & 1][TB * PT + pt][lane];
+            ia[pt] = lds.yin[j & 1][hh][TA * PT + pt][lane];
+            ib[pt] = lds.yin[j & 1][hh][TB * PT + pt][lane];
         }
     };
     auto emit_turn = [&](int j) __attribute__((always_inline)) {
-        char *sta = reinterpret_cast<char *>(&lds.yin[j & 1][TA * PT][0]), *stb = reinterpret_cast<char *>(&lds.yin[j & 1][TB * PT][0]);
+        char *sta = reinterpret_cast<char *>(&lds.yin[j & 1][hh][TA * PT][0]), *stb = reinterpret_cast<char *>(&lds.yin[j & 1][hh][TB * PT][0]);
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             bf16x4 oa, ob;
@@ -371,7 +381,7 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
         }
     };
     auto emit_back = [&](int j) __attribute__((always_inline)) {
-        const char *sta = reinterpret_cast<const char *>(&lds.yin[j & 1][TA * PT][0]), *stb = reinterpret_cast<const char *>(&lds.yin[j & 1][TB * PT][0]);
+        const char *sta = reinterpret_cast<const char *>(&lds.yin[j & 1][hh][TA * PT][0]), *stb = reinterpret_cast<const char *>(&lds.yin[j & 1][hh][TB * PT][0]);
 #pragma unroll
         for (int k = 0; k < 16 / RPI; ++k) {
             const int r = srow + RPI * k;
@@ -396,41 +406,73 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
     __syncthreads();
 
     for (int i = 0; i < nloc; ++i) {
-        const typename L::Scan &sc = lds.scan[i & 1];
-        const typename L::TileBC &tb = lds.bc[i % kRB];
-        const bf16_t *xt = lds.xr[i % kRX].x;
+        const typename L::Scan &sc = lds.scan[hh][i & 1];
+        const typename L::TileBC &tb = lds.bc[i % L::kRB];
+        const bf16_t *xt = lds.xr[i % L::kRX].x;
         const bool prev = i > 0;  // uniform: the step before has outputs waiting
         // fragments: b rows of key blocks 0..TB, c rows of the two query blocks
         strd_s16x4 xr8[NC][8];
-        bf16x8 bf[TB + 1][KS], cfa[KS], cfb[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-            for (int jt = 0; jt <= TB; ++jt)
-                bf[jt][ks] = *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kBP + 32 * ks + 8 * lb]);
-            cfa[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * TA + lr) * L::kCP + 32 * ks + 8 * lb]);
-            cfb[ks] = *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * TB + lr) * L::kCP + 32 * ks + 8 * lb]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // (a)
         f32x4 ga[TA + 1], gb[TB + 1];
 #pragma unroll
         for (int jt = 0; jt <= TA; ++jt) ga[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int jt = 0; jt <= TB; ++jt) gb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto frag_b = [&](int jt, int ks) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8 *>(&tb.b[(16 * jt + lr) * L::kBP + 32 * ks + 8 * lb]);
+        };
+        auto frag_c = [&](int tt, int ks) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8 *>(&tb.c[(16 * tt + lr) * L::kCP + 32 * ks + 8 * lb]);
+        };
+        if constexpr (NH == 1) {
+            // all fragments requested before (a)
+            bf16x8 bf[TB + 1][KS], cfa[KS], cfb[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-            for (int jt = 0; jt <= TA; ++jt) ga[jt] = mfma16(bf[jt][ks], cfa[ks], ga[jt]);
+                for (int jt = 0; jt <= TB; ++jt) bf[jt][ks] = frag_b(jt, ks);
+                cfa[ks] = frag_c(TA, ks);
+                cfb[ks] = frag_c(TB, ks);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // (a)
 #pragma unroll
-            for (int jt = 0; jt <= TB; ++jt) gb[jt] = mfma16(bf[jt][ks], cfb[ks], gb[jt]);
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int jt = 0; jt <= TA; ++jt) ga[jt] = mfma16(bf[jt][ks], cfa[ks], ga[jt]);
+#pragma unroll
+                for (int jt = 0; jt <= TB; ++jt) gb[jt] = mfma16(bf[jt][ks], cfb[ks], gb[jt]);
+            }
+        } else {
+            // three waves share the SIMD's registers: the fragments of one k-step ahead of the products only
+            bf16x8 bf[2][TB + 1], cfa[2], cfb[2];
+            auto request_a = [&](int ks) __attribute__((always_inline)) {
+#pragma unroll
+                for (int jt = 0; jt <= TB; ++jt) bf[ks & 1][jt] = frag_b(jt, ks);
+                cfa[ks & 1] = frag_c(TA, ks);
+                cfb[ks & 1] = frag_c(TB, ks);
+            };
+            request_a(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) request_a(ks + 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int jt = 0; jt <= TA; ++jt) ga[jt] = mfma16(bf[ks & 1][jt], cfa[ks & 1], ga[jt]);
+#pragma unroll
+                for (int jt = 0; jt <= TB; ++jt) gb[jt] = mfma16(bf[ks & 1][jt], cfb[ks & 1], gb[jt]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         // while (a) runs: the x fragments of every channel tile (for (c)) and the carried part of the step
         // before (published by the barrier that ended it) are requested
+        // (NH = 2: after (b) -- three waves share the SIMD's registers, and cover the round trip)
         __builtin_amdgcn_sched_barrier(0);
+        auto request_c = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int c = 0; c < NC; ++c) issue_x_frags<L::kXP>(xt, 32 * c, 4 * lb + (lr >> 2), lr, xr8[c]);
-        if (prev) emit_read(i - 1);
+            for (int c = 0; c < NC; ++c) issue_x_frags<L::kXP>(xt, xc0 + 32 * c, 4 * lb + (lr >> 2), lr, xr8[c]);
+            if (prev) emit_read(i - 1);
+        };
+        if constexpr (NH == 1) request_c();
         // what (b) needs from the scan of the head
         const float el_a = sc.ell[16 * TA + lr], el_b = sc.ell[16 * TB + lr];
         const float ref_a = TA > 0 ? sc.ell[16 * TA - 1] : 0.f, ref_b = sc.ell[16 * TB - 1];
@@ -444,13 +486,16 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
 #pragma unroll
         for (int jt = 0; jt < TB; ++jt) fjb[jt] = *reinterpret_cast<const f32x4 *>(&sc.fw[L::fw_at(TB) + 16 * jt + 4 * lb]);
         bf16x4 xva[PT] = {}, xvb[PT] = {};
-        if (a.D) {
+        auto request_dx = [&]() __attribute__((always_inline)) {  // this lane's x values for the D term
+            if (a.D) {
 #pragma unroll
-            for (int pt = 0; pt < PT; ++pt) {
-                xva[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TA + lr) * L::kXP + 16 * pt + 4 * lb]);
-                xvb[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TB + lr) * L::kXP + 16 * pt + 4 * lb]);
+                for (int pt = 0; pt < PT; ++pt) {
+                    xva[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TA + lr) * L::kXP + xc0 + 16 * pt + 4 * lb]);
+                    xvb[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TB + lr) * L::kXP + xc0 + 16 * pt + 4 * lb]);
+                }
             }
-        }
+        };
+        if constexpr (NH == 1) request_dx();
         __builtin_amdgcn_sched_barrier(0);
         // (b): blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan at
         // the last token before the query block (both exponents <= 0); diagonal block: direct, masked.
@@ -479,6 +524,10 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
             if (jt <= TB) mb[jt] = weigh(TB, jt, gb[jt <= TB ? jt : 0], el_b, erb, fjb[jt < TB ? jt : 0], elj_b, dtj_b);
         }
         // the rows of the step before are summed, written for turning and read back; they travel under (c)
+        if constexpr (NH != 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            request_c();
+        }
         if (prev) {
             emit_turn(i - 1);
             emit_back(i - 1);
@@ -490,6 +539,10 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC> &lds, const SegArgs &a, int 
         // the stores of the step before go out now, not at the end of the step: the copies of the step
         // share the CU's path to memory with them and were requested at its start
         if (prev) emit_store(i - 1);
+        if constexpr (NH != 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            request_dx();
+        }
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             ya[pt] = yb[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -523,12 +576,14 @@ __device__ __forceinline__ uint32_t gather_row(const SegArgs &a, int t, int32_t 
     return min((uint32_t)(t < a.K ? kept : a.N + (t - a.K)), last_row);
 }
 
-// ---- helper wave: dt copies, the scans of the head, the row tables of the gather form ---------
-template <int NS, int NC, bool GATHER>
-__device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a, int h, int tok0, int nloc, int seg) {
-    using L = LdsS<NS, NC>;
+// ---- helper wave: dt copies, the scans of the workgroup's heads, the row tables of the gather form ----
+template <int NS, int NC, int NH, bool GATHER>
+__device__ __forceinline__ void helper_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, int h0, int tok0, int nloc, int seg) {
+    using L = LdsS<NS, NC, NH>;
     const int lane = threadIdx.x & 63;
-    const float Al2 = a.A[h] * kLog2e;
+    float Al2[NH];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) Al2[hh] = a.A[h0 + hh] * kLog2e;
     __builtin_amdgcn_s_setprio(3);
     auto token_of = [&](int i) { return min(tok0 + i * kQ + lane, a.T - 1); };
     auto kept_of = [&](int i) -> int32_t { return a.idx[min(token_of(i), a.K - 1)]; };  // K >= 1 in gather mode
@@ -537,18 +592,20 @@ __device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a,
                                          (__attribute__((address_space(3))) void *)lds.rawidx[i & 3], 4, 0, 0);
     };
     const uint32_t dt_row = (uint32_t)a.H * 4;
-    auto request_dt = [&](int i) __attribute__((always_inline)) {  // 64 lanes x 4 bytes; rows past T re-read the last row
+    auto request_dt = [&](int i) __attribute__((always_inline)) {  // 64 lanes x 4 bytes per head; rows past T re-read the last row
         const uint32_t row = GATHER ? lds.rowtab[i & 3][lane] : (uint32_t)token_of(i);
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(a.dt) + row * dt_row + (uint32_t)h * 4),
-            (__attribute__((address_space(3))) void *)lds.dt[i % kRD], 4, 0, 0);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(reinterpret_cast<const char *>(a.dt) + row * dt_row + (uint32_t)(h0 + hh) * 4),
+                (__attribute__((address_space(3))) void *)lds.dt[hh][i % kRD], 4, 0, 0);
     };
-    // scan of dt*A of local step i, the key factors of (b), the weights of (e), the carries of (d);
-    // returns the total log2 decay of the step
-    auto make_scan = [&](int i, float raw) __attribute__((always_inline)) -> float {
+    // scan of dt*A of local step i of head hh, the key factors of (b), the weights of (e), the carries
+    // of (d); returns the total log2 decay of the step
+    auto make_scan = [&](int hh, int i, float raw) __attribute__((always_inline)) -> float {
         const float dv = (tok0 + i * kQ + lane < a.T) ? raw : 0.f;
-        const float inc = wave_inclusive_scan_f32(dv * Al2);
-        typename L::Scan &m = lds.scan[i & 1];
+        const float inc = wave_inclusive_scan_f32(dv * Al2[hh]);
+        typename L::Scan &m = lds.scan[hh][i & 1];
         const float tot = read_lane_f32(inc, kQ - 1);
         m.ell[lane] = inc;
         m.dtv[lane] = dv;
@@ -561,7 +618,7 @@ __device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a,
         }
         return tot;
     };
-    constexpr int kNewest = 1 + (GATHER ? 1 : 0);  // copies requested per step
+    constexpr int kNewest = NH + (GATHER ? 1 : 0);  // copies requested per step
 
     if (GATHER) {
 #pragma unroll
@@ -575,12 +632,16 @@ __device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a,
         if (i < nloc) request_dt(i);
     async_tile_wait();
     __syncthreads();  // first copies landed
-    float ltot = make_scan(0, lds.dt[0][lane]);
+    float ltot[NH];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) ltot[hh] = make_scan(hh, 0, lds.dt[hh][0][lane]);
     __syncthreads();  // scan of the first step
 
     for (int i = 0; i < nloc; ++i) {
         // dt of step i + 1 landed before the barrier that ended the previous step (or in the prologue)
-        const float raw = lds.dt[(i + 1) % kRD][lane];
+        float raw[NH];
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) raw[hh] = lds.dt[hh][(i + 1) % kRD][lane];
         int32_t kept = 0;
         if (GATHER) kept = lds.rawidx[(i + 4) & 3][lane];
         __builtin_amdgcn_sched_barrier(0);
@@ -589,7 +650,10 @@ __device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a,
             request_dt(i + 3);                     // slot last read in step i - 2
             if (GATHER) request_kept(i + 6);       // slot last read in step i - 2
         }
-        if (i + 1 < nloc) ltot += make_scan(i + 1, raw);  // buffer last read in step i - 1
+        if (i + 1 < nloc) {                        // buffers last read in step i - 1
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) ltot[hh] += make_scan(hh, i + 1, raw[hh]);
+        }
         if (GATHER) lds.rowtab[(i + 4) & 3][lane] = gather_row(a, token_of(i + 4), kept);  // slot last used in step i - 2
         if (more)
             __builtin_amdgcn_s_waitcnt(vm_wait_imm(kNewest));  // everything requested in earlier steps has landed
@@ -597,15 +661,20 @@ __device__ __forceinline__ void helper_wave(LdsS<NS, NC> &lds, const SegArgs &a,
             async_tile_wait();
         lds_barrier();
     }
-    if (lane == 0 && a.ltot) a.ltot[(size_t)seg * a.H + h] = ltot;
+    if (lane == 0 && a.ltot) {
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) a.ltot[(size_t)seg * a.H + h0 + hh] = ltot[hh];
+    }
 }
 
-// ---- copy waves: one tile stream each (WHAT = 0: x, 1: B, 2: C), two steps ahead.  A wave that
-// requests a copy stands still until the CU's copy path takes it, so these waves do nothing else.
-template <int NS, int NC, int WHAT, bool GATHER>
-__device__ __forceinline__ void copy_wave(LdsS<NS, NC> &lds, const SegArgs &a, int col_bytes, int tok0, int nloc) {
-    using L = LdsS<NS, NC>;
+// ---- copy waves: one tile stream each (WHAT = 0: x, 1: B, 2: C), as far ahead as the ring allows
+// (two steps with three tiles, one step with two).  A wave that requests a copy stands still until
+// the CU's copy path takes it, so these waves do nothing else.
+template <int NS, int NC, int NH, int WHAT, bool GATHER>
+__device__ __forceinline__ void copy_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, int col_bytes, int tok0, int nloc) {
+    using L = LdsS<NS, NC, NH>;
     using TT = typename std::conditional<WHAT == 0, typename L::XT, typename std::conditional<WHAT == 1, typename L::BT, typename L::CT>::type>::type;
+    constexpr int RING = WHAT == 0 ? L::kRX : L::kRB;
     const int lane = threadIdx.x & 63;
     __builtin_amdgcn_s_setprio(3);
     const char *src = reinterpret_cast<const char *>(WHAT == 0 ? a.x : WHAT == 1 ? a.B : a.C);
@@ -619,45 +688,45 @@ __device__ __forceinline__ void copy_wave(LdsS<NS, NC> &lds, const SegArgs &a, i
         col_of[k] = (uint32_t)col_bytes + (uint32_t)cv * 16;
     }
     auto request = [&](int i) __attribute__((always_inline)) {
-        bf16_t *dst = WHAT == 0 ? lds.xr[i % kRX].x : WHAT == 1 ? lds.bc[i % kRB].b : lds.bc[i % kRB].c;
+        bf16_t *dst = WHAT == 0 ? lds.xr[i % L::kRX].x : WHAT == 1 ? lds.bc[i % L::kRB].b : lds.bc[i % L::kRB].c;
 #pragma unroll
         for (int k = 0; k < TT::kIssues; ++k) {
             const uint32_t row = GATHER ? lds.rowtab[i & 3][row_of[k]] : (uint32_t)min(tok0 + i * kQ + row_of[k], a.T - 1);
             TT::issue(src + (size_t)row * row_bytes + col_of[k], dst, 0, k);
         }
     };
-    static_assert(TT::kIssues < 64, "vmcnt has 6 bits");
+    static_assert((RING - 2) * TT::kIssues < 64, "vmcnt has 6 bits");
 
     if (GATHER) __syncthreads();  // row tables of steps 0..3 written
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < RING - 1; ++i)
         if (i < nloc) request(i);
     async_tile_wait();
     __syncthreads();  // first copies landed
     __syncthreads();
 
     for (int i = 0; i < nloc; ++i) {
-        const bool more = i + 2 < nloc;  // uniform
-        if (more) request(i + 2);        // slot last read in step i - 1
-        if (more)
-            __builtin_amdgcn_s_waitcnt(vm_wait_imm(TT::kIssues));  // the tile of step i + 1 has landed
+        const bool more = i + RING - 1 < nloc;  // uniform
+        if (more) request(i + RING - 1);        // slot last read in step i - 1
+        if (more && RING > 2)
+            __builtin_amdgcn_s_waitcnt(vm_wait_imm((RING - 2) * TT::kIssues));  // the tile of step i + 1 has landed
         else
             async_tile_wait();
-        lds_barrier();  // publishes it; this step's copies stay in flight
+        lds_barrier();  // publishes it; with a ring of three this step's copies stay in flight
     }
 }
 
-template <int NS, int NC, bool GATHER>
-__global__ __launch_bounds__(threads_for(NC)) void ssd_seg_kernel(SegArgs a, int nunits) {
-    using L = LdsS<NS, NC>;
+template <int NS, int NC, int NH, bool GATHER>
+__global__ __launch_bounds__(threads_for(NC, NH)) void ssd_seg_kernel(SegArgs a, int nunits) {
+    using L = LdsS<NS, NC, NH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     L &lds = *reinterpret_cast<L *>(smem_raw);
 
     const int unit = xcd_swizzle(blockIdx.x, nunits);
     if (unit >= nunits) return;
     const int seg = unit / a.wg_per_seg, u = unit % a.wg_per_seg;
-    const int chan0 = u * (32 * NC);
-    const int h = chan0 / a.P, pin = chan0 % a.P, g = h / (a.H / a.G);
+    const int chan0 = u * (32 * NC * NH);  // NH = 2: two whole heads of one group (P = 32 NC)
+    const int h0 = chan0 / a.P, pin = chan0 % a.P, g = h0 / (a.H / a.G);
     const int nsteps = (a.T + kQ - 1) / kQ;
     const int s0 = seg * a.seg_steps;
     const int nloc = min(a.seg_steps, nsteps - s0);
@@ -665,19 +734,29 @@ __global__ __launch_bounds__(threads_for(NC)) void ssd_seg_kernel(SegArgs a, int
     // where the segment's state comes from and goes to
     const float *s_src = seg == 0 ? a.S_in : nullptr;
     float *s_dst = seg == a.nseg - 1 ? a.S_out : a.lend + (size_t)seg * a.H * a.P * NS;
+    // Wave i runs on SIMD i % 4.  NH = 1, NC = 2: the compute waves have SIMDs 0 and 1, the G waves 2 and 3, each
+    // with one copy wave beside it.  NH = 2: every SIMD has one compute wave, one G wave and one copy wave, so
+    // the vector work of one overlaps the matrix products of the other.
     const int wave = threadIdx.x >> 6;
-    if (wave < NC) {
-        compute_wave<NS, NC, GATHER>(lds, a, wave, h, pin, nloc, s_src, s_dst);
+    if (wave < NH * NC) {
+        const int hh = NH == 1 ? 0 : wave / NC, cw = NH == 1 ? wave : wave % NC;
+        compute_wave<NS, NC, NH, GATHER>(lds, a, hh, cw, h0 + hh, pin, nloc, s_src, s_dst);
         return;
     }
-    // wave i runs on SIMD i % 4 (NC = 2): the compute waves have SIMDs 0 and 1 to themselves but for one copy wave each
-    switch (wave - NC) {
-        case 0: g_wave<NS, NC, 0, GATHER>(lds, a, h, chan0, tok0, nloc); break;
-        case 1: g_wave<NS, NC, 1, GATHER>(lds, a, h, chan0, tok0, nloc); break;
-        case 2: copy_wave<NS, NC, 1, GATHER>(lds, a, g * NS * 2, tok0, nloc); break;
-        case 3: copy_wave<NS, NC, 2, GATHER>(lds, a, g * NS * 2, tok0, nloc); break;
-        case 4: helper_wave<NS, NC, GATHER>(lds, a, h, tok0, nloc, seg); break;
-        default: copy_wave<NS, NC, 0, GATHER>(lds, a, chan0 * 2, tok0, nloc); break;
+    const int r = wave - NH * NC;
+    if (r < 2 * NH) {
+        const int hh = NH == 1 ? 0 : r >> 1;
+        if (r & 1)
+            g_wave<NS, NC, NH, 1, GATHER>(lds, a, hh, h0 + hh, chan0 + hh * 32 * NC, tok0, nloc);
+        else
+            g_wave<NS, NC, NH, 0, GATHER>(lds, a, hh, h0 + hh, chan0 + hh * 32 * NC, tok0, nloc);
+        return;
+    }
+    switch (r - 2 * NH) {
+        case 0: copy_wave<NS, NC, NH, 1, GATHER>(lds, a, g * NS * 2, tok0, nloc); break;
+        case 1: copy_wave<NS, NC, NH, 2, GATHER>(lds, a, g * NS * 2, tok0, nloc); break;
+        case 2: helper_wave<NS, NC, NH, GATHER>(lds, a, h0, tok0, nloc, seg); break;
+        default: copy_wave<NS, NC, NH, 0, GATHER>(lds, a, chan0 * 2, tok0, nloc); break;
     }
 }
 
@@ -801,27 +880,30 @@ __global__ __launch_bounds__(kFixThreads) void ssd_fix_kernel(SegArgs a) {
     }
 }
 
-template <int NS, int NC, bool GATHER>
+template <int NS, int NC, int NH, bool GATHER>
 int launch(const SegArgs &a, hipStream_t st) {
     const int nunits = a.nseg * a.wg_per_seg;
-    const size_t smem = sizeof(LdsS<NS, NC>);
-    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&ssd_seg_kernel<NS, NC, GATHER>), smem)) return STRD_EHIP;
-    ssd_seg_kernel<NS, NC, GATHER><<<xcd_grid(nunits), threads_for(NC), smem, st>>>(a, nunits);
+    const size_t smem = sizeof(LdsS<NS, NC, NH>);
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&ssd_seg_kernel<NS, NC, NH, GATHER>), smem)) return STRD_EHIP;
+    ssd_seg_kernel<NS, NC, NH, GATHER><<<xcd_grid(nunits), threads_for(NC, NH), smem, st>>>(a, nunits);
     if (a.nseg > 1) ssd_fix_kernel<NS, GATHER><<<dim3(a.nseg, a.H, kFixZ), kFixThreads, 0, st>>>(a);
     return launch_status();
 }
 
 // channels per workgroup / 32: the whole head when that divides, else one slab
 int slabs_per_wg(int P) { return P % 64 == 0 ? 2 : 1; }
+// heads per workgroup: two heads of one group share the B and C tiles when a head is one workgroup's
+// worth of channels and the group has an even number of heads
+int heads_per_wg(int H, int P, int G) { return P == 64 && (H / G) % 2 == 0 ? 2 : 1; }
 
 }  // namespace
 
 // How the sequence is cut: as many segments as it takes to give every CU a workgroup, each at least
 // kMinSegSteps steps long (a shorter segment costs more in its prologue and at its seam than it gains).
-void ssd_seg_plan(int T, int H, int P, int *nseg, int *seg_steps) {
+void ssd_seg_plan(int T, int H, int P, int G, int *nseg, int *seg_steps) {
     constexpr int kMinSegSteps = 8, kCUs = 256;
     const int nsteps = (T + kQ - 1) / kQ;
-    const int wg = H * (P / 32) / slabs_per_wg(P);
+    const int wg = H * (P / 32) / slabs_per_wg(P) / heads_per_wg(H, P, G);
     int s = wg >= kCUs ? 1 : (kCUs + wg - 1) / wg;
     s = max(1, min(s, nsteps / kMinSegSteps));
     const int per = (nsteps + s - 1) / s;
@@ -829,9 +911,9 @@ void ssd_seg_plan(int T, int H, int P, int *nseg, int *seg_steps) {
     *nseg = max(1, (nsteps + *seg_steps - 1) / *seg_steps);
 }
 
-size_t ssd_seg_ws(int T, int H, int P, int n) {
+size_t ssd_seg_ws(int T, int H, int P, int G, int n) {
     int nseg, seg_steps;
-    ssd_seg_plan(T, H, P, &nseg, &seg_steps);
+    ssd_seg_plan(T, H, P, G, &nseg, &seg_steps);
     if (nseg <= 1) return 0;
     return align_up((size_t)(nseg - 1) * H * P * n * sizeof(float), 256) + align_up((size_t)nseg * H * sizeof(float), 256);
 }
@@ -848,9 +930,9 @@ bool ssd_seg_supported(int T, int rows, int H, int P, int G, int n, strd_dtype i
 // a CU's copy path (B and C tiles serve the whole head) and fills the chip with few heads, but pays
 // for its segments with a longer prologue and a second launch: it wins once a segment is long
 // (measured: from about 32 steps at 128 heads), or when the other kernel would leave CUs idle.
-bool ssd_seg_preferred(int T, int H, int P) {
+bool ssd_seg_preferred(int T, int H, int P, int G) {
     int nseg, seg_steps;
-    ssd_seg_plan(T, H, P, &nseg, &seg_steps);
+    ssd_seg_plan(T, H, P, G, &nseg, &seg_steps);
     return nseg >= 2 && (seg_steps >= 32 || H * (P / 32) < 128);
 }
 
@@ -860,21 +942,23 @@ int ssd_seg(const void *x, const float *dt, const float *A, const void *B, const
     SegArgs a;
     a.x = (const bf16_t *)x; a.dt = dt; a.A = A; a.B = (const bf16_t *)B; a.C = (const bf16_t *)C; a.D = D; a.S_in = S_in;
     a.y = (bf16_t *)y; a.S_out = S_out; a.idx = idx; a.N = N; a.K = K; a.T = T; a.H = H; a.P = P; a.G = G;
-    ssd_seg_plan(T, H, P, &a.nseg, &a.seg_steps);
-    const int nc = slabs_per_wg(P);
-    a.wg_per_seg = H * (P / 32) / nc;
+    ssd_seg_plan(T, H, P, G, &a.nseg, &a.seg_steps);
+    const int nc = slabs_per_wg(P), nh = heads_per_wg(H, P, G);
+    a.wg_per_seg = H * (P / 32) / nc / nh;
     a.lend = a.ltot = nullptr;
     if (a.nseg > 1) {
         if (!ws) return STRD_EWORKSPACE;
         a.lend = (float *)ws;
         a.ltot = (float *)((char *)ws + align_up((size_t)(a.nseg - 1) * H * P * n * sizeof(float), 256));
     }
-#define STRD_SEG_LAUNCH(NS_, NC_)                                                      \
-    return idx ? launch<NS_, NC_, true>(a, st) : launch<NS_, NC_, false>(a, st)
-    if (n == 128 && nc == 2) { STRD_SEG_LAUNCH(128, 2); }
-    if (n == 128 && nc == 1) { STRD_SEG_LAUNCH(128, 1); }
-    if (n == 64 && nc == 2) { STRD_SEG_LAUNCH(64, 2); }
-    if (n == 64 && nc == 1) { STRD_SEG_LAUNCH(64, 1); }
+#define STRD_SEG_LAUNCH(NS_, NC_, NH_)                                                 \
+    return idx ? launch<NS_, NC_, NH_, true>(a, st) : launch<NS_, NC_, NH_, false>(a, st)
+    if (n == 128 && nc == 2 && nh == 2) { STRD_SEG_LAUNCH(128, 2, 2); }
+    if (n == 64 && nc == 2 && nh == 2) { STRD_SEG_LAUNCH(64, 2, 2); }
+    if (n == 128 && nc == 2) { STRD_SEG_LAUNCH(128, 2, 1); }
+    if (n == 128 && nc == 1) { STRD_SEG_LAUNCH(128, 1, 1); }
+    if (n == 64 && nc == 2) { STRD_SEG_LAUNCH(64, 2, 1); }
+    if (n == 64 && nc == 1) { STRD_SEG_LAUNCH(64, 1, 1); }
 #undef STRD_SEG_LAUNCH
     return STRD_EUNSUPPORTED;
 }
