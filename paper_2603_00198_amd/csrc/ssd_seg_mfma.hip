@@ -342,8 +342,13 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, 
     constexpr int TA = GW == 0 ? 0 : 1, TB = GW == 0 ? 3 : 2;  // the two query blocks of this wave
     const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
     const int HP = a.H * a.P;
+    // The skip term D x_t rides on (c): D is added to the diagonal of the weights, M[t, t] += D, so that
+    // X M carries it (rounded to bf16 with the weight, like every other term of the sum).
     const float Dh = a.D ? a.D[h] : 0.f;
-    f32x4 ya[PT], yb[PT];  // (c) (+ D x) of the step before, until its carried part arrives
+    f32x4 dskip;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dskip[e] = 4 * lb + e == lr ? Dh : 0.f;
+    f32x4 ya[PT], yb[PT];  // (c) of the step before, until its carried part arrives
     // Outputs of a step: what is in ya / yb plus the carried part the compute waves left in LDS.
     // A lane holds 4 channels of one token, i.e. 8 bytes of a 32 PT-byte row of y; stored like that,
     // every store instruction would touch 16 rows with 32 bytes each.  The rows are turned in LDS first
@@ -485,17 +490,6 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, 
         for (int jt = 0; jt < TA; ++jt) fja[jt] = *reinterpret_cast<const f32x4 *>(&sc.fw[L::fw_at(TA) + 16 * jt + 4 * lb]);
 #pragma unroll
         for (int jt = 0; jt < TB; ++jt) fjb[jt] = *reinterpret_cast<const f32x4 *>(&sc.fw[L::fw_at(TB) + 16 * jt + 4 * lb]);
-        bf16x4 xva[PT] = {}, xvb[PT] = {};
-        auto request_dx = [&]() __attribute__((always_inline)) {  // this lane's x values for the D term
-            if (a.D) {
-#pragma unroll
-                for (int pt = 0; pt < PT; ++pt) {
-                    xva[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TA + lr) * L::kXP + xc0 + 16 * pt + 4 * lb]);
-                    xvb[pt] = *reinterpret_cast<const bf16x4 *>(&xt[(16 * TB + lr) * L::kXP + xc0 + 16 * pt + 4 * lb]);
-                }
-            }
-        };
-        if constexpr (NH == 1) request_dx();
         __builtin_amdgcn_sched_barrier(0);
         // (b): blocks below the diagonal: 2^(l_t - l_j) dt_j = 2^(l_t - l_ref) * fw[j] with l_ref the scan at
         // the last token before the query block (both exponents <= 0); diagonal block: direct, masked.
@@ -509,7 +503,7 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, 
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float val = g[e] * fast_exp2(el_t - elj[e]) * dtj[e];
+                    const float val = g[e] * fast_exp2(el_t - elj[e]) * dtj[e] + dskip[e];
                     mv[e] = (bf16_t)((4 * lb + e <= lr) ? val : 0.f);  // causal mask
                 }
             }
@@ -539,20 +533,9 @@ __device__ __forceinline__ void g_wave(LdsS<NS, NC, NH> &lds, const SegArgs &a, 
         // the stores of the step before go out now, not at the end of the step: the copies of the step
         // share the CU's path to memory with them and were requested at its start
         if (prev) emit_store(i - 1);
-        if constexpr (NH != 1) {
-            __builtin_amdgcn_sched_barrier(0);
-            request_dx();
-        }
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             ya[pt] = yb[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (a.D) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    ya[pt][e] = Dh * (float)xva[pt][e];
-                    yb[pt][e] = Dh * (float)xvb[pt][e];
-                }
-            }
 #pragma unroll
             for (int kr = 0; kr < 2; ++kr) {
                 if (2 * kr <= TA) ya[pt] = mfma16(xf[pt >> 1][kr][pt & 1], cat8(ma[2 * kr], ma[2 * kr + 1]), ya[pt]);
