@@ -120,7 +120,12 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     constexpr int KS = NS / 32;
     using L = Lds<NS>;
     const int lane = threadIdx.x & 63, lr = lane & 15, lb = lane >> 4;
+    // The skip term D x_t rides on (c): D is added to the diagonal of the weights, M[t, t] += D (rounded to
+    // bf16 with the weight, like every other term of the sum).
     const float Dh = D ? D[h] : 0.f;
+    f32x4 dskip;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dskip[i] = 4 * lb + i == lr ? Dh : 0.f;
     const int tcol = 16 * W + lr;  // this lane's token inside the step
     bf16_t *yp = y + ((size_t)tcol * H + h) * P + p0 + 4 * lb;
     const size_t y_step = (size_t)kQ * H * P;
@@ -165,6 +170,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
     fetch_issue_x(0);
     fetch_finish();
     __syncthreads();              // scans of steps 0 and 1 published
+    __syncthreads();              // (the state waves have read tile 0)
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
@@ -185,12 +191,6 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
                 sf[pt][ks] = *reinterpret_cast<const bf16x8 *>(&lds.s[cur][16 * pt + lr][32 * ks + 8 * lb]);
-        bf16x4 xv[2] = {};
-        if (D) {
-            const bf16_t *xt = lds.xr[step % kXRing].x;
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt) xv[pt] = *reinterpret_cast<const bf16x4 *>(&xt[tcol * L::kXP + 16 * pt + 4 * lb]);
-        }
         __builtin_amdgcn_sched_barrier(0);
         // (d): inter-step part from the state copy
         f32x4 yin[2];
@@ -220,7 +220,7 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
             } else if (jt == W) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float val = acc[W][i] * fast_exp2(el_t - el_j[i]) * dt_j[i];
+                    const float val = acc[W][i] * fast_exp2(el_t - el_j[i]) * dt_j[i] + dskip[i];
                     m4[jt][i] = (bf16_t)((4 * lb + i <= lr) ? val : 0.f);  // causal mask
                 }
             }
@@ -243,14 +243,8 @@ __device__ __forceinline__ void output_wave(Lds<NS> &lds, const float *__restric
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt) {
                 bf16x4 out;
-                if (D) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i] + Dh * (float)xv[pt][i]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i]);
-                }
+                for (int i = 0; i < 4; ++i) out[i] = (bf16_t)(yacc[pt][i] + carry * yin[pt][i]);
                 *reinterpret_cast<bf16x4 *>(yp + 16 * pt) = out;
             }
         }
@@ -338,6 +332,9 @@ __device__ __forceinline__ void state_wave(Lds<NS> &lds, const float *__restrict
     __syncthreads();
     __syncthreads();
     prepare(0);
+    // The first request of the copy waves' loop (tile 3) goes to the slot of tile 0: they wait here until
+    // its b fragments have been read.  (Every later prepare(q) runs a step before tile q's slot is requested again.)
+    __syncthreads();
 
     for (int step = 0; step < nsteps; ++step) {
         const int cur = step & 1;
@@ -486,6 +483,7 @@ __device__ __forceinline__ void helper_wave(Lds<NS> &lds, const bf16_t *__restri
     make_scan(0, lds.dt[0][lane]);
     make_scan(1, lds.dt[1][lane]);
     __syncthreads();
+    __syncthreads();  // (the state waves have read tile 0)
 
     for (int step = 0; step < nsteps; ++step) {
         const bool more = step + 3 < nsteps;  // uniform; nothing past the last step is requested
@@ -565,6 +563,7 @@ __device__ __forceinline__ void copy_wave(Lds<NS> &lds, const bf16_t *__restrict
     async_tile_wait();
     __syncthreads();  // first copies landed
     __syncthreads();  // (scans of steps 0 and 1)
+    __syncthreads();  // the state waves have read tile 0 (the first request of the loop overwrites it)
 
     for (int step = 0; step < nsteps; ++step) {
         if (step + 3 < nsteps) {  // uniform; nothing past the last step is requested

@@ -4,32 +4,42 @@
 // that own it for a whole segment of the sequence.
 //
 // Decomposition.  One workgroup owns 32*NC consecutive channels of one head (NC = 2: the whole
-// head when P = 64) and one segment of the sequence, which it walks in 64-token steps.  Per
-// step, with l_t the in-step cumulative sum of dt*A (log2 units):
+// head when P = 64) -- or, NH = 2, two whole heads of one group -- and one segment of the
+// sequence, which it walks in 64-token steps.  Per step and head, with l_t the in-step cumulative
+// sum of dt*A (log2 units):
 //   (a) G^T[j,t] = b_j . c_t                                      contraction over the state dim n
-//   (b) M[t,j]   = G^T[j,t] * 2^(l_t-l_j) * dt_j  for j <= t, else 0            (fp32, then bf16)
+//   (b) M[t,j]   = G^T[j,t] * 2^(l_t-l_j) * dt_j  for j <= t, else 0;  M[t,t] += D   (fp32, then bf16)
 //   (c) Y^T[p,t] = sum_j x_j[p] M[t,j]                            contraction over tokens
 //   (d) Y^T[p,t] += 2^(l_t) * sum_n S[p,n] c_t[n]                 S = state before the step
 //   (e) S^T[n,p] = 2^(l_Q) S^T[n,p] + sum_j b_j[n] (w_j x_j[p]),  w_j = dt_j 2^(l_Q-l_j)
-// every product a v_mfma_f32_16x16x32_bf16.  (a) and (b) depend on the head only, not on the
-// channel: two "G waves" do them once per workgroup, two query blocks of 16 tokens each, keep the
-// weights M in registers -- the accumulators of (a), rounded to bf16, are the B operand of (c) as
-// they stand -- and go on to (c) for all the workgroup's channels and to the outputs.  (d) and (e)
-// belong to NC "compute waves", one per slab of 32 channels, which hold their slab's state
-// S^T[n, 32] in fp32 accumulator registers from the first step to the last.  The accumulator
-// layout of (e) is at the same time the A-operand layout of (d) (the contraction index n runs
-// over the accumulator rows a lane holds), so the state is converted to bf16 in registers and
-// never passes through LDS; the carried part (d) of a step's outputs goes to the G waves through
-// LDS in accumulator layout, rounded to bf16 (8 bytes per lane, no bank conflicts).
+// every product a v_mfma_f32_16x16x32_bf16 (the skip term D x_t of the output rides on (c) through
+// the diagonal of M).  (a) and (b) depend on the head only, not on the channel: two "G waves" per
+// head do them once, two query blocks of 16 tokens each, keep the weights M in registers -- the
+// accumulators of (a), rounded to bf16, are the B operand of (c) as they stand -- and go on to (c)
+// for all the head's channels and to the outputs.  (d) and (e) belong to NC "compute waves" per
+// head, one per slab of 32 channels, which hold their slab's state S^T[n, 32] in fp32 accumulator
+// registers from the first step to the last.  The accumulator layout of (e) is at the same time
+// the A-operand layout of (d) (the contraction index n runs over the accumulator rows a lane
+// holds), so the state is converted to bf16 in registers and never passes through LDS; the
+// carried part (d) of a step's outputs goes to the G waves through LDS in accumulator layout,
+// rounded to bf16 (8 bytes per lane, no bank conflicts).
 //
-// Waves (NC + 6): NC compute waves; 2 G waves; one wave each that only requests the asynchronous
-// global -> LDS copies of the B tiles, the C tiles and the x tiles, two steps ahead (rings of 3);
-// a helper wave that requests dt three steps ahead and turns it into the scan l_t, the key
-// factors of (b), the weights of (e) and the carries of (d) one step ahead (and keeps the row
-// tables of the gather form).  One LDS-only barrier per step.  The outputs of a step leave one
-// step late: the G waves keep (c) of step i in registers, the compute waves leave the carried
-// part (d) of step i in LDS (bf16, double-buffered), the barrier that ends the step publishes it,
-// and the G waves add the two and store them while the arithmetic of step i + 1 runs.
+// Waves (NH (NC + 2) + 4): per head NC compute waves and 2 G waves; one wave each that only
+// requests the asynchronous global -> LDS copies of the B tiles, the C tiles and the x tiles; a
+// helper wave that requests dt three steps ahead and turns it into the scan l_t, the key factors
+// of (b), the weights of (e) and the carries of (d) one step ahead (and keeps the row tables of
+// the gather form).  One LDS-only barrier per step.  The outputs of a step leave one step late:
+// the G waves keep (c) of step i in registers, the compute waves leave the carried part (d) of
+// step i in LDS (bf16, double-buffered), the barrier that ends the step publishes it, and the G
+// waves add the two and store them while the arithmetic of step i + 1 runs.
+//
+// One head per workgroup (NH = 1): 8 waves, two per SIMD, 256 registers each; tiles two steps
+// ahead (rings of 3), every LDS read of a step requested at its start.  Two heads (NH = 2, P = 64
+// and an even number of heads per group): 12 waves, three per SIMD -- a compute wave, a G wave
+// and a copy wave -- so that the vector work of one arithmetic wave runs under the matrix
+// products and LDS round trips of the other, and the B and C tiles cross the CU's copy path once
+// for both heads.  That leaves 168 registers per wave and LDS for rings of 2 (tiles one step
+// ahead): reads are requested where they are needed instead of at the start of the step.
 //
 // Segments.  A head is a serial chain over time; to fill the chip the sequence is cut into a few
 // long segments that run side by side, each from a zero state (the first from S_in).  A segment
