@@ -294,12 +294,15 @@ def test_ssd_prefill_step_boundaries(T):
 
 
 @pytest.mark.parametrize("a_scale", [1.0, 1e-3, 0.0])
-@pytest.mark.parametrize("T,H,P,G,n", [(1600, 4, 64, 2, 128), (2085, 4, 64, 1, 128), (1100, 6, 96, 2, 64), (1300, 2, 128, 1, 64)])
+@pytest.mark.parametrize("T,H,P,G,n", [(1600, 4, 64, 2, 128), (2085, 4, 64, 1, 128), (1100, 6, 96, 2, 64), (1300, 2, 128, 1, 64),
+                                       (1500, 4, 64, 2, 64), (1990, 8, 64, 4, 64), (1290, 6, 64, 2, 128)])
 def test_ssd_prefill_segments_of_the_sequence(T, H, P, G, n, a_scale):
     """Few heads and a long sequence: the kernel cuts the sequence into segments that run side by
     side and repairs the seams afterwards.  With the workload's A the state at a seam dies within a
     few tokens; with A scaled down, or A = 0 (no decay at all), it reaches across whole segments and
-    through several seams.  Dense with D and a carried-in state, and through an index list."""
+    through several seams.  Dense with D and a carried-in state, and through an index list.  Head sizes of
+    64 with an even number of heads per group run two heads per workgroup (both state sizes), the others
+    (96, 128 channels; three heads per group) one."""
     _say("ssd_prefill segments T=%d H=%d P=%d G=%d n=%d A x %g" % (T, H, P, G, n, a_scale))
     g = torch.Generator().manual_seed(T + H)
     M = 19
