@@ -256,6 +256,9 @@ int strd_compact_varlen(const strd_compact_item *items, int n_items, const int32
  *   B,C [dev] [T, G, n]          D  [dev] [H] fp32 or NULL
  *   S_in  [dev] [H, P, n] fp32 or NULL (zero state)
  *   y     [dev] [T, H, P]        S_out [dev] [H, P, n] fp32 or NULL
+ * The bf16 matrix-core kernels add D x_t inside the token product (D joins the bf16 weight of
+ * token t on itself), i.e. that term carries a relative rounding error of up to 2^-9, like every
+ * other term of the sum and like the bf16 output itself.
  * `chunk` is the chunk length of the caller's formulation (> 0).  It is validated and
  * otherwise unused: it does NOT select the tiling.  The kernels always cut time into
  * 64-token steps and carry the state across them on chip, so results do not depend on
