@@ -1,0 +1,96 @@
+"""The first launch of a kernel in a process against the second, bit for bit.  Needs a GPU.
+
+A first launch runs with cold instruction and data caches, so the waves of a workgroup drift apart
+by microseconds where later launches keep them within nanoseconds of each other: an ordering between
+a copy and a read that the barriers do not enforce, but that the usual timing happens to provide,
+shows up there and nowhere else (the whole-sequence scan once built the state after its first step
+from the wrong tile of B that way).  Every kernel here has a fixed summation order, so two launches
+on the same inputs must agree in every bit.  Each case runs in a process of its own, after a few
+launches of other kernels, as in an application."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+SCRIPT = r"""
+import sys, torch
+sys.path.insert(0, sys.argv[1])
+import paper_2603_00198_amd as strd
+from paper_2603_00198_amd import synth
+case = sys.argv[2]
+DEV = "cuda"
+g = torch.Generator().manual_seed(7)
+def rnd(*shape, scale=1.0, dtype=torch.bfloat16):
+    return (torch.randn(*shape, generator=g) * scale).to(dtype).to(DEV)
+# launches of other kernels first: what the caches and the LDS hold when the case starts is not its own
+a = rnd(3000, 1024)
+strd.rmsnorm(a, rnd(1024))
+strd.select_topk(torch.rand(20000, generator=g).to(DEV), 5000)
+torch.cuda.synchronize()
+
+def mamba(T, H, P, G, n):
+    x, B, C = rnd(T, H, P), rnd(T, G, n, scale=n ** -0.5), rnd(T, G, n)
+    dt = torch.nn.functional.softplus(torch.randn(T, H, generator=g) - 2).to(DEV)
+    A = (-torch.exp(2 * torch.rand(H, generator=g))).to(DEV)
+    D = torch.randn(H, generator=g).to(DEV)
+    return x, dt, A, B, C, D
+
+if case == "ssd_whole_sequence":          # one workgroup per (head, 32 channels) walks the sequence
+    x, dt, A, B, C, D = mamba(2176, 128, 64, 8, 128)
+    call = lambda: strd.ssd_prefill(x, dt, A, B, C, D=D)
+elif case == "ssd_segments_two_heads":    # segments side by side, two heads per workgroup
+    x, dt, A, B, C, D = mamba(8320, 128, 64, 8, 128)
+    call = lambda: strd.ssd_prefill(x, dt, A, B, C, D=D)
+elif case == "ssd_segments_one_head":     # three heads per group: one head per workgroup
+    x, dt, A, B, C, D = mamba(4200, 12, 64, 4, 64)
+    call = lambda: strd.ssd_prefill(x, dt, A, B, C, D=D)
+elif case == "ssd_gather":
+    N, M, K = 8192, 128, 2048
+    x, dt, A, B, C, D = mamba(N + M, 128, 64, 8, 128)
+    idx = torch.sort(torch.randperm(N, generator=g)[:K]).values.to(torch.int32).to(DEV)
+    call = lambda: strd.ssd_prefill_gather(x, dt, A, B, C, idx, N, M, D=D)
+elif case == "attn_prefill":
+    q, k, v = rnd(4224, 32, 128), rnd(4224, 8, 128), rnd(4224, 8, 128)
+    call = lambda: (strd.attn_prefill(q, k, v),)
+elif case == "score_attn":
+    q, k = rnd(96, 32, 128), rnd(16384, 8, 128)
+    call = lambda: (strd.score_attn(q, k),)
+elif case == "score_mamba_short":
+    B, C = rnd(8192, 8, 128, scale=128 ** -0.5), rnd(128, 8, 128)
+    dt = torch.rand(8192, 128, generator=g).to(DEV)
+    call = lambda: (strd.score_mamba(B, C, dt),)
+elif case == "score_mamba_long":
+    B, C = rnd(65536, 8, 128, scale=128 ** -0.5), rnd(200, 8, 128)
+    dt = torch.rand(65536, 128, generator=g).to(DEV)
+    call = lambda: (strd.score_mamba(B, C, dt),)
+elif case == "linear_mfma":
+    xx, w, r = rnd(2300, 1024), rnd(1024, 2056, scale=1 / 32), rnd(2300, 2056)
+    call = lambda: (strd.linear_mfma(xx, w, r),)
+else:
+    raise SystemExit("unknown case " + case)
+first = [t.clone() for t in call() if t is not None]
+torch.cuda.synchronize()
+for rep in range(2):
+    again = [t for t in call() if t is not None]
+    torch.cuda.synchronize()
+    for i, (u, v_) in enumerate(zip(first, again)):
+        bad = int((u != v_).sum())
+        if bad:
+            raise SystemExit("%s: output %d of the first launch differs from launch %d in %d of %d elements"
+                             % (case, i, rep + 2, bad, u.numel()))
+print("ok", case, flush=True)
+"""
+
+CASES = ["ssd_whole_sequence", "ssd_segments_two_heads", "ssd_segments_one_head", "ssd_gather", "attn_prefill",
+         "score_attn", "score_mamba_short", "score_mamba_long", "linear_mfma"]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_first_launch_in_a_process_equals_the_second(case):
+    print("[case] cold start: " + case, flush=True)
+    r = subprocess.run([sys.executable, "-c", SCRIPT, ROOT, case], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and ("ok " + case) in r.stdout, (r.stdout[-2000:], r.stderr[-2000:])
