@@ -12,15 +12,18 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
-constexpr int kVecPerThread = 2;  // whole rows per workgroup, about this many vectors per thread (many small workgroups
-                                  // measured 5-7 % faster than 8 or 16 vectors per thread)
+constexpr int kVecPerThread = 2;  // about this many vectors per thread: whole rows per workgroup, or a piece of a row
+                                  // longer than that (many small workgroups measured 5-7 % faster than 8 or 16
+                                  // vectors per thread, and 16 KB rows 4 % faster in two pieces than whole; one
+                                  // vector per thread is 15 % slower)
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 struct Item {
     const void *src;
     void *dst;
     int vec_per_row;     // row length in vectors
-    int rows_per_block;  // whole rows handled by one workgroup
+    int rows_per_block;  // whole rows handled by one workgroup (1 when blocks_per_row > 1)
+    int blocks_per_row;  // workgroups that share one row: a row longer than a workgroup's share is cut into pieces
     int vec16;           // 1: 16-byte vectors, 0: 4-byte vectors
     int identity;        // 1: write the source row number itself (position map without pos_in)
 };
@@ -56,10 +59,13 @@ __device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restr
     const int vpr = it.vec_per_row;
     const Vec *__restrict__ src = reinterpret_cast<const Vec *>(it.src) + src_row0 * vpr;
     Vec *__restrict__ dst = reinterpret_cast<Vec *>(it.dst) + dst_row0 * vpr;
-    const int row0 = block * it.rows_per_block;
+    // whole rows, or (long rows) one piece of kThreads * kVecPerThread vectors of one row
+    const int bpr = it.blocks_per_row;
+    const int row0 = bpr > 1 ? block / bpr : block * it.rows_per_block;
+    const int col0 = bpr > 1 ? (block - row0 * bpr) * (kThreads * kVecPerThread) : 0;
     if (row0 >= rows_out) return;
     const int nrows = min(it.rows_per_block, rows_out - row0);
-    const int total = nrows * vpr;
+    const int total = bpr > 1 ? min(kThreads * kVecPerThread, vpr - col0) : nrows * vpr;
     for (int e0 = threadIdx.x; e0 < total; e0 += kThreads * kUnroll) {
         Vec v[kUnroll];
         size_t off[kUnroll];
@@ -67,8 +73,8 @@ __device__ __forceinline__ void copy_rows(const Item &it, const int32_t *__restr
         for (int u = 0; u < kUnroll; ++u) {
             const int e = e0 + u * kThreads;
             if (e < total) {
-                const int rl = e / vpr;
-                const int c = e - rl * vpr;
+                const int rl = bpr > 1 ? 0 : e / vpr;
+                const int c = bpr > 1 ? col0 + e : e - rl * vpr;
                 const int r = row0 + rl;
                 const int sr = (r < K) ? idx[r] : (N + (r - K));
                 v[u] = __builtin_nontemporal_load(src + (size_t)sr * vpr + c);  // streamed once: keep it out of L2
@@ -135,11 +141,15 @@ static int compact_plan(const strd_compact_item *items, int n_items, const int32
         const int64_t vpr = it.vec16 ? ci.row_bytes / 16 : ci.row_bytes / 4;
         if (vpr > (1 << 26)) return STRD_EUNSUPPORTED;
         it.vec_per_row = (int)vpr;
-        // whole rows only
+        // whole rows per workgroup, or several workgroups per row: about kVecPerThread vectors per thread either way
         it.rows_per_block = (kThreads * kVecPerThread) / it.vec_per_row;
         if (it.rows_per_block < 1) it.rows_per_block = 1;
-        grid_x = max(grid_x, ceil_div(rows_out, it.rows_per_block));
-        b.first_block[n + 1] = ceil_div(rows_out, it.rows_per_block);
+        it.blocks_per_row = ceil_div(it.vec_per_row, kThreads * kVecPerThread);
+        const long long blocks = it.blocks_per_row > 1 ? (long long)rows_out * it.blocks_per_row
+                                                       : (long long)ceil_div(rows_out, it.rows_per_block);
+        if (blocks > 0x7FFFFFFFLL) return STRD_EUNSUPPORTED;
+        grid_x = max(grid_x, (int)blocks);
+        b.first_block[n + 1] = (int)blocks;
         b.item[n++] = it;
     }
     if (pos_out) {
@@ -149,6 +159,7 @@ static int compact_plan(const strd_compact_item *items, int n_items, const int32
         it.identity = pos_in ? 0 : 1;
         it.vec16 = 0;
         it.vec_per_row = 1;
+        it.blocks_per_row = 1;
         it.rows_per_block = kThreads * 8;
         grid_x = max(grid_x, ceil_div(rows_out, pos_in ? it.rows_per_block : kThreads));
         b.first_block[n + 1] = ceil_div(rows_out, pos_in ? it.rows_per_block : kThreads);
