@@ -822,9 +822,14 @@ __global__ __launch_bounds__(kFixThreads) void ssd_fix_kernel(SegArgs a) {
         }
     };
     load_dt(0);
+    // (the workgroups of the first two tiles only: at the decay rates of a trained layer the later tiles of a
+    // batch are rarely reached, and every workgroup that loads E reads 32 KB -- they fetch it when they need it)
+    bool have_e = z < 2;  // uniform
+    if (have_e) {
 #pragma unroll
-    for (int q = 0; q < kMaxPT; ++q)
-        if (q < npt) load_e(wave + 4 * q, ef[q]);
+        for (int q = 0; q < kMaxPT; ++q)
+            if (q < npt) load_e(wave + 4 * q, ef[q]);
+    }
     float prefix = 0.f;  // log2 decay from the segment's start to the tile's start
     for (int k0 = 0; tok0 + k0 * kQ < tend; k0 += kFixZ) {
         if (k0 > 0) load_dt(k0);
@@ -860,6 +865,12 @@ __global__ __launch_bounds__(kFixThreads) void ssd_fix_kernel(SegArgs a) {
             }
         };
         if (__ballot(cr != 0.f) != 0ull) {
+            if (!have_e) {
+#pragma unroll
+                for (int q = 0; q < kMaxPT; ++q)
+                    if (q < npt) load_e(wave + 4 * q, ef[q]);
+                have_e = true;
+            }
 #pragma unroll
             for (int q = 0; q < kMaxPT; ++q)
                 if (q < npt) repair(wave + 4 * q, ef[q]);
