@@ -683,11 +683,23 @@ __device__ __forceinline__ void copy_wave(LdsS<NS, NC, NH> &lds, const SegArgs &
         TT::slot(0, lane, k, row_of[k], cv);
         col_of[k] = (uint32_t)col_bytes + (uint32_t)cv * 16;
     }
+    // dense form: this lane's byte offsets inside the 64 rows of a step, worked out once -- a step's requests
+    // are then its first row (a uniform pointer) plus these, and cost the SIMD no vector instruction
+    uint32_t voff[TT::kIssues];
+#pragma unroll
+    for (int k = 0; k < TT::kIssues; ++k) voff[k] = (uint32_t)row_of[k] * row_bytes + col_of[k];
     auto request = [&](int i) __attribute__((always_inline)) {
         bf16_t *dst = WHAT == 0 ? lds.xr[i % L::kRX].x : WHAT == 1 ? lds.bc[i % L::kRB].b : lds.bc[i % L::kRB].c;
+        const int t0 = tok0 + i * kQ;
+        if (!GATHER && t0 + kQ <= a.T) {  // uniform: every row of the step exists
+            const char *base = src + (size_t)t0 * row_bytes;
+#pragma unroll
+            for (int k = 0; k < TT::kIssues; ++k) TT::issue(base + voff[k], dst, 0, k);
+            return;
+        }
 #pragma unroll
         for (int k = 0; k < TT::kIssues; ++k) {
-            const uint32_t row = GATHER ? lds.rowtab[i & 3][row_of[k]] : (uint32_t)min(tok0 + i * kQ + row_of[k], a.T - 1);
+            const uint32_t row = GATHER ? lds.rowtab[i & 3][row_of[k]] : (uint32_t)min(t0 + row_of[k], a.T - 1);
             TT::issue(src + (size_t)row * row_bytes + col_of[k], dst, 0, k);
         }
     };
