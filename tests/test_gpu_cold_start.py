@@ -67,6 +67,22 @@ elif case == "score_mamba_long":
     B, C = rnd(65536, 8, 128, scale=128 ** -0.5), rnd(200, 8, 128)
     dt = torch.rand(65536, 128, generator=g).to(DEV)
     call = lambda: (strd.score_mamba(B, C, dt),)
+elif case == "select_topk_one_workgroup":
+    sc = torch.rand(30000, generator=g).to(DEV)
+    sc[::7] = sc[3]                       # many ties at one value
+    call = lambda: (strd.select_topk(sc, 7500),)
+elif case == "select_topk_many_workgroups":
+    sc = torch.rand(131072, generator=g).to(DEV)
+    sc[::5] = sc[11]
+    call = lambda: (strd.select_topk(sc, 32768),)
+elif case == "score_mamba_full":
+    B, C = rnd(4000, 8, 128, scale=128 ** -0.5), rnd(4000 + 96, 8, 128)[4000:].contiguous()
+    dt = torch.rand(4000 + 96, 128, generator=g).to(DEV)
+    A = (-torch.exp(2 * torch.rand(128, generator=g))).to(DEV) * 0.01
+    call = lambda: (strd.score_mamba_full(B, C, dt, A),)
+elif case == "attn_decode_step":
+    q, k, v = rnd(32, 128), rnd(20000, 8, 128), rnd(20000, 8, 128)
+    call = lambda: (strd.attn_decode_step(q, k, v),)
 elif case == "linear_mfma":
     xx, w, r = rnd(2300, 1024), rnd(1024, 2056, scale=1 / 32), rnd(2300, 2056)
     call = lambda: (strd.linear_mfma(xx, w, r),)
@@ -86,7 +102,8 @@ print("ok", case, flush=True)
 """
 
 CASES = ["ssd_whole_sequence", "ssd_segments_two_heads", "ssd_segments_one_head", "ssd_gather", "attn_prefill",
-         "score_attn", "score_mamba_short", "score_mamba_long", "linear_mfma"]
+         "score_attn", "score_mamba_short", "score_mamba_long", "select_topk_one_workgroup",
+         "select_topk_many_workgroups", "score_mamba_full", "attn_decode_step", "linear_mfma"]
 
 
 @pytest.mark.parametrize("case", CASES)
