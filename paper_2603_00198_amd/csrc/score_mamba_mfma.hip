@@ -356,7 +356,9 @@ __global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16
                 for (int nt = 0; nt < NT; ++nt)
                     part_sum[nt] += (fabsf(acc[nt][0]) + fabsf(acc[nt][1])) + (fabsf(acc[nt][2]) + fabsf(acc[nt][3]));
             };
-            for (int mt = 0; mt < nmt; ++mt) {
+            // (four blocks of 32 text rows per trip: at the head of the loop the compiler waits for every LDS read
+            // of the trip before, the last of which has only just been requested -- a quarter as many such waits)
+            auto rows32 = [&](int mt) __attribute__((always_inline)) {
                 const bf16_t *np = ap + (size_t)min(mt + 1, nmt - 1) * 32 * kPitch;
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt) {
@@ -380,6 +382,12 @@ __global__ __launch_bounds__(kResThreads) void score_mamba_res_kernel(const bf16
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) acc[nt] = c[nt];
                 }
+            };
+            for (int mt = 0; mt < nmt; mt += 4) {
+                rows32(mt);
+                if (mt + 1 < nmt) rows32(mt + 1);  // uniform
+                if (mt + 2 < nmt) rows32(mt + 2);
+                if (mt + 3 < nmt) rows32(mt + 3);
             }
             fold();
 #pragma unroll
